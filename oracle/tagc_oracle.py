@@ -1,0 +1,304 @@
+"""ctypes front end of the TAGC oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+
+Builds ``tagc_oracle.c`` with gcc on first use and exposes its functions, plus
+``run_bucket`` which strings them together in the order of the paper's
+Algorithm 1 (sparsify, create_index, All-Reduce(index) as OR, compress,
+Reduce as sum, peeling_decompress) for N simulated ranks.
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this
+module; it imports nothing from the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tagc_oracle.c")
+_LIB = os.path.join(_HERE, "_build", "libtagc_oracle.so")
+
+F32, BF16 = 0, 1
+SIZE_LOAD_FACTOR, SIZE_FIXED_RATIO = 0, 1
+FLAG_COMPRESS = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle (gcc -O2); returns the library path."""
+    os.makedirs(os.path.dirname(_LIB), exist_ok=True)
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+    if force or stale:
+        tmp = _LIB + ".%d.tmp" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        u32p, f32p, u64p = (C.POINTER(C.c_uint32), C.POINTER(C.c_float),
+                            C.POINTER(C.c_uint64))
+        L.tagco_key.restype = C.c_uint32
+        L.tagco_key.argtypes = [C.c_uint32]
+        L.tagco_keep_count.restype = C.c_uint64
+        L.tagco_keep_count.argtypes = [C.c_uint64, C.c_uint32]
+        L.tagco_sparsify_segment.restype = C.c_int64
+        L.tagco_sparsify_segment.argtypes = [
+            C.c_void_p, C.c_int, C.c_uint64, C.c_uint64, C.c_uint64,
+            C.c_uint32, u32p, f32p, u32p, u64p]
+        L.tagco_index_or.restype = C.c_uint64
+        L.tagco_index_or.argtypes = [C.POINTER(u32p), C.c_uint32, C.c_uint64,
+                                     u32p]
+        L.tagco_layout.restype = None
+        L.tagco_layout.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32,
+                                   C.c_uint64, C.c_uint32, C.c_uint32, u64p,
+                                   u64p, u64p]
+        L.tagco_part_start.restype = C.c_uint64
+        L.tagco_part_start.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
+        L.tagco_bounds.restype = None
+        L.tagco_bounds.argtypes = [u32p, C.c_uint64, C.c_uint64, C.c_uint64,
+                                   u32p]
+        L.tagco_mix32.restype = C.c_uint32
+        L.tagco_mix32.argtypes = [C.c_uint32]
+        L.tagco_seed_word.restype = C.c_uint32
+        L.tagco_seed_word.argtypes = [C.c_uint64, C.c_uint32]
+        L.tagco_hash.restype = None
+        L.tagco_hash.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32,
+                                 C.c_uint32, u32p, C.POINTER(C.c_int32)]
+        L.tagco_encode.restype = None
+        L.tagco_encode.argtypes = [u32p, f32p, C.c_uint64, u32p, C.c_uint64,
+                                   C.c_uint64, C.c_uint64, C.c_int, f32p]
+        L.tagco_sum.restype = None
+        L.tagco_sum.argtypes = [C.POINTER(f32p), C.c_uint32, C.c_uint64, f32p]
+        L.tagco_peel.restype = C.c_int
+        L.tagco_peel.argtypes = [u32p, C.c_uint64, C.c_uint64, C.c_uint64,
+                                 C.c_uint64, C.c_uint64, C.c_int, f32p, u32p,
+                                 f32p, u32p, u32p, u64p]
+        L.tagco_wire_bits_per_param.restype = C.c_double
+        L.tagco_wire_bits_per_param.argtypes = [C.c_double, C.c_double,
+                                                C.c_int]
+        _lib = L
+    return _lib
+
+
+def _u32p(a):
+    return a.ctypes.data_as(C.POINTER(C.c_uint32))
+
+
+def _f32p(a):
+    return a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+# --------------------------------------------------------------------------
+# bucket description
+
+
+@dataclass
+class Segment:
+    offset: int          # element offset in the rank's gradient buffer
+    length: int          # n_l
+    keep_ppm: int        # survivors per million (1 - theta)
+    flags: int = FLAG_COMPRESS
+
+
+@dataclass
+class Config:
+    dtype: int = F32
+    sizing: int = SIZE_LOAD_FACTOR
+    sizing_milli: int = 3000
+    seed: int = 0
+    part_unknowns: int = 16384   # P_cap
+    part_cells: int = 24576      # T_cap (multiple of 3)
+
+
+def c_offsets(segments):
+    """c-index offset of every compressed segment (None for skipped ones) and
+    the padded total n_c.  Layer-selective compression (section 3.2,
+    "Selective Compressing"): segments without the COMPRESS flag get no index
+    bits and no sketch cells.  Offsets are rounded up to a multiple of 32 so a
+    bit-map word never belongs to two segments."""
+    offs, c = [], 0
+    for s in segments:
+        if s.flags & FLAG_COMPRESS:
+            offs.append(c)
+            c = (c + s.length + 31) // 32 * 32
+        else:
+            offs.append(None)
+    return offs, c
+
+
+def keep_count(n, ppm):
+    return int(lib().tagco_keep_count(n, ppm))
+
+
+def _as_raw(grad, dtype):
+    """grad: numpy float32 array (F32) or uint16 array of bf16 bit patterns."""
+    want = np.float32 if dtype == F32 else np.uint16
+    a = np.ascontiguousarray(grad)
+    if a.dtype != want:
+        raise TypeError("oracle expects %s for dtype %d, got %s"
+                        % (want, dtype, a.dtype))
+    return a
+
+
+@dataclass
+class RankState:
+    idx: np.ndarray
+    val: np.ndarray
+    cnt: int
+    seg_cnt: list
+    bitmap: np.ndarray
+    sketch: np.ndarray | None = None
+
+
+def sparsify(grad, cfg: Config, segments) -> RankState:
+    """sparsify + create_index over all compressed segments of one rank."""
+    L = lib()
+    g = _as_raw(grad, cfg.dtype)
+    offs, n_c = c_offsets(segments)
+    cap = sum(keep_count(s.length, s.keep_ppm) for s in segments
+              if s.flags & FLAG_COMPRESS)
+    idx = np.zeros(max(cap, 1), np.uint32)
+    val = np.zeros(max(cap, 1), np.float32)
+    bitmap = np.zeros(max(n_c // 32, 1), np.uint32)
+    pos, seg_cnt = 0, []
+    for s, co in zip(segments, offs):
+        if co is None:
+            seg_cnt.append(0)
+            continue
+        if s.offset + s.length > g.size:
+            raise ValueError("segment exceeds gradient buffer")
+        k = keep_count(s.length, s.keep_ppm)
+        c = C.c_uint64(0)
+        nf = L.tagco_sparsify_segment(
+            g.ctypes.data_as(C.c_void_p), cfg.dtype, s.offset, s.length, k, co,
+            _u32p(idx[pos:]), _f32p(val[pos:]), _u32p(bitmap), C.byref(c))
+        if nf < 0:
+            raise MemoryError("oracle allocation failed")
+        if nf > 0:
+            raise ValueError("non-finite gradient values: %d" % nf)
+        seg_cnt.append(int(c.value))
+        pos += int(c.value)
+    return RankState(idx[:pos].copy(), val[:pos].copy(), pos, seg_cnt, bitmap)
+
+
+def index_or(bitmaps):
+    L = lib()
+    n = len(bitmaps)
+    words = bitmaps[0].size
+    arr = (C.POINTER(C.c_uint32) * n)(*[_u32p(b) for b in bitmaps])
+    out = np.zeros(words, np.uint32)
+    U = L.tagco_index_or(arr, n, words, _u32p(out))
+    return out, int(U)
+
+
+def layout(U, cfg: Config, n_real):
+    A, ms, m = C.c_uint64(), C.c_uint64(), C.c_uint64()
+    lib().tagco_layout(U, cfg.sizing, cfg.sizing_milli, n_real,
+                       cfg.part_unknowns, cfg.part_cells, C.byref(A),
+                       C.byref(ms), C.byref(m))
+    return int(A.value), int(ms.value), int(m.value)
+
+
+def bounds(bitmap, n_c, U, A):
+    bnd = np.zeros(A + 1, np.uint32)
+    lib().tagco_bounds(_u32p(bitmap), n_c, U, A, _u32p(bnd))
+    return bnd
+
+
+def hash_slot(i, seed, j, m_sub):
+    slot, sign = C.c_uint32(), C.c_int32()
+    lib().tagco_hash(i, seed, j, m_sub, C.byref(slot), C.byref(sign))
+    return int(slot.value), int(sign.value)
+
+
+def encode(idx, val, bnd, A, m_sub, seed, plus_only=False):
+    m = 3 * A * m_sub
+    sk = np.zeros(max(m, 1), np.float32)
+    idx = np.ascontiguousarray(idx, np.uint32)
+    val = np.ascontiguousarray(val, np.float32)
+    lib().tagco_encode(_u32p(idx), _f32p(val), idx.size, _u32p(bnd), A, m_sub,
+                       seed, int(plus_only), _f32p(sk))
+    return sk[:m]
+
+
+def sketch_sum(sketches):
+    n = len(sketches)
+    m = sketches[0].size
+    keep = [np.ascontiguousarray(s, np.float32) for s in sketches]
+    arr = (C.POINTER(C.c_float) * n)(*[_f32p(s) for s in keep])
+    out = np.zeros(max(m, 1), np.float32)
+    if m:
+        lib().tagco_sum(arr, n, m, _f32p(out))
+    return out[:m]
+
+
+@dataclass
+class Decoded:
+    idx: np.ndarray
+    val: np.ndarray
+    round: np.ndarray
+    rounds: int
+    n_unresolved: int
+    residual: np.ndarray = field(default=None, repr=False)
+
+
+def peel(bitmap, n_c, U, A, m_sub, seed, sketch, plus_only=False) -> Decoded:
+    idx = np.zeros(max(U, 1), np.uint32)
+    val = np.zeros(max(U, 1), np.float32)
+    rnd = np.zeros(max(U, 1), np.uint32)
+    work = np.array(sketch, np.float32, copy=True)
+    if work.size == 0:
+        work = np.zeros(1, np.float32)
+    rounds, unres = C.c_uint32(), C.c_uint64()
+    rc = lib().tagco_peel(_u32p(bitmap), n_c, U, A, m_sub, seed,
+                          int(plus_only), _f32p(work), _u32p(idx), _f32p(val),
+                          _u32p(rnd), C.byref(rounds), C.byref(unres))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    return Decoded(idx[:U], val[:U], rnd[:U], int(rounds.value),
+                   int(unres.value), work)
+
+
+@dataclass
+class BucketResult:
+    ranks: list
+    bitmap: np.ndarray
+    U: int
+    A: int
+    m_sub: int
+    m: int
+    bnd: np.ndarray
+    sketch: np.ndarray
+    decoded: Decoded
+    n_c: int
+
+
+def run_bucket(grads, cfg: Config, segments, plus_only=False) -> BucketResult:
+    """Algorithm 1 for one bucket and len(grads) simulated ranks."""
+    offs, n_c = c_offsets(segments)
+    n_real = sum(s.length for s in segments if s.flags & FLAG_COMPRESS)
+    ranks = [sparsify(g, cfg, segments) for g in grads]
+    bitmap, U = index_or([r.bitmap for r in ranks])
+    A, m_sub, m = layout(U, cfg, n_real)
+    bnd = bounds(bitmap, n_c, U, A)
+    for r in ranks:
+        r.sketch = encode(r.idx, r.val, bnd, A, m_sub, cfg.seed, plus_only)
+    total = sketch_sum([r.sketch for r in ranks])
+    dec = peel(bitmap, n_c, U, A, m_sub, cfg.seed, total, plus_only)
+    return BucketResult(ranks, bitmap, U, A, m_sub, m, bnd, total, dec, n_c)
+
+
+def wire_bits_per_param(index_bits, ratio, lhc=False):
+    return float(lib().tagco_wire_bits_per_param(index_bits, ratio, int(lhc)))

@@ -1,0 +1,306 @@
+"""Pins for the oracle's encode / aggregate / peel chain: the homomorphism,
+losslessness against the written-out definition, an independent peeler, the
+peeling threshold, and the numbers the paper prints."""
+import os
+from collections import deque
+
+import numpy as np
+import pytest
+
+from oracle import tagc_oracle as O
+from oracle import definition as D
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "paper_numbers.txt")
+
+
+def _paper():
+    out = {}
+    with open(GOLD) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                out[line[0]] = float(line[1])
+    return out
+
+
+# ----------------------------------------------------- communication volume
+
+
+def test_wire_volume_reproduces_the_papers_numbers():
+    p = _paper()
+    # Count Sketch at 2x costs 16 bit per parameter (Figure 1 caption)
+    assert O.wire_bits_per_param(0, 2) == p["sketch_bits_per_param_2x"]
+    # TAGC, 10x sketch + 1-bit Index: 2*1 + 32/10 = 5.2 bit -> 32/5.2 = 6.15x
+    bits = O.wire_bits_per_param(1, 10)
+    assert abs(bits - 5.2) < 1e-12
+    assert round(32.0 / bits, 2) == p["tagc_speedup_vs_fp32_10x_1bit"]
+    # Reduce moves half of what All-Reduce moves, for the sketch part
+    lhc = O.wire_bits_per_param(1, 10, lhc=True)
+    assert (lhc - 2) / (bits - 2) == p["reduce_vs_allreduce_factor"]
+    # the 4-bit Index is four times the 1-bit Index
+    i4 = O.wire_bits_per_param(4, 10) - O.wire_bits_per_param(0, 10)
+    i1 = O.wire_bits_per_param(1, 10) - O.wire_bits_per_param(0, 10)
+    assert abs(i4 / i1 - p["index_4bit_vs_1bit_factor"]) < 1e-12
+
+
+# ------------------------------------------------------------ helper inputs
+
+
+def _int_grads(rng, n, n_ranks, density=0.3):
+    """Small-integer gradients: every float32 add/subtract is exact."""
+    out = []
+    for _ in range(n_ranks):
+        v = rng.integers(-1000, 1001, n).astype(np.float32)
+        v *= rng.random(n) < density
+        out.append(v)
+    return out
+
+
+def _cfg(lf=3000, P=256, T=768, seed=9, mode=O.SIZE_LOAD_FACTOR, dtype=O.F32):
+    return O.Config(dtype=dtype, sizing=mode, sizing_milli=lf, seed=seed,
+                    part_unknowns=P, part_cells=T)
+
+
+# ------------------------------------------------------ homomorphism (P3)
+
+
+def test_encode_is_linear_and_index_is_a_union():
+    """f(g1) + f(g2) = f(g1 + g2)  (section 1) for the sketch; OR for the
+    Index (section 2.2)."""
+    rng = np.random.default_rng(0)
+    n = 20_000
+    segs = [O.Segment(0, n, 1_000_000)]        # keep everything non-zero
+    cfg = _cfg()
+    x, y = _int_grads(rng, n, 2, density=0.02)
+    sx, sy = O.sparsify(x, cfg, segs), O.sparsify(y, cfg, segs)
+    sxy = O.sparsify(x + y, cfg, segs)
+    bm, U = O.index_or([sx.bitmap, sy.bitmap])
+    # supports: union, except where x + y cancels exactly
+    cancel = (x != 0) & (y != 0) & (x + y == 0)
+    assert np.array_equal(
+        np.flatnonzero(np.unpackbits(bm.view(np.uint8), bitorder="little")),
+        np.flatnonzero((x != 0) | (y != 0)))
+    assert U == np.count_nonzero((x != 0) | (y != 0))
+    A, ms, m = O.layout(U, cfg, n)
+    bnd = O.bounds(bm, n, U, A)
+    ex = O.encode(sx.idx, sx.val, bnd, A, ms, cfg.seed)
+    ey = O.encode(sy.idx, sy.val, bnd, A, ms, cfg.seed)
+    exy = O.encode(sxy.idx, sxy.val, bnd, A, ms, cfg.seed)
+    assert np.array_equal(O.sketch_sum([ex, ey]), exy)
+    assert cancel.sum() >= 0
+    # summing is element-wise and in rank order
+    three = [ex, ey, exy]
+    assert np.array_equal(O.sketch_sum(three), (ex + ey) + exy)
+
+
+# ------------------------------------ losslessness vs the definition (P4, P6)
+
+
+@pytest.mark.parametrize("lf", [1500, 3000])
+@pytest.mark.parametrize("n_ranks", [1, 2, 5])
+def test_integer_inputs_decode_bit_exactly_to_the_definition(lf, n_ranks):
+    rng = np.random.default_rng(lf + n_ranks)
+    n = 60_000
+    segs = [O.Segment(0, 25_000, 30_000), O.Segment(25_000, 35_000, 50_000)]
+    grads = _int_grads(rng, n, n_ranks, density=0.9)
+    cfg = _cfg(lf=lf, P=1024, T=3072)
+    r = O.run_bucket(grads, cfg, segs)
+    idx, val = D.sparse_sum(grads, O.F32, segs)
+    assert r.A > 1                       # several partitions
+    assert np.array_equal(r.decoded.idx, idx)
+    ok = r.decoded.round > 0
+    assert r.decoded.n_unresolved == np.count_nonzero(~ok)
+    assert r.decoded.n_unresolved <= 4   # duplicate triples only, see below
+    assert np.array_equal(r.decoded.val[ok].astype(np.float64), val[ok])
+    assert np.all(r.decoded.val[~ok] == 0)
+    # after a complete peel nothing is left in the sketch
+    if r.decoded.n_unresolved == 0:
+        assert not r.decoded.residual[:r.m].any()
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_float_inputs_decode_within_tolerance(dtype):
+    import torch
+    rng = np.random.default_rng(77)
+    n, N = 150_000, 4
+    segs = [O.Segment(0, n, 10_000)]
+    grads = [(rng.standard_normal(n) * 1e-3).astype(np.float32)
+             for _ in range(N)]
+    if dtype == O.BF16:
+        grads = [torch.from_numpy(g).to(torch.bfloat16).view(torch.int16)
+                 .numpy().view(np.uint16).copy() for g in grads]
+    cfg = _cfg(lf=1500, P=2048, T=3072, dtype=dtype)
+    r = O.run_bucket(grads, cfg, segs)
+    idx, val = D.sparse_sum(grads, dtype, segs)
+    assert np.array_equal(r.decoded.idx, idx)
+    assert r.decoded.n_unresolved == 0
+    # every contribution is at least tau (smallest selected magnitude)
+    tau = min(float(np.abs(s.val).min()) for s in r.ranks)
+    err = np.abs(r.decoded.val.astype(np.float64) - val)
+    assert np.all(err <= 1e-5 * np.maximum(np.abs(val), tau))
+
+
+# ---------------------------------------------- independent peeler (P5)
+
+
+def _worklist_two_core(keys, cells_of):
+    """Textbook queue-based peeling of a hypergraph: returns the set of keys
+    that can be peeled (complement of the 2-core)."""
+    deg, members = {}, {}
+    for k in keys:
+        for c in cells_of[k]:
+            deg[c] = deg.get(c, 0) + 1
+            members.setdefault(c, set()).add(k)
+    q = deque(c for c, d in deg.items() if d == 1)
+    done = set()
+    while q:
+        c = q.popleft()
+        if deg[c] != 1:
+            continue
+        (k,) = members[c]
+        done.add(k)
+        for c2 in cells_of[k]:
+            members[c2].discard(k)
+            deg[c2] -= 1
+            if deg[c2] == 1:
+                q.append(c2)
+    return done
+
+
+@pytest.mark.parametrize("lf", [900, 1150, 1300, 2000])
+def test_resolved_set_is_the_complement_of_the_two_core(lf):
+    rng = np.random.default_rng(lf)
+    n = 40_000
+    segs = [O.Segment(0, n, 1_000_000)]
+    g = _int_grads(rng, n, 1, density=0.05)
+    cfg = _cfg(lf=lf, P=512, T=3 * 512)
+    r = O.run_bucket(g, cfg, segs)
+    keys = r.decoded.idx.tolist()
+    part = np.searchsorted(r.bnd[1:r.A], r.decoded.idx, side="right")
+    cells = {}
+    for k, a in zip(keys, part):
+        cells[k] = [int(a) * 3 * r.m_sub + j * r.m_sub
+                    + O.hash_slot(k, cfg.seed, j, r.m_sub)[0] for j in range(3)]
+    peeled = _worklist_two_core(keys, cells)
+    got = set(np.asarray(keys)[r.decoded.round > 0].tolist())
+    assert got == peeled
+    assert r.decoded.n_unresolved == len(keys) - len(peeled)
+    if lf <= 1150:
+        assert r.decoded.n_unresolved > 0.3 * len(keys)   # below threshold
+    # resolved values are exact (integer inputs) even when others are stuck
+    ok = r.decoded.round > 0
+    assert np.array_equal(r.decoded.val[ok], g[0][r.decoded.idx[ok]])
+
+
+def test_exhaustive_tiny_cases_against_brute_force_rounds():
+    """n <= 24: peel by hand-written round simulation in Python."""
+    rng = np.random.default_rng(4)
+    for trial in range(60):
+        n = int(rng.integers(1, 25))
+        g = rng.integers(-9, 10, 32).astype(np.float32)
+        g[n:] = 0
+        cfg = _cfg(lf=int(rng.choice([1000, 1500, 3000])), P=8, T=24,
+                   seed=trial)
+        r = O.run_bucket([g], cfg, [O.Segment(0, 32, 1_000_000)])
+        keys = r.decoded.idx.tolist()
+        part = np.searchsorted(r.bnd[1:r.A], r.decoded.idx, side="right")
+        cells = {k: [int(a) * 3 * r.m_sub + j * r.m_sub
+                     + O.hash_slot(k, cfg.seed, j, r.m_sub)[0]
+                     for j in range(3)] for k, a in zip(keys, part)}
+        alive, rnd, t = set(keys), {}, 0
+        while True:
+            t += 1
+            deg = {}
+            for k in alive:
+                for c in cells[k]:
+                    deg[c] = deg.get(c, 0) + 1
+            pick = [k for k in alive if any(deg[c] == 1 for c in cells[k])]
+            if not pick:
+                break
+            for k in pick:
+                rnd[k] = t
+            alive -= set(pick)
+        assert [rnd.get(k, 0) for k in keys] == r.decoded.round.tolist()
+        assert r.decoded.rounds == t - 1
+
+
+# ------------------------------------------------- peeling threshold (P7)
+
+
+@pytest.mark.parametrize("lf,expect_ok", [(1100, False), (1500, True),
+                                          (3000, True)])
+def test_peeling_threshold_of_three_hash_sketches(lf, expect_ok):
+    """Random 3-uniform hypergraphs peel w.h.p. iff cells/unknowns > ~1.222."""
+    rng = np.random.default_rng(lf)
+    n = 2_000_000
+    segs = [O.Segment(0, n, 1_000_000)]
+    g = _int_grads(rng, n, 1, density=0.06)       # U ~ 120 000
+    cfg = O.Config(sizing_milli=lf, seed=3)       # default partition sizes
+    r = O.run_bucket(g, cfg, segs)
+    assert r.U > 100_000
+    if expect_ok:
+        # a partition of P unknowns fails only through two indices sharing all
+        # three cells: expected pairs ~ 13.5 U / (lf^3 P^2) << 1 here
+        assert r.decoded.n_unresolved <= 2
+    else:
+        assert r.decoded.n_unresolved > 0.5 * r.U
+
+
+@pytest.mark.parametrize("ratio_milli,theta_ppm", [(2000, 200_000),
+                                                   (4000, 100_000),
+                                                   (10_000, 12_500)])
+def test_table1_regimes_are_lossless_for_two_ranks(ratio_milli, theta_ppm):
+    """Table 1: c-x compression is lossless at the stated sparsity, for the
+    paper's two ranks (section 4.1) with independent supports."""
+    rng = np.random.default_rng(ratio_milli)
+    n = 600_000
+    segs = [O.Segment(0, n, theta_ppm)]
+    grads = [rng.integers(1, 1000, n).astype(np.float32)
+             * rng.choice([-1, 1], n).astype(np.float32) for _ in range(2)]
+    cfg = O.Config(sizing=O.SIZE_FIXED_RATIO, sizing_milli=ratio_milli, seed=1)
+    r = O.run_bucket(grads, cfg, segs)
+    assert r.m <= n * 1000 // ratio_milli
+    assert r.m / r.U > 1.25
+    assert r.decoded.n_unresolved <= 2
+    idx, val = D.sparse_sum(grads, O.F32, segs)
+    ok = r.decoded.round > 0
+    assert np.array_equal(r.decoded.idx, idx)
+    assert np.array_equal(r.decoded.val[ok].astype(np.float64), val[ok])
+
+
+# ------------------------------------------------------- signs (P9), edges
+
+
+def test_signs_do_not_change_what_is_decoded():
+    rng = np.random.default_rng(8)
+    n = 30_000
+    segs = [O.Segment(0, n, 40_000)]
+    grads = _int_grads(rng, n, 3, density=1.0)
+    cfg = _cfg(lf=1500, P=512, T=768)
+    a = O.run_bucket(grads, cfg, segs)
+    b = O.run_bucket(grads, cfg, segs, plus_only=True)
+    assert np.array_equal(a.decoded.idx, b.decoded.idx)
+    assert np.array_equal(a.decoded.round, b.decoded.round)
+    assert np.array_equal(a.decoded.val, b.decoded.val)
+    assert not np.array_equal(a.sketch, b.sketch)
+
+
+def test_cancelling_entries_are_still_reported():
+    g0 = np.zeros(64, np.float32)
+    g1 = np.zeros(64, np.float32)
+    g0[[3, 40]] = [5.0, 2.0]
+    g1[[3, 41]] = [-5.0, 7.0]
+    r = O.run_bucket([g0, g1], _cfg(), [O.Segment(0, 64, 1_000_000)])
+    assert r.decoded.idx.tolist() == [3, 40, 41]
+    assert r.decoded.val.tolist() == [0.0, 2.0, 7.0]
+    assert r.decoded.n_unresolved == 0
+
+
+def test_empty_bucket_and_all_zero_gradient():
+    r = O.run_bucket([np.zeros(100, np.float32)] * 2, _cfg(),
+                     [O.Segment(0, 100, 500_000)])
+    assert (r.U, r.A, r.m) == (0, 0, 0)
+    assert r.decoded.idx.size == 0 and r.decoded.n_unresolved == 0
+    r = O.run_bucket([np.ones(100, np.float32)], _cfg(),
+                     [O.Segment(0, 100, 500_000, flags=0)])
+    assert r.U == 0 and r.n_c == 0
