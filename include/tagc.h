@@ -1,0 +1,258 @@
+/*
+ * libtagc -- the per-GPU hot path of TAGC (Transformer-Aware Gradient
+ * Compression, arXiv 2504.05638) for AMD MI355X (gfx950).
+ *
+ * One call sequence processes one gradient bucket (what one FSDP
+ * communication hook sees, Algorithm 1) for N ranks simulated on one GPU:
+ *
+ *   tagc_plan            host only, once per bucket shape
+ *   tagc_plan_upload     copies the segment table to the device, once
+ *   for each rank r:  tagc_compress(PHASE_INDEX)    sparsify + create_index
+ *   tagc_aggregate(PHASE_INDEX)                     All-Reduce(index) as OR
+ *   for each rank r:  tagc_compress(PHASE_SKETCH)   compress -> Count Sketch
+ *   tagc_aggregate(PHASE_SKETCH)                    Reduce as element-wise sum
+ *   tagc_decompress                                 peeling_decompress
+ *
+ * Conventions for every function below
+ *   - returns TAGC_OK (0) or a negative tagc_error; never throws;
+ *   - "dev" pointers are device (HBM) addresses owned by the caller, "host"
+ *     pointers are ordinary host memory; the library never allocates or frees
+ *     device memory and never synchronises a stream;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); all
+ *     device work of a call is enqueued on it, in order;
+ *   - device buffers must be 16-byte aligned and at least as large as
+ *     tagc_plan_sizes reports; their contents on entry do not matter unless
+ *     stated;
+ *   - argument errors are reported by return code before anything is
+ *     enqueued; data-dependent conditions (peeling left a residue, non-finite
+ *     inputs) are reported in device-side status words that the caller reads
+ *     after synchronising.
+ */
+#ifndef TAGC_H
+#define TAGC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tagc_error {
+    TAGC_OK = 0,
+    TAGC_EINVAL = -1,       /* bad argument (null pointer, misaligned, bad enum) */
+    TAGC_ESIZE = -2,        /* a size exceeds what the format can address        */
+    TAGC_EUNSUPPORTED = -3, /* valid request this build does not implement       */
+    TAGC_EHIP = -4,         /* a HIP runtime call failed                         */
+    TAGC_ENOMEM = -5        /* host allocation failed                            */
+} tagc_error;
+
+enum { TAGC_F32 = 0, TAGC_BF16 = 1 };                      /* tagc_config.dtype  */
+enum { TAGC_SIZE_LOAD_FACTOR = 0, TAGC_SIZE_FIXED_RATIO = 1 }; /* .sizing        */
+enum { TAGC_INDEX_OR1 = 0 };                               /* .index_mode        */
+enum { TAGC_PHASE_INDEX = 1, TAGC_PHASE_SKETCH = 2 };
+#define TAGC_SEG_COMPRESS 1u
+
+/*
+ * One layer (or layer shard) of the bucket.  Layer-selective compression
+ * (section 3.2, "Selective Compressing"): segments without TAGC_SEG_COMPRESS
+ * are neither read nor written and get no index bits and no sketch cells.
+ * Compressed segments are renumbered, in table order, into one "c-index"
+ * space; each segment's c-offset is rounded up to a multiple of 32.
+ */
+typedef struct tagc_segment {
+    uint64_t offset;   /* element offset inside each rank's gradient buffer   */
+    uint64_t length;   /* n_l, elements; < 2^31                                */
+    uint32_t keep_ppm; /* survivors per million, i.e. (1 - theta) * 10^6; the */
+                       /* segment keeps k_l = floor(n_l*keep_ppm/10^6) entries */
+                       /* (section 3.2: at least theta of the values become 0) */
+    uint32_t flags;    /* TAGC_SEG_COMPRESS or 0                               */
+} tagc_segment;
+
+typedef struct tagc_config {
+    uint32_t dtype;         /* TAGC_F32 | TAGC_BF16: element type of the gradient */
+    uint32_t n_ranks;       /* N, upper bound on ranks aggregated (sizing only)   */
+    uint32_t n_hash;        /* must be 3                                          */
+    uint32_t sizing;        /* TAGC_SIZE_LOAD_FACTOR: cells = sizing_milli/1000 x
+                               non-zeros of the merged Index;
+                               TAGC_SIZE_FIXED_RATIO: cells = n / (sizing_milli/
+                               1000), the "c-x compression" of Table 1          */
+    uint32_t sizing_milli;
+    uint32_t index_mode;    /* TAGC_INDEX_OR1: 1 bit per parameter, merged by OR
+                               (section 2.2)                                    */
+    uint32_t part_unknowns; /* max non-zeros per sketch partition, 0 = default  */
+    uint32_t part_cells;    /* max cells per sketch partition (multiple of 3),
+                               0 = default                                      */
+    uint64_t seed;          /* hash seed; all ranks must use the same           */
+} tagc_config;
+
+typedef struct tagc_plan_s tagc_plan_t; /* opaque, host memory, immutable */
+
+/* Every size a caller needs; bytes unless the name says otherwise. */
+typedef struct tagc_sizes {
+    uint64_t n_seg_compressed;
+    uint64_t n_real;            /* sum of n_l over compressed segments          */
+    uint64_t n_c;               /* size of the c-index space (padded, % 32 == 0) */
+    uint64_t bitmap_words;      /* n_c / 32                                     */
+    uint64_t pair_capacity;     /* K = sum of k_l: most pairs one rank emits    */
+    uint64_t union_capacity;    /* most non-zeros the merged Index can have     */
+    uint64_t partition_capacity;/* most sketch partitions                       */
+    uint64_t sketch_cells_capacity; /* most sketch cells m                      */
+    uint64_t part_unknowns, part_cells; /* format parameters in effect          */
+    uint64_t grad_elems;        /* elements each rank's gradient buffer must hold
+                                   (largest offset + length over compressed segments) */
+
+    uint64_t table_bytes;       /* device copy of the segment table             */
+    /* per rank */
+    uint64_t rank_idx_bytes, rank_val_bytes, rank_cnt_bytes, rank_bitmap_bytes,
+        rank_sketch_bytes, rank_workspace_bytes;
+    /* shared (one per bucket) */
+    uint64_t shared_bitmap_bytes, shared_sketch_bytes, shared_header_bytes,
+        shared_bounds_bytes, shared_workspace_bytes, shared_status_bytes;
+    /* decoder outputs */
+    uint64_t out_idx_bytes, out_val_bytes, out_dense_bytes;
+
+    /* Bits per parameter per rank on the wire (Figures 1 and 2): Index moved
+     * by All-Reduce (payload counted twice), Count Sketch by Reduce (once).
+     * In load-factor mode the sketch term uses sketch_cells_capacity. */
+    double wire_index_bits, wire_sketch_bits, wire_total_bits;
+} tagc_sizes;
+
+/* rank `cnt` words (uint32) */
+enum {
+    TAGC_CNT_TOTAL = 0,     /* pairs emitted by this rank                        */
+    TAGC_CNT_NONFINITE = 1, /* inputs with all-ones exponent seen (result then
+                               unspecified but memory-safe)                      */
+    TAGC_CNT_FLAGS = 2,     /* TAGC_FLAG_* bits                                  */
+    TAGC_CNT_SEG0 = 4       /* [4 + l] = pairs of compressed segment l           */
+};
+/* shared `header` words (uint32), written by tagc_aggregate(PHASE_INDEX) */
+enum {
+    TAGC_HDR_U = 0,       /* non-zeros of the merged Index                       */
+    TAGC_HDR_A = 1,       /* sketch partitions                                   */
+    TAGC_HDR_MSUB = 2,    /* cells per hash function per partition               */
+    TAGC_HDR_M = 3,       /* total cells m = 3 * A * m_sub                       */
+    TAGC_HDR_WORDS = 8
+};
+/* shared `status` words (uint32), written by tagc_decompress */
+enum {
+    TAGC_ST_UNRESOLVED = 0, /* non-zeros peeling could not recover (value 0)     */
+    TAGC_ST_ROUNDS = 1,     /* peeling rounds of the slowest partition           */
+    TAGC_ST_FLAGS = 2,      /* TAGC_FLAG_* bits                                  */
+    TAGC_ST_WORDS = 8
+};
+#define TAGC_FLAG_SPIN_LIMIT 1u /* an internal bounded wait gave up: results invalid */
+#define TAGC_FLAG_OVERFLOW 2u   /* a capacity was exceeded: results invalid          */
+
+/* Device buffers of one simulated rank (all dev, caller-owned). */
+typedef struct tagc_rank_buffers {
+    uint32_t *idx;      /* [pair_capacity] c-indices of survivors, ascending    */
+    float *val;         /* [pair_capacity] their values widened to float32      */
+    uint32_t *cnt;      /* [4 + n_seg_compressed] see TAGC_CNT_*                */
+    uint32_t *bitmap;   /* [bitmap_words] local Index, bit j in word j>>5, bit
+                           j&31                                                 */
+    float *sketch;      /* [sketch_cells_capacity] local Count Sketch; cells
+                           [0, m) are written, the rest untouched              */
+    void *workspace;    /* [rank_workspace_bytes] scratch, may be shared by ranks
+                           processed one after another on one stream           */
+} tagc_rank_buffers;
+
+/* Device buffers shared by the bucket (all dev, caller-owned). */
+typedef struct tagc_shared_buffers {
+    const void *table;  /* [table_bytes] filled by tagc_plan_upload             */
+    uint32_t *bitmap;   /* [bitmap_words] merged Index                          */
+    float *sketch;      /* [sketch_cells_capacity] summed Count Sketch          */
+    uint32_t *header;   /* [TAGC_HDR_WORDS]                                     */
+    uint32_t *bounds;   /* [partition_capacity + 1] first c-index per partition */
+    void *workspace;    /* [shared_workspace_bytes]                             */
+    uint32_t *status;   /* [TAGC_ST_WORDS]                                      */
+} tagc_shared_buffers;
+
+/*
+ * Builds the host-side plan of a bucket: c-offsets, keep counts k_l, tile
+ * decomposition, capacities and byte accounting (Algorithm 1's inputs theta
+ * and the layer selection of section 3.2 become the segment table).
+ * `segments` (host) is copied.  Errors: TAGC_EINVAL (null pointers, unknown
+ * enum, n_hash != 3, n_ranks == 0, sizing_milli == 0, keep_ppm > 10^6,
+ * part_cells not a multiple of 3 or too large for LDS), TAGC_ESIZE (a
+ * segment of 2^31 elements or more, c-index space or sketch of 2^32 or more),
+ * TAGC_ENOMEM.  *out is owned by the caller: tagc_plan_destroy.
+ */
+int tagc_plan(const tagc_config *config, const tagc_segment *segments,
+              uint32_t n_seg, tagc_plan_t **out);
+void tagc_plan_destroy(tagc_plan_t *plan);
+
+/* Fills *out (host).  Never touches the device. */
+int tagc_plan_sizes(const tagc_plan_t *plan, tagc_sizes *out);
+
+/* Copies the plan's segment table into `table_dev` (table_bytes) on `stream`.
+ * The plan must outlive the copy. */
+int tagc_plan_upload(const tagc_plan_t *plan, void *table_dev, void *stream);
+
+/*
+ * PHASE_INDEX  (Algorithm 1: sparsify, create_index; threshold rule of
+ *   section 3.2).  Reads `grad_dev` (dev, dtype of the plan, only the
+ *   compressed segments).  For every compressed segment keeps the k_l entries
+ *   of largest magnitude, ties to the lower position, exact zeros never; writes
+ *   the survivors as (c-index, float32 value) pairs in ascending c-index to
+ *   rank->idx / rank->val, counts to rank->cnt, and the local Index to
+ *   rank->bitmap (every word is written).  Uses rank->workspace.
+ * PHASE_SKETCH (Algorithm 1: compress(g_shard, index)).  Needs the shared
+ *   header and bounds written by tagc_aggregate(PHASE_INDEX) and this rank's
+ *   pairs; hashes every pair with the three hash functions into the rank's
+ *   Count Sketch, cells [0, m) of rank->sketch (all of them are written).
+ * Both phases read shared->table.
+ */
+int tagc_compress(const tagc_plan_t *plan, uint32_t phase, const void *grad_dev,
+                  const tagc_rank_buffers *rank,
+                  const tagc_shared_buffers *shared, void *stream);
+
+/*
+ * Stands in for the two collectives of Algorithm 1 on one GPU.
+ * PHASE_INDEX : shared->bitmap = OR over ranks[r].bitmap (section 2.2: OR is
+ *   the operation the Index needs); counts its non-zeros U, derives the sketch
+ *   layout (A, m_sub, m) and the partition bounds; writes shared->header,
+ *   shared->bounds; clears shared->status.
+ * PHASE_SKETCH: shared->sketch[c] = ((ranks[0].sketch[c] + ranks[1].sketch[c])
+ *   + ...) in rank order, float32, for c < m.
+ * `ranks` is a host array of n_ranks structs (1 <= n_ranks <= config.n_ranks).
+ */
+int tagc_aggregate(const tagc_plan_t *plan, uint32_t phase,
+                   const tagc_rank_buffers *ranks, uint32_t n_ranks,
+                   const tagc_shared_buffers *shared, void *stream);
+
+/*
+ * Algorithm 1: peeling_decompress(index, count_sketch) (section 2.2).
+ * Enumerates the non-zeros of the merged Index in ascending order into
+ * idx_out[0..U), peels the summed sketch (shared->sketch is consumed) and
+ * writes val_out[0..U); entries peeling cannot recover get 0 and are counted
+ * in shared->status.  If dense_out (dev, n_c floats) is not NULL the summed
+ * gradient is also written densely over the whole c-index space (zeros
+ * elsewhere).  idx_out / val_out: dev, union_capacity entries.
+ */
+int tagc_decompress(const tagc_plan_t *plan, const tagc_shared_buffers *shared,
+                    uint32_t *idx_out, float *val_out, float *dense_out,
+                    void *stream);
+
+/*
+ * Optional per-kernel timing.  While enabled, every kernel the library
+ * launches is bracketed by HIP events on the caller's stream.
+ * tagc_profile_read synchronises those events (call it after the stream is
+ * idle), returns up to `cap` entries (kernel name, total milliseconds, launch
+ * count), clears the record, and returns the number of distinct kernels or a
+ * negative error.  Names are static strings owned by the library.
+ */
+int tagc_profile_enable(int on);
+int tagc_profile_read(const char **names, double *total_ms, uint64_t *launches,
+                      uint32_t cap);
+
+/* Hash function j (0..2) of c-index i for a sub-table of m_sub cells, as the
+ * device code computes it (host helper for tests and tools). */
+void tagc_hash_host(uint32_t i, uint64_t seed, uint32_t j, uint32_t m_sub,
+                    uint32_t *slot, int32_t *sign);
+
+const char *tagc_strerror(int err);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAGC_H */

@@ -1,0 +1,214 @@
+// Decoder: g <- peeling_decompress(index, count_sketch) of Algorithm 1 (section 2.2).
+//
+// One workgroup per sketch partition.  The partition's unknowns are the set bits of the
+// merged Index in [bounds[a], bounds[a+1]); its 3*m_sub cells and their degrees live in
+// LDS for the whole peel, so the rounds cost no HBM traffic and no kernel launches.
+//
+// Peeling is round-synchronous: in a round every unresolved unknown that touches a cell
+// of degree 1 takes its value from the smallest such hash function, reading the sketch
+// as it stood when the round began; then all unknowns taken in the round subtract
+// themselves from their three cells.  The first round that takes nothing ends the peel.
+// Unknowns left over are reported with value 0 and counted.
+#include "device_utils.h"
+#include "tagc_internal.h"
+
+namespace tagc {
+
+namespace {
+
+struct Cells {
+    uint32_t c[3];
+    uint32_t neg;  // bit j: sign of hash function j is -1
+};
+
+__device__ inline Cells cells_of(uint32_t i, uint32_t m_sub, uint32_t sw0, uint32_t sw1,
+                                 uint32_t sw2)
+{
+    Cells r;
+    uint32_t n0, n1, n2;
+    r.c[0] = hash_slot(i, sw0, m_sub, &n0);
+    r.c[1] = m_sub + hash_slot(i, sw1, m_sub, &n1);
+    r.c[2] = 2 * m_sub + hash_slot(i, sw2, m_sub, &n2);
+    r.neg = n0 | (n1 << 1) | (n2 << 2);
+    return r;
+}
+
+__device__ inline uint32_t deg_of(const uint32_t *deg2, uint32_t c)
+{
+    return (deg2[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
+}
+
+__global__ void __launch_bounds__(kDecodeThreads)
+decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ sketch,
+              const uint32_t *__restrict__ header, const uint32_t *__restrict__ bounds,
+              uint32_t *idx_out, float *__restrict__ val_out, float *__restrict__ dense_out,
+              uint32_t *status, uint32_t n_c, uint32_t sw0, uint32_t sw1, uint32_t sw2,
+              uint32_t ct_floats, uint32_t deg_words)
+{
+    extern __shared__ uint32_t lds[];
+    float *Ct = reinterpret_cast<float *>(lds);       // [ct_floats] cells, later dense tile
+    uint32_t *deg2 = lds + ct_floats;                 // [deg_words] two 16-bit degrees per word
+    uint32_t *scratch = deg2 + deg_words;             // [32]
+    const uint32_t tid = threadIdx.x;
+    const uint32_t U = header[TAGC_HDR_U], A = header[TAGC_HDR_A];
+    const uint32_t m_sub = header[TAGC_HDR_MSUB];
+    const uint32_t a = blockIdx.x;
+
+    if (a >= A) {
+        // Empty Index: the dense output is still defined (all zeros); the grid shares it.
+        if (A == 0 && dense_out) {
+            const uint64_t per = (uint64_t(n_c) + gridDim.x - 1) / gridDim.x;
+            const uint64_t lo = per * a, hi = min(uint64_t(n_c), lo + per);
+            for (uint64_t i = lo + tid; i < hi; i += kDecodeThreads) dense_out[i] = 0.0f;
+        }
+        return;
+    }
+
+    const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
+    const uint32_t Pa = uint32_t(uint64_t(a + 1) * U / A) - rho0;
+    const uint32_t ilo = bounds[a], ihi = bounds[a + 1];
+    const uint32_t cells = 3 * m_sub;
+
+    // ---- enumerate the set bits of [ilo, ihi) in ascending order into idx_out
+    {
+        const uint32_t wlo = ilo >> 5, whi = (ihi + 31) >> 5;
+        uint32_t running = 0;
+        for (uint32_t wb = wlo; wb < whi; wb += kDecodeThreads) {
+            const uint32_t w = wb + tid;
+            uint32_t word = w < whi ? bitmap[w] : 0u;
+            if (w == wlo) word &= 0xFFFFFFFFu << (ilo & 31);
+            if ((ihi & 31) && w == (ihi >> 5)) word &= (1u << (ihi & 31)) - 1u;
+            uint32_t tot;
+            uint32_t pos = running + block_excl_scan<uint32_t, kDecodeThreads / 64>(
+                                         uint32_t(__popc(word)), &tot, scratch);
+            while (word) {
+                const uint32_t b = __builtin_ctz(word);
+                word &= word - 1;
+                if (pos < Pa) idx_out[rho0 + pos] = w * 32 + b;
+                ++pos;
+            }
+            running += tot;
+        }
+    }
+    // ---- stage the partition's cells, clear degrees
+    for (uint32_t c = tid; c < cells; c += kDecodeThreads)
+        Ct[c] = sketch[uint64_t(a) * cells + c];
+    for (uint32_t c = tid; c < deg_words; c += kDecodeThreads) deg2[c] = 0;
+    __syncthreads();  // also orders this workgroup's idx_out stores before the loads below
+
+    uint32_t myidx[kDecodeMaxQ];
+    float x[kDecodeMaxQ];
+#pragma unroll
+    for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
+        const uint32_t u = tid + q * kDecodeThreads;
+        x[q] = 0.0f;
+        myidx[q] = 0;
+        if (u < Pa) {
+            myidx[q] = idx_out[rho0 + u];
+            const Cells cl = cells_of(myidx[q], m_sub, sw0, sw1, sw2);
+#pragma unroll
+            for (int j = 0; j < 3; ++j) atomicAdd(&deg2[cl.c[j] >> 1], 1u << (16 * (cl.c[j] & 1)));
+        }
+    }
+    __syncthreads();
+
+    // ---- peel
+    uint32_t done = 0, rounds = 0;
+    while (true) {
+        uint32_t pick = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
+            const uint32_t u = tid + q * kDecodeThreads;
+            if (u < Pa && !((done >> q) & 1u)) {
+                const Cells cl = cells_of(myidx[q], m_sub, sw0, sw1, sw2);
+                int j = -1;
+                if (deg_of(deg2, cl.c[0]) == 1) j = 0;
+                else if (deg_of(deg2, cl.c[1]) == 1) j = 1;
+                else if (deg_of(deg2, cl.c[2]) == 1) j = 2;
+                if (j >= 0) {
+                    const float c = Ct[cl.c[j]];
+                    x[q] = ((cl.neg >> j) & 1u) ? -c : c;
+                    pick |= 1u << q;
+                }
+            }
+        }
+        // barrier between the snapshot reads above and the updates below
+        if (!__syncthreads_or(pick != 0)) break;
+        ++rounds;
+#pragma unroll
+        for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
+            if ((pick >> q) & 1u) {
+                const Cells cl = cells_of(myidx[q], m_sub, sw0, sw1, sw2);
+#pragma unroll
+                for (int j = 0; j < 3; ++j) {
+                    atomicAdd(&Ct[cl.c[j]], ((cl.neg >> j) & 1u) ? x[q] : -x[q]);
+                    atomicSub(&deg2[cl.c[j] >> 1], 1u << (16 * (cl.c[j] & 1)));
+                }
+            }
+        }
+        done |= pick;
+        __syncthreads();
+    }
+
+    // ---- sparse output and status
+    uint32_t unresolved = 0;
+#pragma unroll
+    for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
+        const uint32_t u = tid + q * kDecodeThreads;
+        if (u < Pa) {
+            if (!((done >> q) & 1u)) {
+                x[q] = 0.0f;
+                ++unresolved;
+            }
+            val_out[rho0 + u] = x[q];
+        }
+    }
+    unresolved = block_sum<uint32_t, kDecodeThreads / 64>(unresolved, scratch);
+    if (tid == 0) {
+        if (unresolved) atomicAdd(&status[TAGC_ST_UNRESOLVED], unresolved);
+        atomicMax(&status[TAGC_ST_ROUNDS], rounds);
+    }
+
+    // ---- dense output: this partition covers c-indices [dlo, ihi)
+    if (dense_out) {
+        const uint32_t dlo = a == 0 ? 0u : ilo;
+        const uint32_t DT = ct_floats;
+        for (uint32_t tb = dlo; tb < ihi; tb += DT) {
+            const uint32_t len = min(DT, ihi - tb);
+            for (uint32_t c = tid; c < len; c += kDecodeThreads) Ct[c] = 0.0f;
+            __syncthreads();
+#pragma unroll
+            for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
+                const uint32_t u = tid + q * kDecodeThreads;
+                if (u < Pa && myidx[q] >= tb && myidx[q] - tb < len) Ct[myidx[q] - tb] = x[q];
+            }
+            __syncthreads();
+            for (uint32_t c = tid; c < len; c += kDecodeThreads) dense_out[uint64_t(tb) + c] = Ct[c];
+            __syncthreads();
+        }
+    }
+}
+
+}  // namespace
+
+int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t *idx_out,
+                  float *val_out, float *dense_out, hipStream_t s)
+{
+    ProfileScope ps("decode", s);
+    const uint32_t ct_floats = std::max<uint32_t>(p->T_cap, 1024);
+    const uint32_t deg_words = p->T_cap / 2 + 1;
+    const size_t lds = (size_t(ct_floats) + deg_words + 32) * 4;
+    static size_t attr_bytes = 0;
+    if (lds > attr_bytes) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+            return TAGC_EHIP;
+        attr_bytes = lds;
+    }
+    decode_kernel<<<uint32_t(p->A_cap), kDecodeThreads, lds, s>>>(
+        sh->bitmap, sh->sketch, sh->header, sh->bounds, idx_out, val_out, dense_out, sh->status,
+        uint32_t(p->n_c), p->seed_word[0], p->seed_word[1], p->seed_word[2], ct_floats, deg_words);
+    return hip_ok(hipGetLastError());
+}
+
+}  // namespace tagc

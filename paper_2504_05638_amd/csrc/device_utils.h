@@ -1,0 +1,75 @@
+// Wave64 / workgroup primitives used by the libtagc kernels (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tagc {
+
+__device__ inline uint32_t lane_id() { return __lane_id(); }
+
+template <typename T>
+__device__ inline T wave_incl_scan(T v)
+{
+    const uint32_t l = lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        T o = __shfl_up(v, d, 64);
+        if (l >= uint32_t(d)) v += o;
+    }
+    return v;
+}
+
+template <typename T>
+__device__ inline T wave_sum(T v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// Exclusive scan over the NW*64 threads of a workgroup in thread order.  `smem` holds NW
+// entries and may be reused after the call returns.
+template <typename T, int NW>
+__device__ inline T block_excl_scan(T v, T *total, T *smem)
+{
+    const uint32_t w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    T inc = wave_incl_scan(v);
+    if (l == 63) smem[w] = inc;
+    __syncthreads();
+    T base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        T x = smem[i];
+        if (uint32_t(i) < w) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+template <typename T, int NW>
+__device__ inline T block_sum(T v, T *smem)
+{
+    const uint32_t w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    T s = wave_sum(v);
+    if (l == 0) smem[w] = s;
+    __syncthreads();
+    T tot = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) tot += smem[i];
+    __syncthreads();
+    return tot;
+}
+
+__device__ inline uint64_t ld_agent(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_agent(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace tagc

@@ -1,0 +1,190 @@
+// Index aggregation: what All-Reduce(local_index) yields in Algorithm 1, computed on one
+// GPU as the bitwise OR of N ranks' bit maps (section 2.2 names OR as the operation the
+// Index needs), followed by everything the later stages derive from the merged Index:
+// its number of non-zeros U, the sketch layout (A partitions of 3*m_sub cells) and the
+// c-index at which each partition starts.
+#include "device_utils.h"
+#include "tagc_internal.h"
+
+namespace tagc {
+
+namespace {
+
+// One workgroup per chunk of kChunkWords words; 4 words per thread.
+__global__ void __launch_bounds__(256)
+index_or_kernel(RankPtrs rp, uint32_t n_in, uint32_t *__restrict__ out, uint32_t n_words,
+                int accumulate, uint32_t *__restrict__ chunkcnt)
+{
+    __shared__ uint32_t smem[4];
+    const uint32_t w0 = blockIdx.x * kChunkWords + threadIdx.x * 4;
+    uint32_t pc = 0;
+    if (w0 + 4 <= n_words) {
+        uint4 acc = accumulate ? *reinterpret_cast<const uint4 *>(out + w0) : make_uint4(0, 0, 0, 0);
+        for (uint32_t r = 0; r < n_in; ++r) {
+            uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(rp.p[r]) + w0);
+            acc.x |= v.x; acc.y |= v.y; acc.z |= v.z; acc.w |= v.w;
+        }
+        *reinterpret_cast<uint4 *>(out + w0) = acc;
+        pc = __popc(acc.x) + __popc(acc.y) + __popc(acc.z) + __popc(acc.w);
+    } else {
+        for (uint32_t w = w0; w < n_words; ++w) {
+            uint32_t acc = accumulate ? out[w] : 0u;
+            for (uint32_t r = 0; r < n_in; ++r) acc |= static_cast<const uint32_t *>(rp.p[r])[w];
+            out[w] = acc;
+            pc += __popc(acc);
+        }
+    }
+    if (chunkcnt) {
+        pc = block_sum<uint32_t, 4>(pc, smem);
+        if (threadIdx.x == 0) chunkcnt[blockIdx.x] = pc;
+    }
+}
+
+struct LayoutParams {
+    uint32_t mode, milli, P_cap, T_cap;
+    uint64_t n_real, U_cap, A_cap, m_cap;
+};
+
+// Single workgroup: exclusive prefix of the chunk counts (in place, total appended), the
+// sketch layout, and a cleared status block.
+//
+//   target cells  M = ceil(milli*U/1000)  |  ceil(n_real*1000/milli)
+//   partitions    A = max(1, ceil(U/P_cap), ceil(M/(3q))),  q = T_cap/3   (0 if U = 0)
+//   sub-table     m_sub = max(1, ceil(M/(3A)))  |  max(1, floor(M/(3A)))
+//   total         m = 3*A*m_sub
+__global__ void __launch_bounds__(1024)
+header_kernel(uint32_t *chunk, uint32_t n_chunks, LayoutParams lp, uint32_t *header,
+              uint32_t *status)
+{
+    __shared__ uint32_t smem[16];
+    uint32_t running = 0;
+    for (uint32_t base = 0; base < n_chunks; base += 1024) {
+        const uint32_t i = base + threadIdx.x;
+        uint32_t v = i < n_chunks ? chunk[i] : 0u, tot;
+        uint32_t ex = block_excl_scan<uint32_t, 16>(v, &tot, smem);
+        if (i < n_chunks) chunk[i] = running + ex;
+        running += tot;
+    }
+    if (threadIdx.x != 0) return;
+    chunk[n_chunks] = running;
+    uint64_t U = running, A = 0, m_sub = 0, m = 0;
+    uint32_t flags = 0;
+    if (U > 0) {
+        uint64_t M = lp.mode == TAGC_SIZE_LOAD_FACTOR ? (uint64_t(lp.milli) * U + 999) / 1000
+                                                      : (lp.n_real * 1000 + lp.milli - 1) / lp.milli;
+        uint64_t q = lp.T_cap / 3;
+        A = (U + lp.P_cap - 1) / lp.P_cap;
+        uint64_t A2 = (M + 3 * q - 1) / (3 * q);
+        if (A2 > A) A = A2;
+        if (A < 1) A = 1;
+        m_sub = lp.mode == TAGC_SIZE_LOAD_FACTOR ? (M + 3 * A - 1) / (3 * A) : M / (3 * A);
+        if (m_sub < 1) m_sub = 1;
+        m = 3 * A * m_sub;
+        if (U > lp.U_cap || A > lp.A_cap || m > lp.m_cap) {  // caller broke the plan's bounds
+            flags = TAGC_FLAG_OVERFLOW;
+            U = A = m_sub = m = 0;
+        }
+    }
+    header[TAGC_HDR_U] = uint32_t(U);
+    header[TAGC_HDR_A] = uint32_t(A);
+    header[TAGC_HDR_MSUB] = uint32_t(m_sub);
+    header[TAGC_HDR_M] = uint32_t(m);
+    for (int i = 4; i < TAGC_HDR_WORDS; ++i) header[i] = 0;
+    for (int i = 0; i < TAGC_ST_WORDS; ++i) status[i] = 0;
+    status[TAGC_ST_FLAGS] = flags;
+}
+
+// One wave per partition boundary a: bounds[a] = c-index of the non-zero of rank
+// floor(a*U/A); bounds[A] = n_c.
+__global__ void __launch_bounds__(256)
+bounds_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words, uint32_t n_c,
+              const uint32_t *__restrict__ chunkpre, uint32_t n_chunks,
+              const uint32_t *__restrict__ header, uint32_t *__restrict__ bounds)
+{
+    const uint32_t U = header[TAGC_HDR_U], A = header[TAGC_HDR_A];
+    const uint32_t a = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const uint32_t l = lane_id();
+    if (a > A) return;
+    if (a == A) {
+        if (l == 0) bounds[a] = n_c;
+        return;
+    }
+    const uint32_t rho = uint32_t(uint64_t(a) * U / A);
+    uint32_t lo = 0, hi = n_chunks;  // largest chunk with chunkpre <= rho
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (chunkpre[mid] <= rho) lo = mid; else hi = mid;
+    }
+    const uint32_t local = rho - chunkpre[lo];
+    const uint32_t wbase = lo * kChunkWords + l * 16;
+    uint32_t w[16];
+    if (wbase + 16 <= n_words) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint4 v = *reinterpret_cast<const uint4 *>(bitmap + wbase + 4 * i);
+            w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) w[i] = (wbase + i < n_words) ? bitmap[wbase + i] : 0u;
+    }
+    uint32_t tot = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tot += __popc(w[i]);
+    const uint32_t incl = wave_incl_scan<uint32_t>(tot);
+    const uint32_t excl = incl - tot;
+    if (excl <= local && local < incl) {
+        uint32_t r = local - excl;
+        uint32_t found = n_c;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t c = __popc(w[i]);
+            if (found == n_c) {
+                if (r < c) {
+                    uint32_t x = w[i];
+                    for (uint32_t s = 0; s < r; ++s) x &= x - 1;
+                    found = (wbase + i) * 32 + __builtin_ctz(x);
+                } else {
+                    r -= c;
+                }
+            }
+        }
+        bounds[a] = found;
+    }
+}
+
+}  // namespace
+
+int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32_t n_ranks,
+                    const tagc_shared_buffers *sh, hipStream_t s)
+{
+    const uint32_t n_words = uint32_t(p->n_c / 32);
+    const uint32_t n_chunks = uint32_t(p->n_chunks);
+    uint32_t *chunk = static_cast<uint32_t *>(sh->workspace);
+    if (n_chunks) {
+        ProfileScope ps("index_or", s);
+        for (uint32_t r0 = 0; r0 < n_ranks; r0 += kMaxRanksPerPass) {
+            RankPtrs rp{};
+            const uint32_t n_in = std::min(kMaxRanksPerPass, n_ranks - r0);
+            for (uint32_t r = 0; r < n_in; ++r) rp.p[r] = ranks[r0 + r].bitmap;
+            const bool last = r0 + n_in == n_ranks;
+            index_or_kernel<<<n_chunks, 256, 0, s>>>(rp, n_in, sh->bitmap, n_words, r0 != 0,
+                                                     last ? chunk : nullptr);
+        }
+    }
+    {
+        ProfileScope ps("header", s);
+        LayoutParams lp{p->cfg.sizing, p->cfg.sizing_milli, p->P_cap, p->T_cap,
+                        p->n_real,     p->U_cap,            p->A_cap, p->m_cap};
+        header_kernel<<<1, 1024, 0, s>>>(chunk, n_chunks, lp, sh->header, sh->status);
+    }
+    if (n_chunks) {
+        ProfileScope ps("bounds", s);
+        const uint32_t grid = uint32_t((p->A_cap + 1 + 3) / 4);
+        bounds_kernel<<<grid, 256, 0, s>>>(sh->bitmap, n_words, uint32_t(p->n_c), chunk, n_chunks,
+                                           sh->header, sh->bounds);
+    }
+    return hip_ok(hipGetLastError());
+}
+
+}  // namespace tagc

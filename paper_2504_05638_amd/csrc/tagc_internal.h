@@ -1,0 +1,144 @@
+// Internal declarations shared by the libtagc sources (host plan + HIP kernels).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "tagc.h"
+
+namespace tagc {
+
+// ---------------------------------------------------------------- constants
+
+constexpr uint32_t kBins1 = 32768;   // top 15 key bits: all of a bf16 key, key>>16 of fp32
+constexpr uint32_t kBins2 = 65536;   // low 16 key bits (fp32 only)
+constexpr uint32_t kHistThreads = 1024;
+constexpr uint32_t kCompactThreads = 256;
+constexpr uint32_t kCompactRows = 4;  // 16-byte vectors per thread per tile
+constexpr uint32_t kChunkWords = 1024;  // Index words per popcount chunk
+constexpr uint32_t kDefaultPartCells = 24576;  // 3 * 8192 cells: 96 KiB of float
+constexpr uint32_t kMaxPartCells = 24576;
+constexpr uint32_t kMaxPartUnknowns = 16384;
+constexpr uint32_t kDecodeThreads = 1024;
+constexpr uint32_t kDecodeMaxQ = kMaxPartUnknowns / kDecodeThreads;  // unknowns per thread
+constexpr uint32_t kDenseTile = 8192;  // floats staged in LDS per dense-output tile
+constexpr uint32_t kMaxRanksPerPass = 32;
+constexpr uint32_t kSpinLimit = 1u << 20;
+
+// Device copy of one compressed segment.
+struct SegDev {
+    uint64_t offset;      // element offset in the gradient buffer
+    uint32_t n;           // elements
+    uint32_t c_off;       // c-index of element 0 (multiple of 32)
+    uint32_t k;           // keep count
+    uint32_t tile_start;  // first compaction tile of this segment
+    uint32_t aligned;     // 1: offset is a multiple of the 16-byte vector
+    uint32_t pad;
+};
+static_assert(sizeof(SegDev) == 32, "SegDev layout");
+
+// Result of the threshold search for one segment (device memory).
+struct SelDev {
+    uint32_t T;       // threshold key; keep key > T, and `quota` lowest-position ties
+    uint32_t quota;   // ties (key == T) to keep
+    uint32_t G;       // count(key > T)
+    uint32_t cnt;     // pairs this segment emits = G + min(E, quota)
+    uint32_t bin1;    // fp32: level-1 bin that holds T
+    uint32_t G1;      // fp32: count of keys in higher level-1 bins
+    uint32_t need2;   // fp32: 1 if the low 16 bits still have to be searched
+    uint32_t pad;
+};
+static_assert(sizeof(SelDev) == 32, "SelDev layout");
+
+struct RankPtrs {
+    const void *p[kMaxRanksPerPass];
+};
+
+// ------------------------------------------------------------------- plan
+
+struct Workspace {  // byte offsets inside a rank workspace
+    uint64_t hist1, hist2, sel, tile_state, counters, total;
+};
+
+}  // namespace tagc
+
+struct tagc_plan_s {
+    tagc_config cfg;
+    std::vector<tagc_segment> segments;       // as given
+    std::vector<tagc::SegDev> table;          // compressed segments only
+    uint32_t elem_bytes, vec_elems;
+    uint32_t tile_elems;                      // elements per compaction tile
+    uint32_t total_tiles;
+    uint64_t n_real, n_c, K, U_cap, A_cap, m_cap;
+    uint32_t P_cap, T_cap;
+    uint32_t seed_word[3];
+    tagc::Workspace ws;
+    uint64_t zero_bytes;                      // prefix of the rank workspace cleared per call
+    uint64_t n_chunks;                        // popcount chunks of the Index
+    tagc_sizes sizes;
+};
+
+namespace tagc {
+
+// ------------------------------------------------------------------- hash
+
+__host__ __device__ inline uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x6A09E667u;
+    x ^= x >> 15;
+    x *= 0xBB67AE85u;
+    x ^= x >> 16;
+    return x;
+}
+
+__host__ __device__ inline uint32_t seed_word(uint64_t seed, uint32_t j)
+{
+    return mix32(uint32_t(seed) ^ mix32(uint32_t(seed >> 32) + 0x9E3779B9u * (j + 1)));
+}
+
+// slot in [0, m_sub) in the upper bits, sign flag (1 = negative) in bit 31... returned
+// separately: slot via multiply-shift range reduction, sign from the low hash bit.
+__host__ __device__ inline uint32_t hash_slot(uint32_t i, uint32_t sw, uint32_t m_sub,
+                                              uint32_t *neg)
+{
+    uint32_t h = mix32(i ^ sw);
+    *neg = h & 1u;
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umulhi(h, m_sub);
+#else
+    return uint32_t((uint64_t(h) * m_sub) >> 32);
+#endif
+}
+
+// ---------------------------------------------------------------- profile
+
+void profile_begin(const char *name, hipStream_t s);
+void profile_end(hipStream_t s);
+
+struct ProfileScope {
+    hipStream_t s;
+    ProfileScope(const char *name, hipStream_t st) : s(st) { profile_begin(name, st); }
+    ~ProfileScope() { profile_end(s); }
+};
+
+int device_cu_count();
+
+// ------------------------------------------------------ stage entry points
+
+int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buffers *rk,
+                    const tagc_shared_buffers *sh, hipStream_t s);
+int launch_encode(const tagc_plan_t *p, const tagc_rank_buffers *rk,
+                  const tagc_shared_buffers *sh, hipStream_t s);
+int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32_t n_ranks,
+                    const tagc_shared_buffers *sh, hipStream_t s);
+int launch_sketch_sum(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32_t n_ranks,
+                      const tagc_shared_buffers *sh, hipStream_t s);
+int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t *idx_out,
+                  float *val_out, float *dense_out, hipStream_t s);
+
+inline int hip_ok(hipError_t e) { return e == hipSuccess ? TAGC_OK : TAGC_EHIP; }
+
+}  // namespace tagc

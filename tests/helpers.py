@@ -1,0 +1,113 @@
+"""Shared test plumbing: feeds the same seeded inputs to the oracle and to the
+HIP library and compares them stage by stage.  Holds no method arithmetic."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import tagc_oracle as O
+from synth import gradients as G
+
+
+def oracle_segments(bucket):
+    return [O.Segment(s.offset, s.length, s.keep_ppm, s.flags) for s in bucket.segments]
+
+
+def oracle_config(bucket, sizing=O.SIZE_LOAD_FACTOR, seed=0, P=16384, T=24576):
+    return O.Config(dtype=bucket.dtype, sizing=sizing, sizing_milli=bucket.sizing_milli,
+                    seed=seed, part_unknowns=P, part_cells=T)
+
+
+def segment_of(c_index, bucket):
+    """compressed-segment ordinal of each c-index."""
+    offs, _ = O.c_offsets(oracle_segments(bucket))
+    starts = np.array([o for o in offs if o is not None], np.int64)
+    return np.searchsorted(starts, np.asarray(c_index, np.int64), side="right") - 1
+
+
+def value_tolerance(ref_idx, ref_val, oracle_ranks, bucket, rel=1e-5):
+    """|delta| allowed per decoded entry: rel * max(|ref|, tau_l), tau_l being the
+    smallest magnitude any rank selected in the entry's segment (every
+    contribution to the entry is at least that large)."""
+    seg = segment_of(ref_idx, bucket)
+    n_seg = int(seg.max()) + 1 if seg.size else 0
+    tau = np.full(n_seg, np.inf)
+    for r in oracle_ranks:
+        s = segment_of(r.idx, bucket)
+        np.minimum.at(tau, s, np.abs(r.val.astype(np.float64)))
+    tau[~np.isfinite(tau)] = 0.0
+    return rel * np.maximum(np.abs(ref_val.astype(np.float64)), tau[seg])
+
+
+def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTOR, dense=True):
+    """Runs oracle and library on the same inputs; returns (oracle result, TagcBucket)."""
+    import torch
+    from paper_2504_05638_amd.bucket import TagcBucket
+
+    ocfg = oracle_config(bucket, sizing, seed, P or 16384, T or 24576)
+    ores = O.run_bucket([G.to_numpy_raw(g) for g in grads_torch_cpu], ocfg,
+                        oracle_segments(bucket))
+    tb = TagcBucket(bucket.segments, bucket.dtype, len(grads_torch_cpu),
+                    sizing_milli=bucket.sizing_milli, sizing=sizing, seed=seed,
+                    part_unknowns=P, part_cells=T, dense=dense)
+    dev = [g.cuda() for g in grads_torch_cpu]
+    tb.run(dev)
+    torch.cuda.synchronize()
+    return ores, tb
+
+
+def compare_all(bucket, ores, tb, exact_values=False, rel=1e-5):
+    """Stage-by-stage comparison; integer work bit-exact, floats within tolerance
+    (bit-exact too when `exact_values`)."""
+    n_ranks = len(ores.ranks)
+    z = tb.sizes
+    assert z.n_c == ores.n_c
+    # --- stage 1: survivors and local Index
+    for r in range(n_ranks):
+        cnt = tb.rank_counts(r)
+        assert cnt["flags"] == 0 and cnt["nonfinite"] == 0
+        assert cnt["total"] == ores.ranks[r].cnt
+        comp_cnt = [c for c, s in zip(ores.ranks[r].seg_cnt, bucket.segments) if s.flags & 1]
+        assert cnt["seg"] == comp_cnt
+        idx, val = tb.rank_pairs(r)
+        assert np.array_equal(idx, ores.ranks[r].idx)
+        assert np.array_equal(val.view(np.uint32), ores.ranks[r].val.view(np.uint32))
+        assert np.array_equal(tb.rank_bitmap(r), ores.ranks[r].bitmap[:z.bitmap_words])
+    # --- stage 3a: merged Index, layout, bounds
+    hdr = tb.header()
+    assert hdr == dict(U=ores.U, A=ores.A, m_sub=ores.m_sub, m=ores.m)
+    assert np.array_equal(tb.shared_bitmap(), ores.bitmap[:z.bitmap_words])
+    if ores.A:
+        assert np.array_equal(tb.bounds(), ores.bnd)
+    # --- stage 2': sketches
+    scale = max([float(np.abs(r.val).max()) if r.cnt else 0.0 for r in ores.ranks] + [0.0])
+    for r in range(n_ranks):
+        got, want = tb.rank_sketch(r), ores.ranks[r].sketch
+        if exact_values:
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        else:
+            assert np.all(np.abs(got.astype(np.float64) - want) <= rel * np.maximum(
+                np.abs(want), scale * 1e-2))
+            # cells with at most two contributions do not depend on the order
+            assert np.mean(got.view(np.uint32) == want.view(np.uint32)) > 0.99
+    # --- stage 4: decoded gradient
+    st = tb.status()
+    assert st["flags"] == 0
+    assert st["n_unresolved"] == ores.decoded.n_unresolved
+    assert st["rounds"] == ores.decoded.rounds
+    idx, val = tb.outputs()
+    assert np.array_equal(idx, ores.decoded.idx)
+    unresolved = ores.decoded.round == 0
+    assert np.all(val[unresolved] == 0)
+    if exact_values:
+        assert np.array_equal(val.view(np.uint32), ores.decoded.val.view(np.uint32))
+    else:
+        tol = value_tolerance(ores.decoded.idx, ores.decoded.val, ores.ranks, bucket, rel)
+        err = np.abs(val.astype(np.float64) - ores.decoded.val.astype(np.float64))
+        assert np.all(err <= tol), "worst excess %g at %d" % (
+            (err - tol).max(), int(np.argmax(err - tol)))
+    if tb.out_dense is not None:
+        dense = tb.dense()
+        want = np.zeros(z.n_c, np.float32)
+        want[idx] = val
+        assert np.array_equal(dense.view(np.uint32), want.view(np.uint32))
+    return hdr, st

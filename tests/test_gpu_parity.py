@@ -1,0 +1,203 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on the
+same seeded inputs, through the C ABI.  Integer work (selected indices, Index
+bits, layout, bounds, resolved set, rounds) must be bit-exact; float values within
+1e-5 relative (only atomic summation order may differ); exact for inputs whose
+float32 arithmetic is exact."""
+import numpy as np
+import pytest
+import torch
+
+from synth import gradients as G
+from oracle import tagc_oracle as O
+from tests.helpers import run_both, compare_all
+
+pytestmark = pytest.mark.gpu
+
+
+def _grads(bucket, gen=G.rank_gradient):
+    return [gen(bucket, r, "cpu") for r in range(bucket.n_ranks)]
+
+
+def _announce(name):
+    print("\n[case] %s" % name, flush=True)
+
+
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+@pytest.mark.parametrize("lf", [1500, 3000])
+def test_small_mixed_bucket(dtype, lf):
+    """Ragged lengths, unaligned offsets, skipped segments, a k = 0 segment, several
+    sketch partitions."""
+    _announce("small_mixed dtype=%d lf=%d" % (dtype, lf))
+    b = G.small_mixed_bucket(seed=3, dtype=dtype, n_ranks=3, sizing_milli=lf)
+    ores, tb = run_both(b, _grads(b), seed=5, P=256, T=768)
+    hdr, st = compare_all(b, ores, tb)
+    assert hdr["A"] > 1
+
+
+def test_config1_full_size():
+    """BASELINE config 1: 4 ranks x 1,048,576 fp32 ~ N(0, 1e-3), top 1 %, lf 3."""
+    _announce("config1")
+    b = G.config1(seed=0)
+    ores, tb = run_both(b, _grads(b), seed=0)
+    hdr, st = compare_all(b, ores, tb)
+    assert hdr["U"] > 40_000 and st["n_unresolved"] == 0
+    for r in range(4):
+        assert tb.rank_counts(r)["total"] == 10_485
+
+
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+def test_integer_values_are_bit_exact_end_to_end(dtype):
+    """Small-integer inputs: every float32 add is exact, so sketch cells and decoded
+    values must match the oracle bit for bit whatever the atomic order."""
+    _announce("integer exact dtype=%d" % dtype)
+    rng = np.random.default_rng(12)
+    n, N = 300_000, 5
+    segs = [G.Seg(0, 100_000, 30_000, 1, "a"), G.Seg(100_000, 200_000, 20_000, 1, "b")]
+    b = G.Bucket("ints", dtype, N, segs, n, 1500)
+    td = torch.float32 if dtype == G.F32 else torch.bfloat16
+    grads = [torch.from_numpy(rng.integers(-100, 101, n).astype(np.float32)).to(td)
+             for _ in range(N)]
+    ores, tb = run_both(b, grads, seed=1, P=2048, T=3072)
+    hdr, st = compare_all(b, ores, tb, exact_values=True)
+    assert hdr["A"] > 4
+
+
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+@pytest.mark.parametrize("kind", ["all_equal", "two_valued", "mostly_zero", "all_zero"])
+def test_heavy_ties_and_zeros(dtype, kind):
+    """The threshold sits inside a huge tie class (or there are fewer non-zeros than
+    k): the lowest positions must win, zeros must never be kept."""
+    _announce("ties %s dtype=%d" % (kind, dtype))
+    rng = np.random.default_rng(4)
+    n, N = 70_001, 2
+    segs = [G.Seg(0, 40_001, 100_000, 1, "a"), G.Seg(40_008, 29_993, 250_000, 1, "b")]
+    b = G.Bucket("ties", dtype, N, segs, n, 3000)
+    td = torch.float32 if dtype == G.F32 else torch.bfloat16
+    grads = []
+    for r in range(N):
+        if kind == "all_equal":
+            v = np.full(n, 0.5, np.float32) * (1 if r == 0 else -1)
+        elif kind == "two_valued":
+            v = rng.choice([-1.0, 2.0], n).astype(np.float32)
+        elif kind == "mostly_zero":
+            v = (rng.integers(1, 9, n) * (rng.random(n) < 0.01)).astype(np.float32)
+        else:
+            v = np.zeros(n, np.float32)
+        grads.append(torch.from_numpy(v).to(td))
+    ores, tb = run_both(b, grads, seed=2, P=1024, T=3072)
+    compare_all(b, ores, tb, exact_values=True)
+
+
+def test_gpt2_block_shapes_fp32():
+    """One GPT-2-small block of BASELINE config 2 (4 compressed linear layers, biases
+    and LayerNorms skipped, per-layer keep ratio), 3 ranks."""
+    _announce("config2 block0")
+    b = G.config2(seed=0, n_ranks=3)[0]
+    ores, tb = run_both(b, _grads(b), seed=0)
+    hdr, st = compare_all(b, ores, tb)
+    assert st["n_unresolved"] <= 2
+
+
+def test_bf16_many_tiles_ragged_tail_student_t():
+    """bf16, heavy-tailed values, length not a multiple of the tile or the vector,
+    load factor 1.5 (BASELINE config 3 at reduced length, with its overlap recipe)."""
+    _announce("config3 reduced")
+    b = G.config3(seed=0, n=(1 << 21) + 4321, n_ranks=4, keep_ppm=10_000, sizing_milli=1500)
+    grads = [G.config3_rank_gradient(b, r, "cpu") for r in range(4)]
+    ores, tb = run_both(b, grads, seed=0)
+    hdr, st = compare_all(b, ores, tb)
+    k = (b.n_elems * 10_000) // 10 ** 6
+    assert 2.0 * k < hdr["U"] < 3.5 * k        # supports overlap by about half
+
+
+@pytest.mark.parametrize("ratio_milli,theta_ppm", [(2000, 200_000), (10_000, 12_500)])
+def test_fixed_ratio_mode_table1(ratio_milli, theta_ppm):
+    """Table 1 regimes: c-x compression at the stated sparsity, two ranks."""
+    _announce("fixed ratio %d" % ratio_milli)
+    n = 400_000
+    b = G.Bucket("t1", G.F32, 2, [G.Seg(0, n, theta_ppm, 1, "w")], n, ratio_milli)
+    ores, tb = run_both(b, _grads(b), seed=3, sizing=O.SIZE_FIXED_RATIO)
+    hdr, st = compare_all(b, ores, tb)
+    assert hdr["m"] <= n * 1000 // ratio_milli
+    assert st["n_unresolved"] <= 2
+
+
+def test_undersized_sketch_reports_residue():
+    """Below the peeling threshold the decoder must say so, not invent values."""
+    _announce("undersized")
+    b = G.config1(seed=1, n=200_000, n_ranks=2)
+    b.sizing_milli = 1100
+    ores, tb = run_both(b, _grads(b), seed=0, P=1024, T=3072)
+    hdr, st = compare_all(b, ores, tb)
+    assert st["n_unresolved"] > 0.3 * hdr["U"]
+
+
+def test_empty_and_degenerate_buckets():
+    _announce("degenerate")
+    # no compressed segment at all
+    b = G.Bucket("none", G.F32, 2, [G.Seg(0, 100, 500_000, 0, "x")], 100, 3000)
+    ores, tb = run_both(b, _grads(b))
+    assert tb.header() == dict(U=0, A=0, m_sub=0, m=0) and ores.U == 0
+    # keep count rounds to zero everywhere
+    b = G.Bucket("k0", G.BF16, 2, [G.Seg(0, 999, 1_000, 1, "x")], 999, 3000)
+    ores, tb = run_both(b, _grads(b))
+    compare_all(b, ores, tb)
+    assert tb.header()["U"] == 0
+    assert not tb.dense().any()
+    # a single element
+    b = G.Bucket("one", G.F32, 1, [G.Seg(0, 1, 1_000_000, 1, "x")], 1, 3000)
+    ores, tb = run_both(b, _grads(b))
+    compare_all(b, ores, tb, exact_values=True)
+    assert tb.header()["U"] == 1
+
+
+def test_integer_outputs_are_reproducible_run_to_run():
+    """Atomics may only perturb float low bits: two runs give identical indices,
+    bit maps, bounds and resolved sets."""
+    _announce("determinism")
+    b = G.small_mixed_bucket(seed=8, dtype=G.BF16, n_ranks=4, sizing_milli=1500)
+    grads = _grads(b)
+    _, t1 = run_both(b, grads, seed=9, P=256, T=768)
+    _, t2 = run_both(b, grads, seed=9, P=256, T=768)
+    assert np.array_equal(t1.shared_bitmap(), t2.shared_bitmap())
+    assert np.array_equal(t1.bounds(), t2.bounds())
+    for r in range(4):
+        assert np.array_equal(t1.rank_pairs(r)[0], t2.rank_pairs(r)[0])
+    i1, v1 = t1.outputs()
+    i2, v2 = t2.outputs()
+    assert np.array_equal(i1, i2) and np.array_equal(v1 == 0, v2 == 0)
+    assert t1.status() == t2.status()
+
+
+def test_nonfinite_inputs_are_counted():
+    _announce("nonfinite")
+    b = G.config1(seed=2, n=50_000, n_ranks=1)
+    g = G.rank_gradient(b, 0, "cpu")
+    g[[7, 4097, 49_999]] = torch.tensor([float("inf"), float("nan"), float("-inf")])
+    from paper_2504_05638_amd.bucket import TagcBucket
+    tb = TagcBucket(b.segments, b.dtype, 1, sizing_milli=3000)
+    tb.compress_index(0, g.cuda())
+    torch.cuda.synchronize()
+    assert tb.rank_counts(0)["nonfinite"] == 3
+
+
+def test_hash_on_device_matches_host_helper_and_oracle():
+    """Slots are observable through the sketch: one unit pair per rank lands in
+    exactly the three cells the host helper and the oracle name."""
+    _announce("hash slots")
+    n = 4096
+    b = G.Bucket("h", G.F32, 1, [G.Seg(0, n, 1_000_000, 1, "w")], n, 3000)
+    from paper_2504_05638_amd import binding as B
+    for pos in (0, 1, 31, 32, 1000, 4095):
+        g = torch.zeros(n)
+        g[pos] = 1.0
+        ores, tb = run_both(b, [g], seed=77)
+        sk = tb.rank_sketch(0)
+        hdr = tb.header()
+        assert hdr["U"] == 1 and hdr["A"] == 1
+        want = np.zeros(hdr["m"], np.float32)
+        for j in range(3):
+            slot, sign = B.tagc_hash_host(pos, 77, j, hdr["m_sub"])
+            assert (slot, sign) == O.hash_slot(pos, 77, j, hdr["m_sub"])
+            want[j * hdr["m_sub"] + slot] = sign
+        assert np.array_equal(sk, want)
