@@ -1,0 +1,313 @@
+#!/usr/bin/env python3
+"""Benchmark of the TAGC hot path on one MI355X.
+
+One "step" is one pass of the whole hot path (sparsify + index, Index OR, sketch
+encode, sketch sum, peeling decode) over one full synthetic gradient of the
+workload: every bucket, every simulated rank.  Inputs are resident in HBM before
+the timed region starts.  Prints ONE JSON line (see README/DESIGN for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# Kernels of the library grouped into the stages of the path.
+STAGES = {
+    "S1+S2 sparsify+index": ["fill_zero", "hist1", "select1", "hist2", "select2", "compact"],
+    "S3a index OR": ["index_or", "header", "bounds"],
+    "S2' encode": ["encode"],
+    "S3b sketch sum": ["sketch_sum"],
+    "S4 decode": ["decode"],
+}
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="config5",
+                    choices=["config1", "config2", "config3", "config4", "config5"])
+    ap.add_argument("--pool", type=int, default=8,
+                    help="distinct bucket data sets resident in HBM (buckets cycle through them)")
+    ap.add_argument("--lf", type=int, default=0, help="load factor x1000 (0 = workload default)")
+    ap.add_argument("--dense", type=int, default=1, help="also write the dense summed gradient")
+    ap.add_argument("--buckets", type=int, default=0,
+                    help="only the first B buckets of the workload (0 = all; for experiments)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile-pass", action="store_true")
+    return ap.parse_args()
+
+
+def make_buckets(args):
+    from synth import gradients as G
+    w = args.workload
+    if w == "config1":
+        bs = [G.config1(args.seed)]
+    elif w == "config2":
+        bs = G.config2(args.seed)
+    elif w == "config3":
+        bs = [G.config3(args.seed)]
+    elif w == "config4":
+        bs = G.config4(args.seed)
+    else:
+        bs = G.config5(args.seed)
+    if args.buckets:
+        bs = bs[:args.buckets]
+    if args.lf:
+        for b in bs:
+            b.sizing_milli = args.lf
+    return bs
+
+
+def alg_bytes(b, z, hdr, k_total, dense):
+    """Algorithmic bytes per stage for one bucket: one read of the gradient, every
+    message materialised once; work-lists, histograms and degree tables are not
+    credited."""
+    N, e = b.n_ranks, b.elem_bytes
+    n_c, U, m = z.n_c, hdr["U"], hdr["m"]
+    return {
+        "S1+S2 sparsify+index": N * z.n_real * e + 8 * k_total + N * n_c // 8,
+        "S3a index OR": N * n_c // 8 + n_c // 8,
+        "S2' encode": 8 * k_total + N * 4 * m,
+        "S3b sketch sum": (N + 1) * 4 * m,
+        "S4 decode": n_c // 8 + 4 * m + 8 * U + (4 * n_c if dense else 0),
+    }
+
+
+def kernel_alg_bytes(b, z, hdr, k_total, dense):
+    """Bytes each bandwidth-relevant kernel must itself move per bucket (all its
+    launches together).  hist1 and compact each read the gradient once, so their sum
+    exceeds the stage's algorithmic bytes: the stage figure shows the cost of the
+    second read, this one prices each kernel against what it has to touch."""
+    N, e = b.n_ranks, b.elem_bytes
+    n_c, U, m = z.n_c, hdr["U"], hdr["m"]
+    return {
+        "hist1": N * z.n_real * e,
+        "hist2": N * z.n_real * e,
+        "compact": N * z.n_real * e + 8 * k_total + N * n_c // 8,
+        "index_or": (N + 1) * n_c // 8,
+        "encode": 8 * k_total + N * 4 * m,
+        "sketch_sum": (N + 1) * 4 * m,
+        "decode": n_c // 8 + 4 * m + 8 * U + (4 * n_c if dense else 0),
+    }
+
+
+def cpu_baseline(args):
+    """The oracle, as it stands, timed on this machine's host cores on a bounded sample
+    of the same workload."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import tagc_oracle as O
+    from synth import gradients as G
+    b = make_buckets(args)[0]
+    seg = max((s for s in b.segments if s.flags & 1), key=lambda s: -s.length)  # smallest
+    n = min(seg.length, 1 << 24)
+    n_ranks = min(b.n_ranks, 8)
+    sub = G.Bucket("sample", b.dtype, n_ranks, [G.Seg(0, n, seg.keep_ppm, 1, seg.name)], n,
+                   b.sizing_milli, {seg.name: b.sigma.get(seg.name, 1e-3)}, b.kind,
+                   b.seed, b.bucket_id)
+    grads = [G.to_numpy_raw(G.rank_gradient(sub, r, "cpu")) for r in range(n_ranks)]
+    cfg = O.Config(dtype=sub.dtype, sizing_milli=sub.sizing_milli, seed=args.seed)
+    segs = [O.Segment(0, n, seg.keep_ppm, 1)]
+    threads = min(n_ranks, os.cpu_count() or 1, 16)
+    O.lib()
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:   # ranks are independent until the OR
+        ranks = list(ex.map(lambda g: O.sparsify(g, cfg, segs), grads))
+    bitmap, U = O.index_or([r.bitmap for r in ranks])
+    A, m_sub, m = O.layout(U, cfg, n)
+    bnd = O.bounds(bitmap, n, U, A)
+    with ThreadPoolExecutor(threads) as ex:
+        sks = list(ex.map(lambda r: O.encode(r.idx, r.val, bnd, A, m_sub, cfg.seed), ranks))
+    total = O.sketch_sum(sks)
+    dec = O.peel(bitmap, n, U, A, m_sub, cfg.seed, total)
+    dt = time.perf_counter() - t0
+    nbytes = n_ranks * n * sub.elem_bytes
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "%s segment %s (%d elements) x %d ranks, whole path, %.1f s"
+                      % (b.name, seg.name, n, n_ranks, dt),
+            "n_unresolved": dec.n_unresolved}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU only (N simulated ranks are "
+                         "summed locally); --gpus %d is not supported\n" % args.gpus)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible; libtagc has no CPU path\n")
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    from synth import gradients as G
+    from paper_2504_05638_amd import binding as B
+    from paper_2504_05638_amd.bucket import TagcBucket
+
+    buckets = make_buckets(args)
+    n_b = len(buckets)
+    pool = max(1, min(args.pool, n_b))
+    N = buckets[0].n_ranks
+    gen = G.config3_rank_gradient if args.workload == "config3" else G.rank_gradient
+
+    # ---- inputs resident in HBM (pool of distinct bucket data sets)
+    t0 = time.perf_counter()
+    data = [[gen(buckets[d], r, "cuda") for r in range(N)] for d in range(pool)]
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t0
+
+    # ---- one plan per bucket, device buffers shared (buckets run one after another)
+    # (the first bucket allocates every buffer at the largest size any bucket needs)
+    fields = {"sh_bitmap": "shared_bitmap_bytes", "sh_sketch": "shared_sketch_bytes",
+              "sh_bounds": "shared_bounds_bytes", "sh_ws": "shared_workspace_bytes",
+              "rank_ws": "rank_workspace_bytes", "idx": "rank_idx_bytes",
+              "val": "rank_val_bytes", "cnt": "rank_cnt_bytes", "bitmap": "rank_bitmap_bytes",
+              "sketch": "rank_sketch_bytes", "out_idx": "out_idx_bytes",
+              "out_val": "out_val_bytes", "out_dense": "out_dense_bytes"}
+    need = {k: 0 for k in fields}
+    for b in buckets:
+        cfg = B.tagc_config(dtype=b.dtype, n_ranks=N, n_hash=3, sizing=B.TAGC_SIZE_LOAD_FACTOR,
+                            sizing_milli=b.sizing_milli, index_mode=B.TAGC_INDEX_OR1,
+                            part_unknowns=0, part_cells=0, seed=args.seed)
+        plan = B.tagc_plan(cfg, [tuple(s[:4]) for s in b.segments])
+        z = B.tagc_plan_sizes(plan)
+        for k, f in fields.items():
+            need[k] = max(need[k], getattr(z, f))
+        B.tagc_plan_destroy(plan)
+    tbs = []
+    for i, b in enumerate(buckets):
+        tbs.append(TagcBucket(b.segments, b.dtype, N, sizing_milli=b.sizing_milli,
+                              seed=args.seed, dense=bool(args.dense),
+                              share=tbs[0] if tbs else None, min_bytes=need if not tbs else None))
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for i in range(n_b):
+            tbs[i].run(data[i % pool], stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- per-bucket facts (U, m, pairs) for the byte accounting, from one more pass
+    input_bytes = 0
+    balg = {k: 0 for k in STAGES}
+    kalg = {}
+    unresolved = rounds = 0
+    U_tot = m_tot = k_tot = 0
+    flags = 0
+    for i in range(n_b):
+        tbs[i].run(data[i % pool], stream)
+        torch.cuda.synchronize()
+        hdr, st = tbs[i].header(), tbs[i].status()
+        kt = sum(tbs[i].rank_counts(r)["total"] for r in range(N))
+        flags |= st["flags"]
+        for r in range(N):
+            flags |= tbs[i].rank_counts(r)["flags"]
+        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense).items():
+            balg[k] += v
+        for k, v in kernel_alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense).items():
+            kalg[k] = kalg.get(k, 0) + v
+        input_bytes += N * tbs[i].sizes.n_real * buckets[i].elem_bytes
+        unresolved += st["n_unresolved"]
+        rounds = max(rounds, st["rounds"])
+        U_tot += hdr["U"]
+        m_tot += hdr["m"]
+        k_tot += kt
+    if flags:
+        sys.stderr.write("bench.py: library reported error flags %d\n" % flags)
+        sys.exit(1)
+
+    # ---- timed region: exactly K steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+    ms_per_step = 1e3 * t_total / args.steps
+    value = input_bytes / (ms_per_step * 1e-3) / 1e9
+    balg_total = sum(balg.values())
+
+    # ---- same K steps again with the library's per-kernel HIP events switched on
+    stages, roofline = {}, None
+    if not args.no_profile_pass:
+        B.tagc_profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t_prof = time.perf_counter() - t0
+        prof = B.tagc_profile_read(64)
+        B.tagc_profile_enable(False)
+        for sname, kernels in STAGES.items():
+            ms = sum(prof[k][0] for k in kernels if k in prof) / args.steps
+            stages[sname] = {
+                "ms_per_step": round(ms, 4),
+                "gradient_GBps": round(input_bytes / (ms * 1e-3) / 1e9, 1) if ms else None,
+                "alg_bytes": balg[sname],
+                "hbm_frac": round(balg[sname] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if ms else None,
+            }
+        dom = max(prof, key=lambda k: prof[k][0])
+        d_ms, d_n = prof[dom]
+        avg_ms = d_ms / d_n
+        # algorithmic bytes per launch of the dominant kernel (one launch = one rank of
+        # one bucket for per-rank kernels, one bucket for aggregation / decode),
+        # averaged over the launches of the timed steps
+        per_launch = kalg.get(dom, 0) * args.steps / d_n
+        achieved = per_launch / (avg_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": MEASURED_TRAFFIC.get((args.workload, dom)),
+                    "avg_launch_ms": round(avg_ms, 5), "launches": d_n,
+                    "alg_bytes_per_launch": int(per_launch),
+                    "events_pass_ms_per_step": round(1e3 * t_prof / args.steps, 3),
+                    "kernels_ms_per_step": {k: round(v[0] / args.steps, 4)
+                                            for k, v in sorted(prof.items(),
+                                                               key=lambda kv: -kv[1][0])}}
+
+    out = {
+        "metric": "gradient GB/s compressed+aggregated+decoded on 1 MI355X; % of HBM peak",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d buckets x %d simulated ranks, %s grads, lf %.1f, %s"
+                               % (args.workload, n_b, N,
+                                  "bf16" if buckets[0].dtype == G.BF16 else "fp32",
+                                  buckets[0].sizing_milli / 1000.0,
+                                  "sparse+dense output" if args.dense else "sparse output"),
+                   "input_bytes_per_step": input_bytes, "distinct_bucket_data_sets": pool,
+                   "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
+                   "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
+                   "peel_rounds_max": rounds, "input_generation_s": round(t_gen, 2)},
+        "hbm_frac_end_to_end": round(balg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "alg_bytes_per_step": balg_total,
+        "stages": stages,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -27,7 +27,7 @@ class TagcBucket:
 
     def __init__(self, segments, dtype, n_ranks, sizing_milli=3000,
                  sizing=B.TAGC_SIZE_LOAD_FACTOR, seed=0, part_unknowns=0,
-                 part_cells=0, device="cuda", dense=False, share=None):
+                 part_cells=0, device="cuda", dense=False, share=None, min_bytes=None):
         if not torch.cuda.is_available():
             raise RuntimeError("libtagc needs a GPU: no CPU path exists")
         self.device = torch.device(device)
@@ -42,6 +42,7 @@ class TagcBucket:
         self.n_ranks = n_ranks
         z, dev = self.sizes, self.device
         self._share = share
+        self._min_bytes = min_bytes or {}
         self._t = {}
         al = self._alloc
         self.table = _bytes(z.table_bytes, dev)           # per bucket, never shared
@@ -79,6 +80,7 @@ class TagcBucket:
     def _alloc(self, name, nbytes):
         """A device buffer of at least nbytes; taken from `share` (another bucket that
         is never in flight at the same time) when that one is large enough."""
+        nbytes = max(int(nbytes), int(self._min_bytes.get(name.rstrip("0123456789"), 0)))
         t = None
         if self._share is not None:
             t = self._share._t.get(name)

@@ -296,8 +296,9 @@ constexpr uint64_t kStAgg = 1ull << 62, kStPre = 2ull << 62, kStMask = 3ull << 6
 
 // Decoupled look-back over the tiles of one segment, run by the first wave of the
 // workgroup.  state word = status(2) | count(key > T)(31) | count(key == T)(31).
-// Tiles are taken in ticket order, so every predecessor this waits for has already been
-// started by a resident workgroup and publishes without waiting for anyone later.
+// The grid is persistent and fully resident, and workgroup b takes tiles b, b+G, b+2G, ...;
+// so every predecessor tile this waits for belongs to a workgroup that is running and
+// that publishes its counts without waiting for any later tile.
 __device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, uint64_t agg,
                                     uint32_t *flags)
 {
@@ -350,7 +351,6 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
     constexpr uint32_t ROW_ELEMS = kCompactThreads * VEC;
     constexpr uint32_t TILE = ROW_ELEMS * ROWS;
     constexpr uint32_t LPW = 32 / VEC;  // lanes that share one Index word
-    __shared__ uint32_t s_ticket;
     __shared__ uint64_t s_scan[2 * (kCompactThreads / 64)];
     __shared__ uint64_t s_excl;
     __shared__ uint32_t s_base;
@@ -359,11 +359,7 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
     const uint32_t tid = threadIdx.x;
 
-    while (true) {
-        if (tid == 0) s_ticket = atomicAdd(ticket, 1u);
-        __syncthreads();
-        const uint32_t t = s_ticket;
-        if (t >= total_tiles) break;
+    for (uint32_t t = blockIdx.x; t < total_tiles; t += gridDim.x) {
 
         // segment of this tile: the last l with tile_start[l] <= t
         uint32_t lo = 0, hi = L;
@@ -501,7 +497,7 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
             const uint32_t rel0 = rel - (tid & (LPW - 1)) * VEC;  // first element of the word
             if ((tid & (LPW - 1)) == 0 && rel0 < sd.n) bitmap[(sd.c_off + rel0) >> 5] = v;
         }
-        __syncthreads();  // s_ticket / s_excl are rewritten by the next iteration
+        __syncthreads();  // s_excl / s_base are rewritten by the next iteration
     }
 }
 
@@ -575,7 +571,19 @@ int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buff
     }
     if (p->total_tiles) {
         ProfileScope ps("compact", s);
-        uint32_t grid = std::min<uint32_t>(p->total_tiles, uint32_t(cus) * 8);
+        // persistent grid that is resident as a whole (the look-back relies on it)
+        static int per_cu[2] = {0, 0};
+        int &occ = per_cu[bf16 ? 1 : 0];
+        if (occ == 0) {
+            int n = 0;
+            hipError_t e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                                      &n, compact_kernel<kBF16>, kCompactThreads, 0)
+                                : hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                                      &n, compact_kernel<kF32>, kCompactThreads, 0);
+            if (e != hipSuccess || n <= 0) return TAGC_EHIP;
+            occ = n;
+        }
+        uint32_t grid = std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
         if (bf16)
             compact_kernel<kBF16><<<grid, kCompactThreads, 0, s>>>(
                 g, table, sel, tile_state, counters, rk->idx, rk->val, rk->bitmap, rk->cnt);
