@@ -24,7 +24,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # Kernels of the library grouped into the stages of the path.
 STAGES = {
-    "S1+S2 sparsify+index": ["fill_zero", "hist1", "select1", "hist2", "select2", "compact"],
+    "S1+S2 sparsify+index": ["fill_zero", "sample", "scan_spill", "select1", "hist1", "select1d",
+                             "hist2c", "hist2", "select2", "emit", "compact"],
     "S3a index OR": ["index_or", "header", "bounds"],
     "S2' encode": ["encode"],
     "S3b sketch sum": ["sketch_sum"],
@@ -99,9 +100,11 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense):
     N, e = b.n_ranks, b.elem_bytes
     n_c, U, m = z.n_c, hdr["U"], hdr["m"]
     return {
+        "scan_spill": N * z.n_real * e,
         "hist1": N * z.n_real * e,
         "hist2": N * z.n_real * e,
         "compact": N * z.n_real * e + 8 * k_total + N * n_c // 8,
+        "emit": 8 * k_total + N * n_c // 8,
         "index_or": (N + 1) * n_c // 8,
         "encode": 8 * k_total + N * 4 * m,
         "sketch_sum": (N + 1) * 4 * m,

@@ -123,6 +123,7 @@ enum {
     TAGC_CNT_NONFINITE = 1, /* inputs with all-ones exponent seen (result then
                                unspecified but memory-safe)                      */
     TAGC_CNT_FLAGS = 2,     /* TAGC_FLAG_* bits                                  */
+    TAGC_CNT_DENSE = 3,     /* segments that took the two-read route (diagnostic) */
     TAGC_CNT_SEG0 = 4       /* [4 + l] = pairs of compressed segment l           */
 };
 /* shared `header` words (uint32), written by tagc_aggregate(PHASE_INDEX) */

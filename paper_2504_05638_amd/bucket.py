@@ -168,7 +168,7 @@ class TagcBucket:
         c = self._np(self._rk_tensors[r]["cnt"], np.uint32)
         L = self.sizes.n_seg_compressed
         return dict(total=int(c[B.TAGC_CNT_TOTAL]), nonfinite=int(c[B.TAGC_CNT_NONFINITE]),
-                    flags=int(c[B.TAGC_CNT_FLAGS]),
+                    flags=int(c[B.TAGC_CNT_FLAGS]), dense_segments=int(c[B.TAGC_CNT_DENSE]),
                     seg=c[B.TAGC_CNT_SEG0:B.TAGC_CNT_SEG0 + L].tolist())
 
     def rank_pairs(self, r):

@@ -96,71 +96,86 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
     for (uint32_t c = tid; c < deg_words; c += kDecodeThreads) deg2[c] = 0;
     __syncthreads();  // also orders this workgroup's idx_out stores before the loads below
 
-    uint32_t myidx[kDecodeMaxQ];
-    float x[kDecodeMaxQ];
+    // Per-thread state for its unknowns (u = tid + q*1024): the three cell numbers
+    // (15 bits each) and sign bits packed into 64 bits, one "resolved" bit, and one
+    // 2-bit "taken this round via hash j" code.
+    uint64_t pk[kDecodeMaxQ];
 #pragma unroll
     for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
         const uint32_t u = tid + q * kDecodeThreads;
-        x[q] = 0.0f;
-        myidx[q] = 0;
+        pk[q] = 0;
         if (u < Pa) {
-            myidx[q] = idx_out[rho0 + u];
-            const Cells cl = cells_of(myidx[q], m_sub, sw0, sw1, sw2);
+            const Cells cl = cells_of(idx_out[rho0 + u], m_sub, sw0, sw1, sw2);
+            pk[q] = uint64_t(cl.c[0]) | (uint64_t(cl.c[1]) << 15) | (uint64_t(cl.c[2]) << 30) |
+                    (uint64_t(cl.neg) << 45);
 #pragma unroll
             for (int j = 0; j < 3; ++j) atomicAdd(&deg2[cl.c[j] >> 1], 1u << (16 * (cl.c[j] & 1)));
         }
+        __builtin_amdgcn_sched_barrier(0);  // keep the unrolled iterations apart: registers
     }
     __syncthreads();
 
     // ---- peel
     uint32_t done = 0, rounds = 0;
     while (true) {
-        uint32_t pick = 0;
+        uint32_t code = 0;
 #pragma unroll
         for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
             const uint32_t u = tid + q * kDecodeThreads;
             if (u < Pa && !((done >> q) & 1u)) {
-                const Cells cl = cells_of(myidx[q], m_sub, sw0, sw1, sw2);
-                int j = -1;
-                if (deg_of(deg2, cl.c[0]) == 1) j = 0;
-                else if (deg_of(deg2, cl.c[1]) == 1) j = 1;
-                else if (deg_of(deg2, cl.c[2]) == 1) j = 2;
-                if (j >= 0) {
-                    const float c = Ct[cl.c[j]];
-                    x[q] = ((cl.neg >> j) & 1u) ? -c : c;
-                    pick |= 1u << q;
-                }
+                // opaque copy: keeps the unpacking inside the round loop (hoisting it for
+                // all 16 unknowns would cost more registers than the kernel has)
+                uint32_t plo = uint32_t(pk[q]), phi = uint32_t(pk[q] >> 32);
+                asm volatile("" : "+v"(plo), "+v"(phi));
+                const uint64_t pq = uint64_t(plo) | (uint64_t(phi) << 32);
+                const uint32_t c0 = uint32_t(pq) & 0x7FFFu, c1 = uint32_t(pq >> 15) & 0x7FFFu,
+                               c2 = uint32_t(pq >> 30) & 0x7FFFu;
+                uint32_t c = 0;
+                if (deg_of(deg2, c0) == 1) c = 1;
+                else if (deg_of(deg2, c1) == 1) c = 2;
+                else if (deg_of(deg2, c2) == 1) c = 3;
+                code |= c << (2 * q);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // barrier between the snapshot reads above and the updates below
-        if (!__syncthreads_or(pick != 0)) break;
+        // Nothing has been written yet: a cell of degree 1 keeps its value until its
+        // own unknown subtracts itself below, so the value can be read there.
+        if (!__syncthreads_or(code != 0)) break;
         ++rounds;
 #pragma unroll
         for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
-            if ((pick >> q) & 1u) {
-                const Cells cl = cells_of(myidx[q], m_sub, sw0, sw1, sw2);
+            const uint32_t c = (code >> (2 * q)) & 3u;
+            if (c) {
+                uint32_t plo = uint32_t(pk[q]), phi = uint32_t(pk[q] >> 32);
+                asm volatile("" : "+v"(plo), "+v"(phi));
+                const uint64_t pq = uint64_t(plo) | (uint64_t(phi) << 32);
+                const uint32_t cc[3] = {uint32_t(pq) & 0x7FFFu, uint32_t(pq >> 15) & 0x7FFFu,
+                                        uint32_t(pq >> 30) & 0x7FFFu};
+                const uint32_t neg = uint32_t(pq >> 45) & 7u;
+                const uint32_t j = c - 1;
+                const float cv = Ct[j == 0 ? cc[0] : (j == 1 ? cc[1] : cc[2])];
+                const float x = ((neg >> j) & 1u) ? -cv : cv;
+                val_out[rho0 + tid + q * kDecodeThreads] = x;
 #pragma unroll
-                for (int j = 0; j < 3; ++j) {
-                    atomicAdd(&Ct[cl.c[j]], ((cl.neg >> j) & 1u) ? x[q] : -x[q]);
-                    atomicSub(&deg2[cl.c[j] >> 1], 1u << (16 * (cl.c[j] & 1)));
+                for (int jj = 0; jj < 3; ++jj) {
+                    atomicAdd(&Ct[cc[jj]], ((neg >> jj) & 1u) ? x : -x);
+                    atomicSub(&deg2[cc[jj] >> 1], 1u << (16 * (cc[jj] & 1)));
                 }
+                done |= 1u << q;
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        done |= pick;
         __syncthreads();
     }
 
-    // ---- sparse output and status
+    // ---- unresolved unknowns get 0; status
     uint32_t unresolved = 0;
 #pragma unroll
     for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
         const uint32_t u = tid + q * kDecodeThreads;
-        if (u < Pa) {
-            if (!((done >> q) & 1u)) {
-                x[q] = 0.0f;
-                ++unresolved;
-            }
-            val_out[rho0 + u] = x[q];
+        if (u < Pa && !((done >> q) & 1u)) {
+            val_out[rho0 + u] = 0.0f;
+            ++unresolved;
         }
     }
     unresolved = block_sum<uint32_t, kDecodeThreads / 64>(unresolved, scratch);
@@ -173,14 +188,14 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
     if (dense_out) {
         const uint32_t dlo = a == 0 ? 0u : ilo;
         const uint32_t DT = ct_floats;
+        __syncthreads();  // val_out stores of this workgroup are read back below
         for (uint32_t tb = dlo; tb < ihi; tb += DT) {
             const uint32_t len = min(DT, ihi - tb);
             for (uint32_t c = tid; c < len; c += kDecodeThreads) Ct[c] = 0.0f;
             __syncthreads();
-#pragma unroll
-            for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
-                const uint32_t u = tid + q * kDecodeThreads;
-                if (u < Pa && myidx[q] >= tb && myidx[q] - tb < len) Ct[myidx[q] - tb] = x[q];
+            for (uint32_t u = tid; u < Pa; u += kDecodeThreads) {
+                const uint32_t i = idx_out[rho0 + u];
+                if (i >= tb && i - tb < len) Ct[i - tb] = val_out[rho0 + u];
             }
             __syncthreads();
             for (uint32_t c = tid; c < len; c += kDecodeThreads) dense_out[uint64_t(tb) + c] = Ct[c];

@@ -42,9 +42,11 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     p->elem_bytes = cfg->dtype == TAGC_F32 ? 4 : 2;
     p->vec_elems = 16 / p->elem_bytes;
     p->tile_elems = kCompactThreads * p->vec_elems * kCompactRows;
+    p->chunk_elems = 64 * p->vec_elems * kCandRows;
+    p->cand_cap = 32;
     for (uint32_t j = 0; j < 3; ++j) p->seed_word[j] = seed_word(cfg->seed, j);
 
-    uint64_t c = 0, n_real = 0, K = 0, tiles = 0, grad_elems = 0;
+    uint64_t c = 0, n_real = 0, K = 0, tiles = 0, grad_elems = 0, scs = 0;
     try {
         p->segments.assign(segs, segs + n_seg);
         for (uint32_t l = 0; l < n_seg; ++l) {
@@ -65,7 +67,20 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
             d.c_off = uint32_t(c);
             d.k = uint32_t((unsigned __int128)s.length * s.keep_ppm / 1000000u);
             d.tile_start = uint32_t(tiles);
-            d.aligned = (s.offset % p->vec_elems) == 0;
+            d.flags = (s.offset % p->vec_elems) == 0 ? kSegAligned : 0;
+            // Candidate route: slots per chunk for 1.3 x the kept fraction plus six
+            // standard deviations; segments keeping so much that half a chunk would be
+            // candidates gain nothing from it.
+            if ((d.flags & kSegAligned) && d.n >= kFastMinElems && d.k >= kFastMinKeep) {
+                const double mu = 1.3 * double(d.k) / double(d.n) * p->chunk_elems;
+                const uint32_t cap = uint32_t(round_up(uint64_t(mu + 6.0 * sqrt(mu) + 16.0), 32));
+                if (cap <= p->chunk_elems / 2) {
+                    d.flags |= kSegFast;
+                    p->cand_cap = std::max(p->cand_cap, cap);
+                }
+            }
+            d.sc_start = uint32_t(scs);
+            scs += ceil_div(s.length, uint64_t(p->chunk_elems) * kCandChunksPerSuper);
             p->table.push_back(d);
             c = round_up(c + s.length, 32);
             n_real += s.length;
@@ -85,6 +100,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     p->n_c = c;
     p->K = K;
     p->total_tiles = uint32_t(tiles);
+    p->total_sc = uint32_t(scs);
     p->U_cap = std::min<uint64_t>(n_real, uint64_t(cfg->n_ranks) * K);
     uint64_t M_max = cfg->sizing == TAGC_SIZE_LOAD_FACTOR
                          ? ceil_div(uint64_t(cfg->sizing_milli) * p->U_cap, 1000)
@@ -100,20 +116,31 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     const uint64_t words = p->n_c / 32;
     p->n_chunks = ceil_div(words, kChunkWords);
 
-    // rank workspace: [hist1 | hist2 | tile_state | counters] cleared per call, then sel
+    // rank workspace: a prefix that every PHASE_INDEX call clears, then uncleared scratch
     Workspace &w = p->ws;
+    const uint64_t chunks = scs * kCandChunksPerSuper;
     uint64_t off = 0;
     w.hist1 = off;
+    off += L * kBins1 * 4;
+    w.hist1d = off;
     off += L * kBins1 * 4;
     w.hist2 = off;
     off += (cfg->dtype == TAGC_F32 ? L * kBins2 * 4 : 0);
     w.tile_state = off;
     off += round_up(tiles * 8, 16);
+    w.sc_state = off;
+    off += round_up(scs * 8, 16);
     w.counters = off;
     off += 64;
     p->zero_bytes = off;
     w.sel = off;
     off += round_up(L * sizeof(SelDev), 16);
+    w.binlo = off;
+    off += round_up(L * 4, 16);
+    w.chunk_cnt = off;
+    off += round_up(chunks * 4, 16);
+    w.cand = off;
+    off += round_up(chunks * p->cand_cap * (cfg->dtype == TAGC_F32 ? 8 : 4), 16);
     w.total = std::max<uint64_t>(off, 16);
 
     tagc_sizes &z = p->sizes;
@@ -169,7 +196,7 @@ extern "C" int tagc_plan_upload(const tagc_plan_t *p, void *table_dev, void *str
     if (!p || !table_dev || !aligned16(table_dev)) return TAGC_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t hdr[8] = {uint32_t(p->table.size()), p->total_tiles, uint32_t(p->n_c),
-                       uint32_t(p->n_chunks), 0, 0, 0, 0};
+                       uint32_t(p->n_chunks), p->total_sc, 0, 0, 0};
     // Two small copies from pageable host memory: hipMemcpyAsync stages them before it
     // returns, so `hdr` may live on this stack frame.
     if (hipMemcpyAsync(table_dev, hdr, sizeof(hdr), hipMemcpyHostToDevice, s) != hipSuccess)

@@ -6,15 +6,29 @@
 // survivors as (c-index, float32 value) pairs in ascending c-index together with the
 // 1-bit-per-parameter Index (Algorithm 1: sparsify, create_index).
 //
-// Kernels
-//   fill_zero      clears the per-call part of the workspace
-//   hist1          exact histogram of the top 15 key bits (all of a bf16 key) in LDS
-//   select1        threshold bin from that histogram
-//   hist2/select2  fp32 only: the low 16 key bits inside the threshold bin
-//   compact        one ordered pass: survivors + Index words, decoupled look-back
+// Keys: |g| as an unsigned integer (float32 bit pattern with the sign cleared; bf16 is
+// widened first).  Ties at the threshold go to the lower position; exact zeros never
+// survive.
 //
-// Keys: |g| as an unsigned integer (bit pattern with the sign cleared).  Ties at the
-// threshold are broken towards the lower position; exact zeros never survive.
+// Two routes per segment, both exact:
+//
+//  candidate route (one read of the gradient)
+//    sample       a strided sample gives a conservative pre-threshold bin `binlo`
+//    scan_spill   streams the segment once: entries with key bin >= binlo ("candidates",
+//                 ~1.3 x k of them) are histogrammed in LDS and spilled, in position
+//                 order, into fixed slots per 4 KiB chunk -- no cross-wave dependency
+//    select1      exact threshold from the candidate histogram; if the candidates do not
+//                 contain k entries (the sample misled) the segment is re-routed
+//    hist2c/select2  fp32 only: low 16 key bits inside the threshold bin
+//    emit         ordered pass over the candidates only: pairs + every Index word
+//
+//  dense route (segments that are short, unaligned, or re-routed; two reads)
+//    hist1        exact histogram of the top 15 key bits of every entry, in LDS
+//    select1, hist2/select2 as above
+//    compact      ordered pass over the gradient: pairs + Index words
+//
+// Ordered output across workgroups uses a decoupled look-back on persistent, fully
+// resident grids with strided work assignment.
 #include "device_utils.h"
 #include "tagc_internal.h"
 
@@ -34,96 +48,17 @@ __global__ void __launch_bounds__(256) fill_zero_kernel(uint4 *p, uint64_t n16, 
         for (uint32_t i = threadIdx.x; i < n_cnt; i += 256) cnt[i] = 0;
 }
 
-// ------------------------------------------------------------------ hist1
-
-template <int DTYPE>
-__device__ inline void hist_word(uint32_t w, uint32_t *h)
-{
-    if (DTYPE == kBF16) {
-        uint32_t a = w & 0x7FFFu, b = (w >> 16) & 0x7FFFu;
-        if (a) atomicAdd(&h[a], 1u);
-        if (b) atomicAdd(&h[b], 1u);
-    } else {
-        uint32_t key = w & 0x7FFFFFFFu;
-        if (key) atomicAdd(&h[key >> 16], 1u);
-    }
-}
-
-template <int DTYPE>
-__device__ inline void hist_vec(uint4 v, uint32_t *h)
-{
-    hist_word<DTYPE>(v.x, h);
-    hist_word<DTYPE>(v.y, h);
-    hist_word<DTYPE>(v.z, h);
-    hist_word<DTYPE>(v.w, h);
-}
-
 __device__ inline uint32_t load_elem_bits(const char *base, uint64_t i, int dtype)
 {
     if (dtype == kBF16) return uint32_t(reinterpret_cast<const uint16_t *>(base)[i]) << 16;
     return reinterpret_cast<const uint32_t *>(base)[i];
 }
 
+// float32 bit pattern of element e of a 16-byte vector
 template <int DTYPE>
-__device__ inline void hist_elem(uint32_t f32bits, uint32_t *h)
+__device__ inline uint32_t vec_elem_bits(const uint32_t (&w)[4], uint32_t e)
 {
-    uint32_t key = f32bits & 0x7FFFFFFFu;
-    if (key) atomicAdd(&h[key >> 16], 1u);
-}
-
-// One workgroup per CU, 32768 LDS counters.  Segments are processed one after another;
-// after each the non-zero counters are added to the segment's global histogram.
-template <int DTYPE>
-__global__ void __launch_bounds__(kHistThreads)
-hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
-             uint32_t *__restrict__ hist)
-{
-    extern __shared__ uint32_t h[];
-    constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
-    constexpr uint32_t VEC = 16 / EB;
-    const uint32_t L = table[0];
-    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
-    const uint32_t tid = threadIdx.x;
-    for (uint32_t i = tid; i < kBins1; i += kHistThreads) h[i] = 0;
-    __syncthreads();
-    for (uint32_t l = 0; l < L; ++l) {
-        const SegDev sd = segs[l];
-        if (sd.k == 0 || sd.n == 0) continue;
-        const char *base = grad + sd.offset * EB;
-        if (sd.aligned) {
-            const uint4 *vp = reinterpret_cast<const uint4 *>(base);
-            const uint64_t nvec = sd.n / VEC;
-            const uint64_t stride = uint64_t(gridDim.x) * kHistThreads;
-            uint64_t v = uint64_t(blockIdx.x) * kHistThreads + tid;
-            for (; v + 3 * stride < nvec; v += 4 * stride) {
-                uint4 a = vp[v], b = vp[v + stride], c = vp[v + 2 * stride],
-                      d = vp[v + 3 * stride];
-                hist_vec<DTYPE>(a, h);
-                hist_vec<DTYPE>(b, h);
-                hist_vec<DTYPE>(c, h);
-                hist_vec<DTYPE>(d, h);
-            }
-            for (; v < nvec; v += stride) hist_vec<DTYPE>(vp[v], h);
-            if (blockIdx.x == 0) {
-                uint64_t i = nvec * VEC + tid;
-                if (i < sd.n) hist_elem<DTYPE>(load_elem_bits(base, i, DTYPE), h);
-            }
-        } else {
-            for (uint64_t i = uint64_t(blockIdx.x) * kHistThreads + tid; i < sd.n;
-                 i += uint64_t(gridDim.x) * kHistThreads)
-                hist_elem<DTYPE>(load_elem_bits(base, i, DTYPE), h);
-        }
-        __syncthreads();
-        uint32_t *gh = hist + uint64_t(l) * kBins1;
-        for (uint32_t i = tid; i < kBins1; i += kHistThreads) {
-            uint32_t c = h[i];
-            if (c) {
-                atomicAdd(&gh[i], c);
-                h[i] = 0;
-            }
-        }
-        __syncthreads();
-    }
+    return DTYPE == kBF16 ? ((w[e >> 1] >> (16 * (e & 1))) << 16) : w[e];
 }
 
 // ----------------------------------------------------------------- select
@@ -132,9 +67,9 @@ hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
 // owns the BPT consecutive bins starting at t*BPT.  Returns false if the whole histogram
 // holds fewer than `need`; *total_out is the histogram's sum either way.
 template <int BPT>
-__device__ inline bool select_bins(const uint32_t *__restrict__ hist, uint32_t need,
-                                   uint32_t *bin_out, uint32_t *above_out, uint32_t *at_out,
-                                   uint32_t *total_out, uint32_t *smem /* >= 20 words */)
+__device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t *bin_out,
+                                   uint32_t *above_out, uint32_t *at_out, uint32_t *total_out,
+                                   uint32_t *smem /* >= 20 words */)
 {
     const uint32_t t = threadIdx.x;
     const uint4 *hv = reinterpret_cast<const uint4 *>(hist + uint64_t(t) * BPT);
@@ -169,42 +104,336 @@ __device__ inline bool select_bins(const uint32_t *__restrict__ hist, uint32_t n
     return total >= need;
 }
 
+// ----------------------------------------------------------------- sample
+
+// One workgroup per compressed segment.  Initialises the segment's SelDev (route) and,
+// for segments on the candidate route, picks `binlo` from a strided sample of 16-byte
+// vectors: the sample bin above which  k*S/n + 5*sqrt(k*S/n) + 16  sampled entries lie.
+// The margin makes it very unlikely that fewer than k entries of the whole segment pass
+// the pre-threshold; if that still happens select1 notices and re-routes the segment.
+template <int DTYPE>
+__global__ void __launch_bounds__(kHistThreads)
+sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
+              SelDev *__restrict__ sel, uint32_t *__restrict__ binlo)
+{
+    extern __shared__ uint32_t h[];
+    __shared__ uint32_t smem[32];
+    constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
+    constexpr uint32_t VEC = 16 / EB;
+    const uint32_t l = blockIdx.x, tid = threadIdx.x;
+    const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
+    SelDev r{};
+    r.route = (sd.flags & kSegFast) ? 0u : 1u;
+    if (sd.k == 0 || sd.n == 0) {  // nothing survives: no pass needs to read this segment
+        r.T = 0xFFFFFFFFu;
+        r.route = 0;
+        if (tid == 0) {
+            sel[l] = r;
+            binlo[l] = 0x7FFFFFFFu;
+        }
+        return;
+    }
+    if (r.route) {
+        if (tid == 0) {
+            sel[l] = r;
+            binlo[l] = 1;
+        }
+        return;
+    }
+    for (uint32_t i = tid; i < kBins1; i += kHistThreads) h[i] = 0;
+    __syncthreads();
+    const uint32_t nvec = sd.n / VEC;
+    const uint32_t S = min(nvec, kSampleVectors);
+    const uint32_t stride = nvec / S;
+    const uint4 *vp = reinterpret_cast<const uint4 *>(grad + sd.offset * EB);
+    for (uint32_t i = tid; i < S; i += kHistThreads) {
+        const uint4 q = vp[uint64_t(i) * stride + (stride >> 1)];
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (uint32_t e = 0; e < VEC; ++e) {
+            const uint32_t key = vec_elem_bits<DTYPE>(w, e) & 0x7FFFFFFFu;
+            if (key) atomicAdd(&h[key >> 16], 1u);
+        }
+    }
+    __syncthreads();
+    const float ks = float(double(sd.k) * double(S * VEC) / double(sd.n));
+    const uint32_t need = uint32_t(ks + 5.0f * sqrtf(ks) + 16.0f) + 1u;
+    uint32_t bin, above, at, total;
+    const bool found = select_bins<32>(h, need, &bin, &above, &at, &total, smem);
+    if (tid == 0) {
+        if (!found) r.route = 1;  // the sample holds too few non-zeros to say anything
+        sel[l] = r;
+        binlo[l] = max(bin, 1u);  // bin 0 (|g| < 2^-133) is never a candidate
+    }
+}
+
+// ------------------------------------------------------------- scan_spill
+
+// Streams every candidate-route segment once.  A wave owns one chunk (64 lanes x 4 rows
+// of 16-byte vectors, contiguous) at a time; candidates (key bin >= binlo) are counted in
+// the workgroup's LDS histogram and written in position order to the chunk's slot array.
+// bf16 slot: (bf16 bits << 16) | position in chunk.  fp32 slot: value bits in cand[slot],
+// position in cand[n_slots_total + slot].
+//
+// The LDS histogram only covers the kSpillWindow bins from binlo upwards (16 octaves of
+// magnitude); anything above goes straight to the global histogram.  That keeps LDS
+// small enough for two 1024-thread workgroups per CU, i.e. a full complement of waves to
+// hide HBM latency.  Slot order inside a chunk comes from ballots, not from a scan, so a
+// wave never waits on another.
+constexpr uint32_t kSpillWindow = 2048;
+
+template <int DTYPE>
+__global__ void __launch_bounds__(kHistThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
+                  SelDev *sel, const uint32_t *__restrict__ binlo, uint32_t *__restrict__ hist,
+                  uint32_t *__restrict__ cand, uint32_t *__restrict__ chunk_cnt,
+                  uint64_t n_slots_total, uint32_t CAP)
+{
+    __shared__ uint32_t h[kSpillWindow];
+    __shared__ uint32_t s_route;
+    constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
+    constexpr uint32_t VEC = 16 / EB;
+    constexpr uint32_t ROWS = kCandRows;
+    constexpr uint32_t ROW_ELEMS = 64 * VEC;
+    constexpr uint32_t CHUNK = ROW_ELEMS * ROWS;
+    constexpr uint32_t CNT_BITS = DTYPE == kBF16 ? 4 : 3;  // a lane holds 0..VEC candidates
+    const uint32_t L = table[0];
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    const uint32_t wave = blockIdx.x * (kHistThreads / 64) + (tid >> 6);
+    const uint32_t n_waves = gridDim.x * (kHistThreads / 64);
+    for (uint32_t i = tid; i < kSpillWindow; i += kHistThreads) h[i] = 0;
+    __syncthreads();
+    for (uint32_t l = 0; l < L; ++l) {
+        const SegDev sd = segs[l];
+        if (sd.k == 0 || sd.n == 0) continue;
+        // another workgroup may re-route this segment while we look: decide once per
+        // workgroup so that the barriers below stay uniform
+        if (tid == 0) s_route = __hip_atomic_load(&sel[l].route, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const uint32_t route = s_route;
+        __syncthreads();
+        if (route) continue;
+        const uint32_t blo = binlo[l];  // >= 1
+        uint32_t *gh = hist + uint64_t(l) * kBins1;
+        const char *base = grad + sd.offset * EB;
+        const uint32_t n_chunks = (sd.n + CHUNK - 1) / CHUNK;
+        bool overflow = false;
+        for (uint32_t ch = wave; ch < n_chunks; ch += n_waves) {
+            const uint32_t rel0 = ch * CHUNK;
+            uint32_t w[ROWS][4];
+#pragma unroll
+            for (uint32_t r = 0; r < ROWS; ++r) {
+                const uint32_t rel = rel0 + r * ROW_ELEMS + lane * VEC;
+                w[r][0] = w[r][1] = w[r][2] = w[r][3] = 0;
+                if (rel + VEC <= sd.n) {
+                    const uint4 q = *reinterpret_cast<const uint4 *>(base + uint64_t(rel) * EB);
+                    w[r][0] = q.x; w[r][1] = q.y; w[r][2] = q.z; w[r][3] = q.w;
+                } else if (rel < sd.n) {
+#pragma unroll
+                    for (uint32_t e = 0; e < VEC; ++e) {
+                        if (rel + e >= sd.n) continue;
+                        const uint32_t b = load_elem_bits(base, uint64_t(rel) + e, DTYPE);
+                        if (DTYPE == kBF16) w[r][e >> 1] |= (b >> 16) << (16 * (e & 1));
+                        else w[r][e] = b;
+                    }
+                }
+            }
+            uint32_t *slots = cand + uint64_t(sd.sc_start * kCandChunksPerSuper + ch) * CAP;
+            uint32_t *slots_pos = slots + n_slots_total;  // fp32 only
+            uint32_t row_base = 0;
+#pragma unroll
+            for (uint32_t r = 0; r < ROWS; ++r) {
+                uint32_t m = 0;
+#pragma unroll
+                for (uint32_t e = 0; e < VEC; ++e) {
+                    const uint32_t bin = (vec_elem_bits<DTYPE>(w[r], e) & 0x7FFFFFFFu) >> 16;
+                    if (bin >= blo) {
+                        m |= 1u << e;
+                        const uint32_t wi = bin - blo;
+                        if (wi < kSpillWindow) atomicAdd(&h[wi], 1u);
+                        else atomicAdd(&gh[bin], 1u);
+                    }
+                }
+                // slot of this lane's first candidate: candidates of lower lanes in the row
+                const uint32_t cnt = __popc(m);
+                uint32_t pos = row_base, tot = 0;
+#pragma unroll
+                for (uint32_t bit = 0; bit < CNT_BITS; ++bit) {
+                    const uint64_t bal = __ballot((cnt >> bit) & 1u);
+                    pos += uint32_t(__popcll(bal & lt_mask)) << bit;
+                    tot += uint32_t(__popcll(bal)) << bit;
+                }
+                if (m) {
+#pragma unroll
+                    for (uint32_t e = 0; e < VEC; ++e) {  // static indices keep w[] in registers
+                        if (!((m >> e) & 1u)) continue;
+                        if (pos < CAP) {
+                            const uint32_t bits = vec_elem_bits<DTYPE>(w[r], e);
+                            const uint32_t rel = r * ROW_ELEMS + lane * VEC + e;
+                            if (DTYPE == kBF16) {
+                                slots[pos] = bits | rel;
+                            } else {
+                                slots[pos] = bits;
+                                slots_pos[pos] = rel;
+                            }
+                        }
+                        ++pos;
+                    }
+                }
+                row_base += tot;
+            }
+            if (lane == 0) chunk_cnt[sd.sc_start * kCandChunksPerSuper + ch] = row_base;
+            overflow |= row_base > CAP;
+        }
+        if (overflow && lane == 0)  // a chunk denser than its slots: take the dense route
+            atomicOr(&sel[l].route, 1u);
+        __syncthreads();
+        for (uint32_t i = tid; i < kSpillWindow; i += kHistThreads) {
+            const uint32_t c = h[i];
+            if (c) {
+                atomicAdd(&gh[blo + i], c);
+                h[i] = 0;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// true iff some segment is on the dense route (workgroup-uniform)
+__device__ inline bool any_dense_route(const SelDev *sel, uint32_t L)
+{
+    uint32_t any = 0;
+    for (uint32_t l = threadIdx.x; l < L; l += blockDim.x) any |= sel[l].route;
+    return __syncthreads_or(any) != 0;
+}
+
+// ------------------------------------------------------------------ hist1
+
+template <int DTYPE>
+__device__ inline void hist_word(uint32_t w, uint32_t *h)
+{
+    if (DTYPE == kBF16) {
+        uint32_t a = w & 0x7FFFu, b = (w >> 16) & 0x7FFFu;
+        if (a) atomicAdd(&h[a], 1u);
+        if (b) atomicAdd(&h[b], 1u);
+    } else {
+        uint32_t key = w & 0x7FFFFFFFu;
+        if (key) atomicAdd(&h[key >> 16], 1u);
+    }
+}
+
+template <int DTYPE>
+__device__ inline void hist_vec(uint4 v, uint32_t *h)
+{
+    hist_word<DTYPE>(v.x, h);
+    hist_word<DTYPE>(v.y, h);
+    hist_word<DTYPE>(v.z, h);
+    hist_word<DTYPE>(v.w, h);
+}
+
+__device__ inline void hist_elem(uint32_t f32bits, uint32_t *h)
+{
+    uint32_t key = f32bits & 0x7FFFFFFFu;
+    if (key) atomicAdd(&h[key >> 16], 1u);
+}
+
+// Dense route: one workgroup per CU, 32768 LDS counters, all entries of every dense-route
+// segment.  Leaves at once when no segment is on the dense route.
+template <int DTYPE>
+__global__ void __launch_bounds__(kHistThreads)
+hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
+             const SelDev *__restrict__ sel, uint32_t *__restrict__ hist)
+{
+    extern __shared__ uint32_t h[];
+    constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
+    constexpr uint32_t VEC = 16 / EB;
+    const uint32_t L = table[0];
+    if (!any_dense_route(sel, L)) return;
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t i = tid; i < kBins1; i += kHistThreads) h[i] = 0;
+    __syncthreads();
+    for (uint32_t l = 0; l < L; ++l) {
+        const SegDev sd = segs[l];
+        if (sd.k == 0 || sd.n == 0 || !sel[l].route) continue;
+        const char *base = grad + sd.offset * EB;
+        if (sd.flags & kSegAligned) {
+            const uint4 *vp = reinterpret_cast<const uint4 *>(base);
+            const uint64_t nvec = sd.n / VEC;
+            const uint64_t stride = uint64_t(gridDim.x) * kHistThreads;
+            uint64_t v = uint64_t(blockIdx.x) * kHistThreads + tid;
+            for (; v + 3 * stride < nvec; v += 4 * stride) {
+                uint4 a = vp[v], b = vp[v + stride], c = vp[v + 2 * stride],
+                      d = vp[v + 3 * stride];
+                hist_vec<DTYPE>(a, h);
+                hist_vec<DTYPE>(b, h);
+                hist_vec<DTYPE>(c, h);
+                hist_vec<DTYPE>(d, h);
+            }
+            for (; v < nvec; v += stride) hist_vec<DTYPE>(vp[v], h);
+            if (blockIdx.x == 0) {
+                uint64_t i = nvec * VEC + tid;
+                if (i < sd.n) hist_elem(load_elem_bits(base, i, DTYPE), h);
+            }
+        } else {
+            for (uint64_t i = uint64_t(blockIdx.x) * kHistThreads + tid; i < sd.n;
+                 i += uint64_t(gridDim.x) * kHistThreads)
+                hist_elem(load_elem_bits(base, i, DTYPE), h);
+        }
+        __syncthreads();
+        uint32_t *gh = hist + uint64_t(l) * kBins1;
+        for (uint32_t i = tid; i < kBins1; i += kHistThreads) {
+            uint32_t c = h[i];
+            if (c) {
+                atomicAdd(&gh[i], c);
+                h[i] = 0;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Threshold bin of one segment from its 32768-bin histogram.  `dense` = 0: segments on the
+// candidate route, histogram of candidates only (a miss re-routes the segment); 1:
+// segments on the dense route, histogram of everything.
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads)
 select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ hist,
-               SelDev *__restrict__ sel, uint32_t *__restrict__ cnt)
+               SelDev *sel, uint32_t *cnt, uint32_t dense)
 {
     __shared__ uint32_t smem[32];
     const uint32_t l = blockIdx.x;
     const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
-    SelDev r{};
+    SelDev r = sel[l];
+    if (r.route != dense) return;
     if (sd.k == 0 || sd.n == 0) {
-        r.T = 0xFFFFFFFFu;
-        if (threadIdx.x == 0) {
-            sel[l] = r;
-            cnt[TAGC_CNT_SEG0 + l] = 0;
-        }
+        if (threadIdx.x == 0) cnt[TAGC_CNT_SEG0 + l] = 0;
         return;
     }
     const uint32_t *h = hist + uint64_t(l) * kBins1;
-    // inputs with an all-ones exponent fall into bins >= 0x7F80
-    {
-        uint32_t nf = 0;
-        if (threadIdx.x >= 0x7F80u / 32)
-            for (int i = 0; i < 32; ++i) nf += h[threadIdx.x * 32 + i];
-        nf = block_sum<uint32_t, kHistThreads / 64>(nf, smem);
-        if (threadIdx.x == 0 && nf) atomicAdd(&cnt[TAGC_CNT_NONFINITE], nf);
-    }
+    uint32_t nf = 0;  // inputs with an all-ones exponent fall into bins >= 0x7F80
+    if (threadIdx.x >= 0x7F80u / 32)
+        for (int i = 0; i < 32; ++i) nf += h[threadIdx.x * 32 + i];
+    nf = block_sum<uint32_t, kHistThreads / 64>(nf, smem);
     uint32_t bin, above, at, total;
-    bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem);
+    const bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem);
     if (threadIdx.x != 0) return;
+    if (!found && !dense) {  // the candidates hold fewer than k entries: dense route
+        sel[l].route = 1;
+        return;
+    }
+    if (nf) atomicAdd(&cnt[TAGC_CNT_NONFINITE], nf);
+    if (dense) atomicAdd(&cnt[TAGC_CNT_DENSE], 1u);
     if (!found) {  // fewer non-zeros than k: keep every non-zero
         r.T = 0;
         r.quota = 0;
         r.G = total;
         r.cnt = total;
     } else if (DTYPE == kBF16) {
-        r.T = bin << 16;  // keys are compared as float32 bit patterns
+        r.T = bin << 16;
         r.G = above;
         r.quota = sd.k - above;
         r.cnt = sd.k;
@@ -220,21 +449,22 @@ select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     }
 }
 
-// fp32: histogram of the low 16 key bits of the entries inside the threshold bin.
+// fp32, dense route: histogram of the low 16 key bits of the entries in the threshold bin.
 __global__ void __launch_bounds__(256)
 hist2_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
              const SelDev *__restrict__ sel, uint32_t *__restrict__ hist2)
 {
     const uint32_t L = table[0];
+    if (!any_dense_route(sel, L)) return;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
     const uint32_t tid = threadIdx.x;
     for (uint32_t l = 0; l < L; ++l) {
-        if (!sel[l].need2) continue;
+        if (!sel[l].need2 || !sel[l].route) continue;
         const SegDev sd = segs[l];
         const uint32_t bin1 = sel[l].bin1;
         uint32_t *gh = hist2 + uint64_t(l) * kBins2;
         const char *base = grad + sd.offset * 4;
-        if (sd.aligned) {
+        if (sd.flags & kSegAligned) {
             const uint4 *vp = reinterpret_cast<const uint4 *>(base);
             const uint64_t nvec = sd.n / 4;
             for (uint64_t v = blockIdx.x * 256ull + tid; v < nvec; v += gridDim.x * 256ull) {
@@ -262,6 +492,34 @@ hist2_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
     }
 }
 
+// fp32, candidate route: the same histogram from the spilled candidates.
+__global__ void __launch_bounds__(256)
+hist2c_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
+              const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
+              uint32_t CAP, uint32_t *__restrict__ hist2)
+{
+    constexpr uint32_t CHUNK = 64 * 4 * kCandRows;
+    const uint32_t L = table[0];
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
+    for (uint32_t l = 0; l < L; ++l) {
+        if (!sel[l].need2 || sel[l].route) continue;
+        const SegDev sd = segs[l];
+        const uint32_t bin1 = sel[l].bin1;
+        uint32_t *gh = hist2 + uint64_t(l) * kBins2;
+        const uint32_t n_chunks = (sd.n + CHUNK - 1) / CHUNK;
+        for (uint32_t ch = wave; ch < n_chunks; ch += n_waves) {
+            const uint32_t g = sd.sc_start * kCandChunksPerSuper + ch;
+            const uint32_t c = min(chunk_cnt[g], CAP);
+            for (uint32_t i = lane; i < c; i += 64) {
+                const uint32_t key = cand[uint64_t(g) * CAP + i] & 0x7FFFFFFFu;
+                if ((key >> 16) == bin1) atomicAdd(&gh[key & 0xFFFFu], 1u);
+            }
+        }
+    }
+}
+
 __global__ void __launch_bounds__(kHistThreads)
 select2_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ hist2,
                SelDev *__restrict__ sel, uint32_t *__restrict__ cnt)
@@ -275,7 +533,7 @@ select2_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     bool found =
         select_bins<64>(hist2 + uint64_t(l) * kBins2, sd.k - r.G1, &bin, &above, &at, &total, smem);
     if (threadIdx.x != 0) return;
-    if (!found) {  // cannot happen when hist1 and hist2 saw the same data
+    if (!found) {  // cannot happen when both histograms saw the same data
         bin = 0;
         above = total;
         atomicOr(&cnt[TAGC_CNT_FLAGS], TAGC_FLAG_OVERFLOW);
@@ -290,15 +548,16 @@ select2_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     atomicAdd(&cnt[TAGC_CNT_TOTAL], r.cnt);
 }
 
-// ---------------------------------------------------------------- compact
+// --------------------------------------------------------------- look-back
 
 constexpr uint64_t kStAgg = 1ull << 62, kStPre = 2ull << 62, kStMask = 3ull << 62;
 
-// Decoupled look-back over the tiles of one segment, run by the first wave of the
-// workgroup.  state word = status(2) | count(key > T)(31) | count(key == T)(31).
-// The grid is persistent and fully resident, and workgroup b takes tiles b, b+G, b+2G, ...;
-// so every predecessor tile this waits for belongs to a workgroup that is running and
-// that publishes its counts without waiting for any later tile.
+// Decoupled look-back over the work items (tiles / super-chunks) of one segment, run by
+// the first wave of the workgroup.  state word = status(2) | count(key > T)(31) |
+// count(key == T)(31).  The grid is persistent and fully resident, and workgroup b takes
+// items b, b+G, b+2G, ...; so every predecessor this waits for belongs to a workgroup that
+// is running and that publishes its counts without waiting for any later item.  The wait
+// is bounded all the same: after kSpinLimit polls it gives up and raises a flag.
 __device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, uint64_t agg,
                                     uint32_t *flags)
 {
@@ -338,12 +597,150 @@ __device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, ui
     return excl;
 }
 
+// last l with start(l) <= t, start() read through `field` (tile_start or sc_start)
+template <typename F>
+__device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
+{
+    uint32_t lo = 0, hi = L;
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (start(mid) <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ------------------------------------------------------------------- emit
+
+// Candidate route, final pass.  A workgroup handles one super-chunk (32 chunks) at a
+// time: 8 threads per chunk, each owning CAP/8 consecutive slots, which it classifies
+// against the exact threshold twice -- once to count, once (after the workgroup scan and
+// the look-back over the segment's super-chunks) to write the survivors in ascending
+// c-index.  The super-chunk's Index words are assembled in LDS and written whole, zeros
+// included.
+template <int DTYPE>
+__global__ void __launch_bounds__(kEmitThreads)
+emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
+            const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
+            uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_state,
+            uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
+            uint32_t *__restrict__ bitmap, uint32_t *cnt)
+{
+    constexpr uint32_t VEC = DTYPE == kBF16 ? 8 : 4;
+    constexpr uint32_t CHUNK = 64 * VEC * kCandRows;
+    constexpr uint32_t SC_ELEMS = CHUNK * kCandChunksPerSuper;
+    constexpr uint32_t SC_WORDS = SC_ELEMS / 32;
+    __shared__ uint32_t bits[SC_WORDS];
+    __shared__ uint64_t s_scan[kEmitThreads / 64];
+    __shared__ uint64_t s_excl;
+    __shared__ uint32_t s_base;
+    const uint32_t L = table[0], total_sc = table[4];
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    const uint32_t tid = threadIdx.x;
+    const uint32_t ch_in_sc = tid >> 3, part = tid & 7;
+    const uint32_t R = CAP / 8;  // slots per thread, a multiple of 4
+
+    for (uint32_t sc = blockIdx.x; sc < total_sc; sc += gridDim.x) {
+        const uint32_t l = segment_of(L, sc, [&](uint32_t i) { return segs[i].sc_start; });
+        const SegDev sd = segs[l];
+        const SelDev se = sel[l];
+        if (se.route) continue;  // the dense route writes this segment (uniform)
+        const uint32_t sc_rel0 = (sc - sd.sc_start) * SC_ELEMS;
+        const uint32_t g = sc * kCandChunksPerSuper + ch_in_sc;  // global chunk number
+        for (uint32_t i = tid; i < SC_WORDS; i += kEmitThreads) bits[i] = 0;
+
+        const bool chunk_in_seg = sc_rel0 + ch_in_sc * CHUNK < sd.n;
+        const uint32_t c = (se.cnt != 0 && chunk_in_seg) ? min(chunk_cnt[g], CAP) : 0u;
+        const uint32_t s0 = part * R, s1 = min(s0 + R, c);
+        const uint32_t *sp = cand + uint64_t(g) * CAP;
+
+        // ---- pass 1: count this thread's slots above / at the threshold
+        uint32_t n_gt = 0, n_eq = 0;
+        for (uint32_t s4 = s0; s4 < s1; s4 += 4) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(sp + s4);
+            const uint32_t v[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (uint32_t i = 0; i < 4; ++i) {
+                if (s4 + i < s1) {
+                    const uint32_t key = (DTYPE == kBF16 ? (v[i] & 0xFFFF0000u) : v[i]) & 0x7FFFFFFFu;
+                    n_gt += key > se.T;
+                    n_eq += (key == se.T) && se.quota;
+                }
+            }
+        }
+        // ---- order: threads are already in position order (chunk, then slot)
+        uint64_t tot;
+        const uint64_t mine = (uint64_t(n_gt) << 31) | uint64_t(n_eq);
+        const uint64_t ex_blk = block_excl_scan<uint64_t, kEmitThreads / 64>(mine, &tot, s_scan);
+        if (tid < 64) {
+            const uint64_t ex = lookback(sc_state, sc, sd.sc_start, tot, &cnt[TAGC_CNT_FLAGS]);
+            uint32_t sb = 0;
+            for (uint32_t i = tid; i < l; i += 64) sb += sel[i].cnt;
+            sb = wave_sum<uint32_t>(sb);
+            if (tid == 0) {
+                s_excl = ex;
+                s_base = sb;
+            }
+        }
+        __syncthreads();  // also: `bits` is cleared
+        const uint64_t ex = s_excl + ex_blk;
+        uint32_t gb = uint32_t(ex >> 31), eb = uint32_t(ex & 0x7FFFFFFFu);
+        const uint32_t seg_base = s_base;
+
+        // ---- pass 2: write the survivors
+        if (n_gt | n_eq) {
+            for (uint32_t s4 = s0; s4 < s1; s4 += 4) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(sp + s4);
+                const uint32_t v[4] = {q.x, q.y, q.z, q.w};
+                uint32_t rp[4] = {0, 0, 0, 0};
+                if (DTYPE == kF32) {
+                    const uint4 p = *reinterpret_cast<const uint4 *>(sp + n_slots_total + s4);
+                    rp[0] = p.x; rp[1] = p.y; rp[2] = p.z; rp[3] = p.w;
+                }
+#pragma unroll
+                for (uint32_t i = 0; i < 4; ++i) {
+                    if (s4 + i >= s1) continue;
+                    const uint32_t vbits = DTYPE == kBF16 ? (v[i] & 0xFFFF0000u) : v[i];
+                    const uint32_t rel = DTYPE == kBF16 ? (v[i] & 0xFFFFu) : rp[i];
+                    const uint32_t key = vbits & 0x7FFFFFFFu;
+                    uint32_t pos;
+                    bool keep;
+                    if (key > se.T) {
+                        pos = gb + min(eb, se.quota);
+                        keep = true;
+                        ++gb;
+                    } else if (key == se.T && se.quota) {
+                        pos = gb + eb;
+                        keep = eb < se.quota;
+                        ++eb;
+                    } else {
+                        continue;
+                    }
+                    if (keep) {
+                        const uint32_t rel_sc = ch_in_sc * CHUNK + rel;
+                        idx_out[seg_base + pos] = sd.c_off + sc_rel0 + rel_sc;
+                        val_out[seg_base + pos] = __uint_as_float(vbits);
+                        atomicOr(&bits[rel_sc >> 5], 1u << (rel_sc & 31));
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t w0 = (sd.c_off + sc_rel0) >> 5;
+        for (uint32_t i = tid; i < SC_WORDS; i += kEmitThreads)
+            if (sc_rel0 + i * 32 < sd.n) bitmap[w0 + i] = bits[i];
+        __syncthreads();  // bits / s_excl are rewritten by the next iteration
+    }
+}
+
+// ---------------------------------------------------------------- compact
+
+// Dense route, final pass over the gradient itself.
 template <int DTYPE>
 __global__ void __launch_bounds__(kCompactThreads)
 compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
-               const SelDev *__restrict__ sel, uint64_t *tile_state, uint32_t *ticket,
-               uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
-               uint32_t *__restrict__ bitmap, uint32_t *cnt)
+               const SelDev *__restrict__ sel, uint64_t *tile_state,
+               uint32_t *__restrict__ idx_out,
+               float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt)
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
@@ -356,20 +753,15 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
     __shared__ uint32_t s_base;
 
     const uint32_t L = table[0], total_tiles = table[1];
+    if (!any_dense_route(sel, L)) return;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
     const uint32_t tid = threadIdx.x;
 
     for (uint32_t t = blockIdx.x; t < total_tiles; t += gridDim.x) {
-
-        // segment of this tile: the last l with tile_start[l] <= t
-        uint32_t lo = 0, hi = L;
-        while (hi - lo > 1) {
-            uint32_t mid = (lo + hi) >> 1;
-            if (segs[mid].tile_start <= t) lo = mid; else hi = mid;
-        }
-        const uint32_t l = lo;
+        const uint32_t l = segment_of(L, t, [&](uint32_t i) { return segs[i].tile_start; });
         const SegDev sd = segs[l];
         const SelDev se = sel[l];
+        if (!se.route) continue;  // the candidate route writes this segment (uniform)
         const uint32_t base_rel = (t - sd.tile_start) * TILE;
         const char *base = grad + sd.offset * EB;
 
@@ -386,7 +778,7 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
             for (uint32_t r = 0; r < ROWS; ++r) {
                 const uint32_t rel = base_rel + r * ROW_ELEMS + tid * VEC;
                 if (rel >= sd.n) continue;
-                if (sd.aligned && rel + VEC <= sd.n) {
+                if ((sd.flags & kSegAligned) && rel + VEC <= sd.n) {
                     uint4 q = *reinterpret_cast<const uint4 *>(base + uint64_t(rel) * EB);
                     w[r][0] = q.x; w[r][1] = q.y; w[r][2] = q.z; w[r][3] = q.w;
                 } else {
@@ -394,12 +786,9 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
 #pragma unroll
                     for (uint32_t e = 0; e < VEC; ++e) {
                         if (e >= cntv) continue;
-                        if (DTYPE == kBF16) {
-                            uint32_t b = reinterpret_cast<const uint16_t *>(base)[uint64_t(rel) + e];
-                            w[r][e >> 1] |= b << (16 * (e & 1));
-                        } else {
-                            w[r][e] = reinterpret_cast<const uint32_t *>(base)[uint64_t(rel) + e];
-                        }
+                        const uint32_t b = load_elem_bits(base, uint64_t(rel) + e, DTYPE);
+                        if (DTYPE == kBF16) w[r][e >> 1] |= (b >> 16) << (16 * (e & 1));
+                        else w[r][e] = b;
                     }
                 }
             }
@@ -408,9 +797,7 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
             for (uint32_t r = 0; r < ROWS; ++r) {
 #pragma unroll
                 for (uint32_t e = 0; e < VEC; ++e) {
-                    uint32_t bits = DTYPE == kBF16 ? ((w[r][e >> 1] >> (16 * (e & 1))) << 16)
-                                                   : w[r][e];
-                    uint32_t key = bits & 0x7FFFFFFFu;
+                    const uint32_t key = vec_elem_bits<DTYPE>(w[r], e) & 0x7FFFFFFFu;
                     if (key > se.T) gtm[r] |= 1u << e;
                     else if (key == se.T && se.quota) eqm[r] |= 1u << e;
                 }
@@ -478,8 +865,10 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
                 }
                 if (keep) {
                     km |= 1u << e;
-                    uint32_t bits = DTYPE == kBF16 ? ((w[r][e >> 1] >> (16 * (e & 1))) << 16)
-                                                   : w[r][e];
+                    uint32_t bits = 0;
+#pragma unroll
+                    for (uint32_t j = 0; j < VEC; ++j)
+                        if (j == e) bits = vec_elem_bits<DTYPE>(w[r], j);
                     idx_out[seg_base + pos] = sd.c_off + rel + e;
                     val_out[seg_base + pos] = __uint_as_float(bits);
                 }
@@ -501,24 +890,52 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
     }
 }
 
-}  // namespace
+template <typename K>
+int resident_blocks_per_cu(K kernel, int threads, size_t lds, int *cache)
+{
+    if (*cache == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, lds) != hipSuccess ||
+            n <= 0)
+            return 0;
+        *cache = n;
+    }
+    return *cache;
+}
 
-// ------------------------------------------------------------------- host
+template <typename K>
+int allow_lds(K kernel, size_t lds, bool *done)
+{
+    if (*done) return TAGC_OK;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+        return TAGC_EHIP;
+    *done = true;
+    return TAGC_OK;
+}
 
-int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buffers *rk,
-                    const tagc_shared_buffers *sh, hipStream_t s)
+template <int DTYPE>
+int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_buffers *rk,
+                      const tagc_shared_buffers *sh, hipStream_t s)
 {
     const uint32_t L = uint32_t(p->table.size());
     const uint32_t *table = static_cast<const uint32_t *>(sh->table);
     char *ws = static_cast<char *>(rk->workspace);
     uint32_t *hist1 = reinterpret_cast<uint32_t *>(ws + p->ws.hist1);
+    uint32_t *hist1d = reinterpret_cast<uint32_t *>(ws + p->ws.hist1d);
     uint32_t *hist2 = reinterpret_cast<uint32_t *>(ws + p->ws.hist2);
     uint64_t *tile_state = reinterpret_cast<uint64_t *>(ws + p->ws.tile_state);
-    uint32_t *counters = reinterpret_cast<uint32_t *>(ws + p->ws.counters);
+    uint64_t *sc_state = reinterpret_cast<uint64_t *>(ws + p->ws.sc_state);
     SelDev *sel = reinterpret_cast<SelDev *>(ws + p->ws.sel);
+    uint32_t *binlo = reinterpret_cast<uint32_t *>(ws + p->ws.binlo);
+    uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + p->ws.chunk_cnt);
+    uint32_t *cand = reinterpret_cast<uint32_t *>(ws + p->ws.cand);
+    const uint64_t n_slots = uint64_t(p->total_sc) * kCandChunksPerSuper * p->cand_cap;
     const char *g = static_cast<const char *>(grad);
     const int cus = device_cu_count();
-    const bool bf16 = p->cfg.dtype == TAGC_BF16;
+    const size_t lds_hist = kBins1 * sizeof(uint32_t);
+    static bool a_sample = false, a_hist = false;
+    static int occ_emit = 0, occ_compact = 0;
 
     {
         ProfileScope ps("fill_zero", s);
@@ -528,38 +945,35 @@ int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buff
                                                             rk->cnt, TAGC_CNT_SEG0 + L);
     }
     if (L == 0) return hip_ok(hipGetLastError());
+    if (allow_lds(sample_kernel<DTYPE>, lds_hist, &a_sample) ||
+        allow_lds(hist1_kernel<DTYPE>, lds_hist, &a_hist))
+        return TAGC_EHIP;
     {
-        ProfileScope ps("hist1", s);
-        static bool attr_done[2] = {false, false};
-        const size_t lds = kBins1 * sizeof(uint32_t);
-        if (bf16) {
-            if (!attr_done[1]) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void *>(hist1_kernel<kBF16>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        int(lds)) != hipSuccess)
-                    return TAGC_EHIP;
-                attr_done[1] = true;
-            }
-            hist1_kernel<kBF16><<<cus, kHistThreads, lds, s>>>(g, table, hist1);
-        } else {
-            if (!attr_done[0]) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void *>(hist1_kernel<kF32>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        int(lds)) != hipSuccess)
-                    return TAGC_EHIP;
-                attr_done[0] = true;
-            }
-            hist1_kernel<kF32><<<cus, kHistThreads, lds, s>>>(g, table, hist1);
-        }
+        ProfileScope ps("sample", s);
+        sample_kernel<DTYPE><<<L, kHistThreads, lds_hist, s>>>(g, table, sel, binlo);
+    }
+    if (p->total_sc) {
+        ProfileScope ps("scan_spill", s);
+        scan_spill_kernel<DTYPE><<<cus * 2, kHistThreads, 0, s>>>(
+            g, table, sel, binlo, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
     }
     {
         ProfileScope ps("select1", s);
-        if (bf16)
-            select1_kernel<kBF16><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt);
-        else
-            select1_kernel<kF32><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt);
+        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt, 0);
     }
-    if (!bf16) {
+    {
+        ProfileScope ps("hist1", s);
+        hist1_kernel<DTYPE><<<cus, kHistThreads, lds_hist, s>>>(g, table, sel, hist1d);
+    }
+    {
+        ProfileScope ps("select1d", s);
+        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1d, sel, rk->cnt, 1);
+    }
+    if (DTYPE == kF32) {
+        if (p->total_sc) {
+            ProfileScope ps("hist2c", s);
+            hist2c_kernel<<<cus * 4, 256, 0, s>>>(table, sel, cand, chunk_cnt, p->cand_cap, hist2);
+        }
         {
             ProfileScope ps("hist2", s);
             hist2_kernel<<<cus * 8, 256, 0, s>>>(g, table, sel, hist2);
@@ -569,29 +983,34 @@ int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buff
             select2_kernel<<<L, kHistThreads, 0, s>>>(table, hist2, sel, rk->cnt);
         }
     }
+    if (p->total_sc) {
+        ProfileScope ps("emit", s);
+        const int occ = resident_blocks_per_cu(emit_kernel<DTYPE>, kEmitThreads, 0, &occ_emit);
+        if (occ <= 0) return TAGC_EHIP;
+        const uint32_t grid = std::min<uint32_t>(p->total_sc, uint32_t(cus) * uint32_t(occ));
+        emit_kernel<DTYPE><<<grid, kEmitThreads, 0, s>>>(table, sel, cand, chunk_cnt, n_slots,
+                                                         p->cand_cap, sc_state, rk->idx, rk->val,
+                                                         rk->bitmap, rk->cnt);
+    }
     if (p->total_tiles) {
         ProfileScope ps("compact", s);
-        // persistent grid that is resident as a whole (the look-back relies on it)
-        static int per_cu[2] = {0, 0};
-        int &occ = per_cu[bf16 ? 1 : 0];
-        if (occ == 0) {
-            int n = 0;
-            hipError_t e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                                      &n, compact_kernel<kBF16>, kCompactThreads, 0)
-                                : hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                                      &n, compact_kernel<kF32>, kCompactThreads, 0);
-            if (e != hipSuccess || n <= 0) return TAGC_EHIP;
-            occ = n;
-        }
-        uint32_t grid = std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
-        if (bf16)
-            compact_kernel<kBF16><<<grid, kCompactThreads, 0, s>>>(
-                g, table, sel, tile_state, counters, rk->idx, rk->val, rk->bitmap, rk->cnt);
-        else
-            compact_kernel<kF32><<<grid, kCompactThreads, 0, s>>>(
-                g, table, sel, tile_state, counters, rk->idx, rk->val, rk->bitmap, rk->cnt);
+        const int occ =
+            resident_blocks_per_cu(compact_kernel<DTYPE>, kCompactThreads, 0, &occ_compact);
+        if (occ <= 0) return TAGC_EHIP;
+        const uint32_t grid = std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
+        compact_kernel<DTYPE><<<grid, kCompactThreads, 0, s>>>(
+            g, table, sel, tile_state, rk->idx, rk->val, rk->bitmap, rk->cnt);
     }
     return hip_ok(hipGetLastError());
+}
+
+}  // namespace
+
+int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buffers *rk,
+                    const tagc_shared_buffers *sh, hipStream_t s)
+{
+    return p->cfg.dtype == TAGC_BF16 ? launch_sparsify_t<kBF16>(p, grad, rk, sh, s)
+                                     : launch_sparsify_t<kF32>(p, grad, rk, sh, s);
 }
 
 }  // namespace tagc

@@ -17,6 +17,12 @@ constexpr uint32_t kBins2 = 65536;   // low 16 key bits (fp32 only)
 constexpr uint32_t kHistThreads = 1024;
 constexpr uint32_t kCompactThreads = 256;
 constexpr uint32_t kCompactRows = 4;  // 16-byte vectors per thread per tile
+constexpr uint32_t kCandRows = 4;        // 16-byte vectors per lane per candidate chunk
+constexpr uint32_t kCandChunksPerSuper = 32;  // chunks one emit workgroup handles
+constexpr uint32_t kEmitThreads = 256;
+constexpr uint32_t kSampleVectors = 4096;     // 16-byte vectors sampled per segment
+constexpr uint32_t kFastMinElems = 1u << 17;  // shorter segments take the dense path
+constexpr uint32_t kFastMinKeep = 64;
 constexpr uint32_t kChunkWords = 1024;  // Index words per popcount chunk
 constexpr uint32_t kDefaultPartCells = 24576;  // 3 * 8192 cells: 96 KiB of float
 constexpr uint32_t kMaxPartCells = 24576;
@@ -33,10 +39,12 @@ struct SegDev {
     uint32_t n;           // elements
     uint32_t c_off;       // c-index of element 0 (multiple of 32)
     uint32_t k;           // keep count
-    uint32_t tile_start;  // first compaction tile of this segment
-    uint32_t aligned;     // 1: offset is a multiple of the 16-byte vector
-    uint32_t pad;
+    uint32_t tile_start;  // first compaction tile of this segment (dense path)
+    uint32_t flags;       // kSegAligned | kSegFast
+    uint32_t sc_start;    // first super-chunk of this segment (candidate path)
 };
+constexpr uint32_t kSegAligned = 1;  // offset is a multiple of the 16-byte vector
+constexpr uint32_t kSegFast = 2;     // eligible for the single-read candidate path
 static_assert(sizeof(SegDev) == 32, "SegDev layout");
 
 // Result of the threshold search for one segment (device memory).
@@ -48,7 +56,7 @@ struct SelDev {
     uint32_t bin1;    // fp32: level-1 bin that holds T
     uint32_t G1;      // fp32: count of keys in higher level-1 bins
     uint32_t need2;   // fp32: 1 if the low 16 bits still have to be searched
-    uint32_t pad;
+    uint32_t route;   // 0: candidate path, 1: dense path (by plan, or after a miss)
 };
 static_assert(sizeof(SelDev) == 32, "SelDev layout");
 
@@ -59,8 +67,10 @@ struct RankPtrs {
 // ------------------------------------------------------------------- plan
 
 struct Workspace {  // byte offsets inside a rank workspace
-    uint64_t hist1, hist2, sel, tile_state, counters, total;
+    uint64_t hist1, hist1d, hist2, tile_state, sc_state, counters;  // cleared per call
+    uint64_t sel, binlo, chunk_cnt, cand, total;
 };
+
 
 }  // namespace tagc
 
@@ -71,6 +81,8 @@ struct tagc_plan_s {
     uint32_t elem_bytes, vec_elems;
     uint32_t tile_elems;                      // elements per compaction tile
     uint32_t total_tiles;
+    uint32_t total_sc;                        // super-chunks of the candidate path
+    uint32_t chunk_elems, cand_cap;           // elements / candidate slots per chunk
     uint64_t n_real, n_c, K, U_cap, A_cap, m_cap;
     uint32_t P_cap, T_cap;
     uint32_t seed_word[3];

@@ -43,6 +43,7 @@ def test_config1_full_size():
     assert hdr["U"] > 40_000 and st["n_unresolved"] == 0
     for r in range(4):
         assert tb.rank_counts(r)["total"] == 10_485
+        assert tb.rank_counts(r)["dense_segments"] == 0   # single-read route
 
 
 @pytest.mark.parametrize("dtype", [G.F32, G.BF16])
@@ -201,3 +202,67 @@ def test_hash_on_device_matches_host_helper_and_oracle():
             assert (slot, sign) == O.hash_slot(pos, 77, j, hdr["m_sub"])
             want[j * hdr["m_sub"] + slot] = sign
         assert np.array_equal(sk, want)
+
+
+# ---------------------------------------------------------------------------
+# Routes of the sparsifier: long aligned segments stream the gradient once and keep only
+# "candidates" above a sampled pre-threshold; everything else, and every case where that
+# shortcut does not hold k entries, falls back to the two-read dense route.  Both must
+# give the oracle's answer.
+
+
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+def test_candidate_and_dense_routes_in_one_bucket(dtype):
+    _announce("routes mixed dtype=%d" % dtype)
+    segs = [G.Seg(0, (1 << 18) + 13, 10_000, 1, "long_ragged"),
+            G.Seg(262_168, 5000, 20_000, 1, "short"),
+            G.Seg(267_176, (1 << 17), 50_000, 1, "long_dense_keep"),
+            G.Seg(398_251, (1 << 17) + 64, 10_000, 1, "long_unaligned"),
+            G.Seg(529_392, 300_000, 100, 1, "long_tiny_k")]
+    n = 829_392
+    b = G.Bucket("routes", dtype, 3, segs, n, 1500,
+                 {"long_ragged": 1e-3, "short": 1e-2, "long_dense_keep": 1e-4,
+                  "long_unaligned": 3e-3, "long_tiny_k": 1e-3})
+    ores, tb = run_both(b, _grads(b), seed=6, P=4096, T=6144)
+    compare_all(b, ores, tb)
+    # short, unaligned and tiny-k segments read the gradient twice, the other two once
+    assert [tb.rank_counts(r)["dense_segments"] for r in range(3)] == [3, 3, 3]
+
+
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+@pytest.mark.parametrize("kind", ["all_equal", "two_valued", "ints", "sample_high",
+                                  "sample_low", "dense_cluster"])
+def test_candidate_route_fallbacks(dtype, kind):
+    """Inputs that defeat the sampled pre-threshold: huge tie classes (every entry is a
+    candidate, the slots overflow), samples that are all larger / all smaller than the
+    rest, and a cluster denser than the slots of its chunk."""
+    _announce("fallback %s dtype=%d" % (kind, dtype))
+    rng = np.random.default_rng(21)
+    n = 400_000 + 24
+    vec = 4 if dtype == G.F32 else 8
+    if kind == "all_equal":
+        v = np.full(n, -0.25, np.float32)
+    elif kind == "two_valued":
+        v = rng.choice([-1.0, 2.0], n).astype(np.float32)
+    elif kind == "ints":
+        v = rng.integers(-50, 51, n).astype(np.float32)
+    else:
+        v = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        nvec = n // vec
+        stride = nvec // 4096
+        sampled = (np.arange(4096) * stride + stride // 2)[:, None] * vec + np.arange(vec)
+        if kind == "sample_high":       # the sample sees only the largest values
+            v[sampled.ravel()] = rng.choice([-1.0, 1.0], sampled.size) * 0.5
+        elif kind == "sample_low":      # the sample sees only tiny values
+            v[sampled.ravel()] *= 1e-4
+        else:                           # 3000 large values inside one 2048-entry chunk
+            v[100_000:103_000] = rng.choice([-1.0, 1.0], 3000) * (0.1 + rng.random(3000))
+    td = torch.float32 if dtype == G.F32 else torch.bfloat16
+    # the sample covers 4 % of the entries: it only misleads when more than that is kept
+    keep = 100_000 if kind == "sample_high" else 10_000
+    b = G.Bucket("fb", dtype, 2, [G.Seg(0, n, keep, 1, "w")], n, 3000)
+    grads = [torch.from_numpy(v).to(td), torch.from_numpy(np.roll(v, 7777)).to(td)]
+    ores, tb = run_both(b, grads, seed=2)
+    compare_all(b, ores, tb, exact_values=kind in ("all_equal", "two_valued", "ints"))
+    if kind != "ints":   # (a 2 % tie class at the threshold still fits the slots)
+        assert tb.rank_counts(0)["dense_segments"] == 1     # the shortcut was abandoned
