@@ -27,14 +27,16 @@ def hipcc() -> str:
 
 
 def build(verbose: bool = False) -> str:
-    """Compiles every source for gfx950 and links libtagc.so next to this file."""
+    """Compiles every source for gfx950 and links libtagc.so next to this file.
+    TAGC_BUILD_DEFS (space separated, e.g. "-DTAGC_PHASE_TIMING") adds defines."""
+    extra = os.environ.get("TAGC_BUILD_DEFS", "").split()
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     objs = []
     procs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src + ".o")
-        cmd = [hipcc(), *FLAGS, "-x", "hip", "-I", os.path.join(ROOT, "include"),
+        cmd = [hipcc(), *FLAGS, *extra, "-x", "hip", "-I", os.path.join(ROOT, "include"),
                "-I", CSRC, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd))

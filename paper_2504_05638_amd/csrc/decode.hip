@@ -16,6 +16,23 @@ namespace tagc {
 
 namespace {
 
+// Optional phase timing (build with -DTAGC_PHASE_TIMING): thread 0 of every workgroup
+// adds the shader-clock cycles (>> 10) each phase took to status[3 + phase].
+#ifdef TAGC_PHASE_TIMING
+#define PHASE_MARK(k)                                                        \
+    do {                                                                     \
+        if (threadIdx.x == 0) {                                              \
+            const long long now_ = clock64();                                \
+            atomicAdd(&status[3 + (k)], uint32_t((now_ - phase_t0_) >> 10)); \
+            phase_t0_ = now_;                                                \
+        }                                                                    \
+    } while (0)
+#define PHASE_INIT() long long phase_t0_ = clock64()
+#else
+#define PHASE_MARK(k) do { } while (0)
+#define PHASE_INIT() do { } while (0)
+#endif
+
 struct Cells {
     uint32_t c[3];
     uint32_t neg;  // bit j: sign of hash function j is -1
@@ -64,6 +81,7 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
         return;
     }
 
+    PHASE_INIT();
     const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
     const uint32_t Pa = uint32_t(uint64_t(a + 1) * U / A) - rho0;
     const uint32_t ilo = bounds[a], ihi = bounds[a + 1];
@@ -90,11 +108,23 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
             running += tot;
         }
     }
-    // ---- stage the partition's cells, clear degrees
-    for (uint32_t c = tid; c < cells; c += kDecodeThreads)
-        Ct[c] = sketch[uint64_t(a) * cells + c];
+    PHASE_MARK(0);
+    // ---- stage the partition's cells (16-byte loads where the tile is aligned), clear degrees
+    {
+        const float *src = sketch + uint64_t(a) * cells;
+        const uint32_t head = min(cells, uint32_t((4u - (uint64_t(a) * cells & 3u)) & 3u));
+        const uint32_t n4 = (cells - head) / 4;
+        if (tid < head) Ct[tid] = src[tid];
+        for (uint32_t v = tid; v < n4; v += kDecodeThreads) {
+            const float4 q = *reinterpret_cast<const float4 *>(src + head + 4 * v);
+            float *d = Ct + head + 4 * v;
+            d[0] = q.x; d[1] = q.y; d[2] = q.z; d[3] = q.w;
+        }
+        for (uint32_t c = head + 4 * n4 + tid; c < cells; c += kDecodeThreads) Ct[c] = src[c];
+    }
     for (uint32_t c = tid; c < deg_words; c += kDecodeThreads) deg2[c] = 0;
     __syncthreads();  // also orders this workgroup's idx_out stores before the loads below
+    const uint16_t *deg16 = reinterpret_cast<const uint16_t *>(deg2);
 
     // Per-thread state for its unknowns (u = tid + q*1024): the three cell numbers
     // (15 bits each) and sign bits packed into 64 bits, one "resolved" bit, and one
@@ -111,63 +141,66 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
 #pragma unroll
             for (int j = 0; j < 3; ++j) atomicAdd(&deg2[cl.c[j] >> 1], 1u << (16 * (cl.c[j] & 1)));
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep the unrolled iterations apart: registers
     }
     __syncthreads();
+    PHASE_MARK(1);
 
     // ---- peel
     uint32_t done = 0, rounds = 0;
+    const uint32_t live = Pa > tid ? min(kDecodeMaxQ, (Pa - tid + kDecodeThreads - 1) / kDecodeThreads)
+                                   : 0u;
+    const uint32_t live_mask = live >= 32 ? 0xFFFFFFFFu : ((1u << live) - 1u);
     while (true) {
         uint32_t code = 0;
+        if (done != live_mask) {
 #pragma unroll
-        for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
-            const uint32_t u = tid + q * kDecodeThreads;
-            if (u < Pa && !((done >> q) & 1u)) {
-                // opaque copy: keeps the unpacking inside the round loop (hoisting it for
-                // all 16 unknowns would cost more registers than the kernel has)
-                uint32_t plo = uint32_t(pk[q]), phi = uint32_t(pk[q] >> 32);
-                asm volatile("" : "+v"(plo), "+v"(phi));
-                const uint64_t pq = uint64_t(plo) | (uint64_t(phi) << 32);
-                const uint32_t c0 = uint32_t(pq) & 0x7FFFu, c1 = uint32_t(pq >> 15) & 0x7FFFu,
-                               c2 = uint32_t(pq >> 30) & 0x7FFFu;
-                uint32_t c = 0;
-                if (deg_of(deg2, c0) == 1) c = 1;
-                else if (deg_of(deg2, c1) == 1) c = 2;
-                else if (deg_of(deg2, c2) == 1) c = 3;
-                code |= c << (2 * q);
+            for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
+                if (((live_mask & ~done) >> q) & 1u) {
+                    // opaque copy: keeps the unpacking inside the round loop (hoisting it
+                    // for all 16 unknowns would cost more registers than the kernel has)
+                    uint32_t plo = uint32_t(pk[q]), phi = uint32_t(pk[q] >> 32);
+                    asm volatile("" : "+v"(plo), "+v"(phi));
+                    const uint64_t pq = uint64_t(plo) | (uint64_t(phi) << 32);
+                    const uint32_t d0 = deg16[uint32_t(pq) & 0x7FFFu],
+                                   d1 = deg16[uint32_t(pq >> 15) & 0x7FFFu],
+                                   d2 = deg16[uint32_t(pq >> 30) & 0x7FFFu];
+                    const uint32_t c = d0 == 1 ? 1u : (d1 == 1 ? 2u : (d2 == 1 ? 3u : 0u));
+                    code |= c << (2 * q);
+                }
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
         // Nothing has been written yet: a cell of degree 1 keeps its value until its
         // own unknown subtracts itself below, so the value can be read there.
         if (!__syncthreads_or(code != 0)) break;
         ++rounds;
+        if (code) {
 #pragma unroll
-        for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
-            const uint32_t c = (code >> (2 * q)) & 3u;
-            if (c) {
-                uint32_t plo = uint32_t(pk[q]), phi = uint32_t(pk[q] >> 32);
-                asm volatile("" : "+v"(plo), "+v"(phi));
-                const uint64_t pq = uint64_t(plo) | (uint64_t(phi) << 32);
-                const uint32_t cc[3] = {uint32_t(pq) & 0x7FFFu, uint32_t(pq >> 15) & 0x7FFFu,
-                                        uint32_t(pq >> 30) & 0x7FFFu};
-                const uint32_t neg = uint32_t(pq >> 45) & 7u;
-                const uint32_t j = c - 1;
-                const float cv = Ct[j == 0 ? cc[0] : (j == 1 ? cc[1] : cc[2])];
-                const float x = ((neg >> j) & 1u) ? -cv : cv;
-                val_out[rho0 + tid + q * kDecodeThreads] = x;
+            for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
+                const uint32_t c = (code >> (2 * q)) & 3u;
+                if (c) {
+                    uint32_t plo = uint32_t(pk[q]), phi = uint32_t(pk[q] >> 32);
+                    asm volatile("" : "+v"(plo), "+v"(phi));
+                    const uint64_t pq = uint64_t(plo) | (uint64_t(phi) << 32);
+                    const uint32_t cc[3] = {uint32_t(pq) & 0x7FFFu, uint32_t(pq >> 15) & 0x7FFFu,
+                                            uint32_t(pq >> 30) & 0x7FFFu};
+                    const uint32_t neg = uint32_t(pq >> 45) & 7u;
+                    const uint32_t j = c - 1;
+                    const float cv = Ct[j == 0 ? cc[0] : (j == 1 ? cc[1] : cc[2])];
+                    const float x = ((neg >> j) & 1u) ? -cv : cv;
+                    val_out[rho0 + tid + q * kDecodeThreads] = x;
 #pragma unroll
-                for (int jj = 0; jj < 3; ++jj) {
-                    atomicAdd(&Ct[cc[jj]], ((neg >> jj) & 1u) ? x : -x);
-                    atomicSub(&deg2[cc[jj] >> 1], 1u << (16 * (cc[jj] & 1)));
+                    for (int jj = 0; jj < 3; ++jj) {
+                        atomicAdd(&Ct[cc[jj]], ((neg >> jj) & 1u) ? x : -x);
+                        atomicSub(&deg2[cc[jj] >> 1], 1u << (16 * (cc[jj] & 1)));
+                    }
+                    done |= 1u << q;
                 }
-                done |= 1u << q;
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
     }
 
+    PHASE_MARK(2);
     // ---- unresolved unknowns get 0; status
     uint32_t unresolved = 0;
 #pragma unroll
@@ -184,24 +217,49 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
         atomicMax(&status[TAGC_ST_ROUNDS], rounds);
     }
 
-    // ---- dense output: this partition covers c-indices [dlo, ihi)
+    PHASE_MARK(3);
+    // ---- dense output: this partition covers c-indices [dlo, ihi).  A second sweep over
+    // the Index words: the rank of a word's first set bit (workgroup scan) says where its
+    // values sit in val_out, so values are read in order and each tile is written whole.
     if (dense_out) {
         const uint32_t dlo = a == 0 ? 0u : ilo;
-        const uint32_t DT = ct_floats;
+        const uint32_t wlo = ilo >> 5;
+        uint32_t running = 0;
         __syncthreads();  // val_out stores of this workgroup are read back below
-        for (uint32_t tb = dlo; tb < ihi; tb += DT) {
-            const uint32_t len = min(DT, ihi - tb);
-            for (uint32_t c = tid; c < len; c += kDecodeThreads) Ct[c] = 0.0f;
-            __syncthreads();
-            for (uint32_t u = tid; u < Pa; u += kDecodeThreads) {
-                const uint32_t i = idx_out[rho0 + u];
-                if (i >= tb && i - tb < len) Ct[i - tb] = val_out[rho0 + u];
+        for (uint32_t wb = dlo >> 5; wb * 32 < ihi; wb += kDecodeThreads) {
+            const uint32_t w = wb + tid;
+            uint32_t word = (w * 32 < ihi && w >= wlo) ? bitmap[w] : 0u;
+            if (w == wlo) word &= 0xFFFFFFFFu << (ilo & 31);
+            if ((ihi & 31) && w == (ihi >> 5)) word &= (1u << (ihi & 31)) - 1u;
+            uint32_t tot;
+            uint32_t pos = running + block_excl_scan<uint32_t, kDecodeThreads / 64>(
+                                         uint32_t(__popc(word)), &tot, scratch);
+            // the tile of this sweep step: 1024 words = 32768 positions, in two halves
+            // of the staging buffer's size
+            for (uint32_t half = 0; half < 2; ++half) {
+                const uint32_t hbase = (wb + half * 512) * 32;  // first position of the half
+                if (hbase >= ihi) break;
+                for (uint32_t c = tid; c < 16384; c += kDecodeThreads) Ct[c] = 0.0f;
+                __syncthreads();
+                if ((tid >> 9) == half) {
+                    uint32_t ww = word, pp = pos;
+                    while (ww) {
+                        const uint32_t bb = __builtin_ctz(ww);
+                        ww &= ww - 1;
+                        if (pp < Pa) Ct[(tid & 511) * 32 + bb] = val_out[rho0 + pp];
+                        ++pp;
+                    }
+                }
+                __syncthreads();
+                const uint32_t lo = max(hbase, dlo), hi = min(hbase + 16384, ihi);
+                for (uint32_t i = lo + tid; i < hi; i += kDecodeThreads)
+                    dense_out[i] = Ct[i - hbase];
+                __syncthreads();
             }
-            __syncthreads();
-            for (uint32_t c = tid; c < len; c += kDecodeThreads) dense_out[uint64_t(tb) + c] = Ct[c];
-            __syncthreads();
+            running += tot;
         }
     }
+    PHASE_MARK(4);
 }
 
 }  // namespace
@@ -210,7 +268,7 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
                   float *val_out, float *dense_out, hipStream_t s)
 {
     ProfileScope ps("decode", s);
-    const uint32_t ct_floats = std::max<uint32_t>(p->T_cap, 1024);
+    const uint32_t ct_floats = std::max<uint32_t>(p->T_cap, 16384);  // cells, or a dense half-tile
     const uint32_t deg_words = p->T_cap / 2 + 1;
     const size_t lds = (size_t(ct_floats) + deg_words + 32) * 4;
     static size_t attr_bytes = 0;

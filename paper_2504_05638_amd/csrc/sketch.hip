@@ -14,14 +14,26 @@ namespace tagc {
 
 namespace {
 
-__device__ inline uint32_t lower_bound_u32(const uint32_t *__restrict__ a, uint32_t n, uint32_t key)
+// lower_bound over a sorted array by one wave: every step probes 64 evenly spaced
+// positions at once, so a list of millions of pairs needs 4 dependent loads, not 21.
+__device__ inline uint32_t wave_lower_bound(const uint32_t *__restrict__ a, uint32_t n,
+                                            uint32_t key)
 {
-    uint32_t lo = 0, hi = n;
-    while (lo < hi) {
-        uint32_t mid = lo + ((hi - lo) >> 1);
-        if (a[mid] < key) lo = mid + 1; else hi = mid;
+    const uint32_t lane = lane_id();
+    uint32_t lo = 0, hi = n;  // answer in [lo, hi]; a[lo-1] < key <= a[hi]
+    while (hi - lo > 64) {
+        const uint32_t step = (hi - lo + 64) / 65;       // 64 probes split the range in 65
+        const uint32_t pos = lo + (lane + 1) * step - 1;  // probe positions, ascending
+        const bool lt = pos < hi && a[min(pos, n - 1)] < key;
+        const uint32_t n_lt = __popcll(__ballot(lt));     // probes below the key (a prefix)
+        const uint32_t new_lo = lo + n_lt * step;
+        const uint32_t new_hi = n_lt == 64 ? hi : min(hi, lo + (n_lt + 1) * step - 1);
+        lo = min(new_lo, hi);
+        hi = new_hi;
     }
-    return lo;
+    const uint32_t pos = lo + lane;
+    const bool lt = pos < hi && a[pos] < key;
+    return lo + __popcll(__ballot(lt));
 }
 
 __global__ void __launch_bounds__(256)
@@ -37,9 +49,11 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
     if (a >= A) return;
     const uint32_t sw = j == 0 ? sw0 : (j == 1 ? sw1 : sw2);
     for (uint32_t c = threadIdx.x; c < m_sub; c += 256) tile[c] = 0.0f;
-    if (threadIdx.x < 2) {
+    if (threadIdx.x < 128) {  // waves 0 and 1 search one bound each
         const uint32_t n = min(cnt[TAGC_CNT_TOTAL], pair_cap);
-        s_range[threadIdx.x] = lower_bound_u32(idx, n, bounds[a + threadIdx.x]);
+        const uint32_t w = threadIdx.x >> 6;
+        const uint32_t r = wave_lower_bound(idx, n, bounds[a + w]);
+        if ((threadIdx.x & 63) == 0) s_range[w] = r;
     }
     __syncthreads();
     const uint32_t lo = s_range[0], hi = s_range[1];
