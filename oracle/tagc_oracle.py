@@ -119,7 +119,7 @@ class Config:
     sizing_milli: int = 3000
     seed: int = 0
     part_unknowns: int = 16384   # P_cap
-    part_cells: int = 24576      # T_cap (multiple of 3)
+    part_cells: int = 15360      # T_cap (multiple of 3)
 
 
 def c_offsets(segments):

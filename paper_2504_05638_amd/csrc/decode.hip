@@ -1,14 +1,21 @@
 // Decoder: g <- peeling_decompress(index, count_sketch) of Algorithm 1 (section 2.2).
 //
 // One workgroup per sketch partition.  The partition's unknowns are the set bits of the
-// merged Index in [bounds[a], bounds[a+1]); its 3*m_sub cells and their degrees live in
-// LDS for the whole peel, so the rounds cost no HBM traffic and no kernel launches.
+// merged Index in [bounds[a], bounds[a+1]); its 3*m_sub cells live in LDS for the whole
+// peel, so the rounds cost no HBM traffic and no kernel launches.
 //
 // Peeling is round-synchronous: in a round every unresolved unknown that touches a cell
 // of degree 1 takes its value from the smallest such hash function, reading the sketch
 // as it stood when the round began; then all unknowns taken in the round subtract
 // themselves from their three cells.  The first round that takes nothing ends the peel.
 // Unknowns left over are reported with value 0 and counted.
+//
+// The rounds are driven by cells, not by polling unknowns.  Besides its value every cell
+// keeps one 32-bit word: (sum of the local ranks of its unresolved unknowns) << 15 | degree.
+// When the degree is 1 the upper field *is* the remaining unknown, so a queue of the cells
+// whose degree has just become 1 is all a round needs; one atomic subtract removes an
+// unknown from a cell and tells, by the old degree, whether the cell joins the queue.
+// Total work is proportional to the unknowns, not to unknowns x rounds.
 #include "device_utils.h"
 #include "tagc_internal.h"
 
@@ -33,6 +40,8 @@ namespace {
 #define PHASE_INIT() do { } while (0)
 #endif
 
+constexpr uint32_t kDegMask = 0x7FFFu;  // low 15 bits of a cell's meta word
+
 struct Cells {
     uint32_t c[3];
     uint32_t neg;  // bit j: sign of hash function j is -1
@@ -50,22 +59,33 @@ __device__ inline Cells cells_of(uint32_t i, uint32_t m_sub, uint32_t sw0, uint3
     return r;
 }
 
-__device__ inline uint32_t deg_of(const uint32_t *deg2, uint32_t c)
+// Appends `value` to the queue for every active lane with `pred`; one LDS atomic per wave.
+__device__ inline void queue_push(bool pred, uint32_t value, uint32_t *tail, uint16_t *queue)
 {
-    return (deg2[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
+    const uint64_t bal = __ballot(pred);
+    if (bal == 0) return;
+    const uint32_t lane = lane_id();
+    const uint32_t leader = __builtin_ctzll(bal);
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(tail, uint32_t(__popcll(bal)));
+    base = __shfl(base, leader, 64);
+    if (pred) queue[base + uint32_t(__popcll(bal & ((1ull << lane) - 1ull)))] = uint16_t(value);
 }
 
 __global__ void __launch_bounds__(kDecodeThreads)
 decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ sketch,
               const uint32_t *__restrict__ header, const uint32_t *__restrict__ bounds,
-              uint32_t *idx_out, float *__restrict__ val_out, float *__restrict__ dense_out,
+              uint32_t *idx_out, float *val_out, float *__restrict__ dense_out,
               uint32_t *status, uint32_t n_c, uint32_t sw0, uint32_t sw1, uint32_t sw2,
-              uint32_t ct_floats, uint32_t deg_words)
+              uint32_t ct_floats, uint32_t T_cap, uint32_t P_cap)
 {
     extern __shared__ uint32_t lds[];
-    float *Ct = reinterpret_cast<float *>(lds);       // [ct_floats] cells, later dense tile
-    uint32_t *deg2 = lds + ct_floats;                 // [deg_words] two 16-bit degrees per word
-    uint32_t *scratch = deg2 + deg_words;             // [32]
+    float *Ct = reinterpret_cast<float *>(lds);             // [ct_floats] cells, later dense tile
+    uint32_t *meta = lds + ct_floats;                       // [T_cap] rank-sum << 15 | degree
+    uint32_t *claimed = meta + T_cap;                       // [P_cap/32 + 1] resolved unknowns
+    uint32_t *scratch = claimed + (P_cap / 32 + 1);         // [32]
+    uint16_t *queue = reinterpret_cast<uint16_t *>(scratch + 32);  // [T_cap] cells of degree 1
+    __shared__ uint32_t s_tail;
     const uint32_t tid = threadIdx.x;
     const uint32_t U = header[TAGC_HDR_U], A = header[TAGC_HDR_A];
     const uint32_t m_sub = header[TAGC_HDR_MSUB];
@@ -109,7 +129,7 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
         }
     }
     PHASE_MARK(0);
-    // ---- stage the partition's cells (16-byte loads where the tile is aligned), clear degrees
+    // ---- stage the partition's cells (16-byte loads where the tile is aligned), clear state
     {
         const float *src = sketch + uint64_t(a) * cells;
         const uint32_t head = min(cells, uint32_t((4u - (uint64_t(a) * cells & 3u)) & 3u));
@@ -122,98 +142,80 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
         }
         for (uint32_t c = head + 4 * n4 + tid; c < cells; c += kDecodeThreads) Ct[c] = src[c];
     }
-    for (uint32_t c = tid; c < deg_words; c += kDecodeThreads) deg2[c] = 0;
+    for (uint32_t c = tid; c < cells; c += kDecodeThreads) meta[c] = 0;
+    for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) claimed[c] = 0;
+    if (tid == 0) s_tail = 0;
     __syncthreads();  // also orders this workgroup's idx_out stores before the loads below
-    const uint16_t *deg16 = reinterpret_cast<const uint16_t *>(deg2);
 
-    // Per-thread state for its unknowns (u = tid + q*1024): the three cell numbers
-    // (15 bits each) and sign bits packed into 64 bits, one "resolved" bit, and one
-    // 2-bit "taken this round via hash j" code.
-    uint64_t pk[kDecodeMaxQ];
+    // ---- every unknown joins its three cells; all values start at 0
+    for (uint32_t u = tid; u < Pa; u += kDecodeThreads) {
+        const Cells cl = cells_of(idx_out[rho0 + u], m_sub, sw0, sw1, sw2);
 #pragma unroll
-    for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
-        const uint32_t u = tid + q * kDecodeThreads;
-        pk[q] = 0;
-        if (u < Pa) {
-            const Cells cl = cells_of(idx_out[rho0 + u], m_sub, sw0, sw1, sw2);
-            pk[q] = uint64_t(cl.c[0]) | (uint64_t(cl.c[1]) << 15) | (uint64_t(cl.c[2]) << 30) |
-                    (uint64_t(cl.neg) << 45);
-#pragma unroll
-            for (int j = 0; j < 3; ++j) atomicAdd(&deg2[cl.c[j] >> 1], 1u << (16 * (cl.c[j] & 1)));
-        }
+        for (int j = 0; j < 3; ++j) atomicAdd(&meta[cl.c[j]], (u << 15) + 1u);
+        val_out[rho0 + u] = 0.0f;
     }
     __syncthreads();
+    for (uint32_t c0 = 0; c0 < cells; c0 += kDecodeThreads) {
+        const uint32_t c = c0 + tid;
+        queue_push(c < cells && (meta[c] & kDegMask) == 1u, c, &s_tail, queue);
+    }
     PHASE_MARK(1);
 
     // ---- peel
-    uint32_t done = 0, rounds = 0;
-    const uint32_t live = Pa > tid ? min(kDecodeMaxQ, (Pa - tid + kDecodeThreads - 1) / kDecodeThreads)
-                                   : 0u;
-    const uint32_t live_mask = live >= 32 ? 0xFFFFFFFFu : ((1u << live) - 1u);
+    uint32_t rounds = 0, head = 0;
     while (true) {
-        uint32_t code = 0;
-        if (done != live_mask) {
-#pragma unroll
-            for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
-                if (((live_mask & ~done) >> q) & 1u) {
-                    // opaque copy: keeps the unpacking inside the round loop (hoisting it
-                    // for all 16 unknowns would cost more registers than the kernel has)
-                    uint32_t plo = uint32_t(pk[q]), phi = uint32_t(pk[q] >> 32);
-                    asm volatile("" : "+v"(plo), "+v"(phi));
-                    const uint64_t pq = uint64_t(plo) | (uint64_t(phi) << 32);
-                    const uint32_t d0 = deg16[uint32_t(pq) & 0x7FFFu],
-                                   d1 = deg16[uint32_t(pq >> 15) & 0x7FFFu],
-                                   d2 = deg16[uint32_t(pq >> 30) & 0x7FFFu];
-                    const uint32_t c = d0 == 1 ? 1u : (d1 == 1 ? 2u : (d2 == 1 ? 3u : 0u));
-                    code |= c << (2 * q);
-                }
-            }
+        __syncthreads();  // queue and s_tail of the previous phase are complete
+        const uint32_t tail = s_tail;
+        if (tail == head) break;
+        // read phase: claim the unknown of every queued cell that still has degree 1 and
+        // fix, from the degrees as they stand now, the hash function its value comes from
+        uint32_t mine = 0, jcode = 0;
+        for (uint32_t it = 0, e = head + tid; head + it * kDecodeThreads < tail;
+             ++it, e += kDecodeThreads) {
+            if (e >= tail) continue;
+            const uint32_t m = meta[queue[e]];
+            if ((m & kDegMask) != 1u) continue;  // emptied later in the round that queued it
+            const uint32_t u = m >> 15, bit = 1u << (u & 31);
+            if (atomicOr(&claimed[u >> 5], bit) & bit) continue;  // reached through another cell
+            const Cells cl = cells_of(idx_out[rho0 + u], m_sub, sw0, sw1, sw2);
+            const uint32_t j = (meta[cl.c[0]] & kDegMask) == 1u   ? 0u
+                               : (meta[cl.c[1]] & kDegMask) == 1u ? 1u
+                                                                  : 2u;
+            mine |= 1u << it;
+            jcode |= j << (2 * it);
         }
-        // Nothing has been written yet: a cell of degree 1 keeps its value until its
-        // own unknown subtracts itself below, so the value can be read there.
-        if (!__syncthreads_or(code != 0)) break;
+        // barrier between the reads above and the updates below.  A cell of degree 1 is
+        // touched by its own unknown only, so its value and rank can still be read there.
+        if (!__syncthreads_or(mine != 0)) {
+            head = tail;
+            continue;
+        }
         ++rounds;
-        if (code) {
+        for (uint32_t it = 0; mine >> it; ++it) {
+            if (!((mine >> it) & 1u)) continue;
+            const uint32_t u = meta[queue[head + it * kDecodeThreads + tid]] >> 15;
+            const Cells cl = cells_of(idx_out[rho0 + u], m_sub, sw0, sw1, sw2);
+            const uint32_t j = (jcode >> (2 * it)) & 3u;
+            const float cv = Ct[j == 0 ? cl.c[0] : (j == 1 ? cl.c[1] : cl.c[2])];
+            const float x = ((cl.neg >> j) & 1u) ? -cv : cv;
+            val_out[rho0 + u] = x;
 #pragma unroll
-            for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
-                const uint32_t c = (code >> (2 * q)) & 3u;
-                if (c) {
-                    uint32_t plo = uint32_t(pk[q]), phi = uint32_t(pk[q] >> 32);
-                    asm volatile("" : "+v"(plo), "+v"(phi));
-                    const uint64_t pq = uint64_t(plo) | (uint64_t(phi) << 32);
-                    const uint32_t cc[3] = {uint32_t(pq) & 0x7FFFu, uint32_t(pq >> 15) & 0x7FFFu,
-                                            uint32_t(pq >> 30) & 0x7FFFu};
-                    const uint32_t neg = uint32_t(pq >> 45) & 7u;
-                    const uint32_t j = c - 1;
-                    const float cv = Ct[j == 0 ? cc[0] : (j == 1 ? cc[1] : cc[2])];
-                    const float x = ((neg >> j) & 1u) ? -cv : cv;
-                    val_out[rho0 + tid + q * kDecodeThreads] = x;
-#pragma unroll
-                    for (int jj = 0; jj < 3; ++jj) {
-                        atomicAdd(&Ct[cc[jj]], ((neg >> jj) & 1u) ? x : -x);
-                        atomicSub(&deg2[cc[jj] >> 1], 1u << (16 * (cc[jj] & 1)));
-                    }
-                    done |= 1u << q;
-                }
+            for (int jj = 0; jj < 3; ++jj) {
+                atomicAdd(&Ct[cl.c[jj]], ((cl.neg >> jj) & 1u) ? x : -x);
+                const uint32_t old = atomicSub(&meta[cl.c[jj]], (u << 15) + 1u);
+                queue_push((old & kDegMask) == 2u, cl.c[jj], &s_tail, queue);
             }
         }
-        __syncthreads();
+        head = tail;
     }
 
     PHASE_MARK(2);
-    // ---- unresolved unknowns get 0; status
-    uint32_t unresolved = 0;
-#pragma unroll
-    for (uint32_t q = 0; q < kDecodeMaxQ; ++q) {
-        const uint32_t u = tid + q * kDecodeThreads;
-        if (u < Pa && !((done >> q) & 1u)) {
-            val_out[rho0 + u] = 0.0f;
-            ++unresolved;
-        }
-    }
-    unresolved = block_sum<uint32_t, kDecodeThreads / 64>(unresolved, scratch);
+    // ---- status: unknowns never claimed stay at 0
+    uint32_t resolved = 0;
+    for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) resolved += __popc(claimed[c]);
+    resolved = block_sum<uint32_t, kDecodeThreads / 64>(resolved, scratch);
     if (tid == 0) {
-        if (unresolved) atomicAdd(&status[TAGC_ST_UNRESOLVED], unresolved);
+        if (resolved < Pa) atomicAdd(&status[TAGC_ST_UNRESOLVED], Pa - resolved);
         atomicMax(&status[TAGC_ST_ROUNDS], rounds);
     }
 
@@ -264,13 +266,18 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
 
 }  // namespace
 
+size_t decode_lds_bytes(uint32_t T_cap, uint32_t P_cap)
+{
+    const size_t ct_floats = std::max<uint32_t>(T_cap, 16384);  // cells, or a dense half-tile
+    return (ct_floats + T_cap + (P_cap / 32 + 1) + 32) * 4 + size_t(T_cap) * 2 + 16;
+}
+
 int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t *idx_out,
                   float *val_out, float *dense_out, hipStream_t s)
 {
     ProfileScope ps("decode", s);
-    const uint32_t ct_floats = std::max<uint32_t>(p->T_cap, 16384);  // cells, or a dense half-tile
-    const uint32_t deg_words = p->T_cap / 2 + 1;
-    const size_t lds = (size_t(ct_floats) + deg_words + 32) * 4;
+    const uint32_t ct_floats = std::max<uint32_t>(p->T_cap, 16384);
+    const size_t lds = decode_lds_bytes(p->T_cap, p->P_cap);
     static size_t attr_bytes = 0;
     if (lds > attr_bytes) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_kernel),
@@ -280,7 +287,8 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
     }
     decode_kernel<<<uint32_t(p->A_cap), kDecodeThreads, lds, s>>>(
         sh->bitmap, sh->sketch, sh->header, sh->bounds, idx_out, val_out, dense_out, sh->status,
-        uint32_t(p->n_c), p->seed_word[0], p->seed_word[1], p->seed_word[2], ct_floats, deg_words);
+        uint32_t(p->n_c), p->seed_word[0], p->seed_word[1], p->seed_word[2], ct_floats, p->T_cap,
+        p->P_cap);
     return hip_ok(hipGetLastError());
 }
 

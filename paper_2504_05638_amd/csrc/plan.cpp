@@ -31,7 +31,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     if (cfg->index_mode != TAGC_INDEX_OR1) return TAGC_EUNSUPPORTED;
     uint32_t P_cap = cfg->part_unknowns ? cfg->part_unknowns : kMaxPartUnknowns;
     uint32_t T_cap = cfg->part_cells ? cfg->part_cells : kDefaultPartCells;
-    if (P_cap > kMaxPartUnknowns || T_cap > kMaxPartCells || T_cap < 3 || T_cap % 3)
+    if (P_cap > kMaxPartUnknowns || T_cap > kMaxPartCells || T_cap < 3 || T_cap % 3 ||
+        decode_lds_bytes(T_cap, P_cap) + 64 > kLdsBytes)
         return TAGC_EINVAL;
 
     tagc_plan_t *p = new (std::nothrow) tagc_plan_s();

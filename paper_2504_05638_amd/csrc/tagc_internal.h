@@ -24,12 +24,12 @@ constexpr uint32_t kSampleVectors = 4096;     // 16-byte vectors sampled per seg
 constexpr uint32_t kFastMinElems = 1u << 17;  // shorter segments take the dense path
 constexpr uint32_t kFastMinKeep = 64;
 constexpr uint32_t kChunkWords = 1024;  // Index words per popcount chunk
-constexpr uint32_t kDefaultPartCells = 24576;  // 3 * 8192 cells: 96 KiB of float
-constexpr uint32_t kMaxPartCells = 24576;
-constexpr uint32_t kMaxPartUnknowns = 16384;
+constexpr uint32_t kDefaultPartCells = 15360;  // 3 * 5120 cells: value, meta word and queue
+                                               // slot of every cell fit the 160 KiB of LDS
+constexpr uint32_t kMaxPartCells = 16383;      // 16 queue sweeps of 1024 threads at most
+constexpr uint32_t kMaxPartUnknowns = 16384;   // local ranks fit 14 bits
 constexpr uint32_t kDecodeThreads = 1024;
-constexpr uint32_t kDecodeMaxQ = kMaxPartUnknowns / kDecodeThreads;  // unknowns per thread
-constexpr uint32_t kDenseTile = 8192;  // floats staged in LDS per dense-output tile
+constexpr uint32_t kLdsBytes = 160 * 1024;
 constexpr uint32_t kMaxRanksPerPass = 32;
 constexpr uint32_t kSpinLimit = 1u << 20;
 
@@ -150,6 +150,8 @@ int launch_sketch_sum(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint
                       const tagc_shared_buffers *sh, hipStream_t s);
 int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t *idx_out,
                   float *val_out, float *dense_out, hipStream_t s);
+
+size_t decode_lds_bytes(uint32_t T_cap, uint32_t P_cap);
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? TAGC_OK : TAGC_EHIP; }
 

@@ -71,7 +71,7 @@ def test_wire_accounting_reproduces_the_papers_numbers():
 def test_argument_errors():
     seg = [(0, 1000, 10_000, 1)]
     for bad in (dict(dtype=7), dict(n_hash=2), dict(n_ranks=0), dict(sizing=9),
-                dict(sizing_milli=0), dict(part_cells=100), dict(part_cells=3 * 9000),
+                dict(sizing_milli=0), dict(part_cells=100), dict(part_cells=3 * 6000),
                 dict(part_unknowns=1 << 20)):
         with pytest.raises(B.TagcError) as e:
             B.tagc_plan(_cfg(**bad), seg)
