@@ -29,7 +29,7 @@ STAGES = {
     "S3a index OR": ["index_or", "header", "bounds"],
     "S2' encode": ["encode"],
     "S3b sketch sum": ["sketch_sum"],
-    "S4 decode": ["decode"],
+    "S4 decode": ["enumerate", "peel", "dense"],
 }
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
@@ -108,7 +108,9 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense):
         "index_or": (N + 1) * n_c // 8,
         "encode": 8 * k_total + N * 4 * m,
         "sketch_sum": (N + 1) * 4 * m,
-        "decode": n_c // 8 + 4 * m + 8 * U + (4 * n_c if dense else 0),
+        "enumerate": n_c // 8 + 4 * U,
+        "peel": 4 * m + 8 * U,
+        "dense": n_c // 8 + 4 * U + 4 * n_c,
     }
 
 

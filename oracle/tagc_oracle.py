@@ -118,8 +118,8 @@ class Config:
     sizing: int = SIZE_LOAD_FACTOR
     sizing_milli: int = 3000
     seed: int = 0
-    part_unknowns: int = 16384   # P_cap
-    part_cells: int = 15360      # T_cap (multiple of 3)
+    part_unknowns: int = 8192    # P_cap
+    part_cells: int = 12288      # T_cap (multiple of 3)
 
 
 def c_offsets(segments):

@@ -72,63 +72,66 @@ __device__ inline void queue_push(bool pred, uint32_t value, uint32_t *tail, uin
     if (pred) queue[base + uint32_t(__popcll(bal & ((1ull << lane) - 1ull)))] = uint16_t(value);
 }
 
+// Enumerates the set bits of the merged Index in ascending order into idx_out.  One
+// workgroup per 1024-word chunk; chunkpre[] (written by the Index aggregation) holds the
+// number of set bits before each chunk, so workgroups are independent.
+__global__ void __launch_bounds__(256)
+enumerate_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
+                 const uint32_t *__restrict__ chunkpre, const uint32_t *__restrict__ header,
+                 uint32_t *__restrict__ idx_out)
+{
+    __shared__ uint32_t scratch[8];
+    const uint32_t U = header[TAGC_HDR_U];
+    const uint32_t w0 = blockIdx.x * kChunkWords + threadIdx.x * 4;
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (w0 + 4 <= n_words) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(bitmap + w0);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    } else {
+#pragma unroll
+        for (uint32_t i = 0; i < 4; ++i) w[i] = w0 + i < n_words ? bitmap[w0 + i] : 0u;
+    }
+    const uint32_t mine = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);
+    uint32_t tot;
+    uint32_t pos = chunkpre[blockIdx.x] + block_excl_scan<uint32_t, 4>(mine, &tot, scratch);
+#pragma unroll
+    for (uint32_t i = 0; i < 4; ++i) {
+        uint32_t word = w[i];
+        while (word) {
+            const uint32_t b = __builtin_ctz(word);
+            word &= word - 1;
+            if (pos < U) idx_out[pos] = (w0 + i) * 32 + b;
+            ++pos;
+        }
+    }
+}
+
+// Peels one sketch partition: unknowns rho0 .. rho0+Pa-1 of idx_out, cells a*3*m_sub ...
 __global__ void __launch_bounds__(kDecodeThreads)
-decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ sketch,
-              const uint32_t *__restrict__ header, const uint32_t *__restrict__ bounds,
-              uint32_t *idx_out, float *val_out, float *__restrict__ dense_out,
-              uint32_t *status, uint32_t n_c, uint32_t sw0, uint32_t sw1, uint32_t sw2,
-              uint32_t ct_floats, uint32_t T_cap, uint32_t P_cap)
+peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ header,
+            const uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
+            uint32_t *status, uint32_t sw0, uint32_t sw1, uint32_t sw2, uint32_t T_cap,
+            uint32_t P_cap)
 {
     extern __shared__ uint32_t lds[];
-    float *Ct = reinterpret_cast<float *>(lds);             // [ct_floats] cells, later dense tile
-    uint32_t *meta = lds + ct_floats;                       // [T_cap] rank-sum << 15 | degree
-    uint32_t *claimed = meta + T_cap;                       // [P_cap/32 + 1] resolved unknowns
-    uint32_t *scratch = claimed + (P_cap / 32 + 1);         // [32]
+    float *Ct = reinterpret_cast<float *>(lds);      // [T_cap] cell values
+    uint32_t *meta = lds + T_cap;                    // [T_cap] rank-sum << 15 | degree
+    uint32_t *idx = meta + T_cap;                    // [P_cap] c-index of every unknown
+    uint32_t *claimed = idx + P_cap;                 // [P_cap/32 + 1] resolved unknowns
+    uint32_t *scratch = claimed + (P_cap / 32 + 1);  // [32]
     uint16_t *queue = reinterpret_cast<uint16_t *>(scratch + 32);  // [T_cap] cells of degree 1
     __shared__ uint32_t s_tail;
     const uint32_t tid = threadIdx.x;
     const uint32_t U = header[TAGC_HDR_U], A = header[TAGC_HDR_A];
     const uint32_t m_sub = header[TAGC_HDR_MSUB];
     const uint32_t a = blockIdx.x;
-
-    if (a >= A) {
-        // Empty Index: the dense output is still defined (all zeros); the grid shares it.
-        if (A == 0 && dense_out) {
-            const uint64_t per = (uint64_t(n_c) + gridDim.x - 1) / gridDim.x;
-            const uint64_t lo = per * a, hi = min(uint64_t(n_c), lo + per);
-            for (uint64_t i = lo + tid; i < hi; i += kDecodeThreads) dense_out[i] = 0.0f;
-        }
-        return;
-    }
+    if (a >= A) return;
 
     PHASE_INIT();
     const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
     const uint32_t Pa = uint32_t(uint64_t(a + 1) * U / A) - rho0;
-    const uint32_t ilo = bounds[a], ihi = bounds[a + 1];
     const uint32_t cells = 3 * m_sub;
 
-    // ---- enumerate the set bits of [ilo, ihi) in ascending order into idx_out
-    {
-        const uint32_t wlo = ilo >> 5, whi = (ihi + 31) >> 5;
-        uint32_t running = 0;
-        for (uint32_t wb = wlo; wb < whi; wb += kDecodeThreads) {
-            const uint32_t w = wb + tid;
-            uint32_t word = w < whi ? bitmap[w] : 0u;
-            if (w == wlo) word &= 0xFFFFFFFFu << (ilo & 31);
-            if ((ihi & 31) && w == (ihi >> 5)) word &= (1u << (ihi & 31)) - 1u;
-            uint32_t tot;
-            uint32_t pos = running + block_excl_scan<uint32_t, kDecodeThreads / 64>(
-                                         uint32_t(__popc(word)), &tot, scratch);
-            while (word) {
-                const uint32_t b = __builtin_ctz(word);
-                word &= word - 1;
-                if (pos < Pa) idx_out[rho0 + pos] = w * 32 + b;
-                ++pos;
-            }
-            running += tot;
-        }
-    }
-    PHASE_MARK(0);
     // ---- stage the partition's cells (16-byte loads where the tile is aligned), clear state
     {
         const float *src = sketch + uint64_t(a) * cells;
@@ -145,11 +148,14 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
     for (uint32_t c = tid; c < cells; c += kDecodeThreads) meta[c] = 0;
     for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) claimed[c] = 0;
     if (tid == 0) s_tail = 0;
-    __syncthreads();  // also orders this workgroup's idx_out stores before the loads below
+    __syncthreads();
+    PHASE_MARK(0);
 
     // ---- every unknown joins its three cells; all values start at 0
     for (uint32_t u = tid; u < Pa; u += kDecodeThreads) {
-        const Cells cl = cells_of(idx_out[rho0 + u], m_sub, sw0, sw1, sw2);
+        const uint32_t i = idx_out[rho0 + u];
+        idx[u] = i;
+        const Cells cl = cells_of(i, m_sub, sw0, sw1, sw2);
 #pragma unroll
         for (int j = 0; j < 3; ++j) atomicAdd(&meta[cl.c[j]], (u << 15) + 1u);
         val_out[rho0 + u] = 0.0f;
@@ -177,7 +183,7 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
             if ((m & kDegMask) != 1u) continue;  // emptied later in the round that queued it
             const uint32_t u = m >> 15, bit = 1u << (u & 31);
             if (atomicOr(&claimed[u >> 5], bit) & bit) continue;  // reached through another cell
-            const Cells cl = cells_of(idx_out[rho0 + u], m_sub, sw0, sw1, sw2);
+            const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
             const uint32_t j = (meta[cl.c[0]] & kDegMask) == 1u   ? 0u
                                : (meta[cl.c[1]] & kDegMask) == 1u ? 1u
                                                                   : 2u;
@@ -194,22 +200,22 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
         for (uint32_t it = 0; mine >> it; ++it) {
             if (!((mine >> it) & 1u)) continue;
             const uint32_t u = meta[queue[head + it * kDecodeThreads + tid]] >> 15;
-            const Cells cl = cells_of(idx_out[rho0 + u], m_sub, sw0, sw1, sw2);
+            const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
             const uint32_t j = (jcode >> (2 * it)) & 3u;
             const float cv = Ct[j == 0 ? cl.c[0] : (j == 1 ? cl.c[1] : cl.c[2])];
             const float x = ((cl.neg >> j) & 1u) ? -cv : cv;
             val_out[rho0 + u] = x;
 #pragma unroll
             for (int jj = 0; jj < 3; ++jj) {
-                atomicAdd(&Ct[cl.c[jj]], ((cl.neg >> jj) & 1u) ? x : -x);
+                lds_add_f32(&Ct[cl.c[jj]], ((cl.neg >> jj) & 1u) ? x : -x);
                 const uint32_t old = atomicSub(&meta[cl.c[jj]], (u << 15) + 1u);
                 queue_push((old & kDegMask) == 2u, cl.c[jj], &s_tail, queue);
             }
         }
         head = tail;
     }
-
     PHASE_MARK(2);
+
     // ---- status: unknowns never claimed stay at 0
     uint32_t resolved = 0;
     for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) resolved += __popc(claimed[c]);
@@ -218,77 +224,99 @@ decode_kernel(const uint32_t *__restrict__ bitmap, const float *__restrict__ ske
         if (resolved < Pa) atomicAdd(&status[TAGC_ST_UNRESOLVED], Pa - resolved);
         atomicMax(&status[TAGC_ST_ROUNDS], rounds);
     }
-
     PHASE_MARK(3);
-    // ---- dense output: this partition covers c-indices [dlo, ihi).  A second sweep over
-    // the Index words: the rank of a word's first set bit (workgroup scan) says where its
-    // values sit in val_out, so values are read in order and each tile is written whole.
-    if (dense_out) {
-        const uint32_t dlo = a == 0 ? 0u : ilo;
-        const uint32_t wlo = ilo >> 5;
-        uint32_t running = 0;
-        __syncthreads();  // val_out stores of this workgroup are read back below
-        for (uint32_t wb = dlo >> 5; wb * 32 < ihi; wb += kDecodeThreads) {
-            const uint32_t w = wb + tid;
-            uint32_t word = (w * 32 < ihi && w >= wlo) ? bitmap[w] : 0u;
-            if (w == wlo) word &= 0xFFFFFFFFu << (ilo & 31);
-            if ((ihi & 31) && w == (ihi >> 5)) word &= (1u << (ihi & 31)) - 1u;
-            uint32_t tot;
-            uint32_t pos = running + block_excl_scan<uint32_t, kDecodeThreads / 64>(
-                                         uint32_t(__popc(word)), &tot, scratch);
-            // the tile of this sweep step: 1024 words = 32768 positions, in two halves
-            // of the staging buffer's size
-            for (uint32_t half = 0; half < 2; ++half) {
-                const uint32_t hbase = (wb + half * 512) * 32;  // first position of the half
-                if (hbase >= ihi) break;
-                for (uint32_t c = tid; c < 16384; c += kDecodeThreads) Ct[c] = 0.0f;
-                __syncthreads();
-                if ((tid >> 9) == half) {
-                    uint32_t ww = word, pp = pos;
-                    while (ww) {
-                        const uint32_t bb = __builtin_ctz(ww);
-                        ww &= ww - 1;
-                        if (pp < Pa) Ct[(tid & 511) * 32 + bb] = val_out[rho0 + pp];
-                        ++pp;
-                    }
-                }
-                __syncthreads();
-                const uint32_t lo = max(hbase, dlo), hi = min(hbase + 16384, ihi);
-                for (uint32_t i = lo + tid; i < hi; i += kDecodeThreads)
-                    dense_out[i] = Ct[i - hbase];
-                __syncthreads();
-            }
-            running += tot;
-        }
+}
+
+// Dense output: one workgroup per 1024-word chunk of the Index writes the 32768 floats
+// it covers, zeros included, a quarter (8192 floats staged in LDS) at a time.  The rank
+// of a word's first set bit says where its values sit in val_out.
+__global__ void __launch_bounds__(256)
+dense_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
+             const uint32_t *__restrict__ chunkpre, const uint32_t *__restrict__ header,
+             const float *__restrict__ val_out, float *__restrict__ dense_out)
+{
+    __shared__ uint32_t scratch[8];
+    __shared__ float tile[8192];
+    const uint32_t U = header[TAGC_HDR_U];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t w0 = blockIdx.x * kChunkWords + tid * 4;
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (w0 + 4 <= n_words) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(bitmap + w0);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    } else {
+#pragma unroll
+        for (uint32_t i = 0; i < 4; ++i) w[i] = w0 + i < n_words ? bitmap[w0 + i] : 0u;
     }
-    PHASE_MARK(4);
+    const uint32_t mine = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);
+    uint32_t tot;
+    const uint32_t pos0 = chunkpre[blockIdx.x] + block_excl_scan<uint32_t, 4>(mine, &tot, scratch);
+    // thread tid owns words 4*tid .. 4*tid+3 of the chunk: quarter tid/64, 128 floats
+    for (uint32_t quarter = 0; quarter < 4; ++quarter) {
+        const uint32_t qbase = (blockIdx.x * kChunkWords + quarter * 256) * 32;  // first position
+        if (qbase >= n_words * 32) break;
+        for (uint32_t c = tid; c < 8192 / 4; c += 256)
+            reinterpret_cast<float4 *>(tile)[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        __syncthreads();
+        if ((tid >> 6) == quarter) {
+            uint32_t pos = pos0;
+#pragma unroll
+            for (uint32_t i = 0; i < 4; ++i) {
+                uint32_t word = w[i];
+                while (word) {
+                    const uint32_t b = __builtin_ctz(word);
+                    word &= word - 1;
+                    if (pos < U) tile[((tid & 63) * 4 + i) * 32 + b] = val_out[pos];
+                    ++pos;
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t n = min(8192u, n_words * 32 - qbase);  // n_c is a multiple of 32
+        for (uint32_t c = tid; c < n / 4; c += 256)
+            reinterpret_cast<float4 *>(dense_out + qbase)[c] = reinterpret_cast<float4 *>(tile)[c];
+        __syncthreads();
+    }
 }
 
 }  // namespace
 
 size_t decode_lds_bytes(uint32_t T_cap, uint32_t P_cap)
 {
-    const size_t ct_floats = std::max<uint32_t>(T_cap, 16384);  // cells, or a dense half-tile
-    return (ct_floats + T_cap + (P_cap / 32 + 1) + 32) * 4 + size_t(T_cap) * 2 + 16;
+    return (size_t(T_cap) * 2 + P_cap + (P_cap / 32 + 1) + 32) * 4 + size_t(T_cap) * 2 + 16;
 }
 
 int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t *idx_out,
                   float *val_out, float *dense_out, hipStream_t s)
 {
-    ProfileScope ps("decode", s);
-    const uint32_t ct_floats = std::max<uint32_t>(p->T_cap, 16384);
-    const size_t lds = decode_lds_bytes(p->T_cap, p->P_cap);
-    static size_t attr_bytes = 0;
-    if (lds > attr_bytes) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
-            return TAGC_EHIP;
-        attr_bytes = lds;
+    const uint32_t n_words = uint32_t(p->n_c / 32);
+    const uint32_t n_chunks = uint32_t(p->n_chunks);
+    const uint32_t *chunkpre = static_cast<const uint32_t *>(sh->workspace);
+    if (n_chunks) {
+        ProfileScope ps("enumerate", s);
+        enumerate_kernel<<<n_chunks, 256, 0, s>>>(sh->bitmap, n_words, chunkpre, sh->header,
+                                                  idx_out);
     }
-    decode_kernel<<<uint32_t(p->A_cap), kDecodeThreads, lds, s>>>(
-        sh->bitmap, sh->sketch, sh->header, sh->bounds, idx_out, val_out, dense_out, sh->status,
-        uint32_t(p->n_c), p->seed_word[0], p->seed_word[1], p->seed_word[2], ct_floats, p->T_cap,
-        p->P_cap);
+    {
+        ProfileScope ps("peel", s);
+        const size_t lds = decode_lds_bytes(p->T_cap, p->P_cap);
+        static size_t attr_bytes = 0;
+        if (lds > attr_bytes) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(peel_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(lds)) != hipSuccess)
+                return TAGC_EHIP;
+            attr_bytes = lds;
+        }
+        peel_kernel<<<uint32_t(p->A_cap), kDecodeThreads, lds, s>>>(
+            sh->sketch, sh->header, idx_out, val_out, sh->status, p->seed_word[0],
+            p->seed_word[1], p->seed_word[2], p->T_cap, p->P_cap);
+    }
+    if (dense_out && n_chunks) {
+        ProfileScope ps("dense", s);
+        dense_kernel<<<n_chunks, 256, 0, s>>>(sh->bitmap, n_words, chunkpre, sh->header, val_out,
+                                              dense_out);
+    }
     return hip_ok(hipGetLastError());
 }
 

@@ -62,7 +62,7 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
         const float v = val[t];
         uint32_t neg;
         const uint32_t slot = hash_slot(i, sw, m_sub, &neg);
-        atomicAdd(&tile[slot], neg ? -v : v);
+        lds_add_f32(&tile[slot], neg ? -v : v);
     }
     __syncthreads();
     float *out = sketch + (uint64_t(a) * 3 + j) * m_sub;

@@ -24,8 +24,10 @@ constexpr uint32_t kSampleVectors = 4096;     // 16-byte vectors sampled per seg
 constexpr uint32_t kFastMinElems = 1u << 17;  // shorter segments take the dense path
 constexpr uint32_t kFastMinKeep = 64;
 constexpr uint32_t kChunkWords = 1024;  // Index words per popcount chunk
-constexpr uint32_t kDefaultPartCells = 15360;  // 3 * 5120 cells: value, meta word and queue
-                                               // slot of every cell fit the 160 KiB of LDS
+// A partition keeps, in LDS, 10 bytes per cell (value, meta word, queue slot) and 4 per
+// unknown (its c-index): 12288 cells and 8192 unknowns fill the 160 KiB.
+constexpr uint32_t kDefaultPartCells = 12288;
+constexpr uint32_t kDefaultPartUnknowns = 8192;
 constexpr uint32_t kMaxPartCells = 16383;      // 16 queue sweeps of 1024 threads at most
 constexpr uint32_t kMaxPartUnknowns = 16384;   // local ranks fit 14 bits
 constexpr uint32_t kDecodeThreads = 1024;

@@ -12,7 +12,7 @@ def oracle_segments(bucket):
     return [O.Segment(s.offset, s.length, s.keep_ppm, s.flags) for s in bucket.segments]
 
 
-def oracle_config(bucket, sizing=O.SIZE_LOAD_FACTOR, seed=0, P=16384, T=15360):
+def oracle_config(bucket, sizing=O.SIZE_LOAD_FACTOR, seed=0, P=8192, T=12288):
     return O.Config(dtype=bucket.dtype, sizing=sizing, sizing_milli=bucket.sizing_milli,
                     seed=seed, part_unknowns=P, part_cells=T)
 
@@ -47,7 +47,7 @@ def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTO
     import torch
     from paper_2504_05638_amd.bucket import TagcBucket
 
-    ocfg = oracle_config(bucket, sizing, seed, P or 16384, T or 15360)
+    ocfg = oracle_config(bucket, sizing, seed, P or 8192, T or 12288)
     ores = O.run_bucket([G.to_numpy_raw(g) for g in grads_torch_cpu], ocfg,
                         oracle_segments(bucket))
     tb = TagcBucket(bucket.segments, bucket.dtype, len(grads_torch_cpu),
