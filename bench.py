@@ -121,9 +121,9 @@ def cpu_baseline(args):
     from oracle import tagc_oracle as O
     from synth import gradients as G
     b = make_buckets(args)[0]
-    seg = max((s for s in b.segments if s.flags & 1), key=lambda s: -s.length)  # smallest
-    n = min(seg.length, 1 << 24)
-    n_ranks = min(b.n_ranks, 8)
+    seg = max((s for s in b.segments if s.flags & 1), key=lambda s: s.length)  # largest
+    n = min(seg.length, 1 << 26)
+    n_ranks = min(b.n_ranks, 16)
     sub = G.Bucket("sample", b.dtype, n_ranks, [G.Seg(0, n, seg.keep_ppm, 1, seg.name)], n,
                    b.sizing_milli, {seg.name: b.sigma.get(seg.name, 1e-3)}, b.kind,
                    b.seed, b.bucket_id)

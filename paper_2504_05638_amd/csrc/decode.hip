@@ -106,26 +106,49 @@ enumerate_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
     }
 }
 
+// Appends up to three values per lane (those whose predicate holds) with one LDS atomic
+// per wave.  Safe in divergent code: only the active lanes take part.
+__device__ inline void queue_push3(bool p0, uint32_t v0, bool p1, uint32_t v1, bool p2,
+                                   uint32_t v2, uint32_t *tail, uint16_t *queue)
+{
+    const uint64_t b0 = __ballot(p0), b1 = __ballot(p1), b2 = __ballot(p2);
+    const uint32_t n0 = __popcll(b0), n1 = __popcll(b1), n2 = __popcll(b2);
+    if (n0 + n1 + n2 == 0) return;
+    const uint32_t lane = lane_id();
+    const uint64_t lt = (1ull << lane) - 1ull;
+    const uint32_t leader = __builtin_ctzll(__ballot(true));
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(tail, n0 + n1 + n2);
+    base = __shfl(base, leader, 64);
+    if (p0) queue[base + uint32_t(__popcll(b0 & lt))] = uint16_t(v0);
+    if (p1) queue[base + n0 + uint32_t(__popcll(b1 & lt))] = uint16_t(v1);
+    if (p2) queue[base + n0 + n1 + uint32_t(__popcll(b2 & lt))] = uint16_t(v2);
+}
+
+constexpr uint32_t kPeelMaxSweeps = 16;  // queue entries per thread per round, at most
+
 // Peels one sketch partition: unknowns rho0 .. rho0+Pa-1 of idx_out, cells a*3*m_sub ...
+// An LDS cell is 64 bits: value bits in the low half, meta word (rank-sum << 15 | degree)
+// in the high half, so one compare-and-swap subtracts a value and removes an unknown.
 __global__ void __launch_bounds__(kDecodeThreads)
 peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ header,
             const uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
             uint32_t *status, uint32_t sw0, uint32_t sw1, uint32_t sw2, uint32_t T_cap,
             uint32_t P_cap)
 {
-    extern __shared__ uint32_t lds[];
-    float *Ct = reinterpret_cast<float *>(lds);      // [T_cap] cell values
-    uint32_t *meta = lds + T_cap;                    // [T_cap] rank-sum << 15 | degree
-    uint32_t *idx = meta + T_cap;                    // [P_cap] c-index of every unknown
+    extern __shared__ uint64_t lds64[];
+    unsigned long long *cell = reinterpret_cast<unsigned long long *>(lds64);  // [T_cap]
+    uint32_t *idx = reinterpret_cast<uint32_t *>(cell + T_cap);      // [P_cap] c-indices
     uint32_t *claimed = idx + P_cap;                 // [P_cap/32 + 1] resolved unknowns
     uint32_t *scratch = claimed + (P_cap / 32 + 1);  // [32]
     uint16_t *queue = reinterpret_cast<uint16_t *>(scratch + 32);  // [T_cap] cells of degree 1
-    __shared__ uint32_t s_tail;
+    __shared__ uint32_t s_tail, s_any;
     const uint32_t tid = threadIdx.x;
     const uint32_t U = header[TAGC_HDR_U], A = header[TAGC_HDR_A];
     const uint32_t m_sub = header[TAGC_HDR_MSUB];
     const uint32_t a = blockIdx.x;
     if (a >= A) return;
+    const uint32_t *meta_hi = reinterpret_cast<const uint32_t *>(cell) + 1;  // meta of cell c: [2c]
 
     PHASE_INIT();
     const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
@@ -137,17 +160,21 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
         const float *src = sketch + uint64_t(a) * cells;
         const uint32_t head = min(cells, uint32_t((4u - (uint64_t(a) * cells & 3u)) & 3u));
         const uint32_t n4 = (cells - head) / 4;
-        if (tid < head) Ct[tid] = src[tid];
+        if (tid < head) cell[tid] = __float_as_uint(src[tid]);
         for (uint32_t v = tid; v < n4; v += kDecodeThreads) {
             const float4 q = *reinterpret_cast<const float4 *>(src + head + 4 * v);
-            float *d = Ct + head + 4 * v;
-            d[0] = q.x; d[1] = q.y; d[2] = q.z; d[3] = q.w;
+            unsigned long long *d = cell + head + 4 * v;
+            d[0] = __float_as_uint(q.x); d[1] = __float_as_uint(q.y);
+            d[2] = __float_as_uint(q.z); d[3] = __float_as_uint(q.w);
         }
-        for (uint32_t c = head + 4 * n4 + tid; c < cells; c += kDecodeThreads) Ct[c] = src[c];
+        for (uint32_t c = head + 4 * n4 + tid; c < cells; c += kDecodeThreads)
+            cell[c] = __float_as_uint(src[c]);
     }
-    for (uint32_t c = tid; c < cells; c += kDecodeThreads) meta[c] = 0;
     for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) claimed[c] = 0;
-    if (tid == 0) s_tail = 0;
+    if (tid == 0) {
+        s_tail = 0;
+        s_any = 0;
+    }
     __syncthreads();
     PHASE_MARK(0);
 
@@ -156,61 +183,91 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
         const uint32_t i = idx_out[rho0 + u];
         idx[u] = i;
         const Cells cl = cells_of(i, m_sub, sw0, sw1, sw2);
+        const unsigned long long inc = (unsigned long long)((u << 15) + 1u) << 32;
 #pragma unroll
-        for (int j = 0; j < 3; ++j) atomicAdd(&meta[cl.c[j]], (u << 15) + 1u);
+        for (int j = 0; j < 3; ++j) atomicAdd(&cell[cl.c[j]], inc);
         val_out[rho0 + u] = 0.0f;
     }
     __syncthreads();
     for (uint32_t c0 = 0; c0 < cells; c0 += kDecodeThreads) {
         const uint32_t c = c0 + tid;
-        queue_push(c < cells && (meta[c] & kDegMask) == 1u, c, &s_tail, queue);
+        queue_push(c < cells && (meta_hi[2 * c] & kDegMask) == 1u, c, &s_tail, queue);
     }
     PHASE_MARK(1);
 
     // ---- peel
-    uint32_t rounds = 0, head = 0;
+    uint32_t rounds = 0, head = 0, sweep = 0;
     while (true) {
+        ++sweep;
         __syncthreads();  // queue and s_tail of the previous phase are complete
         const uint32_t tail = s_tail;
         if (tail == head) break;
         // read phase: claim the unknown of every queued cell that still has degree 1 and
-        // fix, from the degrees as they stand now, the hash function its value comes from
-        uint32_t mine = 0, jcode = 0;
-        for (uint32_t it = 0, e = head + tid; head + it * kDecodeThreads < tail;
-             ++it, e += kDecodeThreads) {
+        // fix, from the degrees as they stand now, the hash function its value comes from.
+        // item: c0 | c1 << 14 | c2 << 28 | neg << 42 | j << 45 | u << 47
+        unsigned long long item[kPeelMaxSweeps];
+        uint32_t mine = 0;
+#pragma unroll
+        for (uint32_t it = 0; it < kPeelMaxSweeps; ++it) {
+            item[it] = 0;
+            if (head + it * kDecodeThreads >= tail) continue;  // uniform
+            const uint32_t e = head + it * kDecodeThreads + tid;
             if (e >= tail) continue;
-            const uint32_t m = meta[queue[e]];
+            const uint32_t m = meta_hi[2 * queue[e]];
             if ((m & kDegMask) != 1u) continue;  // emptied later in the round that queued it
             const uint32_t u = m >> 15, bit = 1u << (u & 31);
             if (atomicOr(&claimed[u >> 5], bit) & bit) continue;  // reached through another cell
             const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
-            const uint32_t j = (meta[cl.c[0]] & kDegMask) == 1u   ? 0u
-                               : (meta[cl.c[1]] & kDegMask) == 1u ? 1u
-                                                                  : 2u;
+            const uint32_t d0 = meta_hi[2 * cl.c[0]] & kDegMask, d1 = meta_hi[2 * cl.c[1]] & kDegMask;
+            const uint32_t j = d0 == 1u ? 0u : (d1 == 1u ? 1u : 2u);
+            item[it] = (unsigned long long)cl.c[0] | ((unsigned long long)cl.c[1] << 14) |
+                       ((unsigned long long)cl.c[2] << 28) | ((unsigned long long)cl.neg << 42) |
+                       ((unsigned long long)j << 45) | ((unsigned long long)u << 47);
             mine |= 1u << it;
-            jcode |= j << (2 * it);
         }
         // barrier between the reads above and the updates below.  A cell of degree 1 is
-        // touched by its own unknown only, so its value and rank can still be read there.
-        if (!__syncthreads_or(mine != 0)) {
+        // touched by its own unknown only, so its value can still be read there.  "Did
+        // anyone claim anything" travels through an LDS word stamped with the sweep number
+        // (a plain barrier is ten times cheaper than a voting one here).
+        if (mine) s_any = sweep;
+        __syncthreads();
+        if (s_any != sweep) {
             head = tail;
             continue;
         }
         ++rounds;
-        for (uint32_t it = 0; mine >> it; ++it) {
-            if (!((mine >> it) & 1u)) continue;
-            const uint32_t u = meta[queue[head + it * kDecodeThreads + tid]] >> 15;
-            const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
-            const uint32_t j = (jcode >> (2 * it)) & 3u;
-            const float cv = Ct[j == 0 ? cl.c[0] : (j == 1 ? cl.c[1] : cl.c[2])];
-            const float x = ((cl.neg >> j) & 1u) ? -cv : cv;
-            val_out[rho0 + u] = x;
 #pragma unroll
-            for (int jj = 0; jj < 3; ++jj) {
-                lds_add_f32(&Ct[cl.c[jj]], ((cl.neg >> jj) & 1u) ? x : -x);
-                const uint32_t old = atomicSub(&meta[cl.c[jj]], (u << 15) + 1u);
-                queue_push((old & kDegMask) == 2u, cl.c[jj], &s_tail, queue);
+        for (uint32_t it = 0; it < kPeelMaxSweeps; ++it) {
+            if (!((mine >> it) & 1u)) continue;
+            const unsigned long long p = item[it];
+            const uint32_t c[3] = {uint32_t(p) & 0x3FFFu, uint32_t(p >> 14) & 0x3FFFu,
+                                   uint32_t(p >> 28) & 0x3FFFu};
+            const uint32_t neg = uint32_t(p >> 42) & 7u, j = uint32_t(p >> 45) & 3u;
+            const uint32_t u = uint32_t(p >> 47);
+            unsigned long long o[3] = {cell[c[0]], cell[c[1]], cell[c[2]]};
+            const float cv = __uint_as_float(uint32_t(j == 0 ? o[0] : (j == 1 ? o[1] : o[2])));
+            const float x = ((neg >> j) & 1u) ? -cv : cv;
+            val_out[rho0 + u] = x;
+            const unsigned long long dec = (unsigned long long)((u << 15) + 1u) << 32;
+            unsigned long long r[3];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
+                r[k] = atomicCAS(&cell[c[k]], o[k],
+                                 ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
             }
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                while (r[k] != o[k]) {  // another unknown of the round got there first: redo
+                    o[k] = r[k];
+                    const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
+                    r[k] = atomicCAS(&cell[c[k]], o[k],
+                                     ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
+                }
+            }
+            queue_push3((uint32_t(o[0] >> 32) & kDegMask) == 2u, c[0],
+                        (uint32_t(o[1] >> 32) & kDegMask) == 2u, c[1],
+                        (uint32_t(o[2] >> 32) & kDegMask) == 2u, c[2], &s_tail, queue);
         }
         head = tail;
     }
@@ -283,7 +340,7 @@ dense_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
 
 size_t decode_lds_bytes(uint32_t T_cap, uint32_t P_cap)
 {
-    return (size_t(T_cap) * 2 + P_cap + (P_cap / 32 + 1) + 32) * 4 + size_t(T_cap) * 2 + 16;
+    return size_t(T_cap) * 8 + (size_t(P_cap) + (P_cap / 32 + 1) + 32) * 4 + size_t(T_cap) * 2 + 16;
 }
 
 int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t *idx_out,

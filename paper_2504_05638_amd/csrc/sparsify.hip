@@ -73,10 +73,12 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
 {
     const uint32_t t = threadIdx.x;
     const uint4 *hv = reinterpret_cast<const uint4 *>(hist + uint64_t(t) * BPT);
+    uint32_t bins[BPT];
     uint32_t s = 0;
 #pragma unroll
     for (int i = 0; i < BPT / 4; ++i) {
-        uint4 v = hv[i];
+        const uint4 v = hv[i];
+        bins[4 * i] = v.x; bins[4 * i + 1] = v.y; bins[4 * i + 2] = v.z; bins[4 * i + 3] = v.w;
         s += v.x + v.y + v.z + v.w;
     }
     uint32_t total;
@@ -84,15 +86,17 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
     uint32_t suffix = total - prefix;  // bins of this thread and all higher ones
     if (total >= need && suffix >= need && suffix - s < need) {
         uint32_t acc = suffix - s;
+        bool done = false;
+#pragma unroll
         for (int b = BPT - 1; b >= 0; --b) {
-            uint32_t c = hist[uint64_t(t) * BPT + b];
-            if (acc + c >= need) {
+            const uint32_t c = bins[b];
+            if (!done && acc + c >= need) {
                 smem[16] = t * BPT + b;
                 smem[17] = acc;
                 smem[18] = c;
-                break;
+                done = true;
             }
-            acc += c;
+            if (!done) acc += c;
         }
     }
     __syncthreads();
@@ -246,16 +250,12 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
             uint32_t row_base = 0;
 #pragma unroll
             for (uint32_t r = 0; r < ROWS; ++r) {
+                // branch-free classification of the lane's VEC entries
                 uint32_t m = 0;
 #pragma unroll
                 for (uint32_t e = 0; e < VEC; ++e) {
                     const uint32_t bin = (vec_elem_bits<DTYPE>(w[r], e) & 0x7FFFFFFFu) >> 16;
-                    if (bin >= blo) {
-                        m |= 1u << e;
-                        const uint32_t wi = bin - blo;
-                        if (wi < kSpillWindow) atomicAdd(&h[wi], 1u);
-                        else atomicAdd(&gh[bin], 1u);
-                    }
+                    m |= uint32_t(bin >= blo) << e;
                 }
                 // slot of this lane's first candidate: candidates of lower lanes in the row
                 const uint32_t cnt = __popc(m);
@@ -266,22 +266,32 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                     pos += uint32_t(__popcll(bal & lt_mask)) << bit;
                     tot += uint32_t(__popcll(bal)) << bit;
                 }
-                if (m) {
-#pragma unroll
-                    for (uint32_t e = 0; e < VEC; ++e) {  // static indices keep w[] in registers
-                        if (!((m >> e) & 1u)) continue;
-                        if (pos < CAP) {
-                            const uint32_t bits = vec_elem_bits<DTYPE>(w[r], e);
-                            const uint32_t rel = r * ROW_ELEMS + lane * VEC + e;
-                            if (DTYPE == kBF16) {
-                                slots[pos] = bits | rel;
-                            } else {
-                                slots[pos] = bits;
-                                slots_pos[pos] = rel;
-                            }
-                        }
-                        ++pos;
+                // candidates are rare: loop over this lane's few set bits only, so the wave
+                // issues as many histogram / store instructions as its busiest lane needs
+                while (m) {
+                    const uint32_t e = __builtin_ctz(m);
+                    m &= m - 1;
+                    uint32_t bits;  // select without indexing the register array
+                    if (DTYPE == kBF16) {
+                        const uint32_t wsel = e < 4 ? (e < 2 ? w[r][0] : w[r][1])
+                                                    : (e < 6 ? w[r][2] : w[r][3]);
+                        bits = (wsel >> (16 * (e & 1))) << 16;
+                    } else {
+                        bits = e < 2 ? (e == 0 ? w[r][0] : w[r][1]) : (e == 2 ? w[r][2] : w[r][3]);
                     }
+                    const uint32_t bin = (bits & 0x7FFFFFFFu) >> 16, wi = bin - blo;
+                    if (wi < kSpillWindow) atomicAdd(&h[wi], 1u);
+                    else atomicAdd(&gh[bin], 1u);
+                    if (pos < CAP) {
+                        const uint32_t rel = r * ROW_ELEMS + lane * VEC + e;
+                        if (DTYPE == kBF16) {
+                            slots[pos] = bits | rel;
+                        } else {
+                            slots[pos] = bits;
+                            slots_pos[pos] = rel;
+                        }
+                    }
+                    ++pos;
                 }
                 row_base += tot;
             }
@@ -302,12 +312,13 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
     }
 }
 
-// true iff some segment is on the dense route (workgroup-uniform)
+// true iff some segment is on the dense route.  Every thread reads the same words, so the
+// loads are scalar and the answer is uniform without a barrier.
 __device__ inline bool any_dense_route(const SelDev *sel, uint32_t L)
 {
     uint32_t any = 0;
-    for (uint32_t l = threadIdx.x; l < L; l += blockDim.x) any |= sel[l].route;
-    return __syncthreads_or(any) != 0;
+    for (uint32_t l = 0; l < L; ++l) any |= sel[l].route;
+    return any != 0;
 }
 
 // ------------------------------------------------------------------ hist1
