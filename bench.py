@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--buckets", type=int, default=0,
                     help="only the first B buckets of the workload (0 = all; for experiments)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibration-copy", type=int, default=0,
+                    help="before the timed region, copy this many MiB device to device three "
+                         "times (a kernel of known traffic to scale rocprof byte counters by)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     return ap.parse_args()
@@ -209,6 +212,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        src = torch.ones(args.calibration_copy << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- per-bucket facts (U, m, pairs) for the byte accounting, from one more pass
     input_bytes = 0
