@@ -118,13 +118,27 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads)
 sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
-              SelDev *__restrict__ sel, uint32_t *__restrict__ binlo)
+              SelDev *__restrict__ sel, uint32_t *__restrict__ binlo, uint4 *zero_base,
+              uint64_t zero_n16, uint32_t *cnt, uint32_t n_cnt)
 {
     extern __shared__ uint32_t h[];
     __shared__ uint32_t smem[32];
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
-    const uint32_t l = blockIdx.x, tid = threadIdx.x;
+    const uint32_t L = table[0];
+    const uint32_t tid = threadIdx.x;
+    if (blockIdx.x >= L) {
+        // the remaining workgroups clear the per-call part of the workspace and the counts
+        const uint32_t fb = blockIdx.x - L, nfb = gridDim.x - L;
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        for (uint64_t i = uint64_t(fb) * kHistThreads + tid; i < zero_n16;
+             i += uint64_t(nfb) * kHistThreads)
+            zero_base[i] = z;
+        if (fb == 0)
+            for (uint32_t i = tid; i < n_cnt; i += kHistThreads) cnt[i] = 0;
+        return;
+    }
+    const uint32_t l = blockIdx.x;
     const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
     SelDev r{};
     r.route = (sd.flags & kSegFast) ? 0u : 1u;
@@ -622,12 +636,23 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 
 // ------------------------------------------------------------------- emit
 
-// Candidate route, final pass.  A workgroup handles one super-chunk (32 chunks) at a
-// time: 8 threads per chunk, each owning CAP/8 consecutive slots, which it classifies
-// against the exact threshold twice -- once to count, once (after the workgroup scan and
-// the look-back over the segment's super-chunks) to write the survivors in ascending
-// c-index.  The super-chunk's Index words are assembled in LDS and written whole, zeros
-// included.
+// Candidate route, final pass.  A workgroup handles kEmitItems super-chunks (32 chunks
+// each) per iteration: 8 threads per chunk, each owning CAP/8 consecutive slots, which it
+// classifies against the exact threshold twice -- once to count, once (after the workgroup
+// scan and the prefix over the segment's earlier super-chunks) to write the survivors in
+// ascending c-index.  Every step is latency-bound (a dependent memory access costs 2-3 us
+// under load), so the items of an iteration go through each step together: their loads
+// are in flight at the same time.  A super-chunk's Index words are assembled in LDS and
+// written whole, zeros included.
+//
+// The prefix over earlier super-chunks has no chain: an item publishes its own counts,
+// then the workgroup adds up the counts of all predecessors in its segment, each thread
+// waiting (bounded) only for the words it reads.  A predecessor publishes right after
+// counting and waits for nobody before that, and it belongs to a workgroup of the same
+// resident grid (items are dealt out in increasing order), so the wait ends.
+constexpr int kEmitItems = 2;
+constexpr uint32_t kEmitMaxSegTable = 1024;
+
 template <int DTYPE>
 __global__ void __launch_bounds__(kEmitThreads)
 emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
@@ -640,106 +665,169 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
     constexpr uint32_t CHUNK = 64 * VEC * kCandRows;
     constexpr uint32_t SC_ELEMS = CHUNK * kCandChunksPerSuper;
     constexpr uint32_t SC_WORDS = SC_ELEMS / 32;
-    __shared__ uint32_t bits[SC_WORDS];
-    __shared__ uint64_t s_scan[kEmitThreads / 64];
-    __shared__ uint64_t s_excl;
-    __shared__ uint32_t s_base;
+    constexpr int NI = kEmitItems;
+    constexpr int NW = kEmitThreads / 64;
+    __shared__ uint32_t bits[NI][SC_WORDS];
+    __shared__ uint64_t s_scan[NW];
+    __shared__ uint32_t s_segbase[kEmitMaxSegTable];  // pairs emitted by earlier segments
     const uint32_t L = table[0], total_sc = table[4];
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
     const uint32_t tid = threadIdx.x;
     const uint32_t ch_in_sc = tid >> 3, part = tid & 7;
     const uint32_t R = CAP / 8;  // slots per thread, a multiple of 4
 
-    for (uint32_t sc = blockIdx.x; sc < total_sc; sc += gridDim.x) {
-        const uint32_t l = segment_of(L, sc, [&](uint32_t i) { return segs[i].sc_start; });
-        const SegDev sd = segs[l];
-        const SelDev se = sel[l];
-        if (se.route) continue;  // the dense route writes this segment (uniform)
-        const uint32_t sc_rel0 = (sc - sd.sc_start) * SC_ELEMS;
-        const uint32_t g = sc * kCandChunksPerSuper + ch_in_sc;  // global chunk number
-        for (uint32_t i = tid; i < SC_WORDS; i += kEmitThreads) bits[i] = 0;
+    // pair offset of every segment (exclusive prefix of the segments' counts)
+    {
+        uint32_t running = 0;
+        uint32_t *scan32 = reinterpret_cast<uint32_t *>(s_scan);
+        for (uint32_t base = 0; base < min(L, kEmitMaxSegTable); base += kEmitThreads) {
+            const uint32_t i = base + tid;
+            uint32_t tot;
+            const uint32_t v = i < L ? sel[i].cnt : 0u;
+            const uint32_t ex = block_excl_scan<uint32_t, NW>(v, &tot, scan32);
+            if (i < kEmitMaxSegTable) s_segbase[i] = running + ex;
+            running += tot;
+        }
+        __syncthreads();
+    }
 
-        const bool chunk_in_seg = sc_rel0 + ch_in_sc * CHUNK < sd.n;
-        const uint32_t c = (se.cnt != 0 && chunk_in_seg) ? min(chunk_cnt[g], CAP) : 0u;
-        const uint32_t s0 = part * R, s1 = min(s0 + R, c);
-        const uint32_t *sp = cand + uint64_t(g) * CAP;
-
-        // ---- pass 1: count this thread's slots above / at the threshold
-        uint32_t n_gt = 0, n_eq = 0;
-        for (uint32_t s4 = s0; s4 < s1; s4 += 4) {
-            const uint4 q = *reinterpret_cast<const uint4 *>(sp + s4);
-            const uint32_t v[4] = {q.x, q.y, q.z, q.w};
+    for (uint32_t base = blockIdx.x; base < total_sc; base += gridDim.x * NI) {
+        // ---- per item: segment, threshold, this thread's slot range
+        uint32_t sc[NI], l[NI], c_off[NI], n_seg[NI], sc_rel0[NI], sc_first[NI];
+        uint32_t T[NI], quota[NI], s0[NI], s1[NI], ccnt[NI];
+        const uint32_t *sp[NI];
+        bool live[NI];
 #pragma unroll
-            for (uint32_t i = 0; i < 4; ++i) {
-                if (s4 + i < s1) {
-                    const uint32_t key = (DTYPE == kBF16 ? (v[i] & 0xFFFF0000u) : v[i]) & 0x7FFFFFFFu;
-                    n_gt += key > se.T;
-                    n_eq += (key == se.T) && se.quota;
+        for (int k = 0; k < NI; ++k) {
+            sc[k] = base + k * gridDim.x;
+            live[k] = sc[k] < total_sc;
+            const uint32_t scc = live[k] ? sc[k] : 0u;
+            l[k] = segment_of(L, scc, [&](uint32_t i) { return segs[i].sc_start; });
+            const SegDev sd = segs[l[k]];
+            const SelDev se = sel[l[k]];
+            live[k] = live[k] && !se.route;  // the dense route writes re-routed segments
+            c_off[k] = sd.c_off;
+            n_seg[k] = sd.n;
+            sc_first[k] = sd.sc_start;
+            sc_rel0[k] = (scc - sd.sc_start) * SC_ELEMS;
+            T[k] = se.T;
+            quota[k] = se.quota;
+            const uint32_t g = scc * kCandChunksPerSuper + ch_in_sc;  // global chunk number
+            sp[k] = cand + uint64_t(g) * CAP;
+            const bool in_seg = live[k] && se.cnt != 0 && sc_rel0[k] + ch_in_sc * CHUNK < sd.n;
+            ccnt[k] = in_seg ? chunk_cnt[g] : 0u;
+        }
+        for (uint32_t i = tid; i < NI * SC_WORDS; i += kEmitThreads) (&bits[0][0])[i] = 0;
+        // ---- pass 1: count this thread's slots above / at the threshold
+        uint64_t mine[NI];
+#pragma unroll
+        for (int k = 0; k < NI; ++k) {
+            s0[k] = part * R;
+            s1[k] = min(s0[k] + R, min(ccnt[k], CAP));
+        }
+#pragma unroll
+        for (int k = 0; k < NI; ++k) {
+            uint32_t n_gt = 0, n_eq = 0;
+            for (uint32_t s4 = s0[k]; s4 < s1[k]; s4 += 4) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(sp[k] + s4);
+                const uint32_t v[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (uint32_t i = 0; i < 4; ++i) {
+                    if (s4 + i < s1[k]) {
+                        const uint32_t key =
+                            (DTYPE == kBF16 ? (v[i] & 0xFFFF0000u) : v[i]) & 0x7FFFFFFFu;
+                        n_gt += key > T[k];
+                        n_eq += (key == T[k]) && quota[k];
+                    }
                 }
             }
+            mine[k] = (uint64_t(n_gt) << 31) | uint64_t(n_eq);
         }
-        // ---- order: threads are already in position order (chunk, then slot)
-        uint64_t tot;
-        const uint64_t mine = (uint64_t(n_gt) << 31) | uint64_t(n_eq);
-        const uint64_t ex_blk = block_excl_scan<uint64_t, kEmitThreads / 64>(mine, &tot, s_scan);
-        if (tid < 64) {
-            const uint64_t ex = lookback(sc_state, sc, sd.sc_start, tot, &cnt[TAGC_CNT_FLAGS]);
-            uint32_t sb = 0;
-            for (uint32_t i = tid; i < l; i += 64) sb += sel[i].cnt;
-            sb = wave_sum<uint32_t>(sb);
-            if (tid == 0) {
-                s_excl = ex;
-                s_base = sb;
+        // ---- order inside each item (threads are in position order), publish, prefix
+        uint64_t ex[NI];
+#pragma unroll
+        for (int k = 0; k < NI; ++k) {
+            uint64_t tot;
+            ex[k] = block_excl_scan<uint64_t, NW>(mine[k], &tot, s_scan);
+            if (live[k] && tid == 0) st_agent(&sc_state[sc[k]], kStAgg | tot);
+        }
+#pragma unroll
+        for (int k = 0; k < NI; ++k) {
+            uint64_t sum = 0;
+            if (live[k]) {
+                for (uint32_t j = sc_first[k] + tid; j < sc[k]; j += kEmitThreads) {
+                    uint64_t v = ld_agent(&sc_state[j]);
+                    uint32_t spins = 0;
+                    while ((v & kStMask) == 0) {  // bounded wait for a resident predecessor
+                        if (++spins > kSpinLimit) {
+                            atomicOr(&cnt[TAGC_CNT_FLAGS], TAGC_FLAG_SPIN_LIMIT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                        v = ld_agent(&sc_state[j]);
+                    }
+                    sum += v & ~kStMask;
+                }
             }
+            ex[k] += block_sum<uint64_t, NW>(sum, s_scan);
         }
-        __syncthreads();  // also: `bits` is cleared
-        const uint64_t ex = s_excl + ex_blk;
-        uint32_t gb = uint32_t(ex >> 31), eb = uint32_t(ex & 0x7FFFFFFFu);
-        const uint32_t seg_base = s_base;
-
-        // ---- pass 2: write the survivors
-        if (n_gt | n_eq) {
-            for (uint32_t s4 = s0; s4 < s1; s4 += 4) {
-                const uint4 q = *reinterpret_cast<const uint4 *>(sp + s4);
+        // ---- pass 2: write the survivors (block_sum's barrier also covers `bits`)
+#pragma unroll
+        for (int k = 0; k < NI; ++k) {
+            if (!(mine[k])) continue;
+            uint32_t gb = uint32_t(ex[k] >> 31), eb = uint32_t(ex[k] & 0x7FFFFFFFu);
+            uint32_t seg_base;
+            if (l[k] < kEmitMaxSegTable) {
+                seg_base = s_segbase[l[k]];
+            } else {  // more segments than the table holds: add them up directly
+                seg_base = s_segbase[kEmitMaxSegTable - 1] + sel[kEmitMaxSegTable - 1].cnt;
+                for (uint32_t i = kEmitMaxSegTable; i < l[k]; ++i) seg_base += sel[i].cnt;
+            }
+            for (uint32_t s4 = s0[k]; s4 < s1[k]; s4 += 4) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(sp[k] + s4);
                 const uint32_t v[4] = {q.x, q.y, q.z, q.w};
                 uint32_t rp[4] = {0, 0, 0, 0};
                 if (DTYPE == kF32) {
-                    const uint4 p = *reinterpret_cast<const uint4 *>(sp + n_slots_total + s4);
-                    rp[0] = p.x; rp[1] = p.y; rp[2] = p.z; rp[3] = p.w;
+                    const uint4 pq = *reinterpret_cast<const uint4 *>(sp[k] + n_slots_total + s4);
+                    rp[0] = pq.x; rp[1] = pq.y; rp[2] = pq.z; rp[3] = pq.w;
                 }
 #pragma unroll
                 for (uint32_t i = 0; i < 4; ++i) {
-                    if (s4 + i >= s1) continue;
+                    if (s4 + i >= s1[k]) continue;
                     const uint32_t vbits = DTYPE == kBF16 ? (v[i] & 0xFFFF0000u) : v[i];
                     const uint32_t rel = DTYPE == kBF16 ? (v[i] & 0xFFFFu) : rp[i];
                     const uint32_t key = vbits & 0x7FFFFFFFu;
                     uint32_t pos;
                     bool keep;
-                    if (key > se.T) {
-                        pos = gb + min(eb, se.quota);
+                    if (key > T[k]) {
+                        pos = gb + min(eb, quota[k]);
                         keep = true;
                         ++gb;
-                    } else if (key == se.T && se.quota) {
+                    } else if (key == T[k] && quota[k]) {
                         pos = gb + eb;
-                        keep = eb < se.quota;
+                        keep = eb < quota[k];
                         ++eb;
                     } else {
                         continue;
                     }
                     if (keep) {
                         const uint32_t rel_sc = ch_in_sc * CHUNK + rel;
-                        idx_out[seg_base + pos] = sd.c_off + sc_rel0 + rel_sc;
+                        idx_out[seg_base + pos] = c_off[k] + sc_rel0[k] + rel_sc;
                         val_out[seg_base + pos] = __uint_as_float(vbits);
-                        atomicOr(&bits[rel_sc >> 5], 1u << (rel_sc & 31));
+                        atomicOr(&bits[k][rel_sc >> 5], 1u << (rel_sc & 31));
                     }
                 }
             }
         }
         __syncthreads();
-        const uint32_t w0 = (sd.c_off + sc_rel0) >> 5;
-        for (uint32_t i = tid; i < SC_WORDS; i += kEmitThreads)
-            if (sc_rel0 + i * 32 < sd.n) bitmap[w0 + i] = bits[i];
-        __syncthreads();  // bits / s_excl are rewritten by the next iteration
+#pragma unroll
+        for (int k = 0; k < NI; ++k) {
+            if (!live[k]) continue;
+            const uint32_t w0 = (c_off[k] + sc_rel0[k]) >> 5;
+            for (uint32_t i = tid; i < SC_WORDS; i += kEmitThreads)
+                if (sc_rel0[k] + i * 32 < n_seg[k]) bitmap[w0 + i] = bits[k][i];
+        }
+        __syncthreads();  // bits are cleared again by the next iteration
     }
 }
 
@@ -948,20 +1036,22 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     static bool a_sample = false, a_hist = false;
     static int occ_emit = 0, occ_compact = 0;
 
-    {
+    if (L == 0) {  // nothing is compressed: only the counts have to read zero
         ProfileScope ps("fill_zero", s);
-        uint64_t n16 = p->zero_bytes / 16;
-        uint32_t grid = uint32_t(std::min<uint64_t>((n16 + 255) / 256, uint64_t(cus) * 8));
-        fill_zero_kernel<<<std::max(grid, 1u), 256, 0, s>>>(reinterpret_cast<uint4 *>(ws), n16,
-                                                            rk->cnt, TAGC_CNT_SEG0 + L);
+        fill_zero_kernel<<<1, 256, 0, s>>>(reinterpret_cast<uint4 *>(ws), 0, rk->cnt,
+                                           TAGC_CNT_SEG0);
+        return hip_ok(hipGetLastError());
     }
-    if (L == 0) return hip_ok(hipGetLastError());
     if (allow_lds(sample_kernel<DTYPE>, lds_hist, &a_sample) ||
         allow_lds(hist1_kernel<DTYPE>, lds_hist, &a_hist))
         return TAGC_EHIP;
     {
-        ProfileScope ps("sample", s);
-        sample_kernel<DTYPE><<<L, kHistThreads, lds_hist, s>>>(g, table, sel, binlo);
+        ProfileScope ps("sample", s);  // + clears the per-call workspace
+        const uint64_t n16 = p->zero_bytes / 16;
+        const uint32_t fill_blocks = uint32_t(
+            std::max<uint64_t>(1, std::min<uint64_t>((n16 + kHistThreads - 1) / kHistThreads, cus)));
+        sample_kernel<DTYPE><<<L + fill_blocks, kHistThreads, lds_hist, s>>>(
+            g, table, sel, binlo, reinterpret_cast<uint4 *>(ws), n16, rk->cnt, TAGC_CNT_SEG0 + L);
     }
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
@@ -998,7 +1088,8 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         ProfileScope ps("emit", s);
         const int occ = resident_blocks_per_cu(emit_kernel<DTYPE>, kEmitThreads, 0, &occ_emit);
         if (occ <= 0) return TAGC_EHIP;
-        const uint32_t grid = std::min<uint32_t>(p->total_sc, uint32_t(cus) * uint32_t(occ));
+        const uint32_t grid = std::min<uint32_t>((p->total_sc + kEmitItems - 1) / kEmitItems,
+                                                 uint32_t(cus) * uint32_t(occ));
         emit_kernel<DTYPE><<<grid, kEmitThreads, 0, s>>>(table, sel, cand, chunk_cnt, n_slots,
                                                          p->cand_cap, sc_state, rk->idx, rk->val,
                                                          rk->bitmap, rk->cnt);
