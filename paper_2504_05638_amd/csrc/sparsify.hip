@@ -193,12 +193,20 @@ sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
 // bf16 slot: (bf16 bits << 16) | position in chunk.  fp32 slot: value bits in cand[slot],
 // position in cand[n_slots_total + slot].
 //
+// Work assignment: the chunks of all segments form one list (a segment's chunks start at
+// its first super-chunk); each workgroup takes one contiguous span of it, its waves
+// interleaved inside the span.  A workgroup therefore meets a segment boundary -- where
+// the LDS histogram has to be flushed behind barriers -- only if its span straddles one,
+// instead of the whole grid draining at every boundary.
+//
 // The LDS histogram only covers the kSpillWindow bins from binlo upwards (16 octaves of
 // magnitude); anything above goes straight to the global histogram.  That keeps LDS
 // small enough for two 1024-thread workgroups per CU, i.e. a full complement of waves to
-// hide HBM latency.  Slot order inside a chunk comes from ballots, not from a scan, so a
-// wave never waits on another.
+// hide HBM latency.  Slot order inside a chunk comes from a wave-local scan of the
+// per-lane counts, so a wave never waits on another; a chunk's slots are gathered in LDS
+// and leave as one contiguous store per 64 candidates.
 constexpr uint32_t kSpillWindow = 2048;
+constexpr uint32_t kSpillStage = 128;  // slots per chunk staged in LDS (direct stores above)
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
@@ -207,113 +215,185 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                   uint32_t *__restrict__ cand, uint32_t *__restrict__ chunk_cnt,
                   uint64_t n_slots_total, uint32_t CAP)
 {
-    __shared__ uint32_t h[kSpillWindow];
-    __shared__ uint32_t s_route;
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
     constexpr uint32_t ROWS = kCandRows;
     constexpr uint32_t ROW_ELEMS = 64 * VEC;
     constexpr uint32_t CHUNK = ROW_ELEMS * ROWS;
-    constexpr uint32_t CNT_BITS = DTYPE == kBF16 ? 4 : 3;  // a lane holds 0..VEC candidates
+    constexpr uint32_t NW = kHistThreads / 64;
+    constexpr uint32_t STAGE_WORDS = kSpillStage * (DTYPE == kBF16 ? 1 : 2);
+    static_assert(ROWS == 4, "the packed scan below carries four row counts");
+    __shared__ uint32_t h[kSpillWindow];
+    __shared__ uint32_t stage[NW][STAGE_WORDS];
     const uint32_t L = table[0];
+    const uint32_t total_chunks = table[4] * kCandChunksPerSuper;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
     const uint32_t tid = threadIdx.x, lane = tid & 63;
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-    const uint32_t wave = blockIdx.x * (kHistThreads / 64) + (tid >> 6);
-    const uint32_t n_waves = gridDim.x * (kHistThreads / 64);
+    // wave-uniform by construction; saying so keeps chunk addresses in scalar registers
+    const uint32_t wib = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint32_t span = (total_chunks + gridDim.x - 1) / gridDim.x;
+    span = (span + NW - 1) / NW * NW;
+    const uint64_t g0 = uint64_t(blockIdx.x) * span;
+    if (g0 >= total_chunks) return;
+    const uint64_t g1 = min(g0 + span, uint64_t(total_chunks));
     for (uint32_t i = tid; i < kSpillWindow; i += kHistThreads) h[i] = 0;
     __syncthreads();
-    for (uint32_t l = 0; l < L; ++l) {
+    // last segment whose first chunk is not beyond the span's start
+    uint32_t l0 = 0;
+    for (uint32_t hi = L; hi - l0 > 1;) {
+        const uint32_t mid = (l0 + hi) >> 1;
+        if (uint64_t(segs[mid].sc_start) * kCandChunksPerSuper <= g0) l0 = mid;
+        else hi = mid;
+    }
+    uint32_t *st = stage[wib];
+    const bool staged = CAP <= kSpillStage;
+    for (uint32_t l = l0; l < L; ++l) {
         const SegDev sd = segs[l];
+        const uint64_t s0 = uint64_t(sd.sc_start) * kCandChunksPerSuper;
+        if (s0 >= g1) break;
         if (sd.k == 0 || sd.n == 0) continue;
-        // another workgroup may re-route this segment while we look: decide once per
-        // workgroup so that the barriers below stay uniform
-        if (tid == 0) s_route = __hip_atomic_load(&sel[l].route, __ATOMIC_RELAXED,
-                                                  __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        const uint32_t route = s_route;
-        __syncthreads();
-        if (route) continue;
-        const uint32_t blo = binlo[l];  // >= 1
-        uint32_t *gh = hist + uint64_t(l) * kBins1;
-        const char *base = grad + sd.offset * EB;
         const uint32_t n_chunks = (sd.n + CHUNK - 1) / CHUNK;
-        bool overflow = false;
-        for (uint32_t ch = wave; ch < n_chunks; ch += n_waves) {
-            const uint32_t rel0 = ch * CHUNK;
-            uint32_t w[ROWS][4];
+        const uint32_t lo = g0 > s0 ? uint32_t(g0 - s0) : 0u;
+        const uint32_t hi = uint32_t(min(uint64_t(n_chunks), g1 - s0));
+        if (lo >= hi) continue;
+        // Another workgroup may re-route the segment while we look.  Waves that disagree
+        // about it do no harm: a re-routed segment's candidates are never read, and the
+        // barriers below do not depend on the answer.
+        const uint32_t route = __builtin_amdgcn_readfirstlane(
+            __hip_atomic_load(&sel[l].route, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        const uint32_t blo = binlo[l];  // 1 <= blo <= 0x7FFF on this route
+        uint32_t *gh = hist + uint64_t(l) * kBins1;
+        if (!route) {
+            const char *base = grad + sd.offset * EB;
+            const uint32_t swar_add = (0x8000u - blo) * 0x10001u;
+            bool overflow = false;
+            for (uint32_t ch = lo + wib; ch < hi; ch += NW) {
+                const uint32_t rel0 = ch * CHUNK;
+                uint32_t w[ROWS][4];
+                if (rel0 + CHUNK <= sd.n) {
+                    const uint4 *q = reinterpret_cast<const uint4 *>(base + uint64_t(rel0) * EB) + lane;
 #pragma unroll
-            for (uint32_t r = 0; r < ROWS; ++r) {
-                const uint32_t rel = rel0 + r * ROW_ELEMS + lane * VEC;
-                w[r][0] = w[r][1] = w[r][2] = w[r][3] = 0;
-                if (rel + VEC <= sd.n) {
-                    const uint4 q = *reinterpret_cast<const uint4 *>(base + uint64_t(rel) * EB);
-                    w[r][0] = q.x; w[r][1] = q.y; w[r][2] = q.z; w[r][3] = q.w;
-                } else if (rel < sd.n) {
-#pragma unroll
-                    for (uint32_t e = 0; e < VEC; ++e) {
-                        if (rel + e >= sd.n) continue;
-                        const uint32_t b = load_elem_bits(base, uint64_t(rel) + e, DTYPE);
-                        if (DTYPE == kBF16) w[r][e >> 1] |= (b >> 16) << (16 * (e & 1));
-                        else w[r][e] = b;
+                    for (uint32_t r = 0; r < ROWS; ++r) {
+                        const uint4 v = q[64 * r];
+                        w[r][0] = v.x; w[r][1] = v.y; w[r][2] = v.z; w[r][3] = v.w;
                     }
-                }
-            }
-            uint32_t *slots = cand + uint64_t(sd.sc_start * kCandChunksPerSuper + ch) * CAP;
-            uint32_t *slots_pos = slots + n_slots_total;  // fp32 only
-            uint32_t row_base = 0;
+                } else {
 #pragma unroll
-            for (uint32_t r = 0; r < ROWS; ++r) {
-                // branch-free classification of the lane's VEC entries
-                uint32_t m = 0;
+                    for (uint32_t r = 0; r < ROWS; ++r) {
+                        const uint32_t rel = rel0 + r * ROW_ELEMS + lane * VEC;
+                        w[r][0] = w[r][1] = w[r][2] = w[r][3] = 0;
+                        if (rel + VEC <= sd.n) {
+                            const uint4 v = *reinterpret_cast<const uint4 *>(base + uint64_t(rel) * EB);
+                            w[r][0] = v.x; w[r][1] = v.y; w[r][2] = v.z; w[r][3] = v.w;
+                        } else if (rel < sd.n) {
 #pragma unroll
-                for (uint32_t e = 0; e < VEC; ++e) {
-                    const uint32_t bin = (vec_elem_bits<DTYPE>(w[r], e) & 0x7FFFFFFFu) >> 16;
-                    m |= uint32_t(bin >= blo) << e;
-                }
-                // slot of this lane's first candidate: candidates of lower lanes in the row
-                const uint32_t cnt = __popc(m);
-                uint32_t pos = row_base, tot = 0;
-#pragma unroll
-                for (uint32_t bit = 0; bit < CNT_BITS; ++bit) {
-                    const uint64_t bal = __ballot((cnt >> bit) & 1u);
-                    pos += uint32_t(__popcll(bal & lt_mask)) << bit;
-                    tot += uint32_t(__popcll(bal)) << bit;
-                }
-                // candidates are rare: loop over this lane's few set bits only, so the wave
-                // issues as many histogram / store instructions as its busiest lane needs
-                while (m) {
-                    const uint32_t e = __builtin_ctz(m);
-                    m &= m - 1;
-                    uint32_t bits;  // select without indexing the register array
-                    if (DTYPE == kBF16) {
-                        const uint32_t wsel = e < 4 ? (e < 2 ? w[r][0] : w[r][1])
-                                                    : (e < 6 ? w[r][2] : w[r][3]);
-                        bits = (wsel >> (16 * (e & 1))) << 16;
-                    } else {
-                        bits = e < 2 ? (e == 0 ? w[r][0] : w[r][1]) : (e == 2 ? w[r][2] : w[r][3]);
-                    }
-                    const uint32_t bin = (bits & 0x7FFFFFFFu) >> 16, wi = bin - blo;
-                    if (wi < kSpillWindow) atomicAdd(&h[wi], 1u);
-                    else atomicAdd(&gh[bin], 1u);
-                    if (pos < CAP) {
-                        const uint32_t rel = r * ROW_ELEMS + lane * VEC + e;
-                        if (DTYPE == kBF16) {
-                            slots[pos] = bits | rel;
-                        } else {
-                            slots[pos] = bits;
-                            slots_pos[pos] = rel;
+                            for (uint32_t e = 0; e < VEC; ++e) {
+                                if (rel + e >= sd.n) continue;
+                                const uint32_t b = load_elem_bits(base, uint64_t(rel) + e, DTYPE);
+                                if (DTYPE == kBF16) w[r][e >> 1] |= (b >> 16) << (16 * (e & 1));
+                                else w[r][e] = b;
+                            }
                         }
                     }
-                    ++pos;
                 }
-                row_base += tot;
+                // branch-free classification: bit e of m[r] <=> entry e of the lane's vector
+                // in row r is a candidate
+                uint32_t m[ROWS], c[ROWS];
+#pragma unroll
+                for (uint32_t r = 0; r < ROWS; ++r) {
+                    uint32_t f = 0;
+                    if (DTYPE == kBF16) {
+                        // both halves of a word at once: adding 0x8000 - binlo to a 15-bit
+                        // key sets bit 15 exactly when key >= binlo, without carrying over
+#pragma unroll
+                        for (uint32_t j = 0; j < 4; ++j) {
+                            const uint32_t t = ((w[r][j] & 0x7FFF7FFFu) + swar_add) & 0x80008000u;
+                            f |= (t >> 15) << (2 * j);  // low half -> bit 2j, high -> bit 2j+16
+                        }
+                        c[r] = __popc(f);
+                        f = (f & 0xFFFFu) | ((f >> 16) << 1);
+                    } else {
+#pragma unroll
+                        for (uint32_t e = 0; e < VEC; ++e)
+                            f |= uint32_t(((w[r][e] & 0x7FFFFFFFu) >> 16) >= blo) << e;
+                        c[r] = __popc(f);
+                    }
+                    m[r] = f;
+                }
+                // slot of each lane's first candidate per row: one scan over the four
+                // row counts packed in 16-bit fields (a row holds at most 512 candidates)
+                const uint32_t ia = wave_incl_scan<uint32_t>(c[0] | (c[1] << 16));
+                const uint32_t ib = wave_incl_scan<uint32_t>(c[2] | (c[3] << 16));
+                const uint32_t ta = __builtin_amdgcn_readlane(ia, 63);
+                const uint32_t tb = __builtin_amdgcn_readlane(ib, 63);
+                const uint32_t t0 = ta & 0xFFFFu, t1 = ta >> 16, t2 = tb & 0xFFFFu, t3 = tb >> 16;
+                uint32_t pos[ROWS];
+                pos[0] = (ia & 0xFFFFu) - c[0];
+                pos[1] = t0 + (ia >> 16) - c[1];
+                pos[2] = t0 + t1 + (ib & 0xFFFFu) - c[2];
+                pos[3] = t0 + t1 + t2 + (ib >> 16) - c[3];
+                const uint32_t total = t0 + t1 + t2 + t3;
+                const uint64_t chunk_id = s0 + ch;
+                uint32_t *slots = cand + chunk_id * CAP;
+                uint32_t *slots_pos = slots + n_slots_total;  // fp32 only
+#pragma unroll
+                for (uint32_t r = 0; r < ROWS; ++r) {
+                    // candidates are rare: loop over this lane's few set bits only, so the
+                    // wave issues as many histogram / store instructions as its busiest
+                    // lane needs
+                    uint32_t mm = m[r], ps = pos[r];
+                    while (mm) {
+                        const uint32_t e = __builtin_ctz(mm);
+                        mm &= mm - 1;
+                        uint32_t bits;  // select without indexing the register array
+                        if (DTYPE == kBF16) {
+                            const uint32_t wsel = e < 4 ? (e < 2 ? w[r][0] : w[r][1])
+                                                        : (e < 6 ? w[r][2] : w[r][3]);
+                            bits = (wsel >> (16 * (e & 1))) << 16;
+                        } else {
+                            bits = e < 2 ? (e == 0 ? w[r][0] : w[r][1])
+                                         : (e == 2 ? w[r][2] : w[r][3]);
+                        }
+                        const uint32_t bin = (bits & 0x7FFFFFFFu) >> 16, wi = bin - blo;
+                        if (wi < kSpillWindow) atomicAdd(&h[wi], 1u);
+                        else atomicAdd(&gh[bin], 1u);
+                        if (ps < CAP) {
+                            const uint32_t rel = r * ROW_ELEMS + lane * VEC + e;
+                            if (DTYPE == kBF16) {
+                                if (staged) st[ps] = bits | rel;
+                                else slots[ps] = bits | rel;
+                            } else {
+                                if (staged) {
+                                    st[ps] = bits;
+                                    st[kSpillStage + ps] = rel;
+                                } else {
+                                    slots[ps] = bits;
+                                    slots_pos[ps] = rel;
+                                }
+                            }
+                        }
+                        ++ps;
+                    }
+                }
+                if (staged) {
+                    // the wave's own LDS writes, read back by other lanes of the same wave
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    const uint32_t n_out = min(total, CAP);
+                    for (uint32_t i = lane; i < n_out; i += 64) {
+                        slots[i] = st[i];
+                        if (DTYPE != kBF16) slots_pos[i] = st[kSpillStage + i];
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+                if (lane == 0) chunk_cnt[chunk_id] = total;
+                overflow |= total > CAP;
             }
-            if (lane == 0) chunk_cnt[sd.sc_start * kCandChunksPerSuper + ch] = row_base;
-            overflow |= row_base > CAP;
+            if (overflow && lane == 0)  // a chunk denser than its slots: take the dense route
+                atomicOr(&sel[l].route, 1u);
         }
-        if (overflow && lane == 0)  // a chunk denser than its slots: take the dense route
-            atomicOr(&sel[l].route, 1u);
         __syncthreads();
         for (uint32_t i = tid; i < kSpillWindow; i += kHistThreads) {
             const uint32_t c = h[i];
