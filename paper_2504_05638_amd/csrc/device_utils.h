@@ -20,22 +20,28 @@ __device__ inline T wave_incl_scan(T v)
     return v;
 }
 
-// 32-bit inclusive scan on the VALU alone (DPP row shifts, then the two row broadcasts);
-// lanes a shift or a masked-off row does not reach add zero.
+// 32-bit inclusive scan on the VALU alone (DPP row shifts, then the two row broadcasts).
+// A row shift reads zero where it has no source lane; a broadcast leaves the rows it is
+// masked off from unchanged (they add the zero passed as the old value).
+template <int CTRL>
+__device__ inline uint32_t dpp_shr_add(uint32_t x)
+{
+    return x + uint32_t(__builtin_amdgcn_update_dpp(0, int(x), CTRL, 0xF, 0xF, true));
+}
 template <int CTRL, int ROW_MASK>
-__device__ inline uint32_t dpp_add(uint32_t x)
+__device__ inline uint32_t dpp_bcast_add(uint32_t x)
 {
     return x + uint32_t(__builtin_amdgcn_update_dpp(0, int(x), CTRL, ROW_MASK, 0xF, false));
 }
 template <>
 __device__ inline uint32_t wave_incl_scan<uint32_t>(uint32_t x)
 {
-    x = dpp_add<0x111, 0xF>(x);  // row_shr:1
-    x = dpp_add<0x112, 0xF>(x);  // row_shr:2
-    x = dpp_add<0x114, 0xF>(x);  // row_shr:4
-    x = dpp_add<0x118, 0xF>(x);  // row_shr:8
-    x = dpp_add<0x142, 0xA>(x);  // row_bcast:15 into rows 1 and 3
-    x = dpp_add<0x143, 0xC>(x);  // row_bcast:31 into rows 2 and 3
+    x = dpp_shr_add<0x111>(x);          // row_shr:1
+    x = dpp_shr_add<0x112>(x);          // row_shr:2
+    x = dpp_shr_add<0x114>(x);          // row_shr:4
+    x = dpp_shr_add<0x118>(x);          // row_shr:8
+    x = dpp_bcast_add<0x142, 0xA>(x);   // row_bcast:15 into rows 1 and 3
+    x = dpp_bcast_add<0x143, 0xC>(x);   // row_bcast:31 into rows 2 and 3
     return x;
 }
 

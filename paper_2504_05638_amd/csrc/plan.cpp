@@ -140,6 +140,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     off += round_up(L * 4, 16);
     w.chunk_cnt = off;
     off += round_up(chunks * 4, 16);
+    off = round_up(off, 128);  // a chunk's slots then start on a cache-line boundary
     w.cand = off;
     off += round_up(chunks * p->cand_cap * (cfg->dtype == TAGC_F32 ? 8 : 4), 16);
     w.total = std::max<uint64_t>(off, 16);

@@ -199,14 +199,13 @@ sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
 // the LDS histogram has to be flushed behind barriers -- only if its span straddles one,
 // instead of the whole grid draining at every boundary.
 //
-// The LDS histogram only covers the kSpillWindow bins from binlo upwards (16 octaves of
+// The LDS histogram only covers the kSpillWindow bins from binlo upwards (8 octaves of
 // magnitude); anything above goes straight to the global histogram.  That keeps LDS
 // small enough for two 1024-thread workgroups per CU, i.e. a full complement of waves to
 // hide HBM latency.  Slot order inside a chunk comes from a wave-local scan of the
 // per-lane counts, so a wave never waits on another; a chunk's slots are gathered in LDS
 // and leave as one contiguous store per 64 candidates.
-constexpr uint32_t kSpillWindow = 2048;
-constexpr uint32_t kSpillStage = 128;  // slots per chunk staged in LDS (direct stores above)
+constexpr uint32_t kSpillWindow = 1024;
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
@@ -221,10 +220,13 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
     constexpr uint32_t ROW_ELEMS = 64 * VEC;
     constexpr uint32_t CHUNK = ROW_ELEMS * ROWS;
     constexpr uint32_t NW = kHistThreads / 64;
-    constexpr uint32_t STAGE_WORDS = kSpillStage * (DTYPE == kBF16 ? 1 : 2);
-    static_assert(ROWS == 4, "the packed scan below carries four row counts");
+    // slots per chunk gathered in LDS before they are stored (direct stores above that)
+    constexpr uint32_t STAGE = DTYPE == kBF16 ? 128 : 64;
+    constexpr uint32_t STAGE_WORDS = STAGE * (DTYPE == kBF16 ? 1 : 2);
+    static_assert(ROWS == 4 && ROWS * VEC <= 32, "packed masks and row counts below");
     __shared__ uint32_t h[kSpillWindow];
     __shared__ uint32_t stage[NW][STAGE_WORDS];
+    __shared__ uint4 data[NW][ROWS * 64];  // each wave's current chunk
     const uint32_t L = table[0];
     const uint32_t total_chunks = table[4] * kCandChunksPerSuper;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
@@ -246,7 +248,8 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
         else hi = mid;
     }
     uint32_t *st = stage[wib];
-    const bool staged = CAP <= kSpillStage;
+    uint4 *dw = data[wib];
+    const bool staged = CAP <= STAGE;
     for (uint32_t l = l0; l < L; ++l) {
         const SegDev sd = segs[l];
         const uint64_t s0 = uint64_t(sd.sc_start) * kCandChunksPerSuper;
@@ -267,9 +270,9 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
             const char *base = grad + sd.offset * EB;
             const uint32_t swar_add = (0x8000u - blo) * 0x10001u;
             bool overflow = false;
-            for (uint32_t ch = lo + wib; ch < hi; ch += NW) {
+            // the lane's four vectors of chunk `ch`; entries past the segment's end read as 0
+            auto load_chunk = [&](uint32_t ch, uint32_t (&w)[ROWS][4]) {
                 const uint32_t rel0 = ch * CHUNK;
-                uint32_t w[ROWS][4];
                 if (rel0 + CHUNK <= sd.n) {
                     const uint4 *q = reinterpret_cast<const uint4 *>(base + uint64_t(rel0) * EB) + lane;
 #pragma unroll
@@ -296,11 +299,19 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                         }
                     }
                 }
-                // branch-free classification: bit e of m[r] <=> entry e of the lane's vector
-                // in row r is a candidate
-                uint32_t m[ROWS], c[ROWS];
+            };
+            for (uint32_t ch = lo + wib; ch < hi; ch += NW) {
+                uint32_t w[ROWS][4];
+                load_chunk(ch, w);
+                // Keep the chunk in LDS: the few candidates are fetched from there by
+                // position, which is far cheaper than selecting among sixteen registers.
+                // A lane only ever reads back what it wrote itself.
+                // Branch-free classification: bit r*VEC + e of `mask` <=> entry e of the
+                // lane's vector in row r is a candidate.
+                uint32_t mask = 0, c[ROWS];
 #pragma unroll
                 for (uint32_t r = 0; r < ROWS; ++r) {
+                    dw[r * 64 + lane] = make_uint4(w[r][0], w[r][1], w[r][2], w[r][3]);
                     uint32_t f = 0;
                     if (DTYPE == kBF16) {
                         // both halves of a word at once: adding 0x8000 - binlo to a 15-bit
@@ -318,7 +329,7 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                             f |= uint32_t(((w[r][e] & 0x7FFFFFFFu) >> 16) >= blo) << e;
                         c[r] = __popc(f);
                     }
-                    m[r] = f;
+                    mask |= f << (r * VEC);
                 }
                 // slot of each lane's first candidate per row: one scan over the four
                 // row counts packed in 16-bit fields (a row holds at most 512 candidates)
@@ -327,52 +338,44 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                 const uint32_t ta = __builtin_amdgcn_readlane(ia, 63);
                 const uint32_t tb = __builtin_amdgcn_readlane(ib, 63);
                 const uint32_t t0 = ta & 0xFFFFu, t1 = ta >> 16, t2 = tb & 0xFFFFu, t3 = tb >> 16;
-                uint32_t pos[ROWS];
-                pos[0] = (ia & 0xFFFFu) - c[0];
-                pos[1] = t0 + (ia >> 16) - c[1];
-                pos[2] = t0 + t1 + (ib & 0xFFFFu) - c[2];
-                pos[3] = t0 + t1 + t2 + (ib >> 16) - c[3];
+                // exclusive positions, again two per register: rows 0,1 and rows 2,3
+                const uint32_t p01 = ia - (c[0] | (c[1] << 16)) + (t0 << 16);
+                const uint32_t p23 = ib - (c[2] | (c[3] << 16)) + (t0 + t1) * 0x10001u + (t2 << 16);
                 const uint32_t total = t0 + t1 + t2 + t3;
                 const uint64_t chunk_id = s0 + ch;
                 uint32_t *slots = cand + chunk_id * CAP;
                 uint32_t *slots_pos = slots + n_slots_total;  // fp32 only
-#pragma unroll
-                for (uint32_t r = 0; r < ROWS; ++r) {
-                    // candidates are rare: loop over this lane's few set bits only, so the
-                    // wave issues as many histogram / store instructions as its busiest
-                    // lane needs
-                    uint32_t mm = m[r], ps = pos[r];
-                    while (mm) {
-                        const uint32_t e = __builtin_ctz(mm);
-                        mm &= mm - 1;
-                        uint32_t bits;  // select without indexing the register array
+                // Candidates are rare: every lane walks its own few set bits, so the wave
+                // issues as many histogram / store instructions as its busiest lane needs.
+                for (uint32_t mm = mask; mm;) {
+                    const uint32_t e = __builtin_ctz(mm);
+                    mm &= mm - 1;
+                    const uint32_t r = e / VEC;
+                    const uint32_t row_bits = ((1u << VEC) - 1u) << (r * VEC);
+                    const uint32_t before = __popc(mask & row_bits & ((1u << e) - 1u));
+                    const uint32_t ps = (((r & 2u) ? p23 : p01) >> (16 * (r & 1u)) & 0xFFFFu) + before;
+                    const uint32_t rel = r * ROW_ELEMS + lane * VEC + (e % VEC);
+                    uint32_t bits;
+                    if (DTYPE == kBF16)
+                        bits = uint32_t(reinterpret_cast<const uint16_t *>(dw)[rel]) << 16;
+                    else
+                        bits = reinterpret_cast<const uint32_t *>(dw)[rel];
+                    const uint32_t bin = (bits & 0x7FFFFFFFu) >> 16, wi = bin - blo;
+                    if (wi < kSpillWindow) atomicAdd(&h[wi], 1u);
+                    else atomicAdd(&gh[bin], 1u);
+                    if (ps < CAP) {
                         if (DTYPE == kBF16) {
-                            const uint32_t wsel = e < 4 ? (e < 2 ? w[r][0] : w[r][1])
-                                                        : (e < 6 ? w[r][2] : w[r][3]);
-                            bits = (wsel >> (16 * (e & 1))) << 16;
+                            if (staged) st[ps] = bits | rel;
+                            else slots[ps] = bits | rel;
                         } else {
-                            bits = e < 2 ? (e == 0 ? w[r][0] : w[r][1])
-                                         : (e == 2 ? w[r][2] : w[r][3]);
-                        }
-                        const uint32_t bin = (bits & 0x7FFFFFFFu) >> 16, wi = bin - blo;
-                        if (wi < kSpillWindow) atomicAdd(&h[wi], 1u);
-                        else atomicAdd(&gh[bin], 1u);
-                        if (ps < CAP) {
-                            const uint32_t rel = r * ROW_ELEMS + lane * VEC + e;
-                            if (DTYPE == kBF16) {
-                                if (staged) st[ps] = bits | rel;
-                                else slots[ps] = bits | rel;
+                            if (staged) {
+                                st[ps] = bits;
+                                st[STAGE + ps] = rel;
                             } else {
-                                if (staged) {
-                                    st[ps] = bits;
-                                    st[kSpillStage + ps] = rel;
-                                } else {
-                                    slots[ps] = bits;
-                                    slots_pos[ps] = rel;
-                                }
+                                slots[ps] = bits;
+                                slots_pos[ps] = rel;
                             }
                         }
-                        ++ps;
                     }
                 }
                 if (staged) {
@@ -380,10 +383,13 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    const uint32_t n_out = min(total, CAP);
+                    // Whole 128-byte lines: a line written only in part costs the memory
+                    // system a read-modify-write.  The padding words are stale staging
+                    // content, which no reader looks at (the count says how many are real).
+                    const uint32_t n_out = min((total + 31u) & ~31u, CAP);
                     for (uint32_t i = lane; i < n_out; i += 64) {
                         slots[i] = st[i];
-                        if (DTYPE != kBF16) slots_pos[i] = st[kSpillStage + i];
+                        if (DTYPE != kBF16) slots_pos[i] = st[STAGE + i];
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
