@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--dense", type=int, default=1, help="also write the dense summed gradient")
     ap.add_argument("--buckets", type=int, default=0,
                     help="only the first B buckets of the workload (0 = all; for experiments)")
+    ap.add_argument("--lanes", type=int, default=4,
+                    help="buckets in flight at once: bucket i runs on HIP stream i %% lanes with "
+                         "that lane's own buffers (buckets are independent of each other)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="before the timed region, copy this many MiB device to device three "
@@ -198,16 +201,20 @@ def main():
         for k, f in fields.items():
             need[k] = max(need[k], getattr(z, f))
         B.tagc_plan_destroy(plan)
+    lanes = max(1, min(args.lanes, n_b))
     tbs = []
     for i, b in enumerate(buckets):
+        first = i < lanes  # a lane's first bucket owns the buffers the lane's others reuse
         tbs.append(TagcBucket(b.segments, b.dtype, N, sizing_milli=b.sizing_milli,
                               seed=args.seed, dense=bool(args.dense),
-                              share=tbs[0] if tbs else None, min_bytes=need if not tbs else None))
+                              share=None if first else tbs[i % lanes],
+                              min_bytes=need if first else None))
     stream = torch.cuda.current_stream()
+    streams = [stream] + [torch.cuda.Stream() for _ in range(lanes - 1)]
 
-    def step():
+    def step(one_stream=False):
         for i in range(n_b):
-            tbs[i].run(data[i % pool], stream)
+            tbs[i].run(data[i % pool], stream if one_stream else streams[i % lanes])
 
     for _ in range(args.warmup):
         step()
@@ -227,10 +234,12 @@ def main():
     unresolved = rounds = 0
     U_tot = m_tot = k_tot = 0
     flags = 0
+    facts = []
     for i in range(n_b):
         tbs[i].run(data[i % pool], stream)
         torch.cuda.synchronize()
         hdr, st = tbs[i].header(), tbs[i].status()
+        facts.append((hdr, st))
         kt = sum(tbs[i].rank_counts(r)["total"] for r in range(N))
         flags |= st["flags"]
         for r in range(N):
@@ -257,17 +266,29 @@ def main():
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
     ms_per_step = 1e3 * t_total / args.steps
+    # the buffers now hold each lane's last bucket: it must have come out as it did alone
+    for i in range(n_b - lanes, n_b):
+        hdr, st = tbs[i].header(), tbs[i].status()
+        bad = st["flags"]
+        for r in range(N):
+            bad |= tbs[i].rank_counts(r)["flags"]
+        if bad or (hdr, st) != facts[i]:
+            sys.stderr.write("bench.py: bucket %d differs when run with %d buckets in flight "
+                             "(flags %d)\n" % (i, lanes, bad))
+            sys.exit(1)
     value = input_bytes / (ms_per_step * 1e-3) / 1e9
     balg_total = sum(balg.values())
 
-    # ---- same K steps again with the library's per-kernel HIP events switched on
+    # ---- same K steps again with the library's per-kernel HIP events switched on, one
+    # bucket at a time on one stream: a kernel's duration is then its own, not that of
+    # whatever shared the device with it
     stages, roofline = {}, None
     if not args.no_profile_pass:
         B.tagc_profile_enable(True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            step()
+            step(one_stream=True)
         torch.cuda.synchronize()
         t_prof = time.perf_counter() - t0
         prof = B.tagc_profile_read(64)
@@ -294,6 +315,8 @@ def main():
                     "traffic": MEASURED_TRAFFIC.get((args.workload, dom)),
                     "avg_launch_ms": round(avg_ms, 5), "launches": d_n,
                     "alg_bytes_per_launch": int(per_launch),
+                    "events_pass": "same steps, one bucket in flight, HIP events around "
+                                   "every kernel on its stream",
                     "events_pass_ms_per_step": round(1e3 * t_prof / args.steps, 3),
                     "kernels_ms_per_step": {k: round(v[0] / args.steps, 4)
                                             for k, v in sorted(prof.items(),
@@ -311,6 +334,7 @@ def main():
                                   buckets[0].sizing_milli / 1000.0,
                                   "sparse+dense output" if args.dense else "sparse output"),
                    "input_bytes_per_step": input_bytes, "distinct_bucket_data_sets": pool,
+                   "buckets_in_flight": lanes,
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "peel_rounds_max": rounds, "input_generation_s": round(t_gen, 2)},

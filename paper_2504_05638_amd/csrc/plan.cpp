@@ -45,6 +45,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     p->tile_elems = kCompactThreads * p->vec_elems * kCompactRows;
     p->chunk_elems = 64 * p->vec_elems * kCandRows;
     p->cand_cap = 32;
+    p->static_dense = false;
     for (uint32_t j = 0; j < 3; ++j) p->seed_word[j] = seed_word(cfg->seed, j);
 
     uint64_t c = 0, n_real = 0, K = 0, tiles = 0, grad_elems = 0, scs = 0;
@@ -80,6 +81,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
                     p->cand_cap = std::max(p->cand_cap, cap);
                 }
             }
+            if (d.k && d.n && !(d.flags & kSegFast)) p->static_dense = true;
             d.sc_start = uint32_t(scs);
             scs += ceil_div(s.length, uint64_t(p->chunk_elems) * kCandChunksPerSuper);
             p->table.push_back(d);

@@ -665,10 +665,11 @@ constexpr uint64_t kStAgg = 1ull << 62, kStPre = 2ull << 62, kStMask = 3ull << 6
 
 // Decoupled look-back over the work items (tiles / super-chunks) of one segment, run by
 // the first wave of the workgroup.  state word = status(2) | count(key > T)(31) |
-// count(key == T)(31).  The grid is persistent and fully resident, and workgroup b takes
-// items b, b+G, b+2G, ...; so every predecessor this waits for belongs to a workgroup that
-// is running and that publishes its counts without waiting for any later item.  The wait
-// is bounded all the same: after kSpinLimit polls it gives up and raises a flag.
+// count(key == T)(31).  Workgroup b takes items b, b+G, b+2G, ... of a grid of G.  With one
+// item per workgroup every predecessor belongs to a lower-numbered workgroup, dispatched
+// earlier, which publishes its counts without waiting for any later item; with several
+// items per workgroup the same holds only while the whole grid is resident.  The wait is
+// bounded all the same: after kSpinLimit polls it gives up and raises a flag.
 __device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, uint64_t agg,
                                     uint32_t *flags)
 {
@@ -734,8 +735,10 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // The prefix over earlier super-chunks has no chain: an item publishes its own counts,
 // then the workgroup adds up the counts of all predecessors in its segment, each thread
 // waiting (bounded) only for the words it reads.  A predecessor publishes right after
-// counting and waits for nobody before that, and it belongs to a workgroup of the same
-// resident grid (items are dealt out in increasing order), so the wait ends.
+// counting and waits for nobody before that.  The launch has one workgroup per NI adjacent
+// items, so a predecessor always belongs to this or a lower-numbered workgroup, which the
+// hardware has dispatched before this one: the wait ends however few workgroups are
+// resident at a time (other streams may be using the device).
 constexpr int kEmitItems = 2;
 constexpr uint32_t kEmitMaxSegTable = 1024;
 
@@ -777,7 +780,9 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
         __syncthreads();
     }
 
-    for (uint32_t base = blockIdx.x; base < total_sc; base += gridDim.x * NI) {
+    // Workgroup b owns the adjacent super-chunks NI*b .. NI*b+NI-1 (the loop only runs more
+    // than once if the launch was given fewer workgroups than ceil(total_sc / NI)).
+    for (uint32_t base = blockIdx.x * NI; base < total_sc; base += gridDim.x * NI) {
         // ---- per item: segment, threshold, this thread's slot range
         uint32_t sc[NI], l[NI], c_off[NI], n_seg[NI], sc_rel0[NI], sc_first[NI];
         uint32_t T[NI], quota[NI], s0[NI], s1[NI], ccnt[NI];
@@ -785,7 +790,7 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
         bool live[NI];
 #pragma unroll
         for (int k = 0; k < NI; ++k) {
-            sc[k] = base + k * gridDim.x;
+            sc[k] = base + k;
             live[k] = sc[k] < total_sc;
             const uint32_t scc = live[k] ? sc[k] : 0u;
             l[k] = segment_of(L, scc, [&](uint32_t i) { return segs[i].sc_start; });
@@ -1120,7 +1125,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     const int cus = device_cu_count();
     const size_t lds_hist = kBins1 * sizeof(uint32_t);
     static bool a_sample = false, a_hist = false;
-    static int occ_emit = 0, occ_compact = 0;
+    static int occ_compact = 0;
 
     if (L == 0) {  // nothing is compressed: only the counts have to read zero
         ProfileScope ps("fill_zero", s);
@@ -1172,10 +1177,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     if (p->total_sc) {
         ProfileScope ps("emit", s);
-        const int occ = resident_blocks_per_cu(emit_kernel<DTYPE>, kEmitThreads, 0, &occ_emit);
-        if (occ <= 0) return TAGC_EHIP;
-        const uint32_t grid = std::min<uint32_t>((p->total_sc + kEmitItems - 1) / kEmitItems,
-                                                 uint32_t(cus) * uint32_t(occ));
+        const uint32_t grid = (p->total_sc + kEmitItems - 1) / kEmitItems;
         emit_kernel<DTYPE><<<grid, kEmitThreads, 0, s>>>(table, sel, cand, chunk_cnt, n_slots,
                                                          p->cand_cap, sc_state, rk->idx, rk->val,
                                                          rk->bitmap, rk->cnt);
@@ -1185,7 +1187,16 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         const int occ =
             resident_blocks_per_cu(compact_kernel<DTYPE>, kCompactThreads, 0, &occ_compact);
         if (occ <= 0) return TAGC_EHIP;
-        const uint32_t grid = std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
+        // One tile per workgroup when dense-route work is certain: a tile's look-back then
+        // only ever waits for lower-numbered workgroups, which were dispatched before it,
+        // so it ends no matter how few workgroups the device can hold at the moment.  When
+        // no segment is planned for this route the kernel is only a safety net for
+        // re-routed segments and nearly always exits at once; a small persistent grid
+        // keeps that cheap (its look-back then assumes the grid is resident as a whole
+        // and gives up with TAGC_FLAG_SPIN_LIMIT if that fails).
+        const uint32_t grid = p->static_dense
+                                  ? p->total_tiles
+                                  : std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
         compact_kernel<DTYPE><<<grid, kCompactThreads, 0, s>>>(
             g, table, sel, tile_state, rk->idx, rk->val, rk->bitmap, rk->cnt);
     }

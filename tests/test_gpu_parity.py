@@ -266,3 +266,37 @@ def test_candidate_route_fallbacks(dtype, kind):
     compare_all(b, ores, tb, exact_values=kind in ("all_equal", "two_valued", "ints"))
     if kind != "ints":   # (a 2 % tie class at the threshold still fits the slots)
         assert tb.rank_counts(0)["dense_segments"] == 1     # the shortcut was abandoned
+
+
+def test_buckets_in_flight_on_separate_streams():
+    """Three different buckets issued round-robin on three HIP streams, three rounds
+    each, with both sparsifier routes and several super-chunks in play: every bucket
+    must come out as it does alone (no state shared between plans, no kernel that
+    needs the device to itself)."""
+    from paper_2504_05638_amd.bucket import TagcBucket
+    from tests.helpers import oracle_config, oracle_segments
+    _announce("three buckets in flight")
+    routes = G.Bucket("routes", G.BF16, 3,
+                      [G.Seg(0, (1 << 18) + 13, 10_000, 1, "long_ragged"),
+                       G.Seg(262_168, 5000, 20_000, 1, "short"),
+                       G.Seg(267_176, (1 << 17), 50_000, 1, "long_dense_keep"),
+                       G.Seg(398_251, (1 << 17) + 64, 10_000, 1, "long_unaligned"),
+                       G.Seg(529_392, 300_000, 100, 1, "long_tiny_k")], 829_392, 1500,
+                      {"long_ragged": 1e-3, "short": 1e-2, "long_dense_keep": 1e-4,
+                       "long_unaligned": 3e-3, "long_tiny_k": 1e-3})
+    buckets = [routes, G.config1(seed=4, n=(1 << 22) + 777, n_ranks=3),
+               G.small_mixed_bucket(seed=8, dtype=G.BF16, n_ranks=3, sizing_milli=2000)]
+    grads = [_grads(b) for b in buckets]
+    dev = [[g.cuda() for g in gs] for gs in grads]
+    tbs = [TagcBucket(b.segments, b.dtype, b.n_ranks, sizing_milli=b.sizing_milli, seed=11 + i,
+                      dense=True) for i, b in enumerate(buckets)]
+    streams = [torch.cuda.Stream() for _ in buckets]
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for tb, d, s in zip(tbs, dev, streams):
+            tb.run(d, s)
+    torch.cuda.synchronize()
+    for i, (b, gs, tb) in enumerate(zip(buckets, grads, tbs)):
+        ores = O.run_bucket([G.to_numpy_raw(g) for g in gs], oracle_config(b, seed=11 + i),
+                            oracle_segments(b))
+        compare_all(b, ores, tb)
