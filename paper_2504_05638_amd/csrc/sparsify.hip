@@ -199,16 +199,29 @@ sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
 // the LDS histogram has to be flushed behind barriers -- only if its span straddles one,
 // instead of the whole grid draining at every boundary.
 //
-// The LDS histogram only covers the kSpillWindow bins from binlo upwards (8 octaves of
-// magnitude); anything above goes straight to the global histogram.  That keeps LDS
-// small enough for two 1024-thread workgroups per CU, i.e. a full complement of waves to
-// hide HBM latency.  Slot order inside a chunk comes from a wave-local scan of the
-// per-lane counts, so a wave never waits on another; a chunk's slots are gathered in LDS
-// and leave as one contiguous store per 64 candidates.
-constexpr uint32_t kSpillWindow = 1024;
+// Memory operations of a wave complete, as far as the wave can tell, in the order they
+// were issued, and a store is acknowledged later than a load returns: a wave that stores
+// a chunk's slots and then loads the next chunk waits for the acknowledgement as well,
+// about a microsecond per chunk.  So the steady state of this kernel issues loads only.
+// The next chunk is requested while the current one is processed, and the slots of a
+// dozen chunks pile up in the wave's LDS staging area and leave together (when the area
+// is full, and at the end), at which point nothing is waiting behind the stores.
+//
+// Two 512-thread workgroups per CU.  With the next chunk always in flight that keeps about
+// 32 MB of requests outstanding, enough to saturate HBM; more only lengthens the queue the
+// last workgroups to start wait in, and they keep that lag to the end of the kernel.  The
+// LDS pays for the chunk buffer (candidates are fetched from it by position instead of
+// being selected out of sixteen registers) and the staging area.  The LDS histogram only
+// covers the kSpillWindow bins from binlo upwards (6 octaves of magnitude); anything above
+// goes straight to the global one.  Slot order inside a chunk comes from a wave-local scan
+// of the per-lane counts, so a wave never waits on another.
+constexpr uint32_t kSpillWindow = 768;
+constexpr uint32_t kSpillThreads = 512;
+constexpr uint32_t kSpillStage = 512;  // staged slots per wave
+constexpr uint32_t kSpillList = 16;    // staged chunks per wave
 
 template <int DTYPE>
-__global__ void __launch_bounds__(kHistThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+__global__ void __launch_bounds__(kSpillThreads)
 scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
                   SelDev *sel, const uint32_t *__restrict__ binlo, uint32_t *__restrict__ hist,
                   uint32_t *__restrict__ cand, uint32_t *__restrict__ chunk_cnt,
@@ -219,14 +232,13 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
     constexpr uint32_t ROWS = kCandRows;
     constexpr uint32_t ROW_ELEMS = 64 * VEC;
     constexpr uint32_t CHUNK = ROW_ELEMS * ROWS;
-    constexpr uint32_t NW = kHistThreads / 64;
-    // slots per chunk gathered in LDS before they are stored (direct stores above that)
-    constexpr uint32_t STAGE = DTYPE == kBF16 ? 128 : 64;
-    constexpr uint32_t STAGE_WORDS = STAGE * (DTYPE == kBF16 ? 1 : 2);
+    constexpr uint32_t NW = kSpillThreads / 64;
+    constexpr uint32_t STAGE_WORDS = kSpillStage * (DTYPE == kBF16 ? 1 : 2);
     static_assert(ROWS == 4 && ROWS * VEC <= 32, "packed masks and row counts below");
     __shared__ uint32_t h[kSpillWindow];
     __shared__ uint32_t stage[NW][STAGE_WORDS];
-    __shared__ uint4 data[NW][ROWS * 64];  // each wave's current chunk
+    __shared__ uint32_t list[NW][3][kSpillList];  // chunk number, staging offset, count
+    __shared__ uint4 data[NW][ROWS * 64];         // each wave's current chunk
     const uint32_t L = table[0];
     const uint32_t total_chunks = table[4] * kCandChunksPerSuper;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
@@ -238,7 +250,7 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
     const uint64_t g0 = uint64_t(blockIdx.x) * span;
     if (g0 >= total_chunks) return;
     const uint64_t g1 = min(g0 + span, uint64_t(total_chunks));
-    for (uint32_t i = tid; i < kSpillWindow; i += kHistThreads) h[i] = 0;
+    for (uint32_t i = tid; i < kSpillWindow; i += kSpillThreads) h[i] = 0;
     __syncthreads();
     // last segment whose first chunk is not beyond the span's start
     uint32_t l0 = 0;
@@ -248,8 +260,35 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
         else hi = mid;
     }
     uint32_t *st = stage[wib];
+    uint32_t *lst_chunk = list[wib][0], *lst_off = list[wib][1], *lst_cnt = list[wib][2];
     uint4 *dw = data[wib];
-    const bool staged = CAP <= STAGE;
+    const bool staged = CAP <= kSpillStage;
+    uint32_t n_list = 0, fill = 0;  // wave-uniform
+
+    // the staged chunks' slots and counts go out; only this wave touched what it reads
+    auto flush = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (uint32_t e = 0; e < n_list; ++e) {
+            const uint32_t off = lst_off[e];
+            // Whole 128-byte lines: a line written only in part costs the memory system a
+            // read-modify-write.  The padding words are stale staging content, which no
+            // reader looks at (the count says how many are real).
+            const uint32_t n_out = min((lst_cnt[e] + 31u) & ~31u, CAP);
+            uint32_t *slots = cand + uint64_t(lst_chunk[e]) * CAP;
+            for (uint32_t i = lane; i < n_out; i += 64) {
+                slots[i] = st[off + i];
+                if (DTYPE != kBF16) slots[n_slots_total + i] = st[kSpillStage + off + i];
+            }
+        }
+        if (lane < n_list) chunk_cnt[lst_chunk[lane]] = lst_cnt[lane];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        n_list = 0;
+        fill = 0;
+    };
+
     for (uint32_t l = l0; l < L; ++l) {
         const SegDev sd = segs[l];
         const uint64_t s0 = uint64_t(sd.sc_start) * kCandChunksPerSuper;
@@ -300,12 +339,10 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                     }
                 }
             };
+            uint32_t w[ROWS][4];
+            if (lo + wib < hi) load_chunk(lo + wib, w);
             for (uint32_t ch = lo + wib; ch < hi; ch += NW) {
-                uint32_t w[ROWS][4];
-                load_chunk(ch, w);
-                // Keep the chunk in LDS: the few candidates are fetched from there by
-                // position, which is far cheaper than selecting among sixteen registers.
-                // A lane only ever reads back what it wrote itself.
+                // Keep the chunk in LDS (a lane only ever reads back what it wrote itself).
                 // Branch-free classification: bit r*VEC + e of `mask` <=> entry e of the
                 // lane's vector in row r is a candidate.
                 uint32_t mask = 0, c[ROWS];
@@ -331,6 +368,7 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                     }
                     mask |= f << (r * VEC);
                 }
+                if (ch + NW < hi) load_chunk(ch + NW, w);  // in flight during the rest
                 // slot of each lane's first candidate per row: one scan over the four
                 // row counts packed in 16-bit fields (a row holds at most 512 candidates)
                 const uint32_t ia = wave_incl_scan<uint32_t>(c[0] | (c[1] << 16));
@@ -342,9 +380,12 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                 const uint32_t p01 = ia - (c[0] | (c[1] << 16)) + (t0 << 16);
                 const uint32_t p23 = ib - (c[2] | (c[3] << 16)) + (t0 + t1) * 0x10001u + (t2 << 16);
                 const uint32_t total = t0 + t1 + t2 + t3;
-                const uint64_t chunk_id = s0 + ch;
-                uint32_t *slots = cand + chunk_id * CAP;
+                const uint32_t chunk_id = uint32_t(s0) + ch;
+                const uint32_t need = min((total + 31u) & ~31u, CAP);
+                if (staged && (n_list == kSpillList || fill + need > kSpillStage)) flush();
+                uint32_t *slots = cand + uint64_t(chunk_id) * CAP;
                 uint32_t *slots_pos = slots + n_slots_total;  // fp32 only
+                uint32_t *stc = st + fill;
                 // Candidates are rare: every lane walks its own few set bits, so the wave
                 // issues as many histogram / store instructions as its busiest lane needs.
                 for (uint32_t mm = mask; mm;) {
@@ -365,12 +406,12 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                     else atomicAdd(&gh[bin], 1u);
                     if (ps < CAP) {
                         if (DTYPE == kBF16) {
-                            if (staged) st[ps] = bits | rel;
+                            if (staged) stc[ps] = bits | rel;
                             else slots[ps] = bits | rel;
                         } else {
                             if (staged) {
-                                st[ps] = bits;
-                                st[STAGE + ps] = rel;
+                                stc[ps] = bits;
+                                stc[kSpillStage + ps] = rel;
                             } else {
                                 slots[ps] = bits;
                                 slots_pos[ps] = rel;
@@ -379,29 +420,24 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                     }
                 }
                 if (staged) {
-                    // the wave's own LDS writes, read back by other lanes of the same wave
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    // Whole 128-byte lines: a line written only in part costs the memory
-                    // system a read-modify-write.  The padding words are stale staging
-                    // content, which no reader looks at (the count says how many are real).
-                    const uint32_t n_out = min((total + 31u) & ~31u, CAP);
-                    for (uint32_t i = lane; i < n_out; i += 64) {
-                        slots[i] = st[i];
-                        if (DTYPE != kBF16) slots_pos[i] = st[STAGE + i];
+                    if (lane == 0) {
+                        lst_chunk[n_list] = chunk_id;
+                        lst_off[n_list] = fill;
+                        lst_cnt[n_list] = total;
                     }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
+                    ++n_list;
+                    fill += need;
+                } else if (lane == 0) {
+                    chunk_cnt[chunk_id] = total;
                 }
-                if (lane == 0) chunk_cnt[chunk_id] = total;
                 overflow |= total > CAP;
             }
+            if (staged) flush();
             if (overflow && lane == 0)  // a chunk denser than its slots: take the dense route
                 atomicOr(&sel[l].route, 1u);
         }
         __syncthreads();
-        for (uint32_t i = tid; i < kSpillWindow; i += kHistThreads) {
+        for (uint32_t i = tid; i < kSpillWindow; i += kSpillThreads) {
             const uint32_t c = h[i];
             if (c) {
                 atomicAdd(&gh[blo + i], c);
@@ -1146,7 +1182,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
-        scan_spill_kernel<DTYPE><<<cus * 2, kHistThreads, 0, s>>>(
+        scan_spill_kernel<DTYPE><<<cus * 2, kSpillThreads, 0, s>>>(
             g, table, sel, binlo, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
     }
     {
