@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 STAGES = {
     "S1+S2 sparsify+index": ["fill_zero", "sample", "scan_spill", "select1", "hist1", "select1d",
                              "hist2c", "hist2", "select2", "emit", "compact"],
-    "S3a index OR": ["index_or", "header", "bounds"],
+    "S3a index OR": ["index_or", "header", "bounds", "ranges"],
     "S2' encode": ["encode"],
     "S3b sketch sum": ["sketch_sum"],
     "S4 decode": ["enumerate", "peel", "dense"],

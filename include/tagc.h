@@ -126,6 +126,9 @@ enum {
     TAGC_CNT_DENSE = 3,     /* segments that took the two-read route (diagnostic) */
     TAGC_CNT_SEG0 = 4       /* [4 + l] = pairs of compressed segment l           */
 };
+/* Behind the counts (rank_cnt_bytes covers it) tagc_aggregate(PHASE_INDEX) leaves,
+ * for every rank it is given, the A + 1 positions at which that rank's sorted
+ * pair list crosses the partition bounds; PHASE_SKETCH reads them. */
 /* shared `header` words (uint32), written by tagc_aggregate(PHASE_INDEX) */
 enum {
     TAGC_HDR_U = 0,       /* non-zeros of the merged Index                       */
@@ -148,7 +151,7 @@ enum {
 typedef struct tagc_rank_buffers {
     uint32_t *idx;      /* [pair_capacity] c-indices of survivors, ascending    */
     float *val;         /* [pair_capacity] their values widened to float32      */
-    uint32_t *cnt;      /* [4 + n_seg_compressed] see TAGC_CNT_*                */
+    uint32_t *cnt;      /* [rank_cnt_bytes / 4] see TAGC_CNT_*                  */
     uint32_t *bitmap;   /* [bitmap_words] local Index, bit j in word j>>5, bit
                            j&31                                                 */
     float *sketch;      /* [sketch_cells_capacity] local Count Sketch; cells
@@ -198,8 +201,10 @@ int tagc_plan_upload(const tagc_plan_t *plan, void *table_dev, void *stream);
  *   rank->idx / rank->val, counts to rank->cnt, and the local Index to
  *   rank->bitmap (every word is written).  Uses rank->workspace.
  * PHASE_SKETCH (Algorithm 1: compress(g_shard, index)).  Needs the shared
- *   header and bounds written by tagc_aggregate(PHASE_INDEX) and this rank's
- *   pairs; hashes every pair with the three hash functions into the rank's
+ *   header written by tagc_aggregate(PHASE_INDEX), which must have been given
+ *   this rank among its `ranks` (it leaves the rank's partition ranges in
+ *   rank->cnt), and this rank's pairs; hashes every pair with the three hash
+ *   functions into the rank's
  *   Count Sketch, cells [0, m) of rank->sketch (all of them are written).
  * Both phases read shared->table.
  */
@@ -212,7 +217,9 @@ int tagc_compress(const tagc_plan_t *plan, uint32_t phase, const void *grad_dev,
  * PHASE_INDEX : shared->bitmap = OR over ranks[r].bitmap (section 2.2: OR is
  *   the operation the Index needs); counts its non-zeros U, derives the sketch
  *   layout (A, m_sub, m) and the partition bounds; writes shared->header,
- *   shared->bounds; clears shared->status.
+ *   shared->bounds; clears shared->status; locates the bounds in every given
+ *   rank's pair list (ranks[r].idx, ranks[r].cnt are read, the ranges written
+ *   behind the counts in ranks[r].cnt).
  * PHASE_SKETCH: shared->sketch[c] = ((ranks[0].sketch[c] + ranks[1].sketch[c])
  *   + ...) in rank order, float32, for c < m.
  * `ranks` is a host array of n_ranks structs (1 <= n_ranks <= config.n_ranks).

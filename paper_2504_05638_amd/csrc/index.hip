@@ -153,6 +153,31 @@ bounds_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words, uint32_t n_
     }
 }
 
+// ranges[a] of rank r = number of the rank's pairs whose c-index lies below bounds[a]: the
+// pairs of partition a are [ranges[a], ranges[a+1]) of its sorted list.  One thread per
+// (rank, boundary); a binary search costs ~20 dependent loads, but all of them run at once
+// and the encoder's workgroups, which used to search as they started, no longer wait.
+__global__ void __launch_bounds__(256)
+ranges_kernel(RankPtrs idx, RankPtrs cnt, uint32_t n_in, const uint32_t *__restrict__ header,
+              const uint32_t *__restrict__ bounds, uint32_t A_cap, uint32_t ranges_off,
+              uint32_t pair_cap)
+{
+    const uint32_t A = header[TAGC_HDR_A];
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+    const uint32_t r = t / (A_cap + 1), a = t % (A_cap + 1);
+    if (r >= n_in || a > A) return;
+    uint32_t *c = static_cast<uint32_t *>(const_cast<void *>(cnt.p[r]));
+    const uint32_t *ix = static_cast<const uint32_t *>(idx.p[r]);
+    const uint32_t n = min(c[TAGC_CNT_TOTAL], pair_cap);
+    const uint32_t key = bounds[a];
+    uint32_t lo = 0, hi = n;  // first position whose c-index is >= key
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (ix[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    c[ranges_off + a] = lo;
+}
+
 }  // namespace
 
 int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32_t n_ranks,
@@ -183,6 +208,21 @@ int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32
         const uint32_t grid = uint32_t((p->A_cap + 1 + 3) / 4);
         bounds_kernel<<<grid, 256, 0, s>>>(sh->bitmap, n_words, uint32_t(p->n_c), chunk, n_chunks,
                                            sh->header, sh->bounds);
+    }
+    if (n_chunks) {
+        ProfileScope ps("ranges", s);
+        for (uint32_t r0 = 0; r0 < n_ranks; r0 += kMaxRanksPerPass) {
+            RankPtrs ri{}, rc{};
+            const uint32_t n_in = std::min(kMaxRanksPerPass, n_ranks - r0);
+            for (uint32_t r = 0; r < n_in; ++r) {
+                ri.p[r] = ranks[r0 + r].idx;
+                rc.p[r] = ranks[r0 + r].cnt;
+            }
+            const uint64_t threads = uint64_t(n_in) * (p->A_cap + 1);
+            ranges_kernel<<<uint32_t((threads + 255) / 256), 256, 0, s>>>(
+                ri, rc, n_in, sh->header, sh->bounds, uint32_t(p->A_cap), p->cnt_ranges,
+                uint32_t(p->K));
+        }
     }
     return hip_ok(hipGetLastError());
 }

@@ -163,7 +163,10 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     z.table_bytes = 32 + 32 * std::max<uint64_t>(L, 1);
     z.rank_idx_bytes = round_up(4 * std::max<uint64_t>(K, 1), 16);
     z.rank_val_bytes = z.rank_idx_bytes;
-    z.rank_cnt_bytes = round_up(4 * (TAGC_CNT_SEG0 + L), 16);
+    // counts first, then (from the Index aggregation on) the A+1 positions at which the
+    // rank's sorted pair list crosses the partition bounds
+    p->cnt_ranges = uint32_t(round_up(TAGC_CNT_SEG0 + L, 4));
+    z.rank_cnt_bytes = round_up(4 * (p->cnt_ranges + p->A_cap + 2), 16);
     z.rank_bitmap_bytes = round_up(4 * std::max<uint64_t>(words, 1), 16);
     z.rank_sketch_bytes = round_up(4 * p->m_cap, 16);
     z.rank_workspace_bytes = w.total;
