@@ -759,24 +759,37 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 
 // ------------------------------------------------------------------- emit
 
-// Candidate route, final pass.  A workgroup handles kEmitItems super-chunks (32 chunks
-// each) per iteration: 8 threads per chunk, each owning CAP/8 consecutive slots, which it
-// classifies against the exact threshold twice -- once to count, once (after the workgroup
-// scan and the prefix over the segment's earlier super-chunks) to write the survivors in
-// ascending c-index.  Every step is latency-bound (a dependent memory access costs 2-3 us
-// under load), so the items of an iteration go through each step together: their loads
-// are in flight at the same time.  A super-chunk's Index words are assembled in LDS and
-// written whole, zeros included.
+// Candidate route, final pass.  A workgroup handles kEmitItems adjacent super-chunks (32
+// chunks each), two waves per super-chunk: 4 threads per chunk share the chunk's slots
+// evenly, in order, and classify them against the exact threshold twice -- once to count,
+// once (after the scan over the item's threads and the prefix over the segment's earlier
+// super-chunks) to place the survivors in ascending c-index; the second pass finds the
+// slots in the cache.  A super-chunk's Index words are assembled in LDS and written
+// whole, zeros included.
+//
+// Every step is latency-bound (a dependent memory access costs 1-3 us under load), so the
+// kernel is built to need few of them in a row and to be resident all at once (one item's
+// state per thread keeps the register count low enough for that).  Everything whose
+// address follows from the workgroup number alone is requested at once: the chunk counts,
+// and -- lane i taking segment i -- the whole segment and selection tables, from which the
+// item's segment, its threshold and the pair offset of the segment come by ballot,
+// readlane and a wave sum (tables of more than 64 segments take a slower path).
+//
+// An item's survivors are consecutive in the output.  Stored entry by entry, each wave
+// instruction would touch 64 different cache lines (measured: 60 % of the kernel's time);
+// so the first kEmitStage of them are placed in LDS and leave as contiguous stores, and
+// only what exceeds that (items keeping more than about 1 %) is stored directly.
 //
 // The prefix over earlier super-chunks has no chain: an item publishes its own counts,
-// then the workgroup adds up the counts of all predecessors in its segment, each thread
+// then its threads add up the counts of all predecessors in its segment, each thread
 // waiting (bounded) only for the words it reads.  A predecessor publishes right after
-// counting and waits for nobody before that.  The launch has one workgroup per NI adjacent
-// items, so a predecessor always belongs to this or a lower-numbered workgroup, which the
-// hardware has dispatched before this one: the wait ends however few workgroups are
-// resident at a time (other streams may be using the device).
+// counting and waits for nobody before that.  The launch has one workgroup per
+// kEmitItems adjacent items, so a predecessor always belongs to this or a lower-numbered
+// workgroup, which the hardware has dispatched before this one: the wait ends however few
+// workgroups are resident at a time (other streams may be using the device).
 constexpr int kEmitItems = 2;
-constexpr uint32_t kEmitMaxSegTable = 1024;
+constexpr uint32_t kEmitStage = 640;  // survivors of an item that go through LDS
+static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kEmitThreads)
@@ -791,170 +804,189 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
     constexpr uint32_t SC_ELEMS = CHUNK * kCandChunksPerSuper;
     constexpr uint32_t SC_WORDS = SC_ELEMS / 32;
     constexpr int NI = kEmitItems;
-    constexpr int NW = kEmitThreads / 64;
     __shared__ uint32_t bits[NI][SC_WORDS];
-    __shared__ uint64_t s_scan[NW];
-    __shared__ uint32_t s_segbase[kEmitMaxSegTable];  // pairs emitted by earlier segments
+    __shared__ uint32_t st_idx[NI][kEmitStage];
+    __shared__ float st_val[NI][kEmitStage];
+    __shared__ uint32_t s_gt[2 * NI], s_eq[2 * NI];
+    __shared__ uint64_t s_sum[2 * NI];
     const uint32_t L = table[0], total_sc = table[4];
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
-    const uint32_t tid = threadIdx.x;
-    const uint32_t ch_in_sc = tid >> 3, part = tid & 7;
-    const uint32_t R = CAP / 8;  // slots per thread, a multiple of 4
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t k = wave >> 1;  // this wave's item within the workgroup
+    const uint32_t tt = tid & 127;
+    const uint32_t ch_in_sc = tt >> 2, part = tt & 3;
 
-    // pair offset of every segment (exclusive prefix of the segments' counts)
-    {
-        uint32_t running = 0;
-        uint32_t *scan32 = reinterpret_cast<uint32_t *>(s_scan);
-        for (uint32_t base = 0; base < min(L, kEmitMaxSegTable); base += kEmitThreads) {
-            const uint32_t i = base + tid;
-            uint32_t tot;
-            const uint32_t v = i < L ? sel[i].cnt : 0u;
-            const uint32_t ex = block_excl_scan<uint32_t, NW>(v, &tot, scan32);
-            if (i < kEmitMaxSegTable) s_segbase[i] = running + ex;
-            running += tot;
-        }
-        __syncthreads();
-    }
-
-    // Workgroup b owns the adjacent super-chunks NI*b .. NI*b+NI-1 (the loop only runs more
-    // than once if the launch was given fewer workgroups than ceil(total_sc / NI)).
     for (uint32_t base = blockIdx.x * NI; base < total_sc; base += gridDim.x * NI) {
-        // ---- per item: segment, threshold, this thread's slot range
-        uint32_t sc[NI], l[NI], c_off[NI], n_seg[NI], sc_rel0[NI], sc_first[NI];
-        uint32_t T[NI], quota[NI], s0[NI], s1[NI], ccnt[NI];
-        const uint32_t *sp[NI];
-        bool live[NI];
-#pragma unroll
-        for (int k = 0; k < NI; ++k) {
-            sc[k] = base + k;
-            live[k] = sc[k] < total_sc;
-            const uint32_t scc = live[k] ? sc[k] : 0u;
-            l[k] = segment_of(L, scc, [&](uint32_t i) { return segs[i].sc_start; });
-            const SegDev sd = segs[l[k]];
-            const SelDev se = sel[l[k]];
-            live[k] = live[k] && !se.route;  // the dense route writes re-routed segments
-            c_off[k] = sd.c_off;
-            n_seg[k] = sd.n;
-            sc_first[k] = sd.sc_start;
-            sc_rel0[k] = (scc - sd.sc_start) * SC_ELEMS;
-            T[k] = se.T;
-            quota[k] = se.quota;
-            const uint32_t g = scc * kCandChunksPerSuper + ch_in_sc;  // global chunk number
-            sp[k] = cand + uint64_t(g) * CAP;
-            const bool in_seg = live[k] && se.cnt != 0 && sc_rel0[k] + ch_in_sc * CHUNK < sd.n;
-            ccnt[k] = in_seg ? chunk_cnt[g] : 0u;
+        // ---- requests that depend on nothing but the item number
+        const uint32_t sc = base + k;
+        bool live = sc < total_sc;
+        const uint32_t scc = live ? sc : 0u;
+        const uint32_t g = scc * kCandChunksPerSuper + ch_in_sc;  // global chunk number
+        const uint32_t *sp = cand + uint64_t(g) * CAP;
+        const uint32_t craw = chunk_cnt[g];
+        // segment i's table rows in lane i
+        uint32_t t_start = 0xFFFFFFFFu, t_n = 0, t_coff = 0, t_T = 0, t_quota = 0, t_cnt = 0,
+                 t_route = 0;
+        if (L <= 64 && lane < L) {
+            static_assert(sizeof(SegDev) == 32 && sizeof(SelDev) == 32, "two uint4 per row");
+            const uint4 *s4 = reinterpret_cast<const uint4 *>(segs + lane);
+            const uint4 *e4 = reinterpret_cast<const uint4 *>(sel + lane);
+            const uint4 sa = s4[0], sb = s4[1], ea = e4[0], eb = e4[1];
+            t_n = sa.z; t_coff = sa.w; t_start = sb.w;                 // n, c_off, sc_start
+            t_T = ea.x; t_quota = ea.y; t_cnt = ea.w; t_route = eb.w;  // T, quota, cnt, route
         }
-        for (uint32_t i = tid; i < NI * SC_WORDS; i += kEmitThreads) (&bits[0][0])[i] = 0;
-        // ---- pass 1: count this thread's slots above / at the threshold
-        uint64_t mine[NI];
-#pragma unroll
-        for (int k = 0; k < NI; ++k) {
-            s0[k] = part * R;
-            s1[k] = min(s0[k] + R, min(ccnt[k], CAP));
+        for (uint32_t i = tt; i < SC_WORDS; i += 128) bits[k][i] = 0;
+
+        // ---- segment, threshold, pair offset of the segment (all wave-uniform)
+        uint32_t l, c_off, n_seg, sc_first, T, quota, seg_base, se_cnt, se_route;
+        if (L <= 64) {
+            const uint64_t le = __ballot(t_start <= scc);  // a prefix of the lanes
+            l = uint32_t(__popcll(le)) - 1u;               // segment 0 starts at 0
+            n_seg = __builtin_amdgcn_readlane(t_n, l);
+            c_off = __builtin_amdgcn_readlane(t_coff, l);
+            sc_first = __builtin_amdgcn_readlane(t_start, l);
+            T = __builtin_amdgcn_readlane(t_T, l);
+            quota = __builtin_amdgcn_readlane(t_quota, l);
+            se_cnt = __builtin_amdgcn_readlane(t_cnt, l);
+            se_route = __builtin_amdgcn_readlane(t_route, l);
+            seg_base = wave_sum<uint32_t>(lane < l ? t_cnt : 0u);
+        } else {
+            l = segment_of(L, scc, [&](uint32_t i) { return segs[i].sc_start; });
+            const SegDev sd = segs[l];
+            const SelDev se = sel[l];
+            n_seg = sd.n; c_off = sd.c_off; sc_first = sd.sc_start;
+            T = se.T; quota = se.quota; se_cnt = se.cnt; se_route = se.route;
+            uint32_t sum = 0;
+            for (uint32_t i = lane; i < l; i += 64) sum += sel[i].cnt;
+            seg_base = wave_sum<uint32_t>(sum);
         }
-#pragma unroll
-        for (int k = 0; k < NI; ++k) {
-            uint32_t n_gt = 0, n_eq = 0;
-            for (uint32_t s4 = s0[k]; s4 < s1[k]; s4 += 4) {
-                const uint4 q = *reinterpret_cast<const uint4 *>(sp[k] + s4);
-                const uint32_t v[4] = {q.x, q.y, q.z, q.w};
+        live = live && !se_route;  // the dense route writes re-routed segments
+        const uint32_t sc_rel0 = (scc - sc_first) * SC_ELEMS;
+        const bool in_seg = live && se_cnt != 0 && sc_rel0 + ch_in_sc * CHUNK < n_seg;
+        const uint32_t ccnt = in_seg ? min(craw, CAP) : 0u;
+        // the chunk's slots in four equal runs of whole 16-byte groups, one per thread
+        const uint32_t run = ((ccnt + 3) / 4 + 3) & ~3u;
+        const uint32_t s0 = min(part * run, ccnt), s1 = min(s0 + run, ccnt);
+        // fn(value bits, position in chunk) for every slot of this thread
+        auto for_slots = [&](auto &&fn) {
+            for (uint32_t s4 = s0; s4 < s1; s4 += 4) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(sp + s4);
+                uint4 b = make_uint4(0, 0, 0, 0);
+                if (DTYPE == kF32) b = *reinterpret_cast<const uint4 *>(sp + n_slots_total + s4);
+                const uint32_t v[4] = {a.x, a.y, a.z, a.w};
+                const uint32_t rp[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
                 for (uint32_t i = 0; i < 4; ++i) {
-                    if (s4 + i < s1[k]) {
-                        const uint32_t key =
-                            (DTYPE == kBF16 ? (v[i] & 0xFFFF0000u) : v[i]) & 0x7FFFFFFFu;
-                        n_gt += key > T[k];
-                        n_eq += (key == T[k]) && quota[k];
-                    }
+                    if (s4 + i >= s1) continue;
+                    if (DTYPE == kBF16) fn(v[i] & 0xFFFF0000u, v[i] & 0xFFFFu);
+                    else fn(v[i], rp[i]);
                 }
             }
-            mine[k] = (uint64_t(n_gt) << 31) | uint64_t(n_eq);
+        };
+        // ---- pass 1: count this thread's slots above / at the threshold
+        uint32_t n_gt = 0, n_eq = 0;
+        for_slots([&](uint32_t vbits, uint32_t) {
+            const uint32_t key = vbits & 0x7FFFFFFFu;
+            n_gt += key > T;
+            n_eq += (key == T) && quota;
+        });
+        // ---- order inside the item (its 128 threads are in position order), publish
+        const uint32_t inc_gt = wave_incl_scan<uint32_t>(n_gt);
+        const uint32_t inc_eq = wave_incl_scan<uint32_t>(n_eq);
+        if (lane == 63) {
+            s_gt[wave] = inc_gt;
+            s_eq[wave] = inc_eq;
         }
-        // ---- order inside each item (threads are in position order), publish, prefix
-        uint64_t ex[NI];
+        __syncthreads();
+        const uint32_t lo_gt = s_gt[2 * k], lo_eq = s_eq[2 * k];
+        const uint32_t it_gt = lo_gt + s_gt[2 * k + 1], it_eq = lo_eq + s_eq[2 * k + 1];
+        uint32_t gb = inc_gt - n_gt + ((wave & 1u) ? lo_gt : 0u);
+        uint32_t eb = inc_eq - n_eq + ((wave & 1u) ? lo_eq : 0u);
+        if (live && tt == 0)
+            st_agent(&sc_state[sc], kStAgg | (uint64_t(it_gt) << 31) | uint64_t(it_eq));
+        // ---- prefix over the segment's earlier super-chunks: four words requested at a
+        // time, then each is waited for (bounded) only if it has not been published yet
+        uint64_t sum = 0;
+        if (live) {
+            for (uint32_t j0 = sc_first + tt; j0 < sc; j0 += 4 * 128) {
+                uint64_t v[4];
 #pragma unroll
-        for (int k = 0; k < NI; ++k) {
-            uint64_t tot;
-            ex[k] = block_excl_scan<uint64_t, NW>(mine[k], &tot, s_scan);
-            if (live[k] && tid == 0) st_agent(&sc_state[sc[k]], kStAgg | tot);
-        }
+                for (uint32_t u = 0; u < 4; ++u) {
+                    const uint32_t j = j0 + u * 128;
+                    v[u] = j < sc ? ld_agent(&sc_state[j]) : kStAgg;
+                }
 #pragma unroll
-        for (int k = 0; k < NI; ++k) {
-            uint64_t sum = 0;
-            if (live[k]) {
-                for (uint32_t j = sc_first[k] + tid; j < sc[k]; j += kEmitThreads) {
-                    uint64_t v = ld_agent(&sc_state[j]);
+                for (uint32_t u = 0; u < 4; ++u) {
+                    const uint32_t j = j0 + u * 128;
                     uint32_t spins = 0;
-                    while ((v & kStMask) == 0) {  // bounded wait for a resident predecessor
+                    while ((v[u] & kStMask) == 0) {  // an earlier workgroup, still counting
                         if (++spins > kSpinLimit) {
                             atomicOr(&cnt[TAGC_CNT_FLAGS], TAGC_FLAG_SPIN_LIMIT);
                             break;
                         }
                         __builtin_amdgcn_s_sleep(1);
-                        v = ld_agent(&sc_state[j]);
+                        v[u] = ld_agent(&sc_state[j]);
                     }
-                    sum += v & ~kStMask;
+                    sum += v[u] & ~kStMask;
                 }
             }
-            ex[k] += block_sum<uint64_t, NW>(sum, s_scan);
         }
-        // ---- pass 2: write the survivors (block_sum's barrier also covers `bits`)
-#pragma unroll
-        for (int k = 0; k < NI; ++k) {
-            if (!(mine[k])) continue;
-            uint32_t gb = uint32_t(ex[k] >> 31), eb = uint32_t(ex[k] & 0x7FFFFFFFu);
-            uint32_t seg_base;
-            if (l[k] < kEmitMaxSegTable) {
-                seg_base = s_segbase[l[k]];
-            } else {  // more segments than the table holds: add them up directly
-                seg_base = s_segbase[kEmitMaxSegTable - 1] + sel[kEmitMaxSegTable - 1].cnt;
-                for (uint32_t i = kEmitMaxSegTable; i < l[k]; ++i) seg_base += sel[i].cnt;
-            }
-            for (uint32_t s4 = s0[k]; s4 < s1[k]; s4 += 4) {
-                const uint4 q = *reinterpret_cast<const uint4 *>(sp[k] + s4);
-                const uint32_t v[4] = {q.x, q.y, q.z, q.w};
-                uint32_t rp[4] = {0, 0, 0, 0};
-                if (DTYPE == kF32) {
-                    const uint4 pq = *reinterpret_cast<const uint4 *>(sp[k] + n_slots_total + s4);
-                    rp[0] = pq.x; rp[1] = pq.y; rp[2] = pq.z; rp[3] = pq.w;
+        sum = wave_sum<uint64_t>(sum);
+        if (lane == 0) s_sum[wave] = sum;
+        __syncthreads();  // also orders the clearing of `bits` before the ORs below
+        sum = s_sum[2 * k] + s_sum[2 * k + 1];
+        // output position (within the segment) of the item's first survivor, and how many
+        // survivors the item has: entries above T all survive, ties while the quota lasts
+        const uint32_t pre_gt = uint32_t(sum >> 31), pre_eq = uint32_t(sum & 0x7FFFFFFFu);
+        const uint32_t item_pos = pre_gt + min(pre_eq, quota);
+        const uint32_t item_n = pre_gt + it_gt + min(pre_eq + it_eq, quota) - item_pos;
+        gb += pre_gt;
+        eb += pre_eq;
+        // ---- pass 2: place the survivors
+        if (n_gt | n_eq) {
+            for_slots([&](uint32_t vbits, uint32_t rel) {
+                const uint32_t key = vbits & 0x7FFFFFFFu;
+                uint32_t pos;
+                bool keep;
+                if (key > T) {
+                    pos = gb + min(eb, quota);
+                    keep = true;
+                    ++gb;
+                } else if (key == T && quota) {
+                    pos = gb + eb;
+                    keep = eb < quota;
+                    ++eb;
+                } else {
+                    return;
                 }
-#pragma unroll
-                for (uint32_t i = 0; i < 4; ++i) {
-                    if (s4 + i >= s1[k]) continue;
-                    const uint32_t vbits = DTYPE == kBF16 ? (v[i] & 0xFFFF0000u) : v[i];
-                    const uint32_t rel = DTYPE == kBF16 ? (v[i] & 0xFFFFu) : rp[i];
-                    const uint32_t key = vbits & 0x7FFFFFFFu;
-                    uint32_t pos;
-                    bool keep;
-                    if (key > T[k]) {
-                        pos = gb + min(eb, quota[k]);
-                        keep = true;
-                        ++gb;
-                    } else if (key == T[k] && quota[k]) {
-                        pos = gb + eb;
-                        keep = eb < quota[k];
-                        ++eb;
+                if (keep) {
+                    const uint32_t rel_sc = ch_in_sc * CHUNK + rel;
+                    const uint32_t ci = c_off + sc_rel0 + rel_sc;
+                    const uint32_t p = pos - item_pos;
+                    if (p < kEmitStage) {
+                        st_idx[k][p] = ci;
+                        st_val[k][p] = __uint_as_float(vbits);
                     } else {
-                        continue;
-                    }
-                    if (keep) {
-                        const uint32_t rel_sc = ch_in_sc * CHUNK + rel;
-                        idx_out[seg_base + pos] = c_off[k] + sc_rel0[k] + rel_sc;
+                        idx_out[seg_base + pos] = ci;
                         val_out[seg_base + pos] = __uint_as_float(vbits);
-                        atomicOr(&bits[k][rel_sc >> 5], 1u << (rel_sc & 31));
                     }
+                    atomicOr(&bits[k][rel_sc >> 5], 1u << (rel_sc & 31));
                 }
-            }
+            });
         }
         __syncthreads();
-#pragma unroll
-        for (int k = 0; k < NI; ++k) {
-            if (!live[k]) continue;
-            const uint32_t w0 = (c_off[k] + sc_rel0[k]) >> 5;
-            for (uint32_t i = tid; i < SC_WORDS; i += kEmitThreads)
-                if (sc_rel0[k] + i * 32 < n_seg[k]) bitmap[w0 + i] = bits[k][i];
+        if (live) {
+            const uint32_t n_st = min(item_n, kEmitStage);
+            for (uint32_t i = tt; i < n_st; i += 128) {
+                idx_out[seg_base + item_pos + i] = st_idx[k][i];
+                val_out[seg_base + item_pos + i] = st_val[k][i];
+            }
+            const uint32_t w0 = (c_off + sc_rel0) >> 5;
+            for (uint32_t i = tt; i < SC_WORDS; i += 128)
+                if (sc_rel0 + i * 32 < n_seg) bitmap[w0 + i] = bits[k][i];
         }
-        __syncthreads();  // bits are cleared again by the next iteration
+        __syncthreads();  // LDS is reused by the next iteration
     }
 }
 
