@@ -778,7 +778,7 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // An item's survivors are consecutive in the output.  Stored entry by entry, each wave
 // instruction would touch 64 different cache lines (measured: 60 % of the kernel's time);
 // so the first kEmitStage of them are placed in LDS and leave as contiguous stores, and
-// only what exceeds that (items keeping more than about 1 %) is stored directly.
+// only what exceeds that (items keeping more than about 2 %) is stored directly.
 //
 // The prefix over earlier super-chunks has no chain: an item publishes its own counts,
 // then its threads add up the counts of all predecessors in its segment, each thread
@@ -788,7 +788,7 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // workgroup, which the hardware has dispatched before this one: the wait ends however few
 // workgroups are resident at a time (other streams may be using the device).
 constexpr int kEmitItems = 2;
-constexpr uint32_t kEmitStage = 640;  // survivors of an item that go through LDS
+constexpr uint32_t kEmitStage = 1280;  // survivors of an item that go through LDS
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
 template <int DTYPE>
@@ -805,8 +805,11 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
     constexpr uint32_t SC_WORDS = SC_ELEMS / 32;
     constexpr int NI = kEmitItems;
     __shared__ uint32_t bits[NI][SC_WORDS];
-    __shared__ uint32_t st_idx[NI][kEmitStage];
-    __shared__ float st_val[NI][kEmitStage];
+    // staged survivor: value bits and position in the super-chunk (16 bits); bf16 packs
+    // both in one word, like a candidate slot
+    __shared__ uint32_t st_a[NI][kEmitStage];
+    __shared__ uint16_t st_b[NI][DTYPE == kF32 ? kEmitStage : 2];
+    static_assert(SC_ELEMS <= 65536, "a position in the super-chunk fits 16 bits");
     __shared__ uint32_t s_gt[2 * NI], s_eq[2 * NI];
     __shared__ uint64_t s_sum[2 * NI];
     const uint32_t L = table[0], total_sc = table[4];
@@ -965,8 +968,12 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
                     const uint32_t ci = c_off + sc_rel0 + rel_sc;
                     const uint32_t p = pos - item_pos;
                     if (p < kEmitStage) {
-                        st_idx[k][p] = ci;
-                        st_val[k][p] = __uint_as_float(vbits);
+                        if (DTYPE == kBF16) {
+                            st_a[k][p] = vbits | rel_sc;
+                        } else {
+                            st_a[k][p] = vbits;
+                            st_b[k][DTYPE == kF32 ? p : 0] = uint16_t(rel_sc);
+                        }
                     } else {
                         idx_out[seg_base + pos] = ci;
                         val_out[seg_base + pos] = __uint_as_float(vbits);
@@ -979,8 +986,11 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
         if (live) {
             const uint32_t n_st = min(item_n, kEmitStage);
             for (uint32_t i = tt; i < n_st; i += 128) {
-                idx_out[seg_base + item_pos + i] = st_idx[k][i];
-                val_out[seg_base + item_pos + i] = st_val[k][i];
+                const uint32_t a = st_a[k][i];
+                const uint32_t rel_sc = DTYPE == kBF16 ? (a & 0xFFFFu) : st_b[k][DTYPE == kF32 ? i : 0];
+                idx_out[seg_base + item_pos + i] = c_off + sc_rel0 + rel_sc;
+                val_out[seg_base + item_pos + i] =
+                    __uint_as_float(DTYPE == kBF16 ? (a & 0xFFFF0000u) : a);
             }
             const uint32_t w0 = (c_off + sc_rel0) >> 5;
             for (uint32_t i = tt; i < SC_WORDS; i += 128)
