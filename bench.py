@@ -53,6 +53,10 @@ def parse_args():
     ap.add_argument("--lanes", type=int, default=4,
                     help="buckets in flight at once: bucket i runs on HIP stream i %% lanes with "
                          "that lane's own buffers (buckets are independent of each other)")
+    ap.add_argument("--part-unknowns", type=int, default=0,
+                    help="non-zeros per sketch partition (0 = library default)")
+    ap.add_argument("--part-cells", type=int, default=0,
+                    help="sketch cells per partition (0 = library default)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="before the timed region, copy this many MiB device to device three "
@@ -195,7 +199,8 @@ def main():
     for b in buckets:
         cfg = B.tagc_config(dtype=b.dtype, n_ranks=N, n_hash=3, sizing=B.TAGC_SIZE_LOAD_FACTOR,
                             sizing_milli=b.sizing_milli, index_mode=B.TAGC_INDEX_OR1,
-                            part_unknowns=0, part_cells=0, seed=args.seed)
+                            part_unknowns=args.part_unknowns, part_cells=args.part_cells,
+                            seed=args.seed)
         plan = B.tagc_plan(cfg, [tuple(s[:4]) for s in b.segments])
         z = B.tagc_plan_sizes(plan)
         for k, f in fields.items():
@@ -207,6 +212,7 @@ def main():
         first = i < lanes  # a lane's first bucket owns the buffers the lane's others reuse
         tbs.append(TagcBucket(b.segments, b.dtype, N, sizing_milli=b.sizing_milli,
                               seed=args.seed, dense=bool(args.dense),
+                              part_unknowns=args.part_unknowns, part_cells=args.part_cells,
                               share=None if first else tbs[i % lanes],
                               min_bytes=need if first else None))
     stream = torch.cuda.current_stream()

@@ -74,13 +74,19 @@ __device__ inline void queue_push(bool pred, uint32_t value, uint32_t *tail, uin
 
 // Enumerates the set bits of the merged Index in ascending order into idx_out.  One
 // workgroup per 1024-word chunk; chunkpre[] (written by the Index aggregation) holds the
-// number of set bits before each chunk, so workgroups are independent.
+// number of set bits before each chunk, so workgroups are independent.  A thread's
+// indices are consecutive in the output but a wave's stores, taken entry by entry, would
+// hit 64 different cache lines each; so the chunk's first kEnumStage indices are gathered
+// in LDS and leave as contiguous stores.
+constexpr uint32_t kEnumStage = 8192;
+
 __global__ void __launch_bounds__(256)
 enumerate_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
                  const uint32_t *__restrict__ chunkpre, const uint32_t *__restrict__ header,
                  uint32_t *__restrict__ idx_out)
 {
     __shared__ uint32_t scratch[8];
+    __shared__ uint32_t stage[kEnumStage];
     const uint32_t U = header[TAGC_HDR_U];
     const uint32_t w0 = blockIdx.x * kChunkWords + threadIdx.x * 4;
     uint32_t w[4] = {0, 0, 0, 0};
@@ -93,17 +99,24 @@ enumerate_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
     }
     const uint32_t mine = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);
     uint32_t tot;
-    uint32_t pos = chunkpre[blockIdx.x] + block_excl_scan<uint32_t, 4>(mine, &tot, scratch);
+    const uint32_t base = chunkpre[blockIdx.x];
+    uint32_t pl = block_excl_scan<uint32_t, 4>(mine, &tot, scratch);  // position in the chunk
 #pragma unroll
     for (uint32_t i = 0; i < 4; ++i) {
         uint32_t word = w[i];
         while (word) {
             const uint32_t b = __builtin_ctz(word);
             word &= word - 1;
-            if (pos < U) idx_out[pos] = (w0 + i) * 32 + b;
-            ++pos;
+            const uint32_t v = (w0 + i) * 32 + b;
+            if (pl < kEnumStage) stage[pl] = v;
+            else if (base + pl < U) idx_out[base + pl] = v;
+            ++pl;
         }
     }
+    __syncthreads();
+    const uint32_t n = min(tot, kEnumStage);
+    for (uint32_t i = threadIdx.x; i < n; i += 256)
+        if (base + i < U) idx_out[base + i] = stage[i];
 }
 
 // Appends up to three values per lane (those whose predicate holds) with one LDS atomic
@@ -285,54 +298,52 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
 }
 
 // Dense output: one workgroup per 1024-word chunk of the Index writes the 32768 floats
-// it covers, zeros included, a quarter (8192 floats staged in LDS) at a time.  The rank
-// of a word's first set bit says where its values sit in val_out.
-__global__ void __launch_bounds__(256)
+// it covers, zeros included.  The chunk's Index words, the number of set bits before each
+// word, and the chunk's values (one contiguous run of val_out; its first kDenseStage
+// entries, a denser chunk reads the rest one by one) are put in LDS; after that a thread
+// builds any four consecutive outputs on its own -- the rank of a set bit is the word's
+// count plus a popcount -- so the output goes out in plain contiguous 16-byte stores.
+constexpr uint32_t kDenseStage = 8192;
+
+__global__ void __launch_bounds__(kChunkWords)
 dense_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
              const uint32_t *__restrict__ chunkpre, const uint32_t *__restrict__ header,
              const float *__restrict__ val_out, float *__restrict__ dense_out)
 {
-    __shared__ uint32_t scratch[8];
-    __shared__ float tile[8192];
+    constexpr uint32_t NT = kChunkWords;  // one thread per Index word of the chunk
+    __shared__ uint32_t scratch[NT / 64];
+    __shared__ uint32_t s_word[kChunkWords], s_pre[kChunkWords];
+    __shared__ float vals[kDenseStage];
     const uint32_t U = header[TAGC_HDR_U];
     const uint32_t tid = threadIdx.x;
-    const uint32_t w0 = blockIdx.x * kChunkWords + tid * 4;
-    uint32_t w[4] = {0, 0, 0, 0};
-    if (w0 + 4 <= n_words) {
-        const uint4 q = *reinterpret_cast<const uint4 *>(bitmap + w0);
-        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
-    } else {
-#pragma unroll
-        for (uint32_t i = 0; i < 4; ++i) w[i] = w0 + i < n_words ? bitmap[w0 + i] : 0u;
-    }
-    const uint32_t mine = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);
+    const uint32_t cw0 = blockIdx.x * kChunkWords;  // first word of the chunk
+    const uint32_t word = cw0 + tid < n_words ? bitmap[cw0 + tid] : 0u;
+    const uint32_t base = chunkpre[blockIdx.x];
     uint32_t tot;
-    const uint32_t pos0 = chunkpre[blockIdx.x] + block_excl_scan<uint32_t, 4>(mine, &tot, scratch);
-    // thread tid owns words 4*tid .. 4*tid+3 of the chunk: quarter tid/64, 128 floats
-    for (uint32_t quarter = 0; quarter < 4; ++quarter) {
-        const uint32_t qbase = (blockIdx.x * kChunkWords + quarter * 256) * 32;  // first position
-        if (qbase >= n_words * 32) break;
-        for (uint32_t c = tid; c < 8192 / 4; c += 256)
-            reinterpret_cast<float4 *>(tile)[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-        __syncthreads();
-        if ((tid >> 6) == quarter) {
-            uint32_t pos = pos0;
+    const uint32_t pre = block_excl_scan<uint32_t, NT / 64>(uint32_t(__popc(word)), &tot, scratch);
+    s_word[tid] = word;
+    s_pre[tid] = pre;
+    const uint32_t n_st = min(tot, kDenseStage);
+    for (uint32_t i = tid; i < n_st; i += NT) vals[i] = base + i < U ? val_out[base + i] : 0.f;
+    __syncthreads();
+    const uint32_t n4 = min(kChunkWords, n_words - cw0) * 8;  // float4 groups of this chunk
+    float4 *out = reinterpret_cast<float4 *>(dense_out + uint64_t(cw0) * 32);
+    for (uint32_t c = tid; c < n4; c += NT) {
+        const uint32_t wd = s_word[c >> 3], sh = (c & 7u) * 4u;
+        const uint32_t nib = (wd >> sh) & 0xFu;
+        float o[4] = {0.f, 0.f, 0.f, 0.f};
+        if (nib) {
+            uint32_t r = s_pre[c >> 3] + __popc(wd & ((1u << sh) - 1u));  // rank in the chunk
 #pragma unroll
-            for (uint32_t i = 0; i < 4; ++i) {
-                uint32_t word = w[i];
-                while (word) {
-                    const uint32_t b = __builtin_ctz(word);
-                    word &= word - 1;
-                    if (pos < U) tile[((tid & 63) * 4 + i) * 32 + b] = val_out[pos];
-                    ++pos;
+            for (uint32_t b = 0; b < 4; ++b) {
+                if ((nib >> b) & 1u) {
+                    if (r < kDenseStage) o[b] = vals[r];
+                    else if (base + r < U) o[b] = val_out[base + r];
+                    ++r;
                 }
             }
         }
-        __syncthreads();
-        const uint32_t n = min(8192u, n_words * 32 - qbase);  // n_c is a multiple of 32
-        for (uint32_t c = tid; c < n / 4; c += 256)
-            reinterpret_cast<float4 *>(dense_out + qbase)[c] = reinterpret_cast<float4 *>(tile)[c];
-        __syncthreads();
+        out[c] = make_float4(o[0], o[1], o[2], o[3]);
     }
 }
 
@@ -371,7 +382,7 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
     }
     if (dense_out && n_chunks) {
         ProfileScope ps("dense", s);
-        dense_kernel<<<n_chunks, 256, 0, s>>>(sh->bitmap, n_words, chunkpre, sh->header, val_out,
+        dense_kernel<<<n_chunks, kChunkWords, 0, s>>>(sh->bitmap, n_words, chunkpre, sh->header, val_out,
                                               dense_out);
     }
     return hip_ok(hipGetLastError());
