@@ -199,7 +199,6 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
         const unsigned long long inc = (unsigned long long)((u << 15) + 1u) << 32;
 #pragma unroll
         for (int j = 0; j < 3; ++j) atomicAdd(&cell[cl.c[j]], inc);
-        val_out[rho0 + u] = 0.0f;
     }
     __syncthreads();
     for (uint32_t c0 = 0; c0 < cells; c0 += kDecodeThreads) {
@@ -260,7 +259,7 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
             unsigned long long o[3] = {cell[c[0]], cell[c[1]], cell[c[2]]};
             const float cv = __uint_as_float(uint32_t(j == 0 ? o[0] : (j == 1 ? o[1] : o[2])));
             const float x = ((neg >> j) & 1u) ? -cv : cv;
-            val_out[rho0 + u] = x;
+            idx[u] = __float_as_uint(x);  // the c-index has done its job: keep the value there
             const unsigned long long dec = (unsigned long long)((u << 15) + 1u) << 32;
             unsigned long long r[3];
 #pragma unroll
@@ -286,7 +285,11 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     }
     PHASE_MARK(2);
 
-    // ---- status: unknowns never claimed stay at 0
+    // ---- values leave in one contiguous sweep (stored one by one as they were found they
+    // would cost a cache-line access each); unknowns never claimed stay at 0
+    for (uint32_t u = tid; u < Pa; u += kDecodeThreads)
+        val_out[rho0 + u] =
+            (claimed[u >> 5] >> (u & 31)) & 1u ? __uint_as_float(idx[u]) : 0.0f;
     uint32_t resolved = 0;
     for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) resolved += __popc(claimed[c]);
     resolved = block_sum<uint32_t, kDecodeThreads / 64>(resolved, scratch);
