@@ -763,9 +763,8 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // chunks each), two waves per super-chunk: 4 threads per chunk share the chunk's slots
 // evenly, in order, and classify them against the exact threshold twice -- once to count,
 // once (after the scan over the item's threads and the prefix over the segment's earlier
-// super-chunks) to place the survivors in ascending c-index; the second pass finds the
-// slots in the cache.  A super-chunk's Index words are assembled in LDS and written
-// whole, zeros included.
+// super-chunks) to place the survivors in ascending c-index.  A super-chunk's Index words
+// are assembled in LDS and written whole, zeros included.
 //
 // Every step is latency-bound (a dependent memory access costs 1-3 us under load), so the
 // kernel is built to need few of them in a row and to be resident all at once (one item's
@@ -871,9 +870,34 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
         // the chunk's slots in four equal runs of whole 16-byte groups, one per thread
         const uint32_t run = ((ccnt + 3) / 4 + 3) & ~3u;
         const uint32_t s0 = min(part * run, ccnt), s1 = min(s0 + run, ccnt);
+        // The first two 16-byte groups of the run (all of it unless the chunk holds more
+        // than 32 candidates) are requested together and kept for both passes; a longer
+        // run reads the rest group by group.
+        constexpr uint32_t QN = 2;
+        uint4 q[QN], qp[QN];
+#pragma unroll
+        for (uint32_t j = 0; j < QN; ++j) {
+            q[j] = qp[j] = make_uint4(0, 0, 0, 0);
+            if (s0 + 4 * j < s1) {
+                q[j] = *reinterpret_cast<const uint4 *>(sp + s0 + 4 * j);
+                if (DTYPE == kF32)
+                    qp[j] = *reinterpret_cast<const uint4 *>(sp + n_slots_total + s0 + 4 * j);
+            }
+        }
         // fn(value bits, position in chunk) for every slot of this thread
         auto for_slots = [&](auto &&fn) {
-            for (uint32_t s4 = s0; s4 < s1; s4 += 4) {
+#pragma unroll
+            for (uint32_t j = 0; j < QN; ++j) {
+                const uint32_t v[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
+                const uint32_t rp[4] = {qp[j].x, qp[j].y, qp[j].z, qp[j].w};
+#pragma unroll
+                for (uint32_t i = 0; i < 4; ++i) {
+                    if (s0 + 4 * j + i >= s1) continue;
+                    if (DTYPE == kBF16) fn(v[i] & 0xFFFF0000u, v[i] & 0xFFFFu);
+                    else fn(v[i], rp[i]);
+                }
+            }
+            for (uint32_t s4 = s0 + 4 * QN; s4 < s1; s4 += 4) {
                 const uint4 a = *reinterpret_cast<const uint4 *>(sp + s4);
                 uint4 b = make_uint4(0, 0, 0, 0);
                 if (DTYPE == kF32) b = *reinterpret_cast<const uint4 *>(sp + n_slots_total + s4);
