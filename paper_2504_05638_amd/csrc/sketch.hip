@@ -29,9 +29,28 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
     // the partition's run of the sorted pair list, found when the Index was aggregated
     const uint32_t lo = min(cnt[ranges_off + a], pair_cap);
     const uint32_t hi = min(cnt[ranges_off + a + 1], pair_cap);
+    // a thread's first pairs (all of them for a partition of up to 1024 pairs of this rank)
+    // are requested together, before the tile is cleared
+    constexpr uint32_t PRE = 4;
+    uint32_t pi[PRE];
+    float pv[PRE];
+#pragma unroll
+    for (uint32_t u = 0; u < PRE; ++u) {
+        const uint32_t t = lo + threadIdx.x + u * 256;
+        pi[u] = t < hi ? idx[t] : 0u;
+        pv[u] = t < hi ? val[t] : 0.0f;
+    }
     for (uint32_t c = threadIdx.x; c < m_sub; c += 256) tile[c] = 0.0f;
     __syncthreads();
-    for (uint32_t t = lo + threadIdx.x; t < hi; t += 256) {
+#pragma unroll
+    for (uint32_t u = 0; u < PRE; ++u) {
+        if (lo + threadIdx.x + u * 256 < hi) {
+            uint32_t neg;
+            const uint32_t slot = hash_slot(pi[u], sw, m_sub, &neg);
+            lds_add_f32(&tile[slot], neg ? -pv[u] : pv[u]);
+        }
+    }
+    for (uint32_t t = lo + threadIdx.x + PRE * 256; t < hi; t += 256) {
         const uint32_t i = idx[t];
         const float v = val[t];
         uint32_t neg;
@@ -39,8 +58,17 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
         lds_add_f32(&tile[slot], neg ? -v : v);
     }
     __syncthreads();
-    float *out = sketch + (uint64_t(a) * 3 + j) * m_sub;
-    for (uint32_t c = threadIdx.x; c < m_sub; c += 256) out[c] = tile[c];
+    // the tile leaves in 16-byte stores where the sketch is aligned for them
+    const uint64_t b0 = (uint64_t(a) * 3 + j) * m_sub;
+    float *out = sketch + b0;
+    const uint32_t head = min(m_sub, uint32_t((4u - uint32_t(b0 & 3u)) & 3u));
+    const uint32_t n4 = (m_sub - head) / 4;
+    if (threadIdx.x < head) out[threadIdx.x] = tile[threadIdx.x];
+    for (uint32_t v = threadIdx.x; v < n4; v += 256) {
+        const float *t = tile + head + 4 * v;
+        *reinterpret_cast<float4 *>(out + head + 4 * v) = make_float4(t[0], t[1], t[2], t[3]);
+    }
+    for (uint32_t c = head + 4 * n4 + threadIdx.x; c < m_sub; c += 256) out[c] = tile[c];
 }
 
 // Each workgroup sums tiles of kSumRows x 256 float4 cells: per rank it reads one
