@@ -65,11 +65,14 @@ __device__ inline uint32_t vec_elem_bits(const uint32_t (&w)[4], uint32_t e)
 
 // Largest bin b with  sum_{x >= b} hist[x] >= need  (need >= 1).  1024 threads, thread t
 // owns the BPT consecutive bins starting at t*BPT.  Returns false if the whole histogram
-// holds fewer than `need`; *total_out is the histogram's sum either way.
+// holds fewer than `need`; *total_out is the histogram's sum either way.  A second count
+// `need2` (0 = none) is located in the same pass: *bin2_out is the largest bin with at
+// least need2 entries at or above it, or 0xFFFFFFFF if the histogram holds fewer.
 template <int BPT>
 __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t *bin_out,
                                    uint32_t *above_out, uint32_t *at_out, uint32_t *total_out,
-                                   uint32_t *smem /* >= 20 words */)
+                                   uint32_t *smem /* >= 20 words */, uint32_t need2 = 0,
+                                   uint32_t *bin2_out = nullptr)
 {
     const uint32_t t = threadIdx.x;
     const uint4 *hv = reinterpret_cast<const uint4 *>(hist + uint64_t(t) * BPT);
@@ -84,6 +87,8 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
     uint32_t total;
     uint32_t prefix = block_excl_scan<uint32_t, kHistThreads / 64>(s, &total, smem);
     uint32_t suffix = total - prefix;  // bins of this thread and all higher ones
+    if (t == 0) smem[19] = 0xFFFFFFFFu;
+    __syncthreads();
     if (total >= need && suffix >= need && suffix - s < need) {
         uint32_t acc = suffix - s;
         bool done = false;
@@ -99,11 +104,25 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
             if (!done) acc += c;
         }
     }
+    if (need2 && total >= need2 && suffix >= need2 && suffix - s < need2) {
+        uint32_t acc = suffix - s;
+        bool done = false;
+#pragma unroll
+        for (int b = BPT - 1; b >= 0; --b) {
+            const uint32_t c = bins[b];
+            if (!done && acc + c >= need2) {
+                smem[19] = t * BPT + b;
+                done = true;
+            }
+            if (!done) acc += c;
+        }
+    }
     __syncthreads();
     *bin_out = smem[16];
     *above_out = smem[17];
     *at_out = smem[18];
     *total_out = total;
+    if (bin2_out) *bin2_out = smem[19];
     __syncthreads();
     return total >= need;
 }
@@ -118,8 +137,8 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads)
 sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
-              SelDev *__restrict__ sel, uint32_t *__restrict__ binlo, uint4 *zero_base,
-              uint64_t zero_n16, uint32_t *cnt, uint32_t n_cnt)
+              SelDev *__restrict__ sel, uint32_t *__restrict__ binlo, uint32_t *hint,
+              uint4 *zero_base, uint64_t zero_n16, uint32_t *cnt, uint32_t n_cnt)
 {
     extern __shared__ uint32_t h[];
     __shared__ uint32_t smem[32];
@@ -155,6 +174,17 @@ sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
         if (tid == 0) {
             sel[l] = r;
             binlo[l] = 1;
+        }
+        return;
+    }
+    // A pre-threshold left by the previous call on this plan (another rank, or the last
+    // training step) is used as it is: the select kernels keep it tuned and withdraw it
+    // when it fails, and whatever it is worth the result stays exact.
+    const uint32_t hb = hint[l];
+    if (hb) {
+        if (tid == 0) {
+            sel[l] = r;
+            binlo[l] = hb;
         }
         return;
     }
@@ -549,13 +579,18 @@ hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads)
 select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ hist,
-               SelDev *sel, uint32_t *cnt, uint32_t dense)
+               SelDev *sel, uint32_t *cnt, uint32_t dense, const uint32_t *__restrict__ binlo,
+               uint32_t *hint)
 {
     __shared__ uint32_t smem[32];
     const uint32_t l = blockIdx.x;
     const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
     SelDev r = sel[l];
-    if (r.route != dense) return;
+    if (r.route != dense) {
+        // a candidate-route segment that overflowed its slots: the pre-threshold was too low
+        if (!dense && (sd.flags & kSegFast) && sd.k && threadIdx.x == 0) hint[l] = 0;
+        return;
+    }
     if (sd.k == 0 || sd.n == 0) {
         if (threadIdx.x == 0) cnt[TAGC_CNT_SEG0 + l] = 0;
         return;
@@ -565,9 +600,22 @@ select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     if (threadIdx.x >= 0x7F80u / 32)
         for (int i = 0; i < 32; ++i) nf += h[threadIdx.x * 32 + i];
     nf = block_sum<uint32_t, kHistThreads / 64>(nf, smem);
-    uint32_t bin, above, at, total;
-    const bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem);
+    // Besides the threshold bin: the pre-threshold for the next call on this plan, the bin
+    // above which about 1.3 k entries lie (what the slots per chunk are sized for).  The
+    // candidate histogram may not reach that far down; then one bin below this call's
+    // pre-threshold.  A miss withdraws the hint, so that the next call samples again.
+    uint32_t bin, above, at, total, bin2;
+    const bool fast = (sd.flags & kSegFast) != 0;
+    const uint32_t want = fast ? uint32_t(1.3f * float(sd.k)) + 1u : 0u;
+    const bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem, want, &bin2);
     if (threadIdx.x != 0) return;
+    if (fast) {
+        uint32_t nh;
+        if (bin2 != 0xFFFFFFFFu) nh = max(bin2, 1u);
+        else if (dense) nh = 1u;  // fewer non-zeros than that in the whole segment
+        else nh = found ? max(binlo[l], 2u) - 1u : 0u;
+        hint[l] = nh;
+    }
     if (!found && !dense) {  // the candidates hold fewer than k entries: dense route
         sel[l].route = 1;
         return;
@@ -1212,6 +1260,8 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
 {
     const uint32_t L = uint32_t(p->table.size());
     const uint32_t *table = static_cast<const uint32_t *>(sh->table);
+    // behind the segment rows: one pre-threshold per segment, carried from call to call
+    uint32_t *hint = const_cast<uint32_t *>(table) + 8 + 8 * size_t(L);
     char *ws = static_cast<char *>(rk->workspace);
     uint32_t *hist1 = reinterpret_cast<uint32_t *>(ws + p->ws.hist1);
     uint32_t *hist1d = reinterpret_cast<uint32_t *>(ws + p->ws.hist1d);
@@ -1244,7 +1294,8 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         const uint32_t fill_blocks = uint32_t(
             std::max<uint64_t>(1, std::min<uint64_t>((n16 + kHistThreads - 1) / kHistThreads, cus)));
         sample_kernel<DTYPE><<<L + fill_blocks, kHistThreads, lds_hist, s>>>(
-            g, table, sel, binlo, reinterpret_cast<uint4 *>(ws), n16, rk->cnt, TAGC_CNT_SEG0 + L);
+            g, table, sel, binlo, hint, reinterpret_cast<uint4 *>(ws), n16, rk->cnt,
+            TAGC_CNT_SEG0 + L);
     }
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
@@ -1253,7 +1304,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     {
         ProfileScope ps("select1", s);
-        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt, 0);
+        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt, 0, binlo, hint);
     }
     {
         ProfileScope ps("hist1", s);
@@ -1261,7 +1312,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     {
         ProfileScope ps("select1d", s);
-        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1d, sel, rk->cnt, 1);
+        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1d, sel, rk->cnt, 1, binlo, hint);
     }
     if (DTYPE == kF32) {
         if (p->total_sc) {

@@ -300,3 +300,30 @@ def test_buckets_in_flight_on_separate_streams():
         ores = O.run_bucket([G.to_numpy_raw(g) for g in gs], oracle_config(b, seed=11 + i),
                             oracle_segments(b))
         compare_all(b, ores, tb)
+
+
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+def test_pre_threshold_carried_between_calls_never_changes_results(dtype):
+    """A plan keeps each segment's pre-threshold from one PHASE_INDEX call to the next.
+    Here consecutive calls see the same distribution (the hint holds), then gradients 100x
+    larger (far too many candidates: the slots overflow), then 10000x smaller (no
+    candidate at all), then the first scale again with one rank that is mostly zeros.
+    Whatever the hint is worth, every rank's survivors must be exactly the oracle's."""
+    _announce("pre-threshold hints dtype=%d" % dtype)
+    n = (1 << 19) + 40
+    rng = np.random.default_rng(77)
+    scales = [1e-3, 1e-3, 1e-1, 1e-5, 1e-3, 1e-3, 1e-3]
+    td = torch.float32 if dtype == G.F32 else torch.bfloat16
+    grads = []
+    for r, sc in enumerate(scales):
+        v = (rng.standard_normal(n) * sc).astype(np.float32)
+        if r == 4:
+            v[rng.random(n) < 0.97] = 0.0   # fewer non-zeros than the sample can judge
+        grads.append(torch.from_numpy(v).to(td))
+    b = G.Bucket("hints", dtype, len(scales), [G.Seg(0, n, 10_000, 1, "w")], n, 3000)
+    ores, tb = run_both(b, grads, seed=9)
+    compare_all(b, ores, tb)
+    dense = [tb.rank_counts(r)["dense_segments"] for r in range(len(scales))]
+    assert dense[0] == 0 and dense[1] == 0      # sampled, then the carried hint
+    assert dense[2] == 1 and dense[3] == 1      # the hint failed both ways: exact fallback
+    assert dense[6] == 0                        # and recovered (rank 5 still pays for rank 4)
