@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Kernels of the library grouped into the stages of the path.
 STAGES = {
     "S1+S2 sparsify+index": ["fill_zero", "sample", "scan_spill", "select1", "hist1", "select1d",
-                             "hist2c", "hist2", "select2", "emit", "compact"],
+                             "hist2c", "hist2", "select2", "finish"],
     "S3a index OR": ["index_or", "header", "bounds", "ranges"],
     "S2' encode": ["encode"],
     "S3b sketch sum": ["sketch_sum"],
@@ -113,8 +113,9 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense):
         "scan_spill": N * z.n_real * e,
         "hist1": N * z.n_real * e,
         "hist2": N * z.n_real * e,
-        "compact": N * z.n_real * e + 8 * k_total + N * n_c // 8,
-        "emit": 8 * k_total + N * n_c // 8,
+        # finish = emit (candidate route) + compact (dense route: reads the gradient again);
+        # priced as emit, which is all it is for a bucket without dense-route segments
+        "finish": 8 * k_total + N * n_c // 8,
         "index_or": (N + 1) * n_c // 8,
         "encode": 8 * k_total + N * 4 * m,
         "sketch_sum": (N + 1) * 4 * m,

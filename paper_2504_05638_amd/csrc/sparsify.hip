@@ -839,8 +839,7 @@ constexpr uint32_t kEmitStage = 1280;  // survivors of an item that go through L
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
 template <int DTYPE>
-__global__ void __launch_bounds__(kEmitThreads)
-emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
+__device__ inline void emit_body(uint32_t bid, uint32_t nb, const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
             const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
             uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_state,
             uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
@@ -867,7 +866,7 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
     const uint32_t tt = tid & 127;
     const uint32_t ch_in_sc = tt >> 2, part = tt & 3;
 
-    for (uint32_t base = blockIdx.x * NI; base < total_sc; base += gridDim.x * NI) {
+    for (uint32_t base = bid * NI; base < total_sc; base += nb * NI) {
         // ---- requests that depend on nothing but the item number
         const uint32_t sc = base + k;
         bool live = sc < total_sc;
@@ -1076,8 +1075,8 @@ emit_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
 
 // Dense route, final pass over the gradient itself.
 template <int DTYPE>
-__global__ void __launch_bounds__(kCompactThreads)
-compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
+__device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *__restrict__ grad,
+                                    const uint32_t *__restrict__ table,
                const SelDev *__restrict__ sel, uint64_t *tile_state,
                uint32_t *__restrict__ idx_out,
                float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt)
@@ -1097,7 +1096,7 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
     const uint32_t tid = threadIdx.x;
 
-    for (uint32_t t = blockIdx.x; t < total_tiles; t += gridDim.x) {
+    for (uint32_t t = bid; t < total_tiles; t += nb) {
         const uint32_t l = segment_of(L, t, [&](uint32_t i) { return segs[i].tile_start; });
         const SegDev sd = segs[l];
         const SelDev se = sel[l];
@@ -1230,6 +1229,31 @@ compact_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table
     }
 }
 
+// ----------------------------------------------------------------- finish
+
+// The last kernel of PHASE_INDEX: its first `n_emit` workgroups emit the candidate-route
+// segments, the rest compact the dense-route ones (both write pairs and Index words, of
+// different segments).  One launch instead of two: when a bucket has no dense-route work
+// the second part costs nothing, not even an empty kernel's turn-around.  Workgroups are
+// dispatched in order, so inside each part a workgroup still only waits for earlier ones.
+static_assert(kEmitThreads == kCompactThreads, "one launch for both parts");
+
+template <int DTYPE>
+__global__ void __launch_bounds__(kEmitThreads) __attribute__((amdgpu_waves_per_eu(6, 8)))
+finish_kernel(uint32_t n_emit, const char *__restrict__ grad, const uint32_t *__restrict__ table,
+              const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
+              const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
+              uint64_t *sc_state, uint64_t *tile_state, uint32_t *__restrict__ idx_out,
+              float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt)
+{
+    if (blockIdx.x < n_emit)
+        emit_body<DTYPE>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total, CAP,
+                         sc_state, idx_out, val_out, bitmap, cnt);
+    else
+        compact_body<DTYPE>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, table, sel,
+                            tile_state, idx_out, val_out, bitmap, cnt);
+}
+
 template <typename K>
 int resident_blocks_per_cu(K kernel, int threads, size_t lds, int *cache)
 {
@@ -1277,7 +1301,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     const int cus = device_cu_count();
     const size_t lds_hist = kBins1 * sizeof(uint32_t);
     static bool a_sample = false, a_hist = false;
-    static int occ_compact = 0;
+    static int occ_finish = 0;
 
     if (L == 0) {  // nothing is compressed: only the counts have to read zero
         ProfileScope ps("fill_zero", s);
@@ -1328,30 +1352,25 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
             select2_kernel<<<L, kHistThreads, 0, s>>>(table, hist2, sel, rk->cnt);
         }
     }
-    if (p->total_sc) {
-        ProfileScope ps("emit", s);
-        const uint32_t grid = (p->total_sc + kEmitItems - 1) / kEmitItems;
-        emit_kernel<DTYPE><<<grid, kEmitThreads, 0, s>>>(table, sel, cand, chunk_cnt, n_slots,
-                                                         p->cand_cap, sc_state, rk->idx, rk->val,
-                                                         rk->bitmap, rk->cnt);
-    }
-    if (p->total_tiles) {
-        ProfileScope ps("compact", s);
+    if (p->total_sc || p->total_tiles) {
+        ProfileScope ps("finish", s);  // emit + compact
         const int occ =
-            resident_blocks_per_cu(compact_kernel<DTYPE>, kCompactThreads, 0, &occ_compact);
+            resident_blocks_per_cu(finish_kernel<DTYPE>, kEmitThreads, 0, &occ_finish);
         if (occ <= 0) return TAGC_EHIP;
-        // One tile per workgroup when dense-route work is certain: a tile's look-back then
-        // only ever waits for lower-numbered workgroups, which were dispatched before it,
-        // so it ends no matter how few workgroups the device can hold at the moment.  When
-        // no segment is planned for this route the kernel is only a safety net for
-        // re-routed segments and nearly always exits at once; a small persistent grid
-        // keeps that cheap (its look-back then assumes the grid is resident as a whole
-        // and gives up with TAGC_FLAG_SPIN_LIMIT if that fails).
-        const uint32_t grid = p->static_dense
-                                  ? p->total_tiles
-                                  : std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
-        compact_kernel<DTYPE><<<grid, kCompactThreads, 0, s>>>(
-            g, table, sel, tile_state, rk->idx, rk->val, rk->bitmap, rk->cnt);
+        const uint32_t n_emit = (p->total_sc + kEmitItems - 1) / kEmitItems;
+        // Compaction: one tile per workgroup when dense-route work is certain: a tile's
+        // look-back then only ever waits for lower-numbered workgroups, which were
+        // dispatched before it, so it ends no matter how few workgroups the device can hold
+        // at the moment.  When no segment is planned for this route the part is only a
+        // safety net for re-routed segments and nearly always exits at once; a small
+        // persistent grid keeps that cheap (its look-back then assumes that grid is
+        // resident as a whole and gives up with TAGC_FLAG_SPIN_LIMIT if that fails).
+        const uint32_t n_compact =
+            p->static_dense ? p->total_tiles
+                            : std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
+        finish_kernel<DTYPE><<<n_emit + n_compact, kEmitThreads, 0, s>>>(
+            n_emit, g, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state, tile_state,
+            rk->idx, rk->val, rk->bitmap, rk->cnt);
     }
     return hip_ok(hipGetLastError());
 }
