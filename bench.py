@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # Kernels of the library grouped into the stages of the path.
 STAGES = {
-    "S1+S2 sparsify+index": ["fill_zero", "sample", "scan_spill", "select1", "hist1", "select1d",
+    "S1+S2 sparsify+index": ["fill_zero", "sample", "scan_spill", "select1", "hist1",
                              "hist2c", "hist2", "select2", "finish"],
     "S3a index OR": ["index_or", "header", "bounds", "ranges"],
     "S2' encode": ["encode"],

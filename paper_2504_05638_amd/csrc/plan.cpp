@@ -133,8 +133,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     off += round_up(tiles * 8, 16);
     w.sc_state = off;
     off += round_up(scs * 8, 16);
-    w.counters = off;
-    off += 64;
+    w.counters = off;  // one arrival counter per segment
+    off += round_up(4 * std::max<uint64_t>(L, 1), 64);
     p->zero_bytes = off;
     w.sel = off;
     off += round_up(L * sizeof(SelDev), 16);

@@ -517,74 +517,16 @@ __device__ inline void hist_elem(uint32_t f32bits, uint32_t *h)
     if (key) atomicAdd(&h[key >> 16], 1u);
 }
 
-// Dense route: one workgroup per CU, 32768 LDS counters, all entries of every dense-route
-// segment.  Leaves at once when no segment is on the dense route.
+// Threshold bin of one segment from its 32768-bin histogram, by a whole workgroup of
+// kHistThreads threads.  `dense` = 0: segment on the candidate route, histogram of
+// candidates only (a miss re-routes the segment); 1: segment on the dense route, histogram
+// of everything.
 template <int DTYPE>
-__global__ void __launch_bounds__(kHistThreads)
-hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
-             const SelDev *__restrict__ sel, uint32_t *__restrict__ hist)
+__device__ inline void select1_segment(uint32_t l, const SegDev &sd, const uint32_t *hist,
+                                       SelDev *sel, uint32_t *cnt, uint32_t dense,
+                                       const uint32_t *binlo, uint32_t *hint,
+                                       uint32_t *smem /* >= 32 words */)
 {
-    extern __shared__ uint32_t h[];
-    constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
-    constexpr uint32_t VEC = 16 / EB;
-    const uint32_t L = table[0];
-    if (!any_dense_route(sel, L)) return;
-    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
-    const uint32_t tid = threadIdx.x;
-    for (uint32_t i = tid; i < kBins1; i += kHistThreads) h[i] = 0;
-    __syncthreads();
-    for (uint32_t l = 0; l < L; ++l) {
-        const SegDev sd = segs[l];
-        if (sd.k == 0 || sd.n == 0 || !sel[l].route) continue;
-        const char *base = grad + sd.offset * EB;
-        if (sd.flags & kSegAligned) {
-            const uint4 *vp = reinterpret_cast<const uint4 *>(base);
-            const uint64_t nvec = sd.n / VEC;
-            const uint64_t stride = uint64_t(gridDim.x) * kHistThreads;
-            uint64_t v = uint64_t(blockIdx.x) * kHistThreads + tid;
-            for (; v + 3 * stride < nvec; v += 4 * stride) {
-                uint4 a = vp[v], b = vp[v + stride], c = vp[v + 2 * stride],
-                      d = vp[v + 3 * stride];
-                hist_vec<DTYPE>(a, h);
-                hist_vec<DTYPE>(b, h);
-                hist_vec<DTYPE>(c, h);
-                hist_vec<DTYPE>(d, h);
-            }
-            for (; v < nvec; v += stride) hist_vec<DTYPE>(vp[v], h);
-            if (blockIdx.x == 0) {
-                uint64_t i = nvec * VEC + tid;
-                if (i < sd.n) hist_elem(load_elem_bits(base, i, DTYPE), h);
-            }
-        } else {
-            for (uint64_t i = uint64_t(blockIdx.x) * kHistThreads + tid; i < sd.n;
-                 i += uint64_t(gridDim.x) * kHistThreads)
-                hist_elem(load_elem_bits(base, i, DTYPE), h);
-        }
-        __syncthreads();
-        uint32_t *gh = hist + uint64_t(l) * kBins1;
-        for (uint32_t i = tid; i < kBins1; i += kHistThreads) {
-            uint32_t c = h[i];
-            if (c) {
-                atomicAdd(&gh[i], c);
-                h[i] = 0;
-            }
-        }
-        __syncthreads();
-    }
-}
-
-// Threshold bin of one segment from its 32768-bin histogram.  `dense` = 0: segments on the
-// candidate route, histogram of candidates only (a miss re-routes the segment); 1:
-// segments on the dense route, histogram of everything.
-template <int DTYPE>
-__global__ void __launch_bounds__(kHistThreads)
-select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ hist,
-               SelDev *sel, uint32_t *cnt, uint32_t dense, const uint32_t *__restrict__ binlo,
-               uint32_t *hint)
-{
-    __shared__ uint32_t smem[32];
-    const uint32_t l = blockIdx.x;
-    const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
     SelDev r = sel[l];
     if (r.route != dense) {
         // a candidate-route segment that overflowed its slots: the pre-threshold was too low
@@ -641,6 +583,92 @@ select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     if (!r.need2) {
         cnt[TAGC_CNT_SEG0 + l] = r.cnt;
         atomicAdd(&cnt[TAGC_CNT_TOTAL], r.cnt);
+    }
+}
+
+// Candidate route: one workgroup per segment, after scan_spill.
+template <int DTYPE>
+__global__ void __launch_bounds__(kHistThreads)
+select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ hist,
+               SelDev *sel, uint32_t *cnt, const uint32_t *__restrict__ binlo, uint32_t *hint)
+{
+    __shared__ uint32_t smem[32];
+    const uint32_t l = blockIdx.x;
+    const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
+    select1_segment<DTYPE>(l, sd, hist, sel, cnt, 0, binlo, hint, smem);
+}
+
+// Dense route: one workgroup per CU, 32768 LDS counters, all entries of every dense-route
+// segment.  Leaves at once when no segment is on the dense route.  The workgroup that
+// completes a segment's histogram selects its threshold right away, while the others go on
+// with the next segment: no separate selection launch.
+template <int DTYPE>
+__global__ void __launch_bounds__(kHistThreads)
+hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, SelDev *sel,
+             uint32_t *hist, uint32_t *cnt, const uint32_t *__restrict__ binlo, uint32_t *hint,
+             uint32_t *arrive)
+{
+    extern __shared__ uint32_t h[];
+    __shared__ uint32_t s_sel[32];
+    __shared__ uint32_t s_last;
+    constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
+    constexpr uint32_t VEC = 16 / EB;
+    const uint32_t L = table[0];
+    if (!any_dense_route(sel, L)) return;
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t i = tid; i < kBins1; i += kHistThreads) h[i] = 0;
+    __syncthreads();
+    for (uint32_t l = 0; l < L; ++l) {
+        const SegDev sd = segs[l];
+        if (sd.k == 0 || sd.n == 0 || !sel[l].route) continue;
+        const char *base = grad + sd.offset * EB;
+        if (sd.flags & kSegAligned) {
+            const uint4 *vp = reinterpret_cast<const uint4 *>(base);
+            const uint64_t nvec = sd.n / VEC;
+            const uint64_t stride = uint64_t(gridDim.x) * kHistThreads;
+            uint64_t v = uint64_t(blockIdx.x) * kHistThreads + tid;
+            for (; v + 3 * stride < nvec; v += 4 * stride) {
+                uint4 a = vp[v], b = vp[v + stride], c = vp[v + 2 * stride],
+                      d = vp[v + 3 * stride];
+                hist_vec<DTYPE>(a, h);
+                hist_vec<DTYPE>(b, h);
+                hist_vec<DTYPE>(c, h);
+                hist_vec<DTYPE>(d, h);
+            }
+            for (; v < nvec; v += stride) hist_vec<DTYPE>(vp[v], h);
+            if (blockIdx.x == 0) {
+                uint64_t i = nvec * VEC + tid;
+                if (i < sd.n) hist_elem(load_elem_bits(base, i, DTYPE), h);
+            }
+        } else {
+            for (uint64_t i = uint64_t(blockIdx.x) * kHistThreads + tid; i < sd.n;
+                 i += uint64_t(gridDim.x) * kHistThreads)
+                hist_elem(load_elem_bits(base, i, DTYPE), h);
+        }
+        __syncthreads();
+        uint32_t *gh = hist + uint64_t(l) * kBins1;
+        for (uint32_t i = tid; i < kBins1; i += kHistThreads) {
+            uint32_t c = h[i];
+            if (c) {
+                atomicAdd(&gh[i], c);
+                h[i] = 0;
+            }
+        }
+        // The histogram updates are device-scope atomics, performed where every CU sees
+        // them; a thread only has to wait until its own have been acknowledged before the
+        // workgroup is counted as arrived.  (A device-scope release fence would also write
+        // back every dirty line of the L2, at many times the cost.)  The workgroup that
+        // arrives last drops what it may hold of the histogram in its caches and selects.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (tid == 0) s_last = atomicAdd(&arrive[l], 1u) == gridDim.x - 1;
+        __syncthreads();
+        if (s_last) {  // uniform
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            select1_segment<DTYPE>(l, sd, hist, sel, cnt, 1, binlo, hint, s_sel);
+        }
+        __syncthreads();
     }
 }
 
@@ -1289,6 +1317,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     char *ws = static_cast<char *>(rk->workspace);
     uint32_t *hist1 = reinterpret_cast<uint32_t *>(ws + p->ws.hist1);
     uint32_t *hist1d = reinterpret_cast<uint32_t *>(ws + p->ws.hist1d);
+    uint32_t *arrive = reinterpret_cast<uint32_t *>(ws + p->ws.counters);
     uint32_t *hist2 = reinterpret_cast<uint32_t *>(ws + p->ws.hist2);
     uint64_t *tile_state = reinterpret_cast<uint64_t *>(ws + p->ws.tile_state);
     uint64_t *sc_state = reinterpret_cast<uint64_t *>(ws + p->ws.sc_state);
@@ -1328,15 +1357,12 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     {
         ProfileScope ps("select1", s);
-        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt, 0, binlo, hint);
+        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt, binlo, hint);
     }
     {
         ProfileScope ps("hist1", s);
-        hist1_kernel<DTYPE><<<cus, kHistThreads, lds_hist, s>>>(g, table, sel, hist1d);
-    }
-    {
-        ProfileScope ps("select1d", s);
-        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1d, sel, rk->cnt, 1, binlo, hint);
+        hist1_kernel<DTYPE><<<cus, kHistThreads, lds_hist, s>>>(g, table, sel, hist1d, rk->cnt,
+                                                                binlo, hint, arrive);
     }
     if (DTYPE == kF32) {
         if (p->total_sc) {
