@@ -13,22 +13,29 @@
 // Two routes per segment, both exact:
 //
 //  candidate route (one read of the gradient)
-//    sample       a strided sample gives a conservative pre-threshold bin `binlo`
+//    sample       only when the plan knows no pre-threshold for the segment yet: a strided
+//                 sample gives a conservative pre-threshold bin `binlo`; otherwise the bin
+//                 the previous call on the plan left behind is taken (the launch also
+//                 clears the per-call workspace)
 //    scan_spill   streams the segment once: entries with key bin >= binlo ("candidates",
 //                 ~1.3 x k of them) are histogrammed in LDS and spilled, in position
 //                 order, into fixed slots per 4 KiB chunk -- no cross-wave dependency
-//    select1      exact threshold from the candidate histogram; if the candidates do not
-//                 contain k entries (the sample misled) the segment is re-routed
+//    select1      exact threshold from the candidate histogram, and the pre-threshold for
+//                 the next call; if the candidates do not contain k entries (the
+//                 pre-threshold misled) the segment is re-routed
 //    hist2c/select2  fp32 only: low 16 key bits inside the threshold bin
-//    emit         ordered pass over the candidates only: pairs + every Index word
+//    finish       (first part) ordered pass over the candidates only: pairs + every Index
+//                 word
 //
 //  dense route (segments that are short, unaligned, or re-routed; two reads)
-//    hist1        exact histogram of the top 15 key bits of every entry, in LDS
-//    select1, hist2/select2 as above
-//    compact      ordered pass over the gradient: pairs + Index words
+//    hist1        exact histogram of the top 15 key bits of every entry, in LDS; the
+//                 workgroup that completes a segment's histogram selects its threshold
+//    hist2/select2 fp32 only, as above
+//    finish       (second part) ordered pass over the gradient: pairs + Index words
 //
-// Ordered output across workgroups uses a decoupled look-back on persistent, fully
-// resident grids with strided work assignment.
+// Ordered output across workgroups: every item publishes its counts as soon as it has
+// them and learns its offset from the counts of earlier items only, which belong to
+// workgroups dispatched before its own; no kernel needs the device to itself.
 #include "device_utils.h"
 #include "tagc_internal.h"
 
