@@ -34,7 +34,10 @@ STAGES = {
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # (workload, kernel): bytes per launch = (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE) KiB * 1024
+    ("config5", "scan_spill"): int((2.0 * 197685.9 + 17002.9) * 1024),
+}
 
 
 def parse_args():
