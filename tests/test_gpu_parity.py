@@ -327,3 +327,22 @@ def test_pre_threshold_carried_between_calls_never_changes_results(dtype):
     assert dense[0] == 0 and dense[1] == 0      # sampled, then the carried hint
     assert dense[2] == 1 and dense[3] == 1      # the hint failed both ways: exact fallback
     assert dense[6] == 0                        # and recovered (rank 5 still pays for rank 4)
+
+
+def test_more_than_64_candidate_route_segments():
+    """70 segments that all take the candidate route (the final kernel reads the segment
+    tables lane-parallel for up to 64 segments and falls back to a search beyond), with
+    ragged lengths so that super-chunks end inside chunks, and varying keep ratios."""
+    _announce("70 fast segments")
+    rng = np.random.default_rng(5)
+    segs, sigma, off = [], {}, 0
+    for i in range(70):
+        n = (1 << 17) + int(rng.integers(0, 5000))
+        name = "s%d" % i
+        segs.append(G.Seg(off, n, int(rng.integers(5_000, 30_000)), 1, name))
+        sigma[name] = float(10 ** rng.uniform(-4, -2))
+        off = (off + n + 7) // 8 * 8
+    b = G.Bucket("many", G.BF16, 2, segs, off, 1500, sigma)
+    ores, tb = run_both(b, _grads(b), seed=13)
+    compare_all(b, ores, tb)
+    assert [tb.rank_counts(r)["dense_segments"] for r in range(2)] == [0, 0]
