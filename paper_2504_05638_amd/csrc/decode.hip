@@ -168,6 +168,15 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     const uint32_t Pa = uint32_t(uint64_t(a + 1) * U / A) - rho0;
     const uint32_t cells = 3 * m_sub;
 
+    // ---- the partition's c-indices are requested first (P_cap <= 16 per thread), so that
+    // they arrive while the cells are being staged
+    constexpr uint32_t kIdxPre = kMaxPartUnknowns / kDecodeThreads;
+    uint32_t pre_idx[kIdxPre];
+#pragma unroll
+    for (uint32_t q = 0; q < kIdxPre; ++q) {
+        const uint32_t u = tid + q * kDecodeThreads;
+        pre_idx[q] = u < Pa ? idx_out[rho0 + u] : 0u;
+    }
     // ---- stage the partition's cells (16-byte loads where the tile is aligned), clear state
     {
         const float *src = sketch + uint64_t(a) * cells;
@@ -192,13 +201,17 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     PHASE_MARK(0);
 
     // ---- every unknown joins its three cells; all values start at 0
-    for (uint32_t u = tid; u < Pa; u += kDecodeThreads) {
-        const uint32_t i = idx_out[rho0 + u];
-        idx[u] = i;
-        const Cells cl = cells_of(i, m_sub, sw0, sw1, sw2);
-        const unsigned long long inc = (unsigned long long)((u << 15) + 1u) << 32;
 #pragma unroll
-        for (int j = 0; j < 3; ++j) atomicAdd(&cell[cl.c[j]], inc);
+    for (uint32_t q = 0; q < kIdxPre; ++q) {
+        const uint32_t u = tid + q * kDecodeThreads;
+        if (u < Pa) {
+            const uint32_t i = pre_idx[q];
+            idx[u] = i;
+            const Cells cl = cells_of(i, m_sub, sw0, sw1, sw2);
+            const unsigned long long inc = (unsigned long long)((u << 15) + 1u) << 32;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) atomicAdd(&cell[cl.c[j]], inc);
+        }
     }
     __syncthreads();
     for (uint32_t c0 = 0; c0 < cells; c0 += kDecodeThreads) {
