@@ -74,12 +74,14 @@ __device__ inline uint32_t vec_elem_bits(const uint32_t (&w)[4], uint32_t e)
 // owns the BPT consecutive bins starting at t*BPT.  Returns false if the whole histogram
 // holds fewer than `need`; *total_out is the histogram's sum either way.  A second count
 // `need2` (0 = none) is located in the same pass: *bin2_out is the largest bin with at
-// least need2 entries at or above it, or 0xFFFFFFFF if the histogram holds fewer.
+// least need2 entries at or above it, or 0xFFFFFFFF if the histogram holds fewer.  So is,
+// on request, the number of entries in the bins from `tail_from` upwards.
 template <int BPT>
 __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t *bin_out,
                                    uint32_t *above_out, uint32_t *at_out, uint32_t *total_out,
-                                   uint32_t *smem /* >= 20 words */, uint32_t need2 = 0,
-                                   uint32_t *bin2_out = nullptr)
+                                   uint32_t *smem /* >= 24 words */, uint32_t need2 = 0,
+                                   uint32_t *bin2_out = nullptr, uint32_t tail_from = 0,
+                                   uint32_t *tail_out = nullptr)
 {
     const uint32_t t = threadIdx.x;
     const uint4 *hv = reinterpret_cast<const uint4 *>(hist + uint64_t(t) * BPT);
@@ -94,8 +96,13 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
     uint32_t total;
     uint32_t prefix = block_excl_scan<uint32_t, kHistThreads / 64>(s, &total, smem);
     uint32_t suffix = total - prefix;  // bins of this thread and all higher ones
-    if (t == 0) smem[19] = 0xFFFFFFFFu;
+    if (t == 0) {
+        smem[19] = 0xFFFFFFFFu;
+        smem[20] = 0;
+    }
     __syncthreads();
+    // entries in the bins from `tail_from` (a multiple of BPT) upwards, if asked for
+    if (tail_out && t * BPT >= tail_from && s) atomicAdd(&smem[20], s);
     if (total >= need && suffix >= need && suffix - s < need) {
         uint32_t acc = suffix - s;
         bool done = false;
@@ -130,6 +137,7 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
     *at_out = smem[18];
     *total_out = total;
     if (bin2_out) *bin2_out = smem[19];
+    if (tail_out) *tail_out = smem[20];
     __syncthreads();
     return total >= need;
 }
@@ -545,18 +553,16 @@ __device__ inline void select1_segment(uint32_t l, const SegDev &sd, const uint3
         return;
     }
     const uint32_t *h = hist + uint64_t(l) * kBins1;
-    uint32_t nf = 0;  // inputs with an all-ones exponent fall into bins >= 0x7F80
-    if (threadIdx.x >= 0x7F80u / 32)
-        for (int i = 0; i < 32; ++i) nf += h[threadIdx.x * 32 + i];
-    nf = block_sum<uint32_t, kHistThreads / 64>(nf, smem);
     // Besides the threshold bin: the pre-threshold for the next call on this plan, the bin
     // above which about 1.3 k entries lie (what the slots per chunk are sized for).  The
     // candidate histogram may not reach that far down; then one bin below this call's
     // pre-threshold.  A miss withdraws the hint, so that the next call samples again.
-    uint32_t bin, above, at, total, bin2;
+    uint32_t bin, above, at, total, bin2, nf;
     const bool fast = (sd.flags & kSegFast) != 0;
     const uint32_t want = fast ? uint32_t(1.3f * float(sd.k)) + 1u : 0u;
-    const bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem, want, &bin2);
+    // nf: inputs with an all-ones exponent fall into bins >= 0x7F80
+    const bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem, want, &bin2,
+                                       0x7F80u, &nf);
     if (threadIdx.x != 0) return;
     if (fast) {
         uint32_t nh;
