@@ -138,11 +138,19 @@ __device__ inline void queue_push3(bool p0, uint32_t v0, bool p1, uint32_t v1, b
     if (p2) queue[base + n0 + n1 + uint32_t(__popcll(b2 & lt))] = uint16_t(v2);
 }
 
-constexpr uint32_t kPeelMaxSweeps = 16;  // queue entries per thread per round, at most
 
-// Peels one sketch partition: unknowns rho0 .. rho0+Pa-1 of idx_out, cells a*3*m_sub ...
+// Peels sketch partitions: unknowns rho0 .. rho0+Pa-1 of idx_out, cells a*3*m_sub ...
 // An LDS cell is 64 bits: value bits in the low half, meta word (rank-sum << 15 | degree)
 // in the high half, so one compare-and-swap subtracts a value and removes an unknown.
+//
+// The LDS a partition needs leaves room for one workgroup per CU, and the rounds are bound
+// by LDS latency, not by memory.  So the grid is one workgroup per CU, each taking
+// partitions b, b+G, ...; while one partition is being peeled the cells and c-indices of
+// the workgroup's next one are already on their way into registers, and staging it costs
+// LDS stores only.
+// kCellPre / kIdxPre: cells / unknowns per thread the instantiation can hold (a partition has
+// at most kCellPre * kDecodeThreads cells, so a round's queue needs kCellPre sweeps at most).
+template <uint32_t kCellPre, uint32_t kIdxPre>
 __global__ void __launch_bounds__(kDecodeThreads)
 peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ header,
             const uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
@@ -159,44 +167,44 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     const uint32_t tid = threadIdx.x;
     const uint32_t U = header[TAGC_HDR_U], A = header[TAGC_HDR_A];
     const uint32_t m_sub = header[TAGC_HDR_MSUB];
-    const uint32_t a = blockIdx.x;
-    if (a >= A) return;
     const uint32_t *meta_hi = reinterpret_cast<const uint32_t *>(cell) + 1;  // meta of cell c: [2c]
+    const uint32_t cells = 3 * m_sub;
 
+    // the cells and c-indices of partition `p` into registers (zeros beyond their ends)
+    float pre_cell[kCellPre];
+    uint32_t pre_idx[kIdxPre];
+    auto prefetch = [&](uint32_t p) {
+        const uint32_t r0 = uint32_t(uint64_t(p) * U / A);
+        const uint32_t n = uint32_t(uint64_t(p + 1) * U / A) - r0;
+        const float *src = sketch + uint64_t(p) * cells;
+#pragma unroll
+        for (uint32_t q = 0; q < kCellPre; ++q) {
+            const uint32_t c = tid + q * kDecodeThreads;
+            pre_cell[q] = c < cells ? src[c] : 0.0f;
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < kIdxPre; ++q) {
+            const uint32_t u = tid + q * kDecodeThreads;
+            pre_idx[q] = u < n ? idx_out[r0 + u] : 0u;
+        }
+    };
+    if (blockIdx.x < A) prefetch(blockIdx.x);
+    if (tid == 0) s_any = 0;  // ordered before its first use by the barriers below
+
+    uint32_t sweep = 0, max_rounds = 0;
+    for (uint32_t a = blockIdx.x; a < A; a += gridDim.x) {
     PHASE_INIT();
     const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
     const uint32_t Pa = uint32_t(uint64_t(a + 1) * U / A) - rho0;
-    const uint32_t cells = 3 * m_sub;
 
-    // ---- the partition's c-indices are requested first (P_cap <= 16 per thread), so that
-    // they arrive while the cells are being staged
-    constexpr uint32_t kIdxPre = kMaxPartUnknowns / kDecodeThreads;
-    uint32_t pre_idx[kIdxPre];
+    // ---- stage the partition's cells from the registers, clear state
 #pragma unroll
-    for (uint32_t q = 0; q < kIdxPre; ++q) {
-        const uint32_t u = tid + q * kDecodeThreads;
-        pre_idx[q] = u < Pa ? idx_out[rho0 + u] : 0u;
-    }
-    // ---- stage the partition's cells (16-byte loads where the tile is aligned), clear state
-    {
-        const float *src = sketch + uint64_t(a) * cells;
-        const uint32_t head = min(cells, uint32_t((4u - (uint64_t(a) * cells & 3u)) & 3u));
-        const uint32_t n4 = (cells - head) / 4;
-        if (tid < head) cell[tid] = __float_as_uint(src[tid]);
-        for (uint32_t v = tid; v < n4; v += kDecodeThreads) {
-            const float4 q = *reinterpret_cast<const float4 *>(src + head + 4 * v);
-            unsigned long long *d = cell + head + 4 * v;
-            d[0] = __float_as_uint(q.x); d[1] = __float_as_uint(q.y);
-            d[2] = __float_as_uint(q.z); d[3] = __float_as_uint(q.w);
-        }
-        for (uint32_t c = head + 4 * n4 + tid; c < cells; c += kDecodeThreads)
-            cell[c] = __float_as_uint(src[c]);
+    for (uint32_t q = 0; q < kCellPre; ++q) {
+        const uint32_t c = tid + q * kDecodeThreads;
+        if (c < cells) cell[c] = __float_as_uint(pre_cell[q]);
     }
     for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) claimed[c] = 0;
-    if (tid == 0) {
-        s_tail = 0;
-        s_any = 0;
-    }
+    if (tid == 0) s_tail = 0;
     __syncthreads();
     PHASE_MARK(0);
 
@@ -213,6 +221,8 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
             for (int j = 0; j < 3; ++j) atomicAdd(&cell[cl.c[j]], inc);
         }
     }
+    // the registers are free again: the next partition's data travels during the rounds
+    if (a + gridDim.x < A) prefetch(a + gridDim.x);
     __syncthreads();
     for (uint32_t c0 = 0; c0 < cells; c0 += kDecodeThreads) {
         const uint32_t c = c0 + tid;
@@ -220,8 +230,8 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     }
     PHASE_MARK(1);
 
-    // ---- peel
-    uint32_t rounds = 0, head = 0, sweep = 0;
+    // ---- peel (`sweep` keeps counting across partitions: s_any only has to differ)
+    uint32_t rounds = 0, head = 0;
     while (true) {
         ++sweep;
         __syncthreads();  // queue and s_tail of the previous phase are complete
@@ -230,10 +240,10 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
         // read phase: claim the unknown of every queued cell that still has degree 1 and
         // fix, from the degrees as they stand now, the hash function its value comes from.
         // item: c0 | c1 << 14 | c2 << 28 | neg << 42 | j << 45 | u << 47
-        unsigned long long item[kPeelMaxSweeps];
+        unsigned long long item[kCellPre];
         uint32_t mine = 0;
 #pragma unroll
-        for (uint32_t it = 0; it < kPeelMaxSweeps; ++it) {
+        for (uint32_t it = 0; it < kCellPre; ++it) {
             item[it] = 0;
             if (head + it * kDecodeThreads >= tail) continue;  // uniform
             const uint32_t e = head + it * kDecodeThreads + tid;
@@ -262,7 +272,7 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
         }
         ++rounds;
 #pragma unroll
-        for (uint32_t it = 0; it < kPeelMaxSweeps; ++it) {
+        for (uint32_t it = 0; it < kCellPre; ++it) {
             if (!((mine >> it) & 1u)) continue;
             const unsigned long long p = item[it];
             const uint32_t c[3] = {uint32_t(p) & 0x3FFFu, uint32_t(p >> 14) & 0x3FFFu,
@@ -306,11 +316,11 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     uint32_t resolved = 0;
     for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) resolved += __popc(claimed[c]);
     resolved = block_sum<uint32_t, kDecodeThreads / 64>(resolved, scratch);
-    if (tid == 0) {
-        if (resolved < Pa) atomicAdd(&status[TAGC_ST_UNRESOLVED], Pa - resolved);
-        atomicMax(&status[TAGC_ST_ROUNDS], rounds);
-    }
+    if (tid == 0 && resolved < Pa) atomicAdd(&status[TAGC_ST_UNRESOLVED], Pa - resolved);
+    max_rounds = max(max_rounds, rounds);
     PHASE_MARK(3);
+    }  // partitions of this workgroup
+    if (tid == 0 && max_rounds) atomicMax(&status[TAGC_ST_ROUNDS], max_rounds);
 }
 
 // Dense output: one workgroup per 1024-word chunk of the Index writes the 32768 floats
@@ -384,15 +394,23 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
     {
         ProfileScope ps("peel", s);
         const size_t lds = decode_lds_bytes(p->T_cap, p->P_cap);
-        static size_t attr_bytes = 0;
-        if (lds > attr_bytes) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(peel_kernel),
+        const uint32_t grid = uint32_t(std::min<uint64_t>(p->A_cap, uint64_t(device_cu_count())));
+        // the default partition size gets an instantiation that holds exactly its data
+        constexpr uint32_t kC0 = (kDefaultPartCells + kDecodeThreads - 1) / kDecodeThreads;
+        constexpr uint32_t kI0 = (kDefaultPartUnknowns + kDecodeThreads - 1) / kDecodeThreads;
+        constexpr uint32_t kC1 = (kMaxPartCells + kDecodeThreads - 1) / kDecodeThreads;
+        constexpr uint32_t kI1 = (kMaxPartUnknowns + kDecodeThreads - 1) / kDecodeThreads;
+        const bool small = p->T_cap <= kC0 * kDecodeThreads && p->P_cap <= kI0 * kDecodeThreads;
+        auto kernel = small ? peel_kernel<kC0, kI0> : peel_kernel<kC1, kI1>;
+        static size_t attr_bytes[2] = {0, 0};
+        if (lds > attr_bytes[small]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     int(lds)) != hipSuccess)
                 return TAGC_EHIP;
-            attr_bytes = lds;
+            attr_bytes[small] = lds;
         }
-        peel_kernel<<<uint32_t(p->A_cap), kDecodeThreads, lds, s>>>(
+        kernel<<<grid, kDecodeThreads, lds, s>>>(
             sh->sketch, sh->header, idx_out, val_out, sh->status, p->seed_word[0],
             p->seed_word[1], p->seed_word[2], p->T_cap, p->P_cap);
     }
