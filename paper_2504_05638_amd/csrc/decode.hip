@@ -191,7 +191,7 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     if (blockIdx.x < A) prefetch(blockIdx.x);
     if (tid == 0) s_any = 0;  // ordered before its first use by the barriers below
 
-    uint32_t sweep = 0, max_rounds = 0;
+    uint32_t sweep = 1, max_rounds = 0;  // s_any starts at 0: no round has number 0 or 1
     for (uint32_t a = blockIdx.x; a < A; a += gridDim.x) {
     PHASE_INIT();
     const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
@@ -230,61 +230,41 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     }
     PHASE_MARK(1);
 
-    // ---- peel (`sweep` keeps counting across partitions: s_any only has to differ)
+    // ---- peel.  One barrier per round: the queue segment [head, tail) holds the cells
+    // that reached degree 1 in the previous round.  A cell of degree 1 is touched by its own
+    // unknown only, so whoever claims that unknown may read its value there at any time;
+    // every other cell is only ever changed by compare-and-swap.  Removals of a round run
+    // concurrently with its claims, which changes neither the set of unknowns the round
+    // resolves (a cell that reaches degree 1 now is queued for the next round) nor, beyond
+    // rounding order, their values.  "Did the round resolve anything" travels through an
+    // LDS word stamped with the round's number (`sweep` keeps counting across partitions,
+    // so a stale stamp never matches).
     uint32_t rounds = 0, head = 0;
     while (true) {
         ++sweep;
-        __syncthreads();  // queue and s_tail of the previous phase are complete
+        __syncthreads();  // queue, s_tail and cells of the previous round are complete
+        if (s_any == sweep - 1) ++rounds;
         const uint32_t tail = s_tail;
         if (tail == head) break;
-        // read phase: claim the unknown of every queued cell that still has degree 1 and
-        // fix, from the degrees as they stand now, the hash function its value comes from.
-        // item: c0 | c1 << 14 | c2 << 28 | neg << 42 | j << 45 | u << 47
-        unsigned long long item[kCellPre];
-        uint32_t mine = 0;
-#pragma unroll
-        for (uint32_t it = 0; it < kCellPre; ++it) {
-            item[it] = 0;
-            if (head + it * kDecodeThreads >= tail) continue;  // uniform
-            const uint32_t e = head + it * kDecodeThreads + tid;
-            if (e >= tail) continue;
-            const uint32_t m = meta_hi[2 * queue[e]];
-            if ((m & kDegMask) != 1u) continue;  // emptied later in the round that queued it
+        for (uint32_t e = head + tid; e < tail; e += kDecodeThreads) {
+            const uint32_t q = queue[e];
+            const unsigned long long oq = cell[q];
+            const uint32_t m = uint32_t(oq >> 32);
+            if ((m & kDegMask) != 1u) continue;  // emptied since it was queued
             const uint32_t u = m >> 15, bit = 1u << (u & 31);
             if (atomicOr(&claimed[u >> 5], bit) & bit) continue;  // reached through another cell
+            s_any = sweep;
             const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
-            const uint32_t d0 = meta_hi[2 * cl.c[0]] & kDegMask, d1 = meta_hi[2 * cl.c[1]] & kDegMask;
-            const uint32_t j = d0 == 1u ? 0u : (d1 == 1u ? 1u : 2u);
-            item[it] = (unsigned long long)cl.c[0] | ((unsigned long long)cl.c[1] << 14) |
-                       ((unsigned long long)cl.c[2] << 28) | ((unsigned long long)cl.neg << 42) |
-                       ((unsigned long long)j << 45) | ((unsigned long long)u << 47);
-            mine |= 1u << it;
-        }
-        // barrier between the reads above and the updates below.  A cell of degree 1 is
-        // touched by its own unknown only, so its value can still be read there.  "Did
-        // anyone claim anything" travels through an LDS word stamped with the sweep number
-        // (a plain barrier is ten times cheaper than a voting one here).
-        if (mine) s_any = sweep;
-        __syncthreads();
-        if (s_any != sweep) {
-            head = tail;
-            continue;
-        }
-        ++rounds;
-#pragma unroll
-        for (uint32_t it = 0; it < kCellPre; ++it) {
-            if (!((mine >> it) & 1u)) continue;
-            const unsigned long long p = item[it];
-            const uint32_t c[3] = {uint32_t(p) & 0x3FFFu, uint32_t(p >> 14) & 0x3FFFu,
-                                   uint32_t(p >> 28) & 0x3FFFu};
-            const uint32_t neg = uint32_t(p >> 42) & 7u, j = uint32_t(p >> 45) & 3u;
-            const uint32_t u = uint32_t(p >> 47);
-            unsigned long long o[3] = {cell[c[0]], cell[c[1]], cell[c[2]]};
-            const float cv = __uint_as_float(uint32_t(j == 0 ? o[0] : (j == 1 ? o[1] : o[2])));
+            const uint32_t c[3] = {cl.c[0], cl.c[1], cl.c[2]};
+            const uint32_t neg = cl.neg;
+            const uint32_t j = c[0] == q ? 0u : (c[1] == q ? 1u : 2u);
+            const float cv = __uint_as_float(uint32_t(oq));
             const float x = ((neg >> j) & 1u) ? -cv : cv;
             idx[u] = __float_as_uint(x);  // the c-index has done its job: keep the value there
             const unsigned long long dec = (unsigned long long)((u << 15) + 1u) << 32;
-            unsigned long long r[3];
+            unsigned long long o[3], r[3];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) o[k] = uint32_t(k) == j ? oq : cell[c[k]];
 #pragma unroll
             for (int k = 0; k < 3; ++k) {
                 const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
