@@ -3,7 +3,8 @@
  *
  * A plain, sequential, single-threaded C implementation of what one TAGC
  * communication-hook call computes for a gradient bucket (paper Algorithm 1,
- * the sparsify / create_index / compress / peeling_decompress steps, with the
+ * the accumulate / sparsify / create_index / compress / peeling_decompress
+ * steps, with the
  * two collectives replaced by an element-wise OR and an element-wise sum over
  * N simulated ranks).  It exists so that the HIP library can be checked
  * against something that can be read side by side with the paper.  It shares
@@ -147,6 +148,59 @@ int64_t tagco_sparsify_segment(const void *g, int dtype, uint64_t offset,
     free(pos);
     *cnt_out = take;
     return nonfinite;
+}
+
+/* --------------------------------------------------- error feedback */
+
+/* Algorithm 1, first line: g_shard <- g_shard + acc, the local gradient
+ * accumulation of section 3.2 ("Gradient Sparsification": the values that
+ * were zeroed are kept locally and added to the gradient of the next
+ * iteration).  The paper does not say in which precision; this repository
+ * reads it as the in-place add of the hook, i.e. in the gradient's own type:
+ * one float32 add of the two widened operands, rounded to nearest-even back
+ * to bf16 for bf16 gradients.  Elements [offset, offset + n) of `g` and
+ * `acc` (raw buffers of `dtype`) are read, the sums written to `out` (same
+ * layout; may alias either input). */
+void tagco_accumulate(const void *g, const void *acc, int dtype,
+                      uint64_t offset, uint64_t n, void *out)
+{
+    for (uint64_t p = offset; p < offset + n; ++p) {
+        uint32_t ga = f32_bits_at(g, dtype, p), aa = f32_bits_at(acc, dtype, p);
+        float gf, af, sum;
+        memcpy(&gf, &ga, 4);
+        memcpy(&af, &aa, 4);
+        sum = gf + af;
+        uint32_t sb;
+        memcpy(&sb, &sum, 4);
+        if (dtype == TAGCO_F32) {
+            memcpy((char *)out + 4 * p, &sb, 4);
+        } else {
+            /* round to nearest, ties to even, on the 16 discarded bits
+             * (NaN keeps a set mantissa bit) */
+            uint16_t h;
+            if ((sb & 0x7F800000u) == 0x7F800000u && (sb & 0x007FFFFFu))
+                h = (uint16_t)((sb >> 16) | 0x0040u);
+            else
+                h = (uint16_t)((sb + 0x7FFFu + ((sb >> 16) & 1u)) >> 16);
+            memcpy((char *)out + 2 * p, &h, 2);
+        }
+    }
+}
+
+/* Algorithm 1, second line, second result: acc_next keeps what sparsify
+ * removed.  `summed` holds g + acc for segment elements [offset, offset+n);
+ * `sel_pos` the `cnt` selected positions (relative to the segment,
+ * ascending).  acc_next = summed at every other position and zero (+0) at
+ * the selected ones, so that summed = sent + acc_next element by element.
+ * `acc_next` may alias `summed`. */
+void tagco_residual(const void *summed, int dtype, uint64_t offset, uint64_t n,
+                    const uint32_t *sel_pos, uint64_t cnt, void *acc_next)
+{
+    const uint64_t eb = dtype == TAGCO_F32 ? 4 : 2;
+    if (acc_next != summed)
+        memcpy((char *)acc_next + eb * offset, (const char *)summed + eb * offset, eb * n);
+    for (uint64_t t = 0; t < cnt; ++t)
+        memset((char *)acc_next + eb * (offset + sel_pos[t]), 0, eb);
 }
 
 /* --------------------------------------------------------- index merging */

@@ -58,6 +58,12 @@ def lib():
             C.c_void_p, C.c_int, C.c_uint64, C.c_uint64, C.c_uint64,
             C.c_uint32, u32p, f32p, u32p, u64p]
         L.tagco_index_or.restype = C.c_uint64
+        L.tagco_accumulate.restype = None
+        L.tagco_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_uint64,
+                                       C.c_uint64, C.c_void_p]
+        L.tagco_residual.restype = None
+        L.tagco_residual.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint64, u32p,
+                                     C.c_uint64, C.c_void_p]
         L.tagco_index_or.argtypes = [C.POINTER(u32p), C.c_uint32, C.c_uint64,
                                      u32p]
         L.tagco_layout.restype = None
@@ -191,6 +197,35 @@ def sparsify(grad, cfg: Config, segments) -> RankState:
         seg_cnt.append(int(c.value))
         pos += int(c.value)
     return RankState(idx[:pos].copy(), val[:pos].copy(), pos, seg_cnt, bitmap)
+
+
+def error_feedback_step(grad, acc, cfg: Config, segments):
+    """Algorithm 1 lines 1-2 for one rank: g' = g + acc over the compressed segments,
+    sparsify(g'), and acc_next = g' minus what was selected.  `grad`, `acc`: raw arrays
+    as for `sparsify`.  Returns (RankState of g', acc_next raw array).  Elements outside
+    the compressed segments are passed through unchanged in acc_next."""
+    L = lib()
+    g, a = _as_raw(grad, cfg.dtype), _as_raw(acc, cfg.dtype)
+    if a.size < g.size:
+        raise ValueError("accumulator shorter than the gradient")
+    summed = a.copy()
+    offs, _ = c_offsets(segments)
+    for s, co in zip(segments, offs):
+        if co is None:
+            continue
+        L.tagco_accumulate(g.ctypes.data_as(C.c_void_p), a.ctypes.data_as(C.c_void_p),
+                           cfg.dtype, s.offset, s.length, summed.ctypes.data_as(C.c_void_p))
+    st = sparsify(summed[:g.size] if summed.size != g.size else summed, cfg, segments)
+    acc_next = summed.copy()
+    pos = 0
+    for s, co, c in zip(segments, offs, st.seg_cnt):
+        if co is None:
+            continue
+        sel = np.ascontiguousarray(st.idx[pos:pos + c] - np.uint32(co))
+        L.tagco_residual(summed.ctypes.data_as(C.c_void_p), cfg.dtype, s.offset, s.length,
+                         _u32p(sel) if c else None, c, acc_next.ctypes.data_as(C.c_void_p))
+        pos += c
+    return st, acc_next
 
 
 def index_or(bitmaps):
