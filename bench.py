@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # Kernels of the library grouped into the stages of the path.
 STAGES = {
-    "S1+S2 sparsify+index": ["fill_zero", "sample", "scan_spill", "select1", "hist1",
+    "S1+S2 sparsify+index": ["fill_zero", "accumulate", "sample", "scan_spill", "select1", "hist1",
                              "hist2c", "hist2", "select2", "finish"],
     "S3a index OR": ["index_or", "header", "bounds", "ranges"],
     "S2' encode": ["encode"],
@@ -60,6 +60,9 @@ def parse_args():
                     help="non-zeros per sketch partition (0 = library default)")
     ap.add_argument("--part-cells", type=int, default=0,
                     help="sketch cells per partition (0 = library default)")
+    ap.add_argument("--error-feedback", action="store_true",
+                    help="give every rank a gradient accumulator (Algorithm 1, lines 1-2): "
+                         "adds one read and one write of the gradient's size per rank")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="before the timed region, copy this many MiB device to device three "
@@ -90,14 +93,15 @@ def make_buckets(args):
     return bs
 
 
-def alg_bytes(b, z, hdr, k_total, dense):
-    """Algorithmic bytes per stage for one bucket: one read of the gradient, every
-    message materialised once; work-lists, histograms and degree tables are not
-    credited."""
+def alg_bytes(b, z, hdr, k_total, dense, ef=False):
+    """Algorithmic bytes per stage for one bucket: one read of the gradient (with error
+    feedback also one read and one write of the accumulator), every message
+    materialised once; work-lists, histograms and degree tables are not credited."""
     N, e = b.n_ranks, b.elem_bytes
     n_c, U, m = z.n_c, hdr["U"], hdr["m"]
+    passes = 3 if ef else 1
     return {
-        "S1+S2 sparsify+index": N * z.n_real * e + 8 * k_total + N * n_c // 8,
+        "S1+S2 sparsify+index": passes * N * z.n_real * e + 8 * k_total + N * n_c // 8,
         "S3a index OR": N * n_c // 8 + n_c // 8,
         "S2' encode": 8 * k_total + N * 4 * m,
         "S3b sketch sum": (N + 1) * 4 * m,
@@ -105,7 +109,7 @@ def alg_bytes(b, z, hdr, k_total, dense):
     }
 
 
-def kernel_alg_bytes(b, z, hdr, k_total, dense):
+def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False):
     """Bytes each bandwidth-relevant kernel must itself move per bucket (all its
     launches together).  hist1 and compact each read the gradient once, so their sum
     exceeds the stage's algorithmic bytes: the stage figure shows the cost of the
@@ -113,7 +117,7 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense):
     N, e = b.n_ranks, b.elem_bytes
     n_c, U, m = z.n_c, hdr["U"], hdr["m"]
     return {
-        "scan_spill": N * z.n_real * e,
+        "scan_spill": (3 if ef else 1) * N * z.n_real * e,
         "hist1": N * z.n_real * e,
         "hist2": N * z.n_real * e,
         # finish = emit (candidate route) + compact (dense route: reads the gradient again);
@@ -217,6 +221,7 @@ def main():
         tbs.append(TagcBucket(b.segments, b.dtype, N, sizing_milli=b.sizing_milli,
                               seed=args.seed, dense=bool(args.dense),
                               part_unknowns=args.part_unknowns, part_cells=args.part_cells,
+                              error_feedback=args.error_feedback,
                               share=None if first else tbs[i % lanes],
                               min_bytes=need if first else None))
     stream = torch.cuda.current_stream()
@@ -254,9 +259,9 @@ def main():
         flags |= st["flags"]
         for r in range(N):
             flags |= tbs[i].rank_counts(r)["flags"]
-        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense).items():
+        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback).items():
             balg[k] += v
-        for k, v in kernel_alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense).items():
+        for k, v in kernel_alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback).items():
             kalg[k] = kalg.get(k, 0) + v
         input_bytes += N * tbs[i].sizes.n_real * buckets[i].elem_bytes
         unresolved += st["n_unresolved"]
@@ -282,7 +287,9 @@ def main():
         bad = st["flags"]
         for r in range(N):
             bad |= tbs[i].rank_counts(r)["flags"]
-        if bad or (hdr, st) != facts[i]:
+        # (with error feedback every pass starts from different accumulators, so U and the
+        # residue legitimately change from pass to pass: only the flags are checked then)
+        if bad or (not args.error_feedback and (hdr, st) != facts[i]):
             sys.stderr.write("bench.py: bucket %d differs when run with %d buckets in flight "
                              "(flags %d)\n" % (i, lanes, bad))
             sys.exit(1)
@@ -339,7 +346,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d buckets x %d simulated ranks, %s grads, lf %.1f, %s"
-                               % (args.workload, n_b, N,
+                               % (args.workload + (" + error feedback" if args.error_feedback
+                                                   else ""), n_b, N,
                                   "bf16" if buckets[0].dtype == G.BF16 else "fp32",
                                   buckets[0].sizing_milli / 1000.0,
                                   "sparse+dense output" if args.dense else "sparse output"),

@@ -158,6 +158,9 @@ typedef struct tagc_rank_buffers {
                            [0, m) are written, the rest untouched              */
     void *workspace;    /* [rank_workspace_bytes] scratch, may be shared by ranks
                            processed one after another on one stream           */
+    void *acc;          /* NULL, or [grad_elems] of the plan's dtype: the rank's
+                           gradient accumulator (Algorithm 1: acc in, acc_next
+                           out, in place); see PHASE_INDEX                      */
 } tagc_rank_buffers;
 
 /* Device buffers shared by the bucket (all dev, caller-owned). */
@@ -203,6 +206,12 @@ int tagc_plan_upload(const tagc_plan_t *plan, void *table_dev, void *stream);
  *   the survivors as (c-index, float32 value) pairs in ascending c-index to
  *   rank->idx / rank->val, counts to rank->cnt, and the local Index to
  *   rank->bitmap (every word is written).  Uses rank->workspace.
+ *   With rank->acc set (Algorithm 1, lines 1-2; section 3.2, local gradient
+ *   accumulation) the entries of the compressed segments are first replaced by
+ *   grad + acc, added in the gradient's own type (bf16: one float32 add rounded
+ *   to nearest-even), and afterwards acc holds, in those segments, that sum
+ *   where the entry was not selected and zero where it was: what was selected
+ *   plus the new acc is the sum, element by element.  grad_dev is only read.
  * PHASE_SKETCH (Algorithm 1: compress(g_shard, index)).  Needs the shared
  *   header written by tagc_aggregate(PHASE_INDEX), which must have been given
  *   this rank among its `ranks` (it leaves the rank's partition ranges in

@@ -66,7 +66,7 @@ class tagc_sizes(C.Structure):
 class tagc_rank_buffers(C.Structure):
     _fields_ = [("idx", C.c_void_p), ("val", C.c_void_p), ("cnt", C.c_void_p),
                 ("bitmap", C.c_void_p), ("sketch", C.c_void_p),
-                ("workspace", C.c_void_p)]
+                ("workspace", C.c_void_p), ("acc", C.c_void_p)]
 
 
 class tagc_shared_buffers(C.Structure):

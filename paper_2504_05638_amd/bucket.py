@@ -27,7 +27,8 @@ class TagcBucket:
 
     def __init__(self, segments, dtype, n_ranks, sizing_milli=3000,
                  sizing=B.TAGC_SIZE_LOAD_FACTOR, seed=0, part_unknowns=0,
-                 part_cells=0, device="cuda", dense=False, share=None, min_bytes=None):
+                 part_cells=0, device="cuda", dense=False, share=None, min_bytes=None,
+                 error_feedback=False):
         if not torch.cuda.is_available():
             raise RuntimeError("libtagc needs a GPU: no CPU path exists")
         self.device = torch.device(device)
@@ -66,11 +67,15 @@ class TagcBucket:
                      cnt=al("cnt%d" % r, z.rank_cnt_bytes),
                      bitmap=al("bitmap%d" % r, z.rank_bitmap_bytes),
                      sketch=al("sketch%d" % r, z.rank_sketch_bytes))
+            if error_feedback:  # the rank's gradient accumulator, zero before the first step
+                t["acc"] = torch.zeros(max(int(z.grad_elems), 8), device=dev,
+                                       dtype=torch.float32 if dtype == B.TAGC_F32
+                                       else torch.bfloat16)
             self._rk_tensors.append(t)
             self.rk.append(B.tagc_rank_buffers(
                 t["idx"].data_ptr(), t["val"].data_ptr(), t["cnt"].data_ptr(),
                 t["bitmap"].data_ptr(), t["sketch"].data_ptr(),
-                self.rank_ws.data_ptr()))
+                self.rank_ws.data_ptr(), t["acc"].data_ptr() if error_feedback else None))
         self.out_idx = al("out_idx", z.out_idx_bytes)
         self.out_val = al("out_val", z.out_val_bytes)
         self.out_dense = al("out_dense", z.out_dense_bytes) if dense else None
@@ -175,6 +180,12 @@ class TagcBucket:
         n = self.rank_counts(r)["total"]
         return (self._np(self._rk_tensors[r]["idx"], np.uint32, n),
                 self._np(self._rk_tensors[r]["val"], np.float32, n))
+
+    def rank_acc(self, r):
+        """The rank's accumulator as raw bit patterns (uint16 for bf16, uint32 for fp32)."""
+        t = self._rk_tensors[r]["acc"]
+        raw = t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
+        return raw.cpu().numpy().view(np.uint16 if t.dtype == torch.bfloat16 else np.uint32).copy()
 
     def rank_bitmap(self, r):
         return self._np(self._rk_tensors[r]["bitmap"], np.uint32, self.sizes.bitmap_words)

@@ -46,6 +46,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     p->chunk_elems = 64 * p->vec_elems * kCandRows;
     p->cand_cap = 32;
     p->static_dense = false;
+    p->any_nonfast = false;
     for (uint32_t j = 0; j < 3; ++j) p->seed_word[j] = seed_word(cfg->seed, j);
 
     uint64_t c = 0, n_real = 0, K = 0, tiles = 0, grad_elems = 0, scs = 0;
@@ -82,6 +83,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
                 }
             }
             if (d.k && d.n && !(d.flags & kSegFast)) p->static_dense = true;
+            if (d.n && !(d.flags & kSegFast)) p->any_nonfast = true;
             d.sc_start = uint32_t(scs);
             scs += ceil_div(s.length, uint64_t(p->chunk_elems) * kCandChunksPerSuper);
             p->table.push_back(d);
@@ -133,8 +135,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     off += round_up(tiles * 8, 16);
     w.sc_state = off;
     off += round_up(scs * 8, 16);
-    w.counters = off;  // one arrival counter per segment
-    off += round_up(4 * std::max<uint64_t>(L, 1), 64);
+    w.counters = off;  // one arrival counter per segment, one tile ticket
+    off += round_up(4 * (L + 1), 64);
     p->zero_bytes = off;
     w.sel = off;
     off += round_up(L * sizeof(SelDev), 16);
@@ -229,6 +231,7 @@ static int check_rank(const tagc_rank_buffers *r)
     if (!aligned16(r->idx) || !aligned16(r->val) || !aligned16(r->cnt) ||
         !aligned16(r->bitmap) || !aligned16(r->sketch) || !aligned16(r->workspace))
         return TAGC_EINVAL;
+    if (r->acc && !aligned16(r->acc)) return TAGC_EINVAL;
     return TAGC_OK;
 }
 

@@ -68,6 +68,77 @@ __device__ inline uint32_t vec_elem_bits(const uint32_t (&w)[4], uint32_t e)
     return DTYPE == kBF16 ? ((w[e >> 1] >> (16 * (e & 1))) << 16) : w[e];
 }
 
+// g + acc in the gradient's own type (Algorithm 1, line 1; section 3.2, local gradient
+// accumulation): one float32 add per entry; a bf16 result is rounded to nearest-even (a NaN
+// keeps a mantissa bit).  `g`, `a`: one 32-bit word of each buffer (two bf16 entries).
+__device__ inline uint32_t round_to_bf16(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    if ((b & 0x7F800000u) == 0x7F800000u && (b & 0x007FFFFFu)) return (b >> 16) | 0x0040u;
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+template <int DTYPE>
+__device__ inline uint32_t sum_word(uint32_t g, uint32_t a)
+{
+    if (DTYPE == kF32) return __float_as_uint(__uint_as_float(g) + __uint_as_float(a));
+    const float lo = __uint_as_float(g << 16) + __uint_as_float(a << 16);
+    const float hi = __uint_as_float(g & 0xFFFF0000u) + __uint_as_float(a & 0xFFFF0000u);
+    return round_to_bf16(lo) | (round_to_bf16(hi) << 16);
+}
+// the same for one entry given as float32 bit patterns; returns the entry's bit pattern in
+// its own type (low 16 bits for bf16)
+template <int DTYPE>
+__device__ inline uint32_t sum_elem(uint32_t g_f32bits, uint32_t a_f32bits)
+{
+    const float x = __uint_as_float(g_f32bits) + __uint_as_float(a_f32bits);
+    return DTYPE == kF32 ? __float_as_uint(x) : round_to_bf16(x);
+}
+__device__ inline void store_elem(char *base, uint64_t i, uint32_t bits, int dtype)
+{
+    if (dtype == kBF16) reinterpret_cast<uint16_t *>(base)[i] = uint16_t(bits);
+    else reinterpret_cast<uint32_t *>(base)[i] = bits;
+}
+
+// Error feedback for the segments scan_spill never streams (short, unaligned, keeping
+// nothing or too much): acc <- grad + acc, entry by entry.  The dense route then reads its
+// input from acc.  Workgroups stride over each such segment.
+template <int DTYPE>
+__global__ void __launch_bounds__(256)
+accumulate_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, char *acc)
+{
+    constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
+    constexpr uint32_t VEC = 16 / EB;
+    const uint32_t L = table[0];
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    for (uint32_t l = 0; l < L; ++l) {
+        const SegDev sd = segs[l];
+        if (sd.n == 0 || (sd.flags & kSegFast)) continue;
+        const char *gb = grad + sd.offset * EB;
+        char *ab = acc + sd.offset * EB;
+        const uint64_t stride = uint64_t(gridDim.x) * 256;
+        if (sd.flags & kSegAligned) {
+            const uint64_t nvec = sd.n / VEC;
+            for (uint64_t v = uint64_t(blockIdx.x) * 256 + threadIdx.x; v < nvec; v += stride) {
+                const uint4 g = reinterpret_cast<const uint4 *>(gb)[v];
+                const uint4 a = reinterpret_cast<const uint4 *>(ab)[v];
+                reinterpret_cast<uint4 *>(ab)[v] =
+                    make_uint4(sum_word<DTYPE>(g.x, a.x), sum_word<DTYPE>(g.y, a.y),
+                               sum_word<DTYPE>(g.z, a.z), sum_word<DTYPE>(g.w, a.w));
+            }
+            if (blockIdx.x == 0) {
+                const uint64_t i = nvec * VEC + threadIdx.x;
+                if (i < sd.n)
+                    store_elem(ab, i, sum_elem<DTYPE>(load_elem_bits(gb, i, DTYPE),
+                                                      load_elem_bits(ab, i, DTYPE)), DTYPE);
+            }
+        } else {
+            for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < sd.n; i += stride)
+                store_elem(ab, i, sum_elem<DTYPE>(load_elem_bits(gb, i, DTYPE),
+                                                  load_elem_bits(ab, i, DTYPE)), DTYPE);
+        }
+    }
+}
+
 // ----------------------------------------------------------------- select
 
 // Largest bin b with  sum_{x >= b} hist[x] >= need  (need >= 1).  1024 threads, thread t
@@ -151,9 +222,10 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
 // the pre-threshold; if that still happens select1 notices and re-routes the segment.
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads)
-sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
-              SelDev *__restrict__ sel, uint32_t *__restrict__ binlo, uint32_t *hint,
-              uint4 *zero_base, uint64_t zero_n16, uint32_t *cnt, uint32_t n_cnt)
+sample_kernel(const char *__restrict__ grad, const char *acc,
+              const uint32_t *__restrict__ table, SelDev *__restrict__ sel,
+              uint32_t *__restrict__ binlo, uint32_t *hint, uint4 *zero_base, uint64_t zero_n16,
+              uint32_t *cnt, uint32_t n_cnt)
 {
     extern __shared__ uint32_t h[];
     __shared__ uint32_t smem[32];
@@ -209,8 +281,14 @@ sample_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
     const uint32_t S = min(nvec, kSampleVectors);
     const uint32_t stride = nvec / S;
     const uint4 *vp = reinterpret_cast<const uint4 *>(grad + sd.offset * EB);
+    const uint4 *ap = acc ? reinterpret_cast<const uint4 *>(acc + sd.offset * EB) : nullptr;
     for (uint32_t i = tid; i < S; i += kHistThreads) {
-        const uint4 q = vp[uint64_t(i) * stride + (stride >> 1)];
+        uint4 q = vp[uint64_t(i) * stride + (stride >> 1)];
+        if (ap) {  // error feedback: what is sparsified is grad + acc
+            const uint4 a = ap[uint64_t(i) * stride + (stride >> 1)];
+            q = make_uint4(sum_word<DTYPE>(q.x, a.x), sum_word<DTYPE>(q.y, a.y),
+                           sum_word<DTYPE>(q.z, a.z), sum_word<DTYPE>(q.w, a.w));
+        }
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (uint32_t e = 0; e < VEC; ++e) {
@@ -267,7 +345,7 @@ constexpr uint32_t kSpillList = 16;    // staged chunks per wave
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kSpillThreads)
-scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
+scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__restrict__ table,
                   SelDev *sel, const uint32_t *__restrict__ binlo, uint32_t *__restrict__ hist,
                   uint32_t *__restrict__ cand, uint32_t *__restrict__ chunk_cnt,
                   uint64_t n_slots_total, uint32_t CAP)
@@ -338,7 +416,7 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
         const SegDev sd = segs[l];
         const uint64_t s0 = uint64_t(sd.sc_start) * kCandChunksPerSuper;
         if (s0 >= g1) break;
-        if (sd.k == 0 || sd.n == 0) continue;
+        if (sd.k == 0 || sd.n == 0 || !(sd.flags & kSegFast)) continue;
         const uint32_t n_chunks = (sd.n + CHUNK - 1) / CHUNK;
         const uint32_t lo = g0 > s0 ? uint32_t(g0 - s0) : 0u;
         const uint32_t hi = uint32_t(min(uint64_t(n_chunks), g1 - s0));
@@ -350,12 +428,16 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
             __hip_atomic_load(&sel[l].route, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         const uint32_t blo = binlo[l];  // 1 <= blo <= 0x7FFF on this route
         uint32_t *gh = hist + uint64_t(l) * kBins1;
-        if (!route) {
+        // With an accumulator (error feedback) the segment is streamed whatever its route:
+        // this pass is also the one that turns acc into grad + acc, which the dense route
+        // then reads instead of the gradient.
+        if (!route || acc) {
             const char *base = grad + sd.offset * EB;
+            char *abase = acc ? acc + sd.offset * EB : nullptr;
             const uint32_t swar_add = (0x8000u - blo) * 0x10001u;
             bool overflow = false;
             // the lane's four vectors of chunk `ch`; entries past the segment's end read as 0
-            auto load_chunk = [&](uint32_t ch, uint32_t (&w)[ROWS][4]) {
+            auto load_chunk = [&](const char *base, uint32_t ch, uint32_t (&w)[ROWS][4]) {
                 const uint32_t rel0 = ch * CHUNK;
                 if (rel0 + CHUNK <= sd.n) {
                     const uint4 *q = reinterpret_cast<const uint4 *>(base + uint64_t(rel0) * EB) + lane;
@@ -384,9 +466,47 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                     }
                 }
             };
-            uint32_t w[ROWS][4];
-            if (lo + wib < hi) load_chunk(lo + wib, w);
+            // the sums of chunk `ch` back to the accumulator (entries inside the segment only)
+            auto store_chunk = [&](uint32_t ch, const uint32_t (&w)[ROWS][4]) {
+                const uint32_t rel0 = ch * CHUNK;
+                if (rel0 + CHUNK <= sd.n) {
+                    uint4 *q = reinterpret_cast<uint4 *>(abase + uint64_t(rel0) * EB) + lane;
+#pragma unroll
+                    for (uint32_t r = 0; r < ROWS; ++r)
+                        q[64 * r] = make_uint4(w[r][0], w[r][1], w[r][2], w[r][3]);
+                } else {
+#pragma unroll
+                    for (uint32_t r = 0; r < ROWS; ++r) {
+                        const uint32_t rel = rel0 + r * ROW_ELEMS + lane * VEC;
+                        if (rel + VEC <= sd.n) {
+                            *reinterpret_cast<uint4 *>(abase + uint64_t(rel) * EB) =
+                                make_uint4(w[r][0], w[r][1], w[r][2], w[r][3]);
+                        } else if (rel < sd.n) {
+#pragma unroll
+                            for (uint32_t e = 0; e < VEC; ++e) {
+                                if (rel + e >= sd.n) continue;
+                                const uint32_t b = DTYPE == kBF16
+                                                       ? (w[r][e >> 1] >> (16 * (e & 1))) & 0xFFFFu
+                                                       : w[r][e];
+                                store_elem(abase, uint64_t(rel) + e, b, DTYPE);
+                            }
+                        }
+                    }
+                }
+            };
+            uint32_t w[ROWS][4], aw[ROWS][4];
+            if (lo + wib < hi) {
+                load_chunk(base, lo + wib, w);
+                if (acc) load_chunk(abase, lo + wib, aw);
+            }
             for (uint32_t ch = lo + wib; ch < hi; ch += NW) {
+                if (acc) {  // error feedback: sparsify grad + acc, and keep the sums
+#pragma unroll
+                    for (uint32_t r = 0; r < ROWS; ++r)
+#pragma unroll
+                        for (uint32_t j = 0; j < 4; ++j) w[r][j] = sum_word<DTYPE>(w[r][j], aw[r][j]);
+                    store_chunk(ch, w);
+                }
                 // Keep the chunk in LDS (a lane only ever reads back what it wrote itself).
                 // Branch-free classification: bit r*VEC + e of `mask` <=> entry e of the
                 // lane's vector in row r is a candidate.
@@ -413,7 +533,10 @@ scan_spill_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
                     }
                     mask |= f << (r * VEC);
                 }
-                if (ch + NW < hi) load_chunk(ch + NW, w);  // in flight during the rest
+                if (ch + NW < hi) {  // in flight during the rest
+                    load_chunk(base, ch + NW, w);
+                    if (acc) load_chunk(abase, ch + NW, aw);
+                }
                 // slot of each lane's first candidate per row: one scan over the four
                 // row counts packed in 16-bit fields (a row holds at most 512 candidates)
                 const uint32_t ia = wave_incl_scan<uint32_t>(c[0] | (c[1] << 16));
@@ -880,7 +1003,9 @@ constexpr uint32_t kEmitStage = 1280;  // survivors of an item that go through L
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
 template <int DTYPE>
-__device__ inline void emit_body(uint32_t bid, uint32_t nb, const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
+__device__ inline void emit_body(uint32_t bid, uint32_t nb, char *acc,
+                                 const uint32_t *__restrict__ table,
+                                 const SelDev *__restrict__ sel,
             const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
             uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_state,
             uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
@@ -917,12 +1042,13 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, const uint32_t *__re
         const uint32_t craw = chunk_cnt[g];
         // segment i's table rows in lane i
         uint32_t t_start = 0xFFFFFFFFu, t_n = 0, t_coff = 0, t_T = 0, t_quota = 0, t_cnt = 0,
-                 t_route = 0;
+                 t_route = 0, t_olo = 0, t_ohi = 0;
         if (L <= 64 && lane < L) {
             static_assert(sizeof(SegDev) == 32 && sizeof(SelDev) == 32, "two uint4 per row");
             const uint4 *s4 = reinterpret_cast<const uint4 *>(segs + lane);
             const uint4 *e4 = reinterpret_cast<const uint4 *>(sel + lane);
             const uint4 sa = s4[0], sb = s4[1], ea = e4[0], eb = e4[1];
+            t_olo = sa.x; t_ohi = sa.y;                                // offset
             t_n = sa.z; t_coff = sa.w; t_start = sb.w;                 // n, c_off, sc_start
             t_T = ea.x; t_quota = ea.y; t_cnt = ea.w; t_route = eb.w;  // T, quota, cnt, route
         }
@@ -930,6 +1056,7 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, const uint32_t *__re
 
         // ---- segment, threshold, pair offset of the segment (all wave-uniform)
         uint32_t l, c_off, n_seg, sc_first, T, quota, seg_base, se_cnt, se_route;
+        uint64_t seg_off;
         if (L <= 64) {
             const uint64_t le = __ballot(t_start <= scc);  // a prefix of the lanes
             l = uint32_t(__popcll(le)) - 1u;               // segment 0 starts at 0
@@ -940,12 +1067,14 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, const uint32_t *__re
             quota = __builtin_amdgcn_readlane(t_quota, l);
             se_cnt = __builtin_amdgcn_readlane(t_cnt, l);
             se_route = __builtin_amdgcn_readlane(t_route, l);
+            seg_off = uint64_t(__builtin_amdgcn_readlane(t_olo, l)) |
+                      (uint64_t(__builtin_amdgcn_readlane(t_ohi, l)) << 32);
             seg_base = wave_sum<uint32_t>(lane < l ? t_cnt : 0u);
         } else {
             l = segment_of(L, scc, [&](uint32_t i) { return segs[i].sc_start; });
             const SegDev sd = segs[l];
             const SelDev se = sel[l];
-            n_seg = sd.n; c_off = sd.c_off; sc_first = sd.sc_start;
+            n_seg = sd.n; c_off = sd.c_off; sc_first = sd.sc_start; seg_off = sd.offset;
             T = se.T; quota = se.quota; se_cnt = se.cnt; se_route = se.route;
             uint32_t sum = 0;
             for (uint32_t i = lane; i < l; i += 64) sum += sel[i].cnt;
@@ -1091,6 +1220,8 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, const uint32_t *__re
                         val_out[seg_base + pos] = __uint_as_float(vbits);
                     }
                     atomicOr(&bits[k][rel_sc >> 5], 1u << (rel_sc & 31));
+                    // error feedback: what is sent leaves the accumulator
+                    if (acc) store_elem(acc, seg_off + sc_rel0 + rel_sc, 0u, DTYPE);
                 }
             });
         }
@@ -1116,11 +1247,12 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, const uint32_t *__re
 
 // Dense route, final pass over the gradient itself.
 template <int DTYPE>
-__device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *__restrict__ grad,
+__device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad, char *acc,
                                     const uint32_t *__restrict__ table,
                const SelDev *__restrict__ sel, uint64_t *tile_state,
                uint32_t *__restrict__ idx_out,
-               float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt)
+               float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt,
+               uint32_t *ticket)
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
@@ -1137,8 +1269,35 @@ __device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *__res
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
     const uint32_t tid = threadIdx.x;
 
-    for (uint32_t t = bid; t < total_tiles; t += nb) {
-        const uint32_t l = segment_of(L, t, [&](uint32_t i) { return segs[i].tile_start; });
+    __shared__ uint32_t s_ticket;
+    for (uint32_t it = 0;; ++it) {
+        uint32_t t = 0, l = 0;
+        if (ticket) {
+            // Persistent grid: the tiles of the dense-route segments are dealt out in
+            // order, one ticket each, to whichever workgroup asks next.  A tile's
+            // predecessors then belong to workgroups that are running or done, however few
+            // of the grid are resident at a time.
+            if (tid == 0) s_ticket = atomicAdd(ticket, 1u);
+            __syncthreads();
+            uint32_t j = s_ticket;
+            bool found = false;
+            for (l = 0; l < L; ++l) {
+                if (!sel[l].route) continue;
+                const uint32_t t0 = segs[l].tile_start;
+                const uint32_t n_l = (l + 1 < L ? segs[l + 1].tile_start : total_tiles) - t0;
+                if (j < n_l) {
+                    t = t0 + j;
+                    found = true;
+                    break;
+                }
+                j -= n_l;
+            }
+            if (!found) break;
+        } else {  // one tile per workgroup (the loop runs again only on a smaller launch)
+            t = bid + it * nb;
+            if (t >= total_tiles) break;
+            l = segment_of(L, t, [&](uint32_t i) { return segs[i].tile_start; });
+        }
         const SegDev sd = segs[l];
         const SelDev se = sel[l];
         if (!se.route) continue;  // the candidate route writes this segment (uniform)
@@ -1256,6 +1415,14 @@ __device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *__res
             keepm[r] = km;
             grun += Gr[r];
             erun += Er[r];
+            // error feedback (`grad` is then the accumulator itself, already holding
+            // grad + acc): what is sent leaves it
+            if (acc && km) {
+#pragma unroll
+                for (uint32_t e = 0; e < VEC; ++e)
+                    if ((km >> e) & 1u)
+                        store_elem(acc + sd.offset * EB, uint64_t(rel) + e, 0u, DTYPE);
+            }
         }
 #pragma unroll
         for (uint32_t r = 0; r < ROWS; ++r) {
@@ -1281,18 +1448,19 @@ static_assert(kEmitThreads == kCompactThreads, "one launch for both parts");
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kEmitThreads) __attribute__((amdgpu_waves_per_eu(6, 8)))
-finish_kernel(uint32_t n_emit, const char *__restrict__ grad, const uint32_t *__restrict__ table,
+finish_kernel(uint32_t n_emit, const char *grad, char *acc, const uint32_t *__restrict__ table,
               const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
               const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
               uint64_t *sc_state, uint64_t *tile_state, uint32_t *__restrict__ idx_out,
-              float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt)
+              float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt,
+              uint32_t *ticket)
 {
     if (blockIdx.x < n_emit)
-        emit_body<DTYPE>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total, CAP,
-                         sc_state, idx_out, val_out, bitmap, cnt);
+        emit_body<DTYPE>(blockIdx.x, n_emit, acc, table, sel, cand, chunk_cnt, n_slots_total,
+                         CAP, sc_state, idx_out, val_out, bitmap, cnt);
     else
-        compact_body<DTYPE>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, table, sel,
-                            tile_state, idx_out, val_out, bitmap, cnt);
+        compact_body<DTYPE>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, acc, table, sel,
+                            tile_state, idx_out, val_out, bitmap, cnt, ticket);
 }
 
 template <typename K>
@@ -1340,6 +1508,10 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     uint32_t *cand = reinterpret_cast<uint32_t *>(ws + p->ws.cand);
     const uint64_t n_slots = uint64_t(p->total_sc) * kCandChunksPerSuper * p->cand_cap;
     const char *g = static_cast<const char *>(grad);
+    // Error feedback: scan_spill (candidate route) and accumulate_kernel (all other segments)
+    // turn acc into grad + acc; whoever reads the input after them reads it from acc.
+    char *acc = static_cast<char *>(rk->acc);
+    const char *src = acc ? acc : g;
     const int cus = device_cu_count();
     const size_t lds_hist = kBins1 * sizeof(uint32_t);
     static bool a_sample = false, a_hist = false;
@@ -1354,19 +1526,23 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     if (allow_lds(sample_kernel<DTYPE>, lds_hist, &a_sample) ||
         allow_lds(hist1_kernel<DTYPE>, lds_hist, &a_hist))
         return TAGC_EHIP;
+    if (acc && p->any_nonfast) {
+        ProfileScope ps("accumulate", s);
+        accumulate_kernel<DTYPE><<<cus * 4, 256, 0, s>>>(g, table, acc);
+    }
     {
         ProfileScope ps("sample", s);  // + clears the per-call workspace
         const uint64_t n16 = p->zero_bytes / 16;
         const uint32_t fill_blocks = uint32_t(
             std::max<uint64_t>(1, std::min<uint64_t>((n16 + kHistThreads - 1) / kHistThreads, cus)));
         sample_kernel<DTYPE><<<L + fill_blocks, kHistThreads, lds_hist, s>>>(
-            g, table, sel, binlo, hint, reinterpret_cast<uint4 *>(ws), n16, rk->cnt,
+            g, acc, table, sel, binlo, hint, reinterpret_cast<uint4 *>(ws), n16, rk->cnt,
             TAGC_CNT_SEG0 + L);
     }
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
         scan_spill_kernel<DTYPE><<<cus * 2, kSpillThreads, 0, s>>>(
-            g, table, sel, binlo, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
+            g, acc, table, sel, binlo, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
     }
     {
         ProfileScope ps("select1", s);
@@ -1374,7 +1550,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     {
         ProfileScope ps("hist1", s);
-        hist1_kernel<DTYPE><<<cus, kHistThreads, lds_hist, s>>>(g, table, sel, hist1d, rk->cnt,
+        hist1_kernel<DTYPE><<<cus, kHistThreads, lds_hist, s>>>(src, table, sel, hist1d, rk->cnt,
                                                                 binlo, hint, arrive);
     }
     if (DTYPE == kF32) {
@@ -1384,7 +1560,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         }
         {
             ProfileScope ps("hist2", s);
-            hist2_kernel<<<cus * 8, 256, 0, s>>>(g, table, sel, hist2);
+            hist2_kernel<<<cus * 8, 256, 0, s>>>(src, table, sel, hist2);
         }
         {
             ProfileScope ps("select2", s);
@@ -1402,14 +1578,16 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         // dispatched before it, so it ends no matter how few workgroups the device can hold
         // at the moment.  When no segment is planned for this route the part is only a
         // safety net for re-routed segments and nearly always exits at once; a small
-        // persistent grid keeps that cheap (its look-back then assumes that grid is
-        // resident as a whole and gives up with TAGC_FLAG_SPIN_LIMIT if that fails).
+        // persistent grid keeps that cheap, and deals its tiles out by ticket so that the
+        // same guarantee holds (one atomic per tile is affordable on that rare path).
         const uint32_t n_compact =
             p->static_dense ? p->total_tiles
                             : std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
+        uint32_t *ticket = p->static_dense ? nullptr : arrive + L;
         finish_kernel<DTYPE><<<n_emit + n_compact, kEmitThreads, 0, s>>>(
-            n_emit, g, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state, tile_state,
-            rk->idx, rk->val, rk->bitmap, rk->cnt);
+            n_emit, src, acc, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state,
+            tile_state,
+            rk->idx, rk->val, rk->bitmap, rk->cnt, ticket);
     }
     return hip_ok(hipGetLastError());
 }

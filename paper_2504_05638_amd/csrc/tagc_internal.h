@@ -86,6 +86,7 @@ struct tagc_plan_s {
     uint32_t total_sc;                        // super-chunks of the candidate path
     uint32_t chunk_elems, cand_cap;           // elements / candidate slots per chunk
     uint32_t cnt_ranges;                      // word offset of the partition ranges in a rank's cnt buffer
+    bool any_nonfast;                         // some non-empty segment is never streamed by scan_spill
     bool static_dense;                        // some segment with k > 0 never takes the candidate route
     uint64_t n_real, n_c, K, U_cap, A_cap, m_cap;
     uint32_t P_cap, T_cap;
