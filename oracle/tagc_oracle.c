@@ -493,6 +493,47 @@ int tagco_peel(const uint32_t *bitmap, uint64_t n_c, uint64_t U, uint64_t A,
     return 0;
 }
 
+/*
+ * Estimation, the second of the two decompression algorithms named in
+ * section 2.2 (it works at any density but is noisy; TAGC sparsifies so that
+ * peeling suffices, section 3.2).  The paper gives no formula; this is the
+ * textbook Count Sketch point query: an unknown with index i is estimated as
+ * the median of its three readings sign_j(i) * C[cell_j(i)].
+ *
+ * It is applied to the unknowns with round_in[t] == 0 (all of them when
+ * round_in is NULL), on `sketch` as it is handed in: the raw summed sketch
+ * for estimation-only decoding, or what tagco_peel left behind (every
+ * resolved unknown already subtracted) for the residue of a stalled peeling.
+ * Estimates do not interact: nothing is subtracted between them.  val_out[t]
+ * of the other unknowns is left alone.  The median of three is the middle one
+ * in numeric order.  Returns the number of unknowns estimated.
+ */
+uint64_t tagco_estimate(const uint32_t *idx, const uint32_t *round_in,
+                        uint64_t U, uint64_t A, uint64_t m_sub, uint64_t seed,
+                        const float *sketch, float *val_out)
+{
+    uint64_t a = 0, n_est = 0;
+    for (uint64_t t = 0; t < U; ++t) {
+        while (a + 1 < A && tagco_part_start(a + 1, U, A) <= t)
+            ++a;
+        if (round_in && round_in[t])
+            continue;
+        float r[3];
+        for (uint32_t j = 0; j < 3; ++j) {
+            float s;
+            uint64_t c = cell_of(idx[t], a, j, m_sub, seed, 0, &s);
+            r[j] = s * sketch[c];
+        }
+        /* sort the three readings ascending, take the middle one */
+        if (r[0] > r[1]) { float x = r[0]; r[0] = r[1]; r[1] = x; }
+        if (r[1] > r[2]) { float x = r[1]; r[1] = r[2]; r[2] = x; }
+        if (r[0] > r[1]) { float x = r[0]; r[0] = r[1]; r[1] = x; }
+        val_out[t] = r[1];
+        ++n_est;
+    }
+    return n_est;
+}
+
 /* --------------------------------------------------- communication volume */
 
 /*

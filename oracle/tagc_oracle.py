@@ -91,6 +91,9 @@ def lib():
         L.tagco_peel.argtypes = [u32p, C.c_uint64, C.c_uint64, C.c_uint64,
                                  C.c_uint64, C.c_uint64, C.c_int, f32p, u32p,
                                  f32p, u32p, u32p, u64p]
+        L.tagco_estimate.restype = C.c_uint64
+        L.tagco_estimate.argtypes = [u32p, u32p, C.c_uint64, C.c_uint64, C.c_uint64,
+                                     C.c_uint64, f32p, f32p]
         L.tagco_wire_bits_per_param.restype = C.c_double
         L.tagco_wire_bits_per_param.argtypes = [C.c_double, C.c_double,
                                                 C.c_int]
@@ -306,6 +309,41 @@ def peel(bitmap, n_c, U, A, m_sub, seed, sketch, plus_only=False) -> Decoded:
                    int(unres.value), work)
 
 
+DECODE_PEEL, DECODE_PEEL_ESTIMATE, DECODE_ESTIMATE = 0, 1, 2
+
+
+def estimate(dec: Decoded, A, m_sub, seed, sketch, only_unresolved=True) -> int:
+    """Count Sketch point queries (median of the three signed readings) for the unknowns
+    of `dec` that peeling left (or for all of them), on `sketch`; fills dec.val in place
+    and returns how many were estimated (section 2.2, the estimation algorithm)."""
+    U = dec.idx.size
+    if U == 0:
+        return 0
+    sk = np.ascontiguousarray(sketch, np.float32)
+    rnd = np.ascontiguousarray(dec.round, np.uint32)
+    return int(lib().tagco_estimate(
+        _u32p(dec.idx), _u32p(rnd) if only_unresolved else None, U, A, m_sub, seed,
+        _f32p(sk), _f32p(dec.val)))
+
+
+def decompress(bitmap, n_c, U, A, m_sub, seed, sketch, mode=DECODE_PEEL) -> Decoded:
+    """peeling_decompress of Algorithm 1, optionally followed by estimation of what it
+    could not recover (mode 1), or estimation alone on the raw sketch (mode 2)."""
+    if mode == DECODE_ESTIMATE:
+        bits = np.unpackbits(np.ascontiguousarray(bitmap, np.uint32).view(np.uint8),
+                             bitorder="little")[:n_c]
+        idx = np.flatnonzero(bits).astype(np.uint32)  # the unknowns, ascending
+        assert idx.size == U
+        dec = Decoded(idx, np.zeros(U, np.float32), np.zeros(U, np.uint32), 0, U,
+                      np.array(sketch, np.float32, copy=True))
+        estimate(dec, A, m_sub, seed, dec.residual, only_unresolved=False)
+        return dec
+    dec = peel(bitmap, n_c, U, A, m_sub, seed, sketch)
+    if mode == DECODE_PEEL_ESTIMATE and dec.n_unresolved:
+        estimate(dec, A, m_sub, seed, dec.residual)
+    return dec
+
+
 @dataclass
 class BucketResult:
     ranks: list
@@ -320,7 +358,8 @@ class BucketResult:
     n_c: int
 
 
-def run_bucket(grads, cfg: Config, segments, plus_only=False) -> BucketResult:
+def run_bucket(grads, cfg: Config, segments, plus_only=False,
+               decode_mode=DECODE_PEEL) -> BucketResult:
     """Algorithm 1 for one bucket and len(grads) simulated ranks."""
     offs, n_c = c_offsets(segments)
     n_real = sum(s.length for s in segments if s.flags & FLAG_COMPRESS)
@@ -331,7 +370,11 @@ def run_bucket(grads, cfg: Config, segments, plus_only=False) -> BucketResult:
     for r in ranks:
         r.sketch = encode(r.idx, r.val, bnd, A, m_sub, cfg.seed, plus_only)
     total = sketch_sum([r.sketch for r in ranks])
-    dec = peel(bitmap, n_c, U, A, m_sub, cfg.seed, total, plus_only)
+    if decode_mode == DECODE_PEEL:
+        dec = peel(bitmap, n_c, U, A, m_sub, cfg.seed, total, plus_only)
+    else:
+        assert not plus_only
+        dec = decompress(bitmap, n_c, U, A, m_sub, cfg.seed, total, decode_mode)
     return BucketResult(ranks, bitmap, U, A, m_sub, m, bnd, total, dec, n_c)
 
 
