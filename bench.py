@@ -63,6 +63,9 @@ def parse_args():
     ap.add_argument("--error-feedback", action="store_true",
                     help="give every rank a gradient accumulator (Algorithm 1, lines 1-2): "
                          "adds one read and one write of the gradient's size per rank")
+    ap.add_argument("--decode-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="0 peeling only (the headline), 1 peeling + estimation of what it "
+                         "leaves, 2 estimation only (section 2.2's two decompression algorithms)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="before the timed region, copy this many MiB device to device three "
@@ -208,7 +211,7 @@ def main():
         cfg = B.tagc_config(dtype=b.dtype, n_ranks=N, n_hash=3, sizing=B.TAGC_SIZE_LOAD_FACTOR,
                             sizing_milli=b.sizing_milli, index_mode=B.TAGC_INDEX_OR1,
                             part_unknowns=args.part_unknowns, part_cells=args.part_cells,
-                            seed=args.seed)
+                            seed=args.seed, decode_mode=args.decode_mode)
         plan = B.tagc_plan(cfg, [tuple(s[:4]) for s in b.segments])
         z = B.tagc_plan_sizes(plan)
         for k, f in fields.items():
@@ -222,6 +225,7 @@ def main():
                               seed=args.seed, dense=bool(args.dense),
                               part_unknowns=args.part_unknowns, part_cells=args.part_cells,
                               error_feedback=args.error_feedback,
+                              decode_mode=args.decode_mode,
                               share=None if first else tbs[i % lanes],
                               min_bytes=need if first else None))
     stream = torch.cuda.current_stream()
@@ -246,7 +250,7 @@ def main():
     input_bytes = 0
     balg = {k: 0 for k in STAGES}
     kalg = {}
-    unresolved = rounds = 0
+    unresolved = estimated = rounds = 0
     U_tot = m_tot = k_tot = 0
     flags = 0
     facts = []
@@ -265,6 +269,7 @@ def main():
             kalg[k] = kalg.get(k, 0) + v
         input_bytes += N * tbs[i].sizes.n_real * buckets[i].elem_bytes
         unresolved += st["n_unresolved"]
+        estimated += st["n_estimated"]
         rounds = max(rounds, st["rounds"])
         U_tot += hdr["U"]
         m_tot += hdr["m"]
@@ -355,6 +360,7 @@ def main():
                    "buckets_in_flight": lanes,
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
+                   "n_estimated": estimated, "decode_mode": args.decode_mode,
                    "peel_rounds_max": rounds, "input_generation_s": round(t_gen, 2)},
         "hbm_frac_end_to_end": round(balg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "alg_bytes_per_step": balg_total,

@@ -83,7 +83,19 @@ typedef struct tagc_config {
     uint32_t part_cells;    /* max cells per sketch partition (multiple of 3),
                                0 = default                                      */
     uint64_t seed;          /* hash seed; all ranks must use the same           */
+    uint32_t decode_mode;   /* TAGC_DECODE_*; 0 = peeling only                  */
+    uint32_t reserved;      /* must be 0                                        */
 } tagc_config;
+
+/* What tagc_decompress does with the summed sketch (section 2.2 names the two
+ * decompression algorithms, peeling and estimation; the latter is a Count
+ * Sketch point query: the median of an entry's three signed cell readings). */
+#define TAGC_DECODE_PEEL 0u          /* peel; what cannot be recovered is 0       */
+#define TAGC_DECODE_PEEL_ESTIMATE 1u /* peel; the rest is estimated from the cells
+                                        as peeling left them (everything recovered
+                                        already subtracted)                       */
+#define TAGC_DECODE_ESTIMATE 2u      /* no peeling: every entry is estimated from
+                                        the summed sketch as it is                */
 
 typedef struct tagc_plan_s tagc_plan_t; /* opaque, host memory, immutable */
 
@@ -139,9 +151,11 @@ enum {
 };
 /* shared `status` words (uint32), written by tagc_decompress */
 enum {
-    TAGC_ST_UNRESOLVED = 0, /* non-zeros peeling could not recover (value 0)     */
+    TAGC_ST_UNRESOLVED = 0, /* non-zeros peeling did not recover (value 0, or an
+                               estimate if the plan's decode mode asks for one)  */
     TAGC_ST_ROUNDS = 1,     /* peeling rounds of the slowest partition           */
     TAGC_ST_FLAGS = 2,      /* TAGC_FLAG_* bits                                  */
+    TAGC_ST_ESTIMATED = 3,  /* entries whose value is an estimate                */
     TAGC_ST_WORDS = 8
 };
 #define TAGC_FLAG_SPIN_LIMIT 1u /* an internal bounded wait gave up: results invalid */
@@ -244,8 +258,9 @@ int tagc_aggregate(const tagc_plan_t *plan, uint32_t phase,
  * Algorithm 1: peeling_decompress(index, count_sketch) (section 2.2).
  * Enumerates the non-zeros of the merged Index in ascending order into
  * idx_out[0..U), peels the summed sketch (shared->sketch is consumed) and
- * writes val_out[0..U); entries peeling cannot recover get 0 and are counted
- * in shared->status.  If dense_out (dev, n_c floats) is not NULL the summed
+ * writes val_out[0..U); entries peeling cannot recover are counted in
+ * shared->status and get 0 or, by the plan's decode_mode, an estimate (with
+ * TAGC_DECODE_ESTIMATE there is no peeling and every entry is an estimate).  If dense_out (dev, n_c floats) is not NULL the summed
  * gradient is also written densely over the whole c-index space (zeros
  * elsewhere).  idx_out / val_out: dev, union_capacity entries.
  */

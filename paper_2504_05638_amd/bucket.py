@@ -28,7 +28,7 @@ class TagcBucket:
     def __init__(self, segments, dtype, n_ranks, sizing_milli=3000,
                  sizing=B.TAGC_SIZE_LOAD_FACTOR, seed=0, part_unknowns=0,
                  part_cells=0, device="cuda", dense=False, share=None, min_bytes=None,
-                 error_feedback=False):
+                 error_feedback=False, decode_mode=B.TAGC_DECODE_PEEL):
         if not torch.cuda.is_available():
             raise RuntimeError("libtagc needs a GPU: no CPU path exists")
         self.device = torch.device(device)
@@ -36,7 +36,8 @@ class TagcBucket:
                                  sizing=sizing, sizing_milli=sizing_milli,
                                  index_mode=B.TAGC_INDEX_OR1,
                                  part_unknowns=part_unknowns,
-                                 part_cells=part_cells, seed=seed)
+                                 part_cells=part_cells, seed=seed,
+                                 decode_mode=decode_mode)
         self.segments = [tuple(s[:4]) for s in segments]
         self.plan = B.tagc_plan(self.cfg, self.segments)
         self.sizes = B.tagc_plan_sizes(self.plan)
@@ -167,7 +168,8 @@ class TagcBucket:
     def status(self):
         s = self._np(self.sh_status, np.uint32, B.TAGC_ST_WORDS)
         return dict(n_unresolved=int(s[B.TAGC_ST_UNRESOLVED]),
-                    rounds=int(s[B.TAGC_ST_ROUNDS]), flags=int(s[B.TAGC_ST_FLAGS]))
+                    rounds=int(s[B.TAGC_ST_ROUNDS]), flags=int(s[B.TAGC_ST_FLAGS]),
+                    n_estimated=int(s[B.TAGC_ST_ESTIMATED]))
 
     def rank_counts(self, r):
         c = self._np(self._rk_tensors[r]["cnt"], np.uint32)

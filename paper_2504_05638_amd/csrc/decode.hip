@@ -24,13 +24,13 @@ namespace tagc {
 namespace {
 
 // Optional phase timing (build with -DTAGC_PHASE_TIMING): thread 0 of every workgroup
-// adds the shader-clock cycles (>> 10) each phase took to status[3 + phase].
+// adds the shader-clock cycles (>> 10) each phase took to status[4 + phase].
 #ifdef TAGC_PHASE_TIMING
 #define PHASE_MARK(k)                                                        \
     do {                                                                     \
         if (threadIdx.x == 0) {                                              \
             const long long now_ = clock64();                                \
-            atomicAdd(&status[3 + (k)], uint32_t((now_ - phase_t0_) >> 10)); \
+            atomicAdd(&status[4 + (k)], uint32_t((now_ - phase_t0_) >> 10)); \
             phase_t0_ = now_;                                                \
         }                                                                    \
     } while (0)
@@ -155,7 +155,7 @@ __global__ void __launch_bounds__(kDecodeThreads)
 peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ header,
             const uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
             uint32_t *status, uint32_t sw0, uint32_t sw1, uint32_t sw2, uint32_t T_cap,
-            uint32_t P_cap)
+            uint32_t P_cap, uint32_t mode)
 {
     extern __shared__ uint64_t lds64[];
     unsigned long long *cell = reinterpret_cast<unsigned long long *>(lds64);  // [T_cap]
@@ -224,9 +224,11 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     // the registers are free again: the next partition's data travels during the rounds
     if (a + gridDim.x < A) prefetch(a + gridDim.x);
     __syncthreads();
-    for (uint32_t c0 = 0; c0 < cells; c0 += kDecodeThreads) {
-        const uint32_t c = c0 + tid;
-        queue_push(c < cells && (meta_hi[2 * c] & kDegMask) == 1u, c, &s_tail, queue);
+    if (mode != TAGC_DECODE_ESTIMATE) {  // estimation alone: the queue stays empty
+        for (uint32_t c0 = 0; c0 < cells; c0 += kDecodeThreads) {
+            const uint32_t c = c0 + tid;
+            queue_push(c < cells && (meta_hi[2 * c] & kDegMask) == 1u, c, &s_tail, queue);
+        }
     }
     PHASE_MARK(1);
 
@@ -290,13 +292,31 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
 
     // ---- values leave in one contiguous sweep (stored one by one as they were found they
     // would cost a cache-line access each); unknowns never claimed stay at 0
-    for (uint32_t u = tid; u < Pa; u += kDecodeThreads)
-        val_out[rho0 + u] =
-            (claimed[u >> 5] >> (u & 31)) & 1u ? __uint_as_float(idx[u]) : 0.0f;
+    // or, when the plan asks for it, the median of their three signed readings of the
+    // cells as the rounds left them (idx[u] still holds the c-index of such an unknown)
+    for (uint32_t u = tid; u < Pa; u += kDecodeThreads) {
+        float x = 0.0f;
+        if ((claimed[u >> 5] >> (u & 31)) & 1u) {
+            x = __uint_as_float(idx[u]);
+        } else if (mode != TAGC_DECODE_PEEL) {
+            const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
+            float r[3];
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const float cv = __uint_as_float(uint32_t(cell[cl.c[j]]));
+                r[j] = ((cl.neg >> j) & 1u) ? -cv : cv;
+            }
+            x = fmaxf(fminf(r[0], r[1]), fminf(fmaxf(r[0], r[1]), r[2]));
+        }
+        val_out[rho0 + u] = x;
+    }
     uint32_t resolved = 0;
     for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) resolved += __popc(claimed[c]);
     resolved = block_sum<uint32_t, kDecodeThreads / 64>(resolved, scratch);
-    if (tid == 0 && resolved < Pa) atomicAdd(&status[TAGC_ST_UNRESOLVED], Pa - resolved);
+    if (tid == 0 && resolved < Pa) {
+        atomicAdd(&status[TAGC_ST_UNRESOLVED], Pa - resolved);
+        if (mode != TAGC_DECODE_PEEL) atomicAdd(&status[TAGC_ST_ESTIMATED], Pa - resolved);
+    }
     max_rounds = max(max_rounds, rounds);
     PHASE_MARK(3);
     }  // partitions of this workgroup
@@ -392,7 +412,7 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
         }
         kernel<<<grid, kDecodeThreads, lds, s>>>(
             sh->sketch, sh->header, idx_out, val_out, sh->status, p->seed_word[0],
-            p->seed_word[1], p->seed_word[2], p->T_cap, p->P_cap);
+            p->seed_word[1], p->seed_word[2], p->T_cap, p->P_cap, p->cfg.decode_mode);
     }
     if (dense_out && n_chunks) {
         ProfileScope ps("dense", s);

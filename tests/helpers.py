@@ -42,17 +42,42 @@ def value_tolerance(ores, rel=1e-5):
     return rel * np.maximum(ref, vmax[part])
 
 
-def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTOR, dense=True):
+def estimate_tolerance(ores, seed, rel=1e-5):
+    """Tolerance for estimated entries: an estimate is a cell reading, and a cell is the
+    outcome of float32 adds (encode, aggregation) and subtracts (peeling) of everything
+    that was ever in it; in another order each of them rounds differently by at most
+    6e-8 of a partial sum, which the cell's total magnitude bounds.  An entry's tolerance
+    is `rel` times the largest such total among its three cells."""
+    mag = np.zeros(max(ores.m, 1), np.float64)
+    for r in ores.ranks:
+        mag[:ores.m] += O.encode(r.idx, np.abs(r.val), ores.bnd, ores.A, ores.m_sub, seed,
+                                 plus_only=True).astype(np.float64)
+    U = ores.U
+    tol = np.zeros(U)
+    part = (np.arange(U, dtype=np.int64) * 0)
+    if ores.A:
+        starts = np.array([a * U // ores.A for a in range(ores.A)], np.int64)
+        part = np.searchsorted(starts, np.arange(U), side="right") - 1
+    for t in np.flatnonzero(ores.decoded.round == 0):
+        i = int(ores.decoded.idx[t])
+        tol[t] = rel * max(
+            mag[(int(part[t]) * 3 + j) * ores.m_sub + O.hash_slot(i, seed, j, ores.m_sub)[0]]
+            for j in range(3))
+    return tol
+
+
+def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTOR, dense=True,
+             decode_mode=0):
     """Runs oracle and library on the same inputs; returns (oracle result, TagcBucket)."""
     import torch
     from paper_2504_05638_amd.bucket import TagcBucket
 
     ocfg = oracle_config(bucket, sizing, seed, P or 8192, T or 12288)
     ores = O.run_bucket([G.to_numpy_raw(g) for g in grads_torch_cpu], ocfg,
-                        oracle_segments(bucket))
+                        oracle_segments(bucket), decode_mode=decode_mode)
     tb = TagcBucket(bucket.segments, bucket.dtype, len(grads_torch_cpu),
                     sizing_milli=bucket.sizing_milli, sizing=sizing, seed=seed,
-                    part_unknowns=P, part_cells=T, dense=dense)
+                    part_unknowns=P, part_cells=T, dense=dense, decode_mode=decode_mode)
     dev = [g.cuda() for g in grads_torch_cpu]
     tb.run(dev)
     torch.cuda.synchronize()
@@ -103,13 +128,18 @@ def compare_all(bucket, ores, tb, exact_values=False, rel=1e-5):
     idx, val = tb.outputs()
     assert np.array_equal(idx, ores.decoded.idx)
     unresolved = ores.decoded.round == 0
-    assert np.all(val[unresolved] == 0)
+    mode = tb.cfg.decode_mode
+    assert st["n_estimated"] == (ores.decoded.n_unresolved if mode else 0)
+    if mode == 0:
+        assert np.all(val[unresolved] == 0)
     if exact_values:
         # equal as numbers: an entry that cancels to zero across ranks may come out as +0
         # or -0 depending on which of its clean cells (and so which hash sign) supplied it
         assert np.array_equal(val, ores.decoded.val)
     else:
         tol = value_tolerance(ores, rel)
+        if mode and unresolved.any():
+            tol[unresolved] = estimate_tolerance(ores, tb.cfg.seed, rel)[unresolved]
         err = np.abs(val.astype(np.float64) - ores.decoded.val.astype(np.float64))
         assert np.all(err <= tol), "worst excess %g at %d" % (
             (err - tol).max(), int(np.argmax(err - tol)))
