@@ -224,6 +224,72 @@ uint64_t tagco_index_or(const uint32_t *const *maps, uint32_t n_ranks,
 
 /* ---------------------------------------------------------- sketch layout */
 
+/*
+ * The Index as the paper's implementation has to move it: NCCL has no bitwise
+ * OR, so the OR is simulated by addition (section 2.2), either on the 1-bit
+ * Index ("faster, but with a higher amount of collisions") or on a 4-bit one
+ * ("stable, but 4 times bigger").  The paper gives no layout; this
+ * repository's reading:
+ *
+ *   wire words are unsigned 32-bit integers and the All-Reduce adds them as
+ *   such (wrapping), so a carry runs into the next parameter's field and the
+ *   carry out of a word is lost;
+ *   1 bit:  the wire Index is the local Index itself (parameter j = bit j&31
+ *           of word j>>5);
+ *   4 bit:  one counter per parameter, 0 or 1 locally, parameter j in bits
+ *           4*(j&7) .. 4*(j&7)+3 of wire word j>>3;
+ *   the merged Index has parameter j set iff its field of the sum is not 0.
+ *
+ * With 4 bits and at most 15 ranks no field can overflow and the result is
+ * the OR.  With 1 bit every position that an even number of ranks kept
+ * disappears and its carries set or clear higher positions of the word: the
+ * "collisions".
+ */
+
+/* local 1-bit Index -> 4-bit wire Index (4 * words words) */
+void tagco_index_widen4(const uint32_t *map, uint64_t words, uint32_t *wire)
+{
+    for (uint64_t w = 0; w < words; ++w)
+        for (uint32_t q = 0; q < 4; ++q) {
+            uint32_t x = 0;
+            for (uint32_t p = 0; p < 8; ++p)
+                x |= ((map[w] >> (8 * q + p)) & 1u) << (4 * p);
+            wire[4 * w + q] = x;
+        }
+}
+
+/* All-Reduce by addition of the ranks' wire Indexes; `maps` are the local
+ * 1-bit Indexes, `bits` is 1 or 4; writes the merged 1-bit Index and returns
+ * its number of set bits. */
+uint64_t tagco_index_add(const uint32_t *const *maps, uint32_t n_ranks,
+                         uint64_t words, uint32_t bits, uint32_t *out)
+{
+    uint64_t U = 0;
+    for (uint64_t w = 0; w < words; ++w) {
+        uint32_t merged = 0;
+        if (bits == 1) {
+            for (uint32_t r = 0; r < n_ranks; ++r)
+                merged += maps[r][w];
+        } else {
+            for (uint32_t q = 0; q < 4; ++q) {
+                uint32_t sum = 0;
+                for (uint32_t r = 0; r < n_ranks; ++r) {
+                    uint32_t wire[4];
+                    tagco_index_widen4(&maps[r][w], 1, wire);
+                    sum += wire[q];
+                }
+                for (uint32_t p = 0; p < 8; ++p)
+                    if ((sum >> (4 * p)) & 0xFu)
+                        merged |= 1u << (8 * q + p);
+            }
+        }
+        out[w] = merged;
+        for (uint32_t b = 0; b < 32; ++b)
+            U += (merged >> b) & 1u;
+    }
+    return U;
+}
+
 static uint64_t ceil_div_u64(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 /*
@@ -356,10 +422,17 @@ static uint64_t cell_of(uint32_t i, uint64_t a, uint32_t j, uint64_t m_sub,
  * Pairs are taken in ascending c-index, hash functions j = 0,1,2 in order,
  * each update one float32 add.  `plus_only` replaces every sign by +1 (used
  * by a test that shows signs do not matter to peeling).
+ *
+ * `mask` (NULL, or the merged Index): a pair whose position is not set in it
+ * is left out.  With a true OR every pair is in the merged Index; after an
+ * addition-simulated OR (tagco_index_add) some are not, and this repository
+ * reads compress(g_shard, index) as encoding the entries the Index names and
+ * no others, so that the decoder's unknowns are exactly what the cells hold.
  */
 void tagco_encode(const uint32_t *idx, const float *val, uint64_t cnt,
                   const uint32_t *bnd, uint64_t A, uint64_t m_sub,
-                  uint64_t seed, int plus_only, float *sketch)
+                  uint64_t seed, int plus_only, const uint32_t *mask,
+                  float *sketch)
 {
     uint64_t m = 3 * A * m_sub;
     for (uint64_t c = 0; c < m; ++c)
@@ -367,6 +440,8 @@ void tagco_encode(const uint32_t *idx, const float *val, uint64_t cnt,
     uint64_t a = 0;
     for (uint64_t t = 0; t < cnt; ++t) {
         uint32_t i = idx[t];
+        if (mask && !((mask[i >> 5] >> (i & 31)) & 1u))
+            continue;
         while (a + 1 < A && i >= bnd[a + 1])
             ++a;
         for (uint32_t j = 0; j < 3; ++j) {

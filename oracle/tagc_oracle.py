@@ -84,7 +84,12 @@ def lib():
                                  C.c_uint32, u32p, C.POINTER(C.c_int32)]
         L.tagco_encode.restype = None
         L.tagco_encode.argtypes = [u32p, f32p, C.c_uint64, u32p, C.c_uint64,
-                                   C.c_uint64, C.c_uint64, C.c_int, f32p]
+                                   C.c_uint64, C.c_uint64, C.c_int, u32p, f32p]
+        L.tagco_index_add.restype = C.c_uint64
+        L.tagco_index_add.argtypes = [C.POINTER(u32p), C.c_uint32, C.c_uint64, C.c_uint32,
+                                      u32p]
+        L.tagco_index_widen4.restype = None
+        L.tagco_index_widen4.argtypes = [u32p, C.c_uint64, u32p]
         L.tagco_sum.restype = None
         L.tagco_sum.argtypes = [C.POINTER(f32p), C.c_uint32, C.c_uint64, f32p]
         L.tagco_peel.restype = C.c_int
@@ -129,6 +134,7 @@ class Config:
     seed: int = 0
     part_unknowns: int = 8192    # P_cap
     part_cells: int = 12288      # T_cap (multiple of 3)
+    index_mode: int = 0          # INDEX_OR1 | INDEX_ADD1 | INDEX_ADD4
 
 
 def c_offsets(segments):
@@ -241,6 +247,33 @@ def index_or(bitmaps):
     return out, int(U)
 
 
+INDEX_OR1, INDEX_ADD1, INDEX_ADD4 = 0, 1, 2
+
+
+def index_add(bitmaps, bits):
+    """All-Reduce of the Index simulated by addition (section 2.2), 1-bit or 4-bit
+    fields; returns the merged 1-bit Index and its number of set bits."""
+    n, words = len(bitmaps), bitmaps[0].size
+    arr = (C.POINTER(C.c_uint32) * n)(*[_u32p(b) for b in bitmaps])
+    out = np.zeros(words, np.uint32)
+    U = lib().tagco_index_add(arr, n, words, bits, _u32p(out))
+    return out, int(U)
+
+
+def index_widen4(bitmap):
+    """A rank's 4-bit wire Index (four words per word of the local 1-bit Index)."""
+    bitmap = np.ascontiguousarray(bitmap, np.uint32)
+    out = np.zeros(4 * bitmap.size, np.uint32)
+    lib().tagco_index_widen4(_u32p(bitmap), bitmap.size, _u32p(out))
+    return out
+
+
+def merge_index(bitmaps, mode):
+    if mode == INDEX_OR1:
+        return index_or(bitmaps)
+    return index_add(bitmaps, 1 if mode == INDEX_ADD1 else 4)
+
+
 def layout(U, cfg: Config, n_real):
     A, ms, m = C.c_uint64(), C.c_uint64(), C.c_uint64()
     lib().tagco_layout(U, cfg.sizing, cfg.sizing_milli, n_real,
@@ -261,13 +294,14 @@ def hash_slot(i, seed, j, m_sub):
     return int(slot.value), int(sign.value)
 
 
-def encode(idx, val, bnd, A, m_sub, seed, plus_only=False):
+def encode(idx, val, bnd, A, m_sub, seed, plus_only=False, mask=None):
     m = 3 * A * m_sub
     sk = np.zeros(max(m, 1), np.float32)
     idx = np.ascontiguousarray(idx, np.uint32)
     val = np.ascontiguousarray(val, np.float32)
     lib().tagco_encode(_u32p(idx), _f32p(val), idx.size, _u32p(bnd), A, m_sub,
-                       seed, int(plus_only), _f32p(sk))
+                       seed, int(plus_only), None if mask is None else _u32p(mask),
+                       _f32p(sk))
     return sk[:m]
 
 
@@ -364,11 +398,12 @@ def run_bucket(grads, cfg: Config, segments, plus_only=False,
     offs, n_c = c_offsets(segments)
     n_real = sum(s.length for s in segments if s.flags & FLAG_COMPRESS)
     ranks = [sparsify(g, cfg, segments) for g in grads]
-    bitmap, U = index_or([r.bitmap for r in ranks])
+    bitmap, U = merge_index([r.bitmap for r in ranks], cfg.index_mode)
     A, m_sub, m = layout(U, cfg, n_real)
     bnd = bounds(bitmap, n_c, U, A)
+    mask = None if cfg.index_mode == INDEX_OR1 else bitmap
     for r in ranks:
-        r.sketch = encode(r.idx, r.val, bnd, A, m_sub, cfg.seed, plus_only)
+        r.sketch = encode(r.idx, r.val, bnd, A, m_sub, cfg.seed, plus_only, mask)
     total = sketch_sum([r.sketch for r in ranks])
     if decode_mode == DECODE_PEEL:
         dec = peel(bitmap, n_c, U, A, m_sub, cfg.seed, total, plus_only)
