@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Kernels of the library grouped into the stages of the path.
 STAGES = {
     "S1+S2 sparsify+index": ["fill_zero", "accumulate", "sample", "scan_spill", "select1", "hist1",
-                             "hist2c", "hist2", "select2", "finish"],
+                             "hist2c", "hist2", "select2", "finish", "widen4"],
     "S3a index OR": ["index_or", "header", "bounds", "ranges"],
     "S2' encode": ["encode"],
     "S3b sketch sum": ["sketch_sum"],
@@ -63,6 +63,17 @@ def parse_args():
     ap.add_argument("--error-feedback", action="store_true",
                     help="give every rank a gradient accumulator (Algorithm 1, lines 1-2): "
                          "adds one read and one write of the gradient's size per rank")
+    ap.add_argument("--index-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="0 Index merged by OR (the headline), 1 by addition of the 1-bit "
+                         "Index, 2 by addition of 4-bit counters (section 2.2)")
+    ap.add_argument("--ranks", type=int, default=0,
+                    help="simulated ranks (0 = the workload's)")
+    ap.add_argument("--ratio", type=int, default=0,
+                    help="fixed-ratio sketch, c x1000 (Table 1: cells = n / c); 0 = sized by "
+                         "load factor")
+    ap.add_argument("--keep-ppm", type=int, default=0,
+                    help="survivors per million for every compressed segment (Table 1: "
+                         "(1 - theta) * 10^6); 0 = the workload's dynamic ratios")
     ap.add_argument("--decode-mode", type=int, default=0, choices=[0, 1, 2],
                     help="0 peeling only (the headline), 1 peeling + estimation of what it "
                          "leaves, 2 estimation only (section 2.2's two decompression algorithms)")
@@ -90,13 +101,20 @@ def make_buckets(args):
         bs = G.config5(args.seed)
     if args.buckets:
         bs = bs[:args.buckets]
-    if args.lf:
-        for b in bs:
+    for b in bs:
+        if args.lf:
             b.sizing_milli = args.lf
+        if args.ratio:
+            b.sizing_milli = args.ratio
+        if args.ranks:
+            b.n_ranks = args.ranks
+        if args.keep_ppm:
+            b.segments = [s._replace(keep_ppm=args.keep_ppm) if s.flags & 1 else s
+                          for s in b.segments]
     return bs
 
 
-def alg_bytes(b, z, hdr, k_total, dense, ef=False):
+def alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1):
     """Algorithmic bytes per stage for one bucket: one read of the gradient (with error
     feedback also one read and one write of the accumulator), every message
     materialised once; work-lists, histograms and degree tables are not credited."""
@@ -104,15 +122,15 @@ def alg_bytes(b, z, hdr, k_total, dense, ef=False):
     n_c, U, m = z.n_c, hdr["U"], hdr["m"]
     passes = 3 if ef else 1
     return {
-        "S1+S2 sparsify+index": passes * N * z.n_real * e + 8 * k_total + N * n_c // 8,
-        "S3a index OR": N * n_c // 8 + n_c // 8,
+        "S1+S2 sparsify+index": passes * N * z.n_real * e + 8 * k_total + wire * N * n_c // 8,
+        "S3a index OR": wire * N * n_c // 8 + n_c // 8,
         "S2' encode": 8 * k_total + N * 4 * m,
         "S3b sketch sum": (N + 1) * 4 * m,
         "S4 decode": n_c // 8 + 4 * m + 8 * U + (4 * n_c if dense else 0),
     }
 
 
-def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False):
+def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1):
     """Bytes each bandwidth-relevant kernel must itself move per bucket (all its
     launches together).  hist1 and compact each read the gradient once, so their sum
     exceeds the stage's algorithmic bytes: the stage figure shows the cost of the
@@ -126,7 +144,8 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False):
         # finish = emit (candidate route) + compact (dense route: reads the gradient again);
         # priced as emit, which is all it is for a bucket without dense-route segments
         "finish": 8 * k_total + N * n_c // 8,
-        "index_or": (N + 1) * n_c // 8,
+        "index_or": (wire * N + 1) * n_c // 8,
+        "widen4": (1 + 4) * N * n_c // 8,
         "encode": 8 * k_total + N * 4 * m,
         "sketch_sum": (N + 1) * 4 * m,
         "enumerate": n_c // 8 + 4 * U,
@@ -207,9 +226,10 @@ def main():
               "sketch": "rank_sketch_bytes", "out_idx": "out_idx_bytes",
               "out_val": "out_val_bytes", "out_dense": "out_dense_bytes"}
     need = {k: 0 for k in fields}
+    sizing = B.TAGC_SIZE_FIXED_RATIO if args.ratio else B.TAGC_SIZE_LOAD_FACTOR
     for b in buckets:
-        cfg = B.tagc_config(dtype=b.dtype, n_ranks=N, n_hash=3, sizing=B.TAGC_SIZE_LOAD_FACTOR,
-                            sizing_milli=b.sizing_milli, index_mode=B.TAGC_INDEX_OR1,
+        cfg = B.tagc_config(dtype=b.dtype, n_ranks=N, n_hash=3, sizing=sizing,
+                            sizing_milli=b.sizing_milli, index_mode=args.index_mode,
                             part_unknowns=args.part_unknowns, part_cells=args.part_cells,
                             seed=args.seed, decode_mode=args.decode_mode)
         plan = B.tagc_plan(cfg, [tuple(s[:4]) for s in b.segments])
@@ -225,7 +245,8 @@ def main():
                               seed=args.seed, dense=bool(args.dense),
                               part_unknowns=args.part_unknowns, part_cells=args.part_cells,
                               error_feedback=args.error_feedback,
-                              decode_mode=args.decode_mode,
+                              decode_mode=args.decode_mode, index_mode=args.index_mode,
+                              sizing=sizing,
                               share=None if first else tbs[i % lanes],
                               min_bytes=need if first else None))
     stream = torch.cuda.current_stream()
@@ -251,6 +272,7 @@ def main():
     balg = {k: 0 for k in STAGES}
     kalg = {}
     unresolved = estimated = rounds = 0
+    wire = 4 if args.index_mode == B.TAGC_INDEX_ADD4 else 1
     U_tot = m_tot = k_tot = 0
     flags = 0
     facts = []
@@ -263,9 +285,9 @@ def main():
         flags |= st["flags"]
         for r in range(N):
             flags |= tbs[i].rank_counts(r)["flags"]
-        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback).items():
+        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire).items():
             balg[k] += v
-        for k, v in kernel_alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback).items():
+        for k, v in kernel_alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire).items():
             kalg[k] = kalg.get(k, 0) + v
         input_bytes += N * tbs[i].sizes.n_real * buckets[i].elem_bytes
         unresolved += st["n_unresolved"]
@@ -350,10 +372,11 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d buckets x %d simulated ranks, %s grads, lf %.1f, %s"
+        "config": {"workload": "%s: %d buckets x %d simulated ranks, %s grads, %s %.1f, %s"
                                % (args.workload + (" + error feedback" if args.error_feedback
                                                    else ""), n_b, N,
                                   "bf16" if buckets[0].dtype == G.BF16 else "fp32",
+                                  "fixed ratio" if args.ratio else "lf",
                                   buckets[0].sizing_milli / 1000.0,
                                   "sparse+dense output" if args.dense else "sparse output"),
                    "input_bytes_per_step": input_bytes, "distinct_bucket_data_sets": pool,
@@ -361,6 +384,7 @@ def main():
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,
+                   "index_mode": args.index_mode,
                    "peel_rounds_max": rounds, "input_generation_s": round(t_gen, 2)},
         "hbm_frac_end_to_end": round(balg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "alg_bytes_per_step": balg_total,

@@ -48,7 +48,7 @@ typedef enum tagc_error {
 
 enum { TAGC_F32 = 0, TAGC_BF16 = 1 };                      /* tagc_config.dtype  */
 enum { TAGC_SIZE_LOAD_FACTOR = 0, TAGC_SIZE_FIXED_RATIO = 1 }; /* .sizing        */
-enum { TAGC_INDEX_OR1 = 0 };                               /* .index_mode        */
+enum { TAGC_INDEX_OR1 = 0, TAGC_INDEX_ADD1 = 1, TAGC_INDEX_ADD4 = 2 }; /* .index_mode */
 enum { TAGC_PHASE_INDEX = 1, TAGC_PHASE_SKETCH = 2 };
 #define TAGC_SEG_COMPRESS 1u
 
@@ -78,7 +78,9 @@ typedef struct tagc_config {
                                1000), the "c-x compression" of Table 1          */
     uint32_t sizing_milli;
     uint32_t index_mode;    /* TAGC_INDEX_OR1: 1 bit per parameter, merged by OR
-                               (section 2.2)                                    */
+                               (section 2.2).  TAGC_INDEX_ADD1 / TAGC_INDEX_ADD4:
+                               the OR simulated by addition as over NCCL (same
+                               section), see "Index modes" below                */
     uint32_t part_unknowns; /* max non-zeros per sketch partition, 0 = default  */
     uint32_t part_cells;    /* max cells per sketch partition (multiple of 3),
                                0 = default                                      */
@@ -86,6 +88,25 @@ typedef struct tagc_config {
     uint32_t decode_mode;   /* TAGC_DECODE_*; 0 = peeling only                  */
     uint32_t reserved;      /* must be 0                                        */
 } tagc_config;
+
+/*
+ * Index modes (section 2.2).  The paper's implementation cannot OR over NCCL
+ * and adds instead, on a 1-bit Index (fast, collides) or a 4-bit one (stable,
+ * four times bigger); no layout is given.  Here the wire Index is an array of
+ * unsigned 32-bit words that the aggregation adds as such (wrapping; a carry
+ * runs into the next parameter's field, the carry out of a word is lost):
+ *   TAGC_INDEX_ADD1  wire Index = local Index (parameter j = bit j&31 of word
+ *                    j>>5); a position kept by an even number of ranks drops
+ *                    out of the merged Index and its carries flip higher ones;
+ *   TAGC_INDEX_ADD4  one 4-bit counter per parameter, parameter j in bits
+ *                    4*(j&7).. of word j>>3 (4 * bitmap_words words per rank,
+ *                    what tagc_rank_buffers.bitmap then holds); merged bit j =
+ *                    counter j of the sum != 0: the OR for up to 15 ranks.
+ * The merged Index stays 1 bit per parameter in both.  PHASE_SKETCH then
+ * encodes only the pairs whose position the merged Index names, so that the
+ * decoder's unknowns are exactly what the cells hold: a position a carry
+ * erased is lost, one a carry invented decodes to 0.
+ */
 
 /* What tagc_decompress does with the summed sketch (section 2.2 names the two
  * decompression algorithms, peeling and estimation; the latter is a Count
@@ -166,8 +187,9 @@ typedef struct tagc_rank_buffers {
     uint32_t *idx;      /* [pair_capacity] c-indices of survivors, ascending    */
     float *val;         /* [pair_capacity] their values widened to float32      */
     uint32_t *cnt;      /* [rank_cnt_bytes / 4] see TAGC_CNT_*                  */
-    uint32_t *bitmap;   /* [bitmap_words] local Index, bit j in word j>>5, bit
-                           j&31                                                 */
+    uint32_t *bitmap;   /* [rank_bitmap_bytes / 4] local Index as it goes on the
+                           wire: bit j in word j>>5, bit j&31 (bitmap_words
+                           words), or 4-bit counters with TAGC_INDEX_ADD4       */
     float *sketch;      /* [sketch_cells_capacity] local Count Sketch; cells
                            [0, m) are written, the rest untouched              */
     void *workspace;    /* [rank_workspace_bytes] scratch, may be shared by ranks

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libtagc.so")
 
 TAGC_F32, TAGC_BF16 = 0, 1
 TAGC_SIZE_LOAD_FACTOR, TAGC_SIZE_FIXED_RATIO = 0, 1
-TAGC_INDEX_OR1 = 0
+TAGC_INDEX_OR1, TAGC_INDEX_ADD1, TAGC_INDEX_ADD4 = 0, 1, 2
 TAGC_PHASE_INDEX, TAGC_PHASE_SKETCH = 1, 2
 TAGC_SEG_COMPRESS = 1
 TAGC_CNT_TOTAL, TAGC_CNT_NONFINITE, TAGC_CNT_FLAGS, TAGC_CNT_DENSE, TAGC_CNT_SEG0 = 0, 1, 2, 3, 4

@@ -28,13 +28,14 @@ class TagcBucket:
     def __init__(self, segments, dtype, n_ranks, sizing_milli=3000,
                  sizing=B.TAGC_SIZE_LOAD_FACTOR, seed=0, part_unknowns=0,
                  part_cells=0, device="cuda", dense=False, share=None, min_bytes=None,
-                 error_feedback=False, decode_mode=B.TAGC_DECODE_PEEL):
+                 error_feedback=False, decode_mode=B.TAGC_DECODE_PEEL,
+                 index_mode=B.TAGC_INDEX_OR1):
         if not torch.cuda.is_available():
             raise RuntimeError("libtagc needs a GPU: no CPU path exists")
         self.device = torch.device(device)
         self.cfg = B.tagc_config(dtype=dtype, n_ranks=n_ranks, n_hash=3,
                                  sizing=sizing, sizing_milli=sizing_milli,
-                                 index_mode=B.TAGC_INDEX_OR1,
+                                 index_mode=index_mode,
                                  part_unknowns=part_unknowns,
                                  part_cells=part_cells, seed=seed,
                                  decode_mode=decode_mode)
@@ -190,7 +191,11 @@ class TagcBucket:
         return raw.cpu().numpy().view(np.uint16 if t.dtype == torch.bfloat16 else np.uint32).copy()
 
     def rank_bitmap(self, r):
-        return self._np(self._rk_tensors[r]["bitmap"], np.uint32, self.sizes.bitmap_words)
+        """The rank's Index as it goes on the wire (4 words per 32 parameters with 4-bit
+        counters, 1 otherwise)."""
+        wire = 4 if self.cfg.index_mode == B.TAGC_INDEX_ADD4 else 1
+        return self._np(self._rk_tensors[r]["bitmap"], np.uint32,
+                        wire * self.sizes.bitmap_words)
 
     def rank_sketch(self, r):
         return self._np(self._rk_tensors[r]["sketch"], np.float32, self.header()["m"])

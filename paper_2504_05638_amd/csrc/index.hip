@@ -10,26 +10,76 @@ namespace tagc {
 
 namespace {
 
-// One workgroup per chunk of kChunkWords words; 4 words per thread.
+// One workgroup per chunk of kChunkWords words of the merged Index; 4 words per thread.
+// MODE says how the ranks' wire Indexes combine (section 2.2): the OR the Index needs, or the
+// addition that simulates it over a library without OR -- of the 1-bit words themselves
+// (carries and all), or of 4-bit counters, four wire words per merged word, a merged bit
+// being set where the summed counter is not 0.  Sums wrap as unsigned 32-bit adds do.  With
+// more ranks than one launch takes, the running result is carried in `out` (OR, 1-bit add)
+// or, for the counters, in `sum4`.
+__device__ __forceinline__ uint32_t nonzero_nibbles(uint32_t x)  // bit p = nibble p != 0
+{
+    x |= x >> 2;
+    x |= x >> 1;
+    x &= 0x11111111u;             // bit 4p = nibble p != 0
+    x = (x | (x >> 3)) & 0x03030303u;
+    x = (x | (x >> 6)) & 0x000F000Fu;
+    return (x | (x >> 12)) & 0xFFu;
+}
+
+template <int MODE>
 __global__ void __launch_bounds__(256)
-index_or_kernel(RankPtrs rp, uint32_t n_in, uint32_t *__restrict__ out, uint32_t n_words,
-                int accumulate, uint32_t *__restrict__ chunkcnt)
+index_merge_kernel(RankPtrs rp, uint32_t n_in, uint32_t *__restrict__ out, uint32_t n_words,
+                   int accumulate, int last, uint32_t *__restrict__ sum4,
+                   uint32_t *__restrict__ chunkcnt)
 {
     __shared__ uint32_t smem[4];
     const uint32_t w0 = blockIdx.x * kChunkWords + threadIdx.x * 4;
     uint32_t pc = 0;
-    if (w0 + 4 <= n_words) {
+    if (MODE == TAGC_INDEX_ADD4) {
+        // a thread merges the words tid, tid + 256, ... of the chunk: the four wire words of
+        // one merged word are one 16-byte load per rank, consecutive across the lanes
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            const uint32_t w = blockIdx.x * kChunkWords + k * 256 + threadIdx.x;
+            if (w >= n_words) break;
+            const size_t q = 4 * size_t(w);
+            uint4 acc = accumulate ? *reinterpret_cast<const uint4 *>(sum4 + q)
+                                   : make_uint4(0, 0, 0, 0);
+#pragma unroll 8
+            for (uint32_t r = 0; r < n_in; ++r) {
+                const uint4 v =
+                    *reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(rp.p[r]) + q);
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+            if (!last) {
+                *reinterpret_cast<uint4 *>(sum4 + q) = acc;
+            } else {
+                const uint32_t m = nonzero_nibbles(acc.x) | (nonzero_nibbles(acc.y) << 8) |
+                                   (nonzero_nibbles(acc.z) << 16) | (nonzero_nibbles(acc.w) << 24);
+                out[w] = m;
+                pc += __popc(m);
+            }
+        }
+    } else if (w0 + 4 <= n_words) {
         uint4 acc = accumulate ? *reinterpret_cast<const uint4 *>(out + w0) : make_uint4(0, 0, 0, 0);
         for (uint32_t r = 0; r < n_in; ++r) {
             uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(rp.p[r]) + w0);
-            acc.x |= v.x; acc.y |= v.y; acc.z |= v.z; acc.w |= v.w;
+            if (MODE == TAGC_INDEX_OR1) {
+                acc.x |= v.x; acc.y |= v.y; acc.z |= v.z; acc.w |= v.w;
+            } else {
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
         }
         *reinterpret_cast<uint4 *>(out + w0) = acc;
         pc = __popc(acc.x) + __popc(acc.y) + __popc(acc.z) + __popc(acc.w);
     } else {
         for (uint32_t w = w0; w < n_words; ++w) {
             uint32_t acc = accumulate ? out[w] : 0u;
-            for (uint32_t r = 0; r < n_in; ++r) acc |= static_cast<const uint32_t *>(rp.p[r])[w];
+            for (uint32_t r = 0; r < n_in; ++r) {
+                const uint32_t v = static_cast<const uint32_t *>(rp.p[r])[w];
+                acc = MODE == TAGC_INDEX_OR1 ? (acc | v) : (acc + v);
+            }
             out[w] = acc;
             pc += __popc(acc);
         }
@@ -193,8 +243,15 @@ int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32
             const uint32_t n_in = std::min(kMaxRanksPerPass, n_ranks - r0);
             for (uint32_t r = 0; r < n_in; ++r) rp.p[r] = ranks[r0 + r].bitmap;
             const bool last = r0 + n_in == n_ranks;
-            index_or_kernel<<<n_chunks, 256, 0, s>>>(rp, n_in, sh->bitmap, n_words, r0 != 0,
-                                                     last ? chunk : nullptr);
+            // the 4-bit running sum lives behind the chunk prefixes (the plan sized it)
+            uint32_t *sum4 = chunk + ((size_t(n_chunks) + 1 + 3) & ~size_t(3));
+            auto kernel = p->cfg.index_mode == TAGC_INDEX_ADD4
+                              ? index_merge_kernel<TAGC_INDEX_ADD4>
+                              : (p->cfg.index_mode == TAGC_INDEX_ADD1
+                                     ? index_merge_kernel<TAGC_INDEX_ADD1>
+                                     : index_merge_kernel<TAGC_INDEX_OR1>);
+            kernel<<<n_chunks, 256, 0, s>>>(rp, n_in, sh->bitmap, n_words, r0 != 0, last, sum4,
+                                            last ? chunk : nullptr);
         }
     }
     {

@@ -28,7 +28,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     if (cfg->n_hash != 3 || cfg->n_ranks == 0 || cfg->sizing_milli == 0) return TAGC_EINVAL;
     if (cfg->sizing != TAGC_SIZE_LOAD_FACTOR && cfg->sizing != TAGC_SIZE_FIXED_RATIO)
         return TAGC_EINVAL;
-    if (cfg->index_mode != TAGC_INDEX_OR1) return TAGC_EUNSUPPORTED;
+    if (cfg->index_mode > TAGC_INDEX_ADD4) return TAGC_EUNSUPPORTED;
     if (cfg->decode_mode > TAGC_DECODE_ESTIMATE || cfg->reserved) return TAGC_EINVAL;
     uint32_t P_cap = cfg->part_unknowns ? cfg->part_unknowns : kDefaultPartUnknowns;
     uint32_t T_cap = cfg->part_cells ? cfg->part_cells : kDefaultPartCells;
@@ -73,12 +73,14 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
             d.tile_start = uint32_t(tiles);
             d.flags = (s.offset % p->vec_elems) == 0 ? kSegAligned : 0;
             // Candidate route: slots per chunk for 1.3 x the kept fraction plus six
-            // standard deviations; segments keeping so much that half a chunk would be
-            // candidates gain nothing from it.
+            // standard deviations.  Its second pass costs in proportion to the candidates;
+            // measured on 7B-shaped buckets it beats reading the gradient twice up to about
+            // 3 % kept (4 % of a chunk expected as candidates), beyond that (Table 1's 2x and
+            // 4x regimes) the dense route is several times faster.
             if ((d.flags & kSegAligned) && d.n >= kFastMinElems && d.k >= kFastMinKeep) {
                 const double mu = 1.3 * double(d.k) / double(d.n) * p->chunk_elems;
                 const uint32_t cap = uint32_t(round_up(uint64_t(mu + 6.0 * sqrt(mu) + 16.0), 32));
-                if (cap <= p->chunk_elems / 2) {
+                if (mu <= kFastMaxCandFrac * p->chunk_elems) {
                     d.flags |= kSegFast;
                     p->cand_cap = std::max(p->cand_cap, cap);
                 }
@@ -148,6 +150,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     off = round_up(off, 128);  // a chunk's slots then start on a cache-line boundary
     w.cand = off;
     off += round_up(chunks * p->cand_cap * (cfg->dtype == TAGC_F32 ? 8 : 4), 16);
+    w.bitmap1 = off;  // 4-bit Index: the 1-bit Index is built here and widened from here
+    if (cfg->index_mode == TAGC_INDEX_ADD4) off += round_up(4 * words, 16);
     w.total = std::max<uint64_t>(off, 16);
 
     tagc_sizes &z = p->sizes;
@@ -171,20 +175,25 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     // rank's sorted pair list crosses the partition bounds
     p->cnt_ranges = uint32_t(round_up(TAGC_CNT_SEG0 + L, 4));
     z.rank_cnt_bytes = round_up(4 * (p->cnt_ranges + p->A_cap + 2), 16);
-    z.rank_bitmap_bytes = round_up(4 * std::max<uint64_t>(words, 1), 16);
+    const uint64_t wire = cfg->index_mode == TAGC_INDEX_ADD4 ? 4 : 1;  // bits per parameter
+    z.rank_bitmap_bytes = round_up(4 * wire * std::max<uint64_t>(words, 1), 16);
     z.rank_sketch_bytes = round_up(4 * p->m_cap, 16);
     z.rank_workspace_bytes = w.total;
-    z.shared_bitmap_bytes = z.rank_bitmap_bytes;
+    z.shared_bitmap_bytes = round_up(4 * std::max<uint64_t>(words, 1), 16);
     z.shared_sketch_bytes = z.rank_sketch_bytes;
     z.shared_header_bytes = 4 * TAGC_HDR_WORDS;
     z.shared_bounds_bytes = round_up(4 * (p->A_cap + 1), 16);
+    // chunk prefixes; behind them, when the 4-bit Index of more ranks than one pass takes is
+    // summed, the running 4-bit sum
     z.shared_workspace_bytes = round_up(4 * (p->n_chunks + 1), 16);
+    if (cfg->index_mode == TAGC_INDEX_ADD4 && cfg->n_ranks > kMaxRanksPerPass)
+        z.shared_workspace_bytes += round_up(16 * words, 16);
     z.shared_status_bytes = 4 * TAGC_ST_WORDS;
     z.out_idx_bytes = round_up(4 * std::max<uint64_t>(p->U_cap, 1), 16);
     z.out_val_bytes = z.out_idx_bytes;
     z.out_dense_bytes = round_up(4 * std::max<uint64_t>(p->n_c, 1), 16);
     if (n_real) {
-        z.wire_index_bits = 2.0 * double(p->n_c) / double(n_real);
+        z.wire_index_bits = 2.0 * double(wire) * double(p->n_c) / double(n_real);
         double cells = cfg->sizing == TAGC_SIZE_LOAD_FACTOR ? double(p->m_cap) : double(M_max);
         z.wire_sketch_bits = 32.0 * cells / double(n_real);
         z.wire_total_bits = z.wire_index_bits + z.wire_sketch_bits;

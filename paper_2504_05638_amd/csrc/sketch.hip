@@ -1,7 +1,7 @@
 // Count Sketch encode and aggregation.
 //
 // encode: local_count_sketch <- compress(g_shard, index) of Algorithm 1.  The merged Index
-//   enters through the layout only: partition a owns the pairs whose c-index lies in
+//   enters through the layout (and, when it was merged by addition, as a mask): partition a owns the pairs whose c-index lies in
 //   [bounds[a], bounds[a+1]) -- a contiguous run of the rank's sorted pair list, whose ends
 //   the Index aggregation leaves in the rank's cnt buffer -- and the
 //   3*m_sub cells starting at a*3*m_sub.  One workgroup builds one sub-table (partition a,
@@ -19,7 +19,7 @@ __global__ void __launch_bounds__(256)
 encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
               const uint32_t *__restrict__ cnt, const uint32_t *__restrict__ header,
               float *__restrict__ sketch, uint32_t sw0, uint32_t sw1, uint32_t sw2,
-              uint32_t ranges_off, uint32_t pair_cap)
+              uint32_t ranges_off, uint32_t pair_cap, const uint32_t *__restrict__ mask)
 {
     extern __shared__ float tile[];
     const uint32_t A = header[TAGC_HDR_A], m_sub = header[TAGC_HDR_MSUB];
@@ -31,6 +31,9 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
     const uint32_t hi = min(cnt[ranges_off + a + 1], pair_cap);
     // a thread's first pairs (all of them for a partition of up to 1024 pairs of this rank)
     // are requested together, before the tile is cleared
+    // after an addition-simulated Index All-Reduce (section 2.2) the merged Index need not
+    // hold every pair: only the positions it names are encoded (mask = merged Index then)
+    auto named = [&](uint32_t i) { return !mask || ((mask[i >> 5] >> (i & 31)) & 1u); };
     constexpr uint32_t PRE = 4;
     uint32_t pi[PRE];
     float pv[PRE];
@@ -44,7 +47,7 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
     __syncthreads();
 #pragma unroll
     for (uint32_t u = 0; u < PRE; ++u) {
-        if (lo + threadIdx.x + u * 256 < hi) {
+        if (lo + threadIdx.x + u * 256 < hi && named(pi[u])) {
             uint32_t neg;
             const uint32_t slot = hash_slot(pi[u], sw, m_sub, &neg);
             lds_add_f32(&tile[slot], neg ? -pv[u] : pv[u]);
@@ -53,6 +56,7 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
     for (uint32_t t = lo + threadIdx.x + PRE * 256; t < hi; t += 256) {
         const uint32_t i = idx[t];
         const float v = val[t];
+        if (!named(i)) continue;
         uint32_t neg;
         const uint32_t slot = hash_slot(i, sw, m_sub, &neg);
         lds_add_f32(&tile[slot], neg ? -v : v);
@@ -134,7 +138,8 @@ int launch_encode(const tagc_plan_t *p, const tagc_rank_buffers *rk, const tagc_
     dim3 grid(uint32_t(p->A_cap), 3, 1);
     encode_kernel<<<grid, 256, lds, s>>>(rk->idx, rk->val, rk->cnt, sh->header, rk->sketch,
                                          p->seed_word[0], p->seed_word[1], p->seed_word[2],
-                                         p->cnt_ranges, uint32_t(p->K));
+                                         p->cnt_ranges, uint32_t(p->K),
+                                         p->cfg.index_mode == TAGC_INDEX_OR1 ? nullptr : sh->bitmap);
     return hip_ok(hipGetLastError());
 }
 

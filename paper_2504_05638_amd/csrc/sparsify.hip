@@ -1487,6 +1487,28 @@ int allow_lds(K kernel, size_t lds, bool *done)
     return TAGC_OK;
 }
 
+// 4-bit wire Index (section 2.2: the stable, four times bigger variant that an All-Reduce
+// by addition can merge): one 0/1 counter per parameter, parameter j in bits 4*(j&7).. of
+// word j>>3.  One thread per word of the 1-bit Index: 4 bytes in, one 16-byte store out.
+__device__ __forceinline__ uint32_t spread8(uint32_t b)  // bit p of a byte -> bit 4p
+{
+    uint32_t x = (b | (b << 12)) & 0x000F000Fu;  // nibbles 0,1 -> 16-bit fields
+    x = (x | (x << 6)) & 0x03030303u;            // 2 bits per byte
+    x = (x | (x << 3)) & 0x11111111u;            // 1 bit per nibble
+    return x;
+}
+
+__global__ void __launch_bounds__(256)
+widen4_kernel(const uint32_t *__restrict__ map, uint32_t n_words, uint32_t *__restrict__ wire)
+{
+    const uint32_t w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= n_words) return;
+    const uint32_t m = map[w];
+    *reinterpret_cast<uint4 *>(wire + 4 * size_t(w)) =
+        make_uint4(spread8(m & 0xFFu), spread8((m >> 8) & 0xFFu), spread8((m >> 16) & 0xFFu),
+                   spread8(m >> 24));
+}
+
 template <int DTYPE>
 int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_buffers *rk,
                       const tagc_shared_buffers *sh, hipStream_t s)
@@ -1508,6 +1530,9 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     uint32_t *cand = reinterpret_cast<uint32_t *>(ws + p->ws.cand);
     const uint64_t n_slots = uint64_t(p->total_sc) * kCandChunksPerSuper * p->cand_cap;
     const char *g = static_cast<const char *>(grad);
+    // with 4-bit counters on the wire the 1-bit Index is built in the workspace and widened
+    const bool wide = p->cfg.index_mode == TAGC_INDEX_ADD4;
+    uint32_t *bitmap1 = wide ? reinterpret_cast<uint32_t *>(ws + p->ws.bitmap1) : rk->bitmap;
     // Error feedback: scan_spill (candidate route) and accumulate_kernel (all other segments)
     // turn acc into grad + acc; whoever reads the input after them reads it from acc.
     char *acc = static_cast<char *>(rk->acc);
@@ -1587,7 +1612,12 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         finish_kernel<DTYPE><<<n_emit + n_compact, kEmitThreads, 0, s>>>(
             n_emit, src, acc, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state,
             tile_state,
-            rk->idx, rk->val, rk->bitmap, rk->cnt, ticket);
+            rk->idx, rk->val, bitmap1, rk->cnt, ticket);
+    }
+    if (wide && p->n_c) {
+        ProfileScope ps("widen4", s);
+        const uint32_t n_words = uint32_t(p->n_c / 32);
+        widen4_kernel<<<(n_words + 255) / 256, 256, 0, s>>>(bitmap1, n_words, rk->bitmap);
     }
     return hip_ok(hipGetLastError());
 }

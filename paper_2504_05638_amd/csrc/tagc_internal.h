@@ -23,6 +23,7 @@ constexpr uint32_t kEmitThreads = 256;
 constexpr uint32_t kSampleVectors = 4096;     // 16-byte vectors sampled per segment
 constexpr uint32_t kFastMinElems = 1u << 17;  // shorter segments take the dense path
 constexpr uint32_t kFastMinKeep = 64;
+constexpr double kFastMaxCandFrac = 0.04;  // expected candidates per element beyond which the dense path wins
 constexpr uint32_t kChunkWords = 1024;  // Index words per popcount chunk
 // A partition keeps, in LDS, 10 bytes per cell (value, meta word, queue slot) and 4 per
 // unknown (its c-index): 12288 cells and 8192 unknowns fill the 160 KiB.
@@ -70,7 +71,7 @@ struct RankPtrs {
 
 struct Workspace {  // byte offsets inside a rank workspace
     uint64_t hist1, hist1d, hist2, tile_state, sc_state, counters;  // cleared per call
-    uint64_t sel, binlo, chunk_cnt, cand, total;
+    uint64_t sel, binlo, chunk_cnt, cand, bitmap1, total;
 };
 
 

@@ -12,9 +12,9 @@ def oracle_segments(bucket):
     return [O.Segment(s.offset, s.length, s.keep_ppm, s.flags) for s in bucket.segments]
 
 
-def oracle_config(bucket, sizing=O.SIZE_LOAD_FACTOR, seed=0, P=8192, T=12288):
+def oracle_config(bucket, sizing=O.SIZE_LOAD_FACTOR, seed=0, P=8192, T=12288, index_mode=0):
     return O.Config(dtype=bucket.dtype, sizing=sizing, sizing_milli=bucket.sizing_milli,
-                    seed=seed, part_unknowns=P, part_cells=T)
+                    seed=seed, part_unknowns=P, part_cells=T, index_mode=index_mode)
 
 
 def segment_of(c_index, bucket):
@@ -67,17 +67,18 @@ def estimate_tolerance(ores, seed, rel=1e-5):
 
 
 def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTOR, dense=True,
-             decode_mode=0):
+             decode_mode=0, index_mode=0):
     """Runs oracle and library on the same inputs; returns (oracle result, TagcBucket)."""
     import torch
     from paper_2504_05638_amd.bucket import TagcBucket
 
-    ocfg = oracle_config(bucket, sizing, seed, P or 8192, T or 12288)
+    ocfg = oracle_config(bucket, sizing, seed, P or 8192, T or 12288, index_mode)
     ores = O.run_bucket([G.to_numpy_raw(g) for g in grads_torch_cpu], ocfg,
                         oracle_segments(bucket), decode_mode=decode_mode)
     tb = TagcBucket(bucket.segments, bucket.dtype, len(grads_torch_cpu),
                     sizing_milli=bucket.sizing_milli, sizing=sizing, seed=seed,
-                    part_unknowns=P, part_cells=T, dense=dense, decode_mode=decode_mode)
+                    part_unknowns=P, part_cells=T, dense=dense, decode_mode=decode_mode,
+                    index_mode=index_mode)
     dev = [g.cuda() for g in grads_torch_cpu]
     tb.run(dev)
     torch.cuda.synchronize()
@@ -100,7 +101,9 @@ def compare_all(bucket, ores, tb, exact_values=False, rel=1e-5):
         idx, val = tb.rank_pairs(r)
         assert np.array_equal(idx, ores.ranks[r].idx)
         assert np.array_equal(val.view(np.uint32), ores.ranks[r].val.view(np.uint32))
-        assert np.array_equal(tb.rank_bitmap(r), ores.ranks[r].bitmap[:z.bitmap_words])
+        local = ores.ranks[r].bitmap[:z.bitmap_words]
+        assert np.array_equal(tb.rank_bitmap(r), O.index_widen4(local)
+                              if tb.cfg.index_mode == O.INDEX_ADD4 else local)
     # --- stage 3a: merged Index, layout, bounds
     hdr = tb.header()
     assert hdr == dict(U=ores.U, A=ores.A, m_sub=ores.m_sub, m=ores.m)
@@ -116,7 +119,8 @@ def compare_all(bucket, ores, tb, exact_values=False, rel=1e-5):
             assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
         else:
             mag = O.encode(ores.ranks[r].idx, np.abs(ores.ranks[r].val), ores.bnd, ores.A,
-                           ores.m_sub, tb.cfg.seed, plus_only=True)
+                           ores.m_sub, tb.cfg.seed, plus_only=True,
+                           mask=ores.bitmap if tb.cfg.index_mode else None)
             assert np.all(np.abs(got.astype(np.float64) - want) <= rel * mag.astype(np.float64))
             # cells with at most two contributions do not depend on the order
             assert got.size == 0 or np.mean(got.view(np.uint32) == want.view(np.uint32)) > 0.8

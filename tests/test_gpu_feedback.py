@@ -19,7 +19,7 @@ def _mixed_bucket(dtype, n_ranks):
     segs = [G.Seg(0, (1 << 18) + 13, 10_000, 1, "long_ragged"),
             G.Seg(262_168, 5000, 20_000, 1, "short"),
             G.Seg(267_176, 4096, 0, 0, "skipped"),
-            G.Seg(271_272, (1 << 17), 50_000, 1, "long_dense_keep"),
+            G.Seg(271_272, (1 << 17), 25_000, 1, "long_dense_keep"),
             G.Seg(402_347, (1 << 17) + 64, 10_000, 1, "long_unaligned"),
             G.Seg(533_488, 300_000, 100, 1, "long_tiny_k"),
             G.Seg(833_488, 1000, 0, 1, "keeps_nothing")]

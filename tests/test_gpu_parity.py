@@ -216,7 +216,7 @@ def test_candidate_and_dense_routes_in_one_bucket(dtype):
     _announce("routes mixed dtype=%d" % dtype)
     segs = [G.Seg(0, (1 << 18) + 13, 10_000, 1, "long_ragged"),
             G.Seg(262_168, 5000, 20_000, 1, "short"),
-            G.Seg(267_176, (1 << 17), 50_000, 1, "long_dense_keep"),
+            G.Seg(267_176, (1 << 17), 25_000, 1, "long_dense_keep"),
             G.Seg(398_251, (1 << 17) + 64, 10_000, 1, "long_unaligned"),
             G.Seg(529_392, 300_000, 100, 1, "long_tiny_k")]
     n = 829_392
@@ -279,7 +279,7 @@ def test_buckets_in_flight_on_separate_streams():
     routes = G.Bucket("routes", G.BF16, 3,
                       [G.Seg(0, (1 << 18) + 13, 10_000, 1, "long_ragged"),
                        G.Seg(262_168, 5000, 20_000, 1, "short"),
-                       G.Seg(267_176, (1 << 17), 50_000, 1, "long_dense_keep"),
+                       G.Seg(267_176, (1 << 17), 25_000, 1, "long_dense_keep"),
                        G.Seg(398_251, (1 << 17) + 64, 10_000, 1, "long_unaligned"),
                        G.Seg(529_392, 300_000, 100, 1, "long_tiny_k")], 829_392, 1500,
                       {"long_ragged": 1e-3, "short": 1e-2, "long_dense_keep": 1e-4,

@@ -68,6 +68,24 @@ def test_wire_accounting_reproduces_the_papers_numbers():
     assert abs(z.wire_total_bits - O.wire_bits_per_param(1, 2)) < 1e-9
 
 
+def test_four_bit_index_sizes_and_wire_volume():
+    """The 4-bit Index is four times the 1-bit one, on the wire and in the rank's buffer
+    (section 2.2); the merged Index stays 1 bit per parameter."""
+    seg = [(0, 1_024_000, 12_500, 1)]
+    z1 = B.tagc_plan_sizes(B.tagc_plan(_cfg(sizing=B.TAGC_SIZE_FIXED_RATIO, sizing_milli=10_000),
+                                       seg))
+    z4 = B.tagc_plan_sizes(B.tagc_plan(_cfg(sizing=B.TAGC_SIZE_FIXED_RATIO, sizing_milli=10_000,
+                                            index_mode=B.TAGC_INDEX_ADD4), seg))
+    za = B.tagc_plan_sizes(B.tagc_plan(_cfg(sizing=B.TAGC_SIZE_FIXED_RATIO, sizing_milli=10_000,
+                                            index_mode=B.TAGC_INDEX_ADD1), seg))
+    assert z4.rank_bitmap_bytes == 4 * z1.rank_bitmap_bytes == 4 * za.rank_bitmap_bytes
+    assert z4.shared_bitmap_bytes == z1.shared_bitmap_bytes
+    assert abs(z4.wire_index_bits - 4 * z1.wire_index_bits) < 1e-12
+    assert abs(z1.wire_total_bits - O.wire_bits_per_param(1, 10)) < 1e-9   # 5.2 bit
+    assert abs(z4.wire_total_bits - O.wire_bits_per_param(4, 10)) < 1e-9   # 11.2 bit
+    assert z4.rank_workspace_bytes >= z1.rank_workspace_bytes + 1_024_000 // 8
+
+
 def test_argument_errors():
     seg = [(0, 1000, 10_000, 1)]
     for bad in (dict(dtype=7), dict(n_hash=2), dict(n_ranks=0), dict(sizing=9),
@@ -77,8 +95,10 @@ def test_argument_errors():
             B.tagc_plan(_cfg(**bad), seg)
         assert e.value.code == -1
     with pytest.raises(B.TagcError) as e:
-        B.tagc_plan(_cfg(index_mode=1), seg)
+        B.tagc_plan(_cfg(index_mode=3), seg)
     assert e.value.code == -3
+    with pytest.raises(B.TagcError):
+        B.tagc_plan(_cfg(decode_mode=3), seg)
     with pytest.raises(B.TagcError) as e:
         B.tagc_plan(_cfg(), [(0, 1 << 31, 10_000, 1)])
     assert e.value.code == -2
