@@ -53,7 +53,7 @@ def parse_args():
     ap.add_argument("--dense", type=int, default=1, help="also write the dense summed gradient")
     ap.add_argument("--buckets", type=int, default=0,
                     help="only the first B buckets of the workload (0 = all; for experiments)")
-    ap.add_argument("--lanes", type=int, default=4,
+    ap.add_argument("--lanes", type=int, default=6,
                     help="buckets in flight at once: bucket i runs on HIP stream i %% lanes with "
                          "that lane's own buffers (buckets are independent of each other)")
     ap.add_argument("--part-unknowns", type=int, default=0,

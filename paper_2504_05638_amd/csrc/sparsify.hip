@@ -373,6 +373,17 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__re
     const uint64_t g0 = uint64_t(blockIdx.x) * span;
     if (g0 >= total_chunks) return;
     const uint64_t g1 = min(g0 + span, uint64_t(total_chunks));
+#ifdef TAGC_PHASE_TIMING
+    // per-workgroup time stamps (100 MHz counter) in the unused dense-route histogram area:
+    // start, first chunk classified, streaming done, histogram flushed
+    unsigned long long *stamp =
+        reinterpret_cast<unsigned long long *>(hist + uint64_t(L) * kBins1) + 8 * blockIdx.x;
+    bool first_done = false;
+    if (tid == 0) stamp[0] = wall_clock64();
+#define SPILL_STAMP(k) do { if (tid == 0) stamp[k] = wall_clock64(); } while (0)
+#else
+#define SPILL_STAMP(k) do { } while (0)
+#endif
     for (uint32_t i = tid; i < kSpillWindow; i += kSpillThreads) h[i] = 0;
     __syncthreads();
     // last segment whose first chunk is not beyond the span's start
@@ -599,8 +610,13 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__re
                     chunk_cnt[chunk_id] = total;
                 }
                 overflow |= total > CAP;
+#ifdef TAGC_PHASE_TIMING
+                if (!first_done) { SPILL_STAMP(1); first_done = true; }
+#endif
             }
+            SPILL_STAMP(2);
             if (staged) flush();
+            SPILL_STAMP(3);
             if (overflow && lane == 0)  // a chunk denser than its slots: take the dense route
                 atomicOr(&sel[l].route, 1u);
         }
@@ -613,8 +629,10 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__re
             }
         }
         __syncthreads();
+        SPILL_STAMP(4);
     }
 }
+#undef SPILL_STAMP
 
 // true iff some segment is on the dense route.  Every thread reads the same words, so the
 // loads are scalar and the answer is uniform without a barrier.
