@@ -180,12 +180,12 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
 #pragma unroll
         for (uint32_t q = 0; q < kCellPre; ++q) {
             const uint32_t c = tid + q * kDecodeThreads;
-            pre_cell[q] = c < cells ? src[c] : 0.0f;
+            pre_cell[q] = c < cells ? __builtin_nontemporal_load(src + c) : 0.0f;
         }
 #pragma unroll
         for (uint32_t q = 0; q < kIdxPre; ++q) {
             const uint32_t u = tid + q * kDecodeThreads;
-            pre_idx[q] = u < n ? idx_out[r0 + u] : 0u;
+            pre_idx[q] = u < n ? __builtin_nontemporal_load(idx_out + r0 + u) : 0u;
         }
     };
     if (blockIdx.x < A) prefetch(blockIdx.x);
@@ -369,7 +369,7 @@ dense_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
                 }
             }
         }
-        out[c] = make_float4(o[0], o[1], o[2], o[3]);
+        st_stream(out + c, make_float4(o[0], o[1], o[2], o[3]));
     }
 }
 

@@ -102,6 +102,36 @@ __device__ inline void lds_add_f32(float *p, float v)
     } while (old != assumed);
 }
 
+// Streaming accesses: data that is read or written once and not touched again by the same
+// kernel.  The non-temporal hint keeps such lines from displacing what the caches are for
+// (measured on a 17-stream sum: 5.3 -> 5.9 TB/s, the rate of a pure read).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ inline uint4 ld_stream(const uint4 *p)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ inline float4 ld_stream(const float4 *p)
+{
+    const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+__device__ inline void st_stream(uint4 *p, uint4 v)
+{
+    const u32x4_t x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<u32x4_t *>(p));
+}
+
+__device__ inline void st_stream(float4 *p, float4 v)
+{
+    const f32x4_t x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<f32x4_t *>(p));
+}
+
 __device__ inline uint64_t ld_agent(const uint64_t *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -48,8 +48,8 @@ index_merge_kernel(RankPtrs rp, uint32_t n_in, uint32_t *__restrict__ out, uint3
                                    : make_uint4(0, 0, 0, 0);
 #pragma unroll 8
             for (uint32_t r = 0; r < n_in; ++r) {
-                const uint4 v =
-                    *reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(rp.p[r]) + q);
+                const uint4 v = ld_stream(
+                    reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(rp.p[r]) + q));
                 acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
             }
             if (!last) {
@@ -64,7 +64,8 @@ index_merge_kernel(RankPtrs rp, uint32_t n_in, uint32_t *__restrict__ out, uint3
     } else if (w0 + 4 <= n_words) {
         uint4 acc = accumulate ? *reinterpret_cast<const uint4 *>(out + w0) : make_uint4(0, 0, 0, 0);
         for (uint32_t r = 0; r < n_in; ++r) {
-            uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(rp.p[r]) + w0);
+            const uint4 v =
+                ld_stream(reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(rp.p[r]) + w0));
             if (MODE == TAGC_INDEX_OR1) {
                 acc.x |= v.x; acc.y |= v.y; acc.z |= v.z; acc.w |= v.w;
             } else {

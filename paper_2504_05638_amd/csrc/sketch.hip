@@ -70,14 +70,17 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
     if (threadIdx.x < head) out[threadIdx.x] = tile[threadIdx.x];
     for (uint32_t v = threadIdx.x; v < n4; v += 256) {
         const float *t = tile + head + 4 * v;
-        *reinterpret_cast<float4 *>(out + head + 4 * v) = make_float4(t[0], t[1], t[2], t[3]);
+        st_stream(reinterpret_cast<float4 *>(out + head + 4 * v),
+                  make_float4(t[0], t[1], t[2], t[3]));
     }
     for (uint32_t c = head + 4 * n4 + threadIdx.x; c < m_sub; c += 256) out[c] = tile[c];
 }
 
-// Each workgroup sums tiles of kSumRows x 256 float4 cells: per rank it reads one
-// contiguous 16 KiB piece (four loads per thread in flight), ranks in order.
-constexpr uint32_t kSumRows = 4;
+// One float4 of cells per thread: the loads of up to kSumBatch ranks are issued together
+// (streaming, each byte is read once) and added in rank order, ((C_0 + C_1) + C_2) + ...;
+// more ranks than that take another round of loads, more than one launch holds continue
+// from `out`.
+constexpr uint32_t kSumBatch = 16;
 
 __global__ void __launch_bounds__(256)
 sketch_sum_kernel(RankPtrs rp, uint32_t n_in, float *__restrict__ out,
@@ -85,45 +88,40 @@ sketch_sum_kernel(RankPtrs rp, uint32_t n_in, float *__restrict__ out,
 {
     const uint32_t m = header[TAGC_HDR_M];
     const uint32_t m4 = m / 4;
-    constexpr uint32_t TILE = 256 * kSumRows;
-    for (uint32_t c0 = blockIdx.x * TILE; c0 < m4; c0 += gridDim.x * TILE) {
-        float4 acc[kSumRows];
-        const uint32_t c = c0 + threadIdx.x;
-        uint32_t r = 0;
-        const float4 *first = accumulate ? reinterpret_cast<const float4 *>(out)
-                                         : static_cast<const float4 *>(rp.p[0]);
-        if (!accumulate) r = 1;
+    const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+    if (c < m4) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (accumulate) acc = reinterpret_cast<const float4 *>(out)[c];
+        for (uint32_t r0 = 0; r0 < n_in; r0 += kSumBatch) {
+            float4 v[kSumBatch];
 #pragma unroll
-        for (uint32_t i = 0; i < kSumRows; ++i)
-            acc[i] = c + i * 256 < m4 ? first[c + i * 256] : make_float4(0.f, 0.f, 0.f, 0.f);
-        for (; r < n_in; ++r) {
-            const float4 *src = static_cast<const float4 *>(rp.p[r]);
-            float4 v[kSumRows];
+            for (uint32_t i = 0; i < kSumBatch; ++i)
+                if (r0 + i < n_in) v[i] = ld_stream(static_cast<const float4 *>(rp.p[r0 + i]) + c);
 #pragma unroll
-            for (uint32_t i = 0; i < kSumRows; ++i)
-                v[i] = c + i * 256 < m4 ? src[c + i * 256] : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-            for (uint32_t i = 0; i < kSumRows; ++i) {
-                acc[i].x += v[i].x; acc[i].y += v[i].y; acc[i].z += v[i].z; acc[i].w += v[i].w;
+            for (uint32_t i = 0; i < kSumBatch; ++i) {
+                if (r0 + i >= n_in) continue;
+                if (r0 + i == 0 && !accumulate) {
+                    acc = v[0];  // the first term as it is: -0 stays -0
+                } else {
+                    acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w;
+                }
             }
         }
-#pragma unroll
-        for (uint32_t i = 0; i < kSumRows; ++i)
-            if (c + i * 256 < m4) reinterpret_cast<float4 *>(out)[c + i * 256] = acc[i];
+        st_stream(reinterpret_cast<float4 *>(out) + c, acc);
     }
     if (blockIdx.x == 0) {
-        const uint32_t c = m4 * 4 + threadIdx.x;
-        if (c < m) {
+        const uint32_t t = m4 * 4 + threadIdx.x;
+        if (t < m) {
             float acc;
             uint32_t r = 0;
             if (accumulate) {
-                acc = out[c];
+                acc = out[t];
             } else {
-                acc = static_cast<const float *>(rp.p[0])[c];
+                acc = static_cast<const float *>(rp.p[0])[t];
                 r = 1;
             }
-            for (; r < n_in; ++r) acc += static_cast<const float *>(rp.p[r])[c];
-            out[c] = acc;
+            for (; r < n_in; ++r) acc += static_cast<const float *>(rp.p[r])[t];
+            out[t] = acc;
         }
     }
 }
@@ -147,10 +145,8 @@ int launch_sketch_sum(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint
                       const tagc_shared_buffers *sh, hipStream_t s)
 {
     ProfileScope ps("sketch_sum", s);
-    const uint64_t m4cap = p->m_cap / 4 + 1;
-    const uint64_t tile = 256 * kSumRows;
-    const uint32_t grid = uint32_t(std::max<uint64_t>(
-        1, std::min<uint64_t>((m4cap + tile - 1) / tile, uint64_t(device_cu_count()) * 8)));
+    // one thread per float4 up to the plan's capacity; those beyond the m in the header leave
+    const uint32_t grid = uint32_t(std::max<uint64_t>(1, (p->m_cap / 4 + 255) / 256));
     for (uint32_t r0 = 0; r0 < n_ranks; r0 += kMaxRanksPerPass) {
         RankPtrs rp{};
         const uint32_t n_in = std::min(kMaxRanksPerPass, n_ranks - r0);

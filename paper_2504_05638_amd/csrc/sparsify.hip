@@ -119,8 +119,8 @@ accumulate_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
         if (sd.flags & kSegAligned) {
             const uint64_t nvec = sd.n / VEC;
             for (uint64_t v = uint64_t(blockIdx.x) * 256 + threadIdx.x; v < nvec; v += stride) {
-                const uint4 g = reinterpret_cast<const uint4 *>(gb)[v];
-                const uint4 a = reinterpret_cast<const uint4 *>(ab)[v];
+                const uint4 g = ld_stream(reinterpret_cast<const uint4 *>(gb) + v);
+                const uint4 a = ld_stream(reinterpret_cast<const uint4 *>(ab) + v);
                 reinterpret_cast<uint4 *>(ab)[v] =
                     make_uint4(sum_word<DTYPE>(g.x, a.x), sum_word<DTYPE>(g.y, a.y),
                                sum_word<DTYPE>(g.z, a.z), sum_word<DTYPE>(g.w, a.w));
@@ -454,7 +454,7 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__re
                     const uint4 *q = reinterpret_cast<const uint4 *>(base + uint64_t(rel0) * EB) + lane;
 #pragma unroll
                     for (uint32_t r = 0; r < ROWS; ++r) {
-                        const uint4 v = q[64 * r];
+                        const uint4 v = ld_stream(q + 64 * r);  // read once, never again
                         w[r][0] = v.x; w[r][1] = v.y; w[r][2] = v.z; w[r][3] = v.w;
                     }
                 } else {
@@ -783,14 +783,14 @@ hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, 
             const uint64_t stride = uint64_t(gridDim.x) * kHistThreads;
             uint64_t v = uint64_t(blockIdx.x) * kHistThreads + tid;
             for (; v + 3 * stride < nvec; v += 4 * stride) {
-                uint4 a = vp[v], b = vp[v + stride], c = vp[v + 2 * stride],
-                      d = vp[v + 3 * stride];
+                const uint4 a = ld_stream(vp + v), b = ld_stream(vp + v + stride),
+                            c = ld_stream(vp + v + 2 * stride), d = ld_stream(vp + v + 3 * stride);
                 hist_vec<DTYPE>(a, h);
                 hist_vec<DTYPE>(b, h);
                 hist_vec<DTYPE>(c, h);
                 hist_vec<DTYPE>(d, h);
             }
-            for (; v < nvec; v += stride) hist_vec<DTYPE>(vp[v], h);
+            for (; v < nvec; v += stride) hist_vec<DTYPE>(ld_stream(vp + v), h);
             if (blockIdx.x == 0) {
                 uint64_t i = nvec * VEC + tid;
                 if (i < sd.n) hist_elem(load_elem_bits(base, i, DTYPE), h);
@@ -1336,7 +1336,8 @@ __device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad,
                 const uint32_t rel = base_rel + r * ROW_ELEMS + tid * VEC;
                 if (rel >= sd.n) continue;
                 if ((sd.flags & kSegAligned) && rel + VEC <= sd.n) {
-                    uint4 q = *reinterpret_cast<const uint4 *>(base + uint64_t(rel) * EB);
+                    const uint4 q =
+                        ld_stream(reinterpret_cast<const uint4 *>(base + uint64_t(rel) * EB));
                     w[r][0] = q.x; w[r][1] = q.y; w[r][2] = q.z; w[r][3] = q.w;
                 } else {
                     const uint32_t cntv = min(VEC, sd.n - rel);
@@ -1522,9 +1523,9 @@ widen4_kernel(const uint32_t *__restrict__ map, uint32_t n_words, uint32_t *__re
     const uint32_t w = blockIdx.x * 256 + threadIdx.x;
     if (w >= n_words) return;
     const uint32_t m = map[w];
-    *reinterpret_cast<uint4 *>(wire + 4 * size_t(w)) =
-        make_uint4(spread8(m & 0xFFu), spread8((m >> 8) & 0xFFu), spread8((m >> 16) & 0xFFu),
-                   spread8(m >> 24));
+    st_stream(reinterpret_cast<uint4 *>(wire + 4 * size_t(w)),
+              make_uint4(spread8(m & 0xFFu), spread8((m >> 8) & 0xFFu),
+                         spread8((m >> 16) & 0xFFu), spread8(m >> 24)));
 }
 
 template <int DTYPE>
