@@ -196,7 +196,10 @@ typedef struct tagc_rank_buffers {
                            processed one after another on one stream           */
     void *acc;          /* NULL, or [grad_elems] of the plan's dtype: the rank's
                            gradient accumulator (Algorithm 1: acc in, acc_next
-                           out, in place); see PHASE_INDEX                      */
+                           out, in place).  Together with `bitmap` it is the
+                           rank's error-feedback state: zero both before the
+                           first step and keep both between steps; see
+                           PHASE_INDEX                                          */
 } tagc_rank_buffers;
 
 /* Device buffers shared by the bucket (all dev, caller-owned). */
@@ -245,9 +248,16 @@ int tagc_plan_upload(const tagc_plan_t *plan, void *table_dev, void *stream);
  *   With rank->acc set (Algorithm 1, lines 1-2; section 3.2, local gradient
  *   accumulation) the entries of the compressed segments are first replaced by
  *   grad + acc, added in the gradient's own type (bf16: one float32 add rounded
- *   to nearest-even), and afterwards acc holds, in those segments, that sum
+ *   to nearest-even), and afterwards acc_next is, in those segments, that sum
  *   where the entry was not selected and zero where it was: what was selected
- *   plus the new acc is the sum, element by element.  grad_dev is only read.
+ *   plus acc_next is the sum, element by element.  grad_dev is only read.
+ *   acc_next is left in two parts: rank->acc holds the sums everywhere, and
+ *   rank->bitmap, the rank's new Index, names the entries that read as zero.
+ *   The call reads acc through the Index the rank's previous call left in
+ *   rank->bitmap in the same way (so rank->bitmap is an input too: all zero
+ *   before the first step), then overwrites both.  Clearing the ~1 % selected
+ *   entries in acc itself would cost a second pass over half of its cache
+ *   lines; tagc_feedback_apply does it for a caller who wants the plain array.
  * PHASE_SKETCH (Algorithm 1: compress(g_shard, index)).  Needs the shared
  *   header written by tagc_aggregate(PHASE_INDEX), which must have been given
  *   this rank among its `ranks` (it leaves the rank's partition ranges in
@@ -259,6 +269,16 @@ int tagc_plan_upload(const tagc_plan_t *plan, void *table_dev, void *stream);
 int tagc_compress(const tagc_plan_t *plan, uint32_t phase, const void *grad_dev,
                   const tagc_rank_buffers *rank,
                   const tagc_shared_buffers *shared, void *stream);
+
+/*
+ * Error feedback, optional: clears in rank->acc the entries that rank->bitmap
+ * names, after which rank->acc alone is acc_next of Algorithm 1 (line 2).  For
+ * inspection and checkpoints; idempotent, and the following PHASE_INDEX call
+ * gives the same results with or without it.  Needs rank->acc, rank->bitmap as
+ * the rank's last PHASE_INDEX call left them, and shared->table.
+ */
+int tagc_feedback_apply(const tagc_plan_t *plan, const tagc_rank_buffers *rank,
+                        const tagc_shared_buffers *shared, void *stream);
 
 /*
  * Stands in for the two collectives of Algorithm 1 on one GPU.

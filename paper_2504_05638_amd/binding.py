@@ -26,7 +26,7 @@ TAGC_DECODE_PEEL, TAGC_DECODE_PEEL_ESTIMATE, TAGC_DECODE_ESTIMATE = 0, 1, 2
 TAGC_FLAG_SPIN_LIMIT, TAGC_FLAG_OVERFLOW = 1, 2
 
 EXPORTS = ["tagc_plan", "tagc_plan_destroy", "tagc_plan_sizes",
-           "tagc_plan_upload", "tagc_compress", "tagc_aggregate",
+           "tagc_plan_upload", "tagc_compress", "tagc_feedback_apply", "tagc_aggregate",
            "tagc_decompress", "tagc_profile_enable", "tagc_profile_read",
            "tagc_hash_host", "tagc_strerror"]
 
@@ -112,6 +112,9 @@ def lib():
                                     C.POINTER(tagc_rank_buffers),
                                     C.POINTER(tagc_shared_buffers), vp]
         L.tagc_aggregate.restype = C.c_int
+        L.tagc_feedback_apply.restype = C.c_int
+        L.tagc_feedback_apply.argtypes = [vp, C.POINTER(tagc_rank_buffers),
+                                          C.POINTER(tagc_shared_buffers), vp]
         L.tagc_aggregate.argtypes = [vp, C.c_uint32,
                                      C.POINTER(tagc_rank_buffers), C.c_uint32,
                                      C.POINTER(tagc_shared_buffers), vp]
@@ -176,6 +179,12 @@ def tagc_compress(plan, phase, grad_dev, rank: tagc_rank_buffers,
                   shared: tagc_shared_buffers, stream: int = 0):
     _check(lib().tagc_compress(plan, phase, grad_dev, C.byref(rank),
                                C.byref(shared), stream), "tagc_compress")
+
+
+def tagc_feedback_apply(plan, rank: tagc_rank_buffers, shared: tagc_shared_buffers,
+                        stream: int = 0):
+    _check(lib().tagc_feedback_apply(plan, C.byref(rank), C.byref(shared), stream),
+           "tagc_feedback_apply")
 
 
 def tagc_aggregate(plan, phase, ranks, shared: tagc_shared_buffers,

@@ -69,7 +69,11 @@ class TagcBucket:
                      cnt=al("cnt%d" % r, z.rank_cnt_bytes),
                      bitmap=al("bitmap%d" % r, z.rank_bitmap_bytes),
                      sketch=al("sketch%d" % r, z.rank_sketch_bytes))
-            if error_feedback:  # the rank's gradient accumulator, zero before the first step
+            if error_feedback:
+                # the rank's error-feedback state: its accumulator and its own Index, both
+                # zero before the first step and never shared with another bucket
+                t["bitmap"] = torch.zeros(max(int(z.rank_bitmap_bytes), 16), dtype=torch.uint8,
+                                          device=dev)
                 t["acc"] = torch.zeros(max(int(z.grad_elems), 8), device=dev,
                                        dtype=torch.float32 if dtype == B.TAGC_F32
                                        else torch.bfloat16)
@@ -117,6 +121,10 @@ class TagcBucket:
             raise ValueError("gradient must be a contiguous %s CUDA tensor" % want)
         if grad.numel() < self.sizes.grad_elems:
             raise ValueError("gradient buffer shorter than the segment table needs")
+
+    def feedback_apply(self, r, stream=None):
+        """Clears in rank r's accumulator what the rank sent (optional, see tagc.h)."""
+        B.tagc_feedback_apply(self.plan, self.rk[r], self.shared, _stream_ptr(stream))
 
     def compress_index(self, r, grad, stream=None):
         self._check_grad(grad)

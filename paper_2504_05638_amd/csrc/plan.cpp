@@ -275,6 +275,17 @@ extern "C" int tagc_compress(const tagc_plan_t *p, uint32_t phase, const void *g
     return TAGC_EINVAL;
 }
 
+extern "C" int tagc_feedback_apply(const tagc_plan_t *p, const tagc_rank_buffers *rk,
+                                   const tagc_shared_buffers *sh, void *stream)
+{
+    if (!p || !rk || !rk->acc) return TAGC_EINVAL;
+    int rc = check_shared(sh);
+    if (rc) return rc;
+    rc = check_rank(rk);
+    if (rc) return rc;
+    return launch_feedback_apply(p, rk, sh, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int tagc_aggregate(const tagc_plan_t *p, uint32_t phase,
                               const tagc_rank_buffers *ranks, uint32_t n_ranks,
                               const tagc_shared_buffers *sh, void *stream)

@@ -99,12 +99,69 @@ __device__ inline void store_elem(char *base, uint64_t i, uint32_t bits, int dty
     else reinterpret_cast<uint32_t *>(base)[i] = bits;
 }
 
+// Error feedback keeps the record of what a rank sent in the rank's Index, not in the
+// accumulator: clearing ~1 % of the accumulator's entries one by one after the streaming
+// pass touched almost half of its cache lines a second time (measured: 140 us per rank on
+// 7B-shaped buckets).  Instead an entry of acc whose bit is set in the Index the rank's
+// previous call left (`sent`: 1 bit per parameter, or the 4-bit counters) reads as 0, and
+// the next call's streaming pass, which rewrites all of acc anyway, applies that.
+struct SentMap {
+    const uint32_t *map;  // the rank's Index buffer as the previous call left it
+    uint32_t wire4;       // 4-bit counters instead of bits
+};
+
+__device__ inline uint32_t nibbles_set(uint32_t x)  // bit p = nibble p of x != 0
+{
+    x |= x >> 2;
+    x |= x >> 1;
+    x &= 0x11111111u;
+    x = (x | (x >> 3)) & 0x03030303u;
+    x = (x | (x >> 6)) & 0x000F000Fu;
+    return (x | (x >> 12)) & 0xFFu;
+}
+
+// bit e <=> parameter ci + e was sent, for the VEC parameters of one 16-byte vector
+// (ci a multiple of VEC, VEC = 4 or 8)
+template <uint32_t VEC>
+__device__ inline uint32_t sent_bits(const SentMap sm, uint32_t ci)
+{
+    if (sm.wire4) {
+        const uint32_t w = sm.map[ci >> 3];
+        return VEC == 8 ? nibbles_set(w) : nibbles_set((w >> (4 * (ci & 4u))) & 0xFFFFu);
+    }
+    const uint32_t b = reinterpret_cast<const uint8_t *>(sm.map)[ci >> 3];
+    return VEC == 8 ? b : (b >> (ci & 4u)) & 0xFu;
+}
+
+__device__ inline bool sent_bit(const SentMap sm, uint32_t ci)
+{
+    if (sm.wire4) return ((sm.map[ci >> 3] >> (4 * (ci & 7u))) & 0xFu) != 0;
+    return ((sm.map[ci >> 5] >> (ci & 31u)) & 1u) != 0;
+}
+
+// float32 bit pattern of entry i of a segment's accumulator, 0 if it was sent
+__device__ inline uint32_t unsent_elem(const char *ab, uint64_t i, uint32_t c_off,
+                                       const SentMap sm, int dtype)
+{
+    return sent_bit(sm, c_off + uint32_t(i)) ? 0u : load_elem_bits(ab, i, dtype);
+}
+
+// word j of an accumulator vector with the entries named by `bits` (see sent_bits) cleared
+template <int DTYPE>
+__device__ inline uint32_t unsent_word(uint32_t a, uint32_t bits, uint32_t j)
+{
+    if (DTYPE == kF32) return (bits >> j) & 1u ? 0u : a;
+    const uint32_t two = (bits >> (2 * j)) & 3u;
+    return a & ~((two & 1u ? 0xFFFFu : 0u) | (two & 2u ? 0xFFFF0000u : 0u));
+}
+
 // Error feedback for the segments scan_spill never streams (short, unaligned, keeping
 // nothing or too much): acc <- grad + acc, entry by entry.  The dense route then reads its
 // input from acc.  Workgroups stride over each such segment.
 template <int DTYPE>
 __global__ void __launch_bounds__(256)
-accumulate_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, char *acc)
+accumulate_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, char *acc,
+                  const SentMap sent)
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
@@ -121,20 +178,25 @@ accumulate_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
             for (uint64_t v = uint64_t(blockIdx.x) * 256 + threadIdx.x; v < nvec; v += stride) {
                 const uint4 g = ld_stream(reinterpret_cast<const uint4 *>(gb) + v);
                 const uint4 a = ld_stream(reinterpret_cast<const uint4 *>(ab) + v);
+                const uint32_t sb = sent_bits<VEC>(sent, sd.c_off + uint32_t(v) * VEC);
                 reinterpret_cast<uint4 *>(ab)[v] =
-                    make_uint4(sum_word<DTYPE>(g.x, a.x), sum_word<DTYPE>(g.y, a.y),
-                               sum_word<DTYPE>(g.z, a.z), sum_word<DTYPE>(g.w, a.w));
+                    make_uint4(sum_word<DTYPE>(g.x, unsent_word<DTYPE>(a.x, sb, 0)),
+                               sum_word<DTYPE>(g.y, unsent_word<DTYPE>(a.y, sb, 1)),
+                               sum_word<DTYPE>(g.z, unsent_word<DTYPE>(a.z, sb, 2)),
+                               sum_word<DTYPE>(g.w, unsent_word<DTYPE>(a.w, sb, 3)));
             }
             if (blockIdx.x == 0) {
                 const uint64_t i = nvec * VEC + threadIdx.x;
                 if (i < sd.n)
                     store_elem(ab, i, sum_elem<DTYPE>(load_elem_bits(gb, i, DTYPE),
-                                                      load_elem_bits(ab, i, DTYPE)), DTYPE);
+                                                      unsent_elem(ab, i, sd.c_off, sent, DTYPE)),
+                               DTYPE);
             }
         } else {
             for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < sd.n; i += stride)
                 store_elem(ab, i, sum_elem<DTYPE>(load_elem_bits(gb, i, DTYPE),
-                                                  load_elem_bits(ab, i, DTYPE)), DTYPE);
+                                                  unsent_elem(ab, i, sd.c_off, sent, DTYPE)),
+                           DTYPE);
         }
     }
 }
@@ -222,7 +284,7 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
 // the pre-threshold; if that still happens select1 notices and re-routes the segment.
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads)
-sample_kernel(const char *__restrict__ grad, const char *acc,
+sample_kernel(const char *__restrict__ grad, const char *acc, const SentMap sent,
               const uint32_t *__restrict__ table, SelDev *__restrict__ sel,
               uint32_t *__restrict__ binlo, uint32_t *hint, uint4 *zero_base, uint64_t zero_n16,
               uint32_t *cnt, uint32_t n_cnt)
@@ -285,9 +347,13 @@ sample_kernel(const char *__restrict__ grad, const char *acc,
     for (uint32_t i = tid; i < S; i += kHistThreads) {
         uint4 q = vp[uint64_t(i) * stride + (stride >> 1)];
         if (ap) {  // error feedback: what is sparsified is grad + acc
-            const uint4 a = ap[uint64_t(i) * stride + (stride >> 1)];
-            q = make_uint4(sum_word<DTYPE>(q.x, a.x), sum_word<DTYPE>(q.y, a.y),
-                           sum_word<DTYPE>(q.z, a.z), sum_word<DTYPE>(q.w, a.w));
+            const uint32_t v = i * stride + (stride >> 1);
+            const uint4 a = ap[v];
+            const uint32_t sb = sent_bits<VEC>(sent, sd.c_off + v * VEC);
+            q = make_uint4(sum_word<DTYPE>(q.x, unsent_word<DTYPE>(a.x, sb, 0)),
+                           sum_word<DTYPE>(q.y, unsent_word<DTYPE>(a.y, sb, 1)),
+                           sum_word<DTYPE>(q.z, unsent_word<DTYPE>(a.z, sb, 2)),
+                           sum_word<DTYPE>(q.w, unsent_word<DTYPE>(a.w, sb, 3)));
         }
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
@@ -345,7 +411,8 @@ constexpr uint32_t kSpillList = 16;    // staged chunks per wave
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kSpillThreads)
-scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__restrict__ table,
+scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
+                  const uint32_t *__restrict__ table,
                   SelDev *sel, const uint32_t *__restrict__ binlo, uint32_t *__restrict__ hist,
                   uint32_t *__restrict__ cand, uint32_t *__restrict__ chunk_cnt,
                   uint64_t n_slots_total, uint32_t CAP)
@@ -484,7 +551,7 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__re
                     uint4 *q = reinterpret_cast<uint4 *>(abase + uint64_t(rel0) * EB) + lane;
 #pragma unroll
                     for (uint32_t r = 0; r < ROWS; ++r)
-                        q[64 * r] = make_uint4(w[r][0], w[r][1], w[r][2], w[r][3]);
+                        st_stream(q + 64 * r, make_uint4(w[r][0], w[r][1], w[r][2], w[r][3]));
                 } else {
 #pragma unroll
                     for (uint32_t r = 0; r < ROWS; ++r) {
@@ -505,17 +572,31 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__re
                     }
                 }
             };
-            uint32_t w[ROWS][4], aw[ROWS][4];
+            // which of the lane's accumulator entries of chunk `ch` the previous call sent
+            // (one byte or half a byte of the 1-bit Index per vector, one word or half a
+            // word of the 4-bit one); vectors past the segment's end have none
+            auto load_sent = [&](uint32_t ch, uint32_t (&sb)[ROWS]) {
+#pragma unroll
+                for (uint32_t r = 0; r < ROWS; ++r) {
+                    const uint32_t rel = ch * CHUNK + r * ROW_ELEMS + lane * VEC;
+                    sb[r] = rel < sd.n ? sent_bits<VEC>(sent, sd.c_off + rel) : 0u;
+                }
+            };
+            uint32_t w[ROWS][4], aw[ROWS][4], sb[ROWS];
             if (lo + wib < hi) {
                 load_chunk(base, lo + wib, w);
-                if (acc) load_chunk(abase, lo + wib, aw);
+                if (acc) {
+                    load_chunk(abase, lo + wib, aw);
+                    load_sent(lo + wib, sb);
+                }
             }
             for (uint32_t ch = lo + wib; ch < hi; ch += NW) {
                 if (acc) {  // error feedback: sparsify grad + acc, and keep the sums
 #pragma unroll
                     for (uint32_t r = 0; r < ROWS; ++r)
 #pragma unroll
-                        for (uint32_t j = 0; j < 4; ++j) w[r][j] = sum_word<DTYPE>(w[r][j], aw[r][j]);
+                        for (uint32_t j = 0; j < 4; ++j)
+                            w[r][j] = sum_word<DTYPE>(w[r][j], unsent_word<DTYPE>(aw[r][j], sb[r], j));
                     store_chunk(ch, w);
                 }
                 // Keep the chunk in LDS (a lane only ever reads back what it wrote itself).
@@ -546,7 +627,10 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const uint32_t *__re
                 }
                 if (ch + NW < hi) {  // in flight during the rest
                     load_chunk(base, ch + NW, w);
-                    if (acc) load_chunk(abase, ch + NW, aw);
+                    if (acc) {
+                        load_chunk(abase, ch + NW, aw);
+                        load_sent(ch + NW, sb);
+                    }
                 }
                 // slot of each lane's first candidate per row: one scan over the four
                 // row counts packed in 16-bit fields (a row holds at most 512 candidates)
@@ -1021,7 +1105,7 @@ constexpr uint32_t kEmitStage = 1280;  // survivors of an item that go through L
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
 template <int DTYPE>
-__device__ inline void emit_body(uint32_t bid, uint32_t nb, char *acc,
+__device__ inline void emit_body(uint32_t bid, uint32_t nb,
                                  const uint32_t *__restrict__ table,
                                  const SelDev *__restrict__ sel,
             const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
@@ -1060,13 +1144,12 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, char *acc,
         const uint32_t craw = chunk_cnt[g];
         // segment i's table rows in lane i
         uint32_t t_start = 0xFFFFFFFFu, t_n = 0, t_coff = 0, t_T = 0, t_quota = 0, t_cnt = 0,
-                 t_route = 0, t_olo = 0, t_ohi = 0;
+                 t_route = 0;
         if (L <= 64 && lane < L) {
             static_assert(sizeof(SegDev) == 32 && sizeof(SelDev) == 32, "two uint4 per row");
             const uint4 *s4 = reinterpret_cast<const uint4 *>(segs + lane);
             const uint4 *e4 = reinterpret_cast<const uint4 *>(sel + lane);
             const uint4 sa = s4[0], sb = s4[1], ea = e4[0], eb = e4[1];
-            t_olo = sa.x; t_ohi = sa.y;                                // offset
             t_n = sa.z; t_coff = sa.w; t_start = sb.w;                 // n, c_off, sc_start
             t_T = ea.x; t_quota = ea.y; t_cnt = ea.w; t_route = eb.w;  // T, quota, cnt, route
         }
@@ -1074,7 +1157,6 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, char *acc,
 
         // ---- segment, threshold, pair offset of the segment (all wave-uniform)
         uint32_t l, c_off, n_seg, sc_first, T, quota, seg_base, se_cnt, se_route;
-        uint64_t seg_off;
         if (L <= 64) {
             const uint64_t le = __ballot(t_start <= scc);  // a prefix of the lanes
             l = uint32_t(__popcll(le)) - 1u;               // segment 0 starts at 0
@@ -1085,14 +1167,12 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, char *acc,
             quota = __builtin_amdgcn_readlane(t_quota, l);
             se_cnt = __builtin_amdgcn_readlane(t_cnt, l);
             se_route = __builtin_amdgcn_readlane(t_route, l);
-            seg_off = uint64_t(__builtin_amdgcn_readlane(t_olo, l)) |
-                      (uint64_t(__builtin_amdgcn_readlane(t_ohi, l)) << 32);
             seg_base = wave_sum<uint32_t>(lane < l ? t_cnt : 0u);
         } else {
             l = segment_of(L, scc, [&](uint32_t i) { return segs[i].sc_start; });
             const SegDev sd = segs[l];
             const SelDev se = sel[l];
-            n_seg = sd.n; c_off = sd.c_off; sc_first = sd.sc_start; seg_off = sd.offset;
+            n_seg = sd.n; c_off = sd.c_off; sc_first = sd.sc_start;
             T = se.T; quota = se.quota; se_cnt = se.cnt; se_route = se.route;
             uint32_t sum = 0;
             for (uint32_t i = lane; i < l; i += 64) sum += sel[i].cnt;
@@ -1238,8 +1318,6 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, char *acc,
                         val_out[seg_base + pos] = __uint_as_float(vbits);
                     }
                     atomicOr(&bits[k][rel_sc >> 5], 1u << (rel_sc & 31));
-                    // error feedback: what is sent leaves the accumulator
-                    if (acc) store_elem(acc, seg_off + sc_rel0 + rel_sc, 0u, DTYPE);
                 }
             });
         }
@@ -1265,7 +1343,7 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb, char *acc,
 
 // Dense route, final pass over the gradient itself.
 template <int DTYPE>
-__device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad, char *acc,
+__device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad,
                                     const uint32_t *__restrict__ table,
                const SelDev *__restrict__ sel, uint64_t *tile_state,
                uint32_t *__restrict__ idx_out,
@@ -1434,14 +1512,6 @@ __device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad,
             keepm[r] = km;
             grun += Gr[r];
             erun += Er[r];
-            // error feedback (`grad` is then the accumulator itself, already holding
-            // grad + acc): what is sent leaves it
-            if (acc && km) {
-#pragma unroll
-                for (uint32_t e = 0; e < VEC; ++e)
-                    if ((km >> e) & 1u)
-                        store_elem(acc + sd.offset * EB, uint64_t(rel) + e, 0u, DTYPE);
-            }
         }
 #pragma unroll
         for (uint32_t r = 0; r < ROWS; ++r) {
@@ -1467,7 +1537,7 @@ static_assert(kEmitThreads == kCompactThreads, "one launch for both parts");
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kEmitThreads) __attribute__((amdgpu_waves_per_eu(6, 8)))
-finish_kernel(uint32_t n_emit, const char *grad, char *acc, const uint32_t *__restrict__ table,
+finish_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ table,
               const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
               const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
               uint64_t *sc_state, uint64_t *tile_state, uint32_t *__restrict__ idx_out,
@@ -1475,10 +1545,10 @@ finish_kernel(uint32_t n_emit, const char *grad, char *acc, const uint32_t *__re
               uint32_t *ticket)
 {
     if (blockIdx.x < n_emit)
-        emit_body<DTYPE>(blockIdx.x, n_emit, acc, table, sel, cand, chunk_cnt, n_slots_total,
+        emit_body<DTYPE>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
                          CAP, sc_state, idx_out, val_out, bitmap, cnt);
     else
-        compact_body<DTYPE>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, acc, table, sel,
+        compact_body<DTYPE>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, table, sel,
                             tile_state, idx_out, val_out, bitmap, cnt, ticket);
 }
 
@@ -1504,6 +1574,39 @@ int allow_lds(K kernel, size_t lds, bool *done)
         return TAGC_EHIP;
     *done = true;
     return TAGC_OK;
+}
+
+// Error feedback, on request: clears the entries of acc that the rank's Index names, after
+// which acc is acc_next of Algorithm 1 as a plain array (for inspection or a checkpoint;
+// the next PHASE_INDEX call does not need it and gives the same results either way).  One
+// thread per 32 parameters of the c-index space; ~1 % of the entries get a store.
+__global__ void __launch_bounds__(256)
+feedback_apply_kernel(const uint32_t *__restrict__ table, const SentMap sent, uint32_t n_words,
+                      char *acc, int dtype)
+{
+    const uint32_t w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= n_words) return;
+    uint32_t bits;
+    if (sent.wire4) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(sent.map + 4 * size_t(w));
+        bits = nibbles_set(q.x) | (nibbles_set(q.y) << 8) | (nibbles_set(q.z) << 16) |
+               (nibbles_set(q.w) << 24);
+    } else {
+        bits = sent.map[w];
+    }
+    if (!bits) return;
+    const uint32_t L = table[0];
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    // a word of the Index lies inside one segment (c-offsets are multiples of 32); of several
+    // segments starting at the same c-index only the last is not empty
+    const uint32_t l = segment_of(L, w * 32, [&](uint32_t i) { return segs[i].c_off; });
+    const SegDev sd = segs[l];
+    char *ab = acc + sd.offset * (dtype == kBF16 ? 2 : 4);
+    const uint32_t rel0 = w * 32 - sd.c_off;
+    for (; bits; bits &= bits - 1) {
+        const uint32_t rel = rel0 + __builtin_ctz(bits);
+        if (rel < sd.n) store_elem(ab, rel, 0u, dtype);
+    }
 }
 
 // 4-bit wire Index (section 2.2: the stable, four times bigger variant that an All-Reduce
@@ -1553,9 +1656,12 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     const bool wide = p->cfg.index_mode == TAGC_INDEX_ADD4;
     uint32_t *bitmap1 = wide ? reinterpret_cast<uint32_t *>(ws + p->ws.bitmap1) : rk->bitmap;
     // Error feedback: scan_spill (candidate route) and accumulate_kernel (all other segments)
-    // turn acc into grad + acc; whoever reads the input after them reads it from acc.
+    // turn acc into grad + acc; whoever reads the input after them reads it from acc.  Both
+    // read acc through the Index this rank's previous call left in rk->bitmap (what was
+    // sent reads as 0) before finish / widen4 overwrite that Index with the new one.
     char *acc = static_cast<char *>(rk->acc);
     const char *src = acc ? acc : g;
+    const SentMap sent{rk->bitmap, wide ? 1u : 0u};
     const int cus = device_cu_count();
     const size_t lds_hist = kBins1 * sizeof(uint32_t);
     static bool a_sample = false, a_hist = false;
@@ -1572,7 +1678,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         return TAGC_EHIP;
     if (acc && p->any_nonfast) {
         ProfileScope ps("accumulate", s);
-        accumulate_kernel<DTYPE><<<cus * 4, 256, 0, s>>>(g, table, acc);
+        accumulate_kernel<DTYPE><<<cus * 4, 256, 0, s>>>(g, table, acc, sent);
     }
     {
         ProfileScope ps("sample", s);  // + clears the per-call workspace
@@ -1580,13 +1686,13 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         const uint32_t fill_blocks = uint32_t(
             std::max<uint64_t>(1, std::min<uint64_t>((n16 + kHistThreads - 1) / kHistThreads, cus)));
         sample_kernel<DTYPE><<<L + fill_blocks, kHistThreads, lds_hist, s>>>(
-            g, acc, table, sel, binlo, hint, reinterpret_cast<uint4 *>(ws), n16, rk->cnt,
+            g, acc, sent, table, sel, binlo, hint, reinterpret_cast<uint4 *>(ws), n16, rk->cnt,
             TAGC_CNT_SEG0 + L);
     }
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
         scan_spill_kernel<DTYPE><<<cus * 2, kSpillThreads, 0, s>>>(
-            g, acc, table, sel, binlo, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
+            g, acc, sent, table, sel, binlo, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
     }
     {
         ProfileScope ps("select1", s);
@@ -1629,7 +1735,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
                             : std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
         uint32_t *ticket = p->static_dense ? nullptr : arrive + L;
         finish_kernel<DTYPE><<<n_emit + n_compact, kEmitThreads, 0, s>>>(
-            n_emit, src, acc, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state,
+            n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state,
             tile_state,
             rk->idx, rk->val, bitmap1, rk->cnt, ticket);
     }
@@ -1642,6 +1748,19 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
 }
 
 }  // namespace
+
+int launch_feedback_apply(const tagc_plan_t *p, const tagc_rank_buffers *rk,
+                          const tagc_shared_buffers *sh, hipStream_t s)
+{
+    const uint32_t n_words = uint32_t(p->n_c / 32);
+    if (!n_words) return TAGC_OK;
+    ProfileScope ps("feedback_apply", s);
+    const SentMap sent{rk->bitmap, p->cfg.index_mode == TAGC_INDEX_ADD4 ? 1u : 0u};
+    feedback_apply_kernel<<<(n_words + 255) / 256, 256, 0, s>>>(
+        static_cast<const uint32_t *>(sh->table), sent, n_words, static_cast<char *>(rk->acc),
+        p->cfg.dtype == TAGC_BF16 ? kBF16 : kF32);
+    return hip_ok(hipGetLastError());
+}
 
 int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buffers *rk,
                     const tagc_shared_buffers *sh, hipStream_t s)

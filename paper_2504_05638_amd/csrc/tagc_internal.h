@@ -148,6 +148,8 @@ int device_cu_count();
 
 int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buffers *rk,
                     const tagc_shared_buffers *sh, hipStream_t s);
+int launch_feedback_apply(const tagc_plan_t *p, const tagc_rank_buffers *rk,
+                          const tagc_shared_buffers *sh, hipStream_t s);
 int launch_encode(const tagc_plan_t *p, const tagc_rank_buffers *rk,
                   const tagc_shared_buffers *sh, hipStream_t s);
 int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32_t n_ranks,

@@ -39,14 +39,23 @@ def _step_grads(b, step, scale=1.0):
 
 
 @pytest.mark.parametrize("dtype", [G.F32, G.BF16])
-def test_error_feedback_chain_matches_oracle(dtype):
+@pytest.mark.parametrize("apply_every_step", [False, True])
+@pytest.mark.parametrize("index_mode", [O.INDEX_OR1, O.INDEX_ADD4])
+def test_error_feedback_chain_matches_oracle(dtype, apply_every_step, index_mode):
+    """The library leaves acc_next as (sums everywhere, the rank's Index naming what reads as
+    zero); tagc_feedback_apply turns it into the plain array, compared here with the oracle's
+    bit for bit -- after every step, or only after the last one, with the same pairs at every
+    step either way (the next step does not depend on it).  With 4-bit counters on the wire
+    the sent entries are read from the counters."""
     from paper_2504_05638_amd.bucket import TagcBucket
-    print("\n[case] error feedback chain dtype=%d" % dtype, flush=True)
+    print("\n[case] error feedback chain dtype=%d apply=%d index_mode=%d"
+          % (dtype, apply_every_step, index_mode), flush=True)
     b = _mixed_bucket(dtype, 2)
-    cfg = oracle_config(b, seed=3)
+    cfg = oracle_config(b, seed=3, index_mode=index_mode)
     segs = oracle_segments(b)
     tb = TagcBucket(b.segments, b.dtype, b.n_ranks, sizing_milli=b.sizing_milli, seed=3,
-                    dense=True, error_feedback=True)
+                    dense=True, error_feedback=True, index_mode=index_mode)
+    n_steps = 5
     raw0 = np.zeros(b.n_elems, np.uint16 if dtype == G.BF16 else np.float32)
     acc = [raw0.copy() for _ in range(b.n_ranks)]
     # steps 2 and 3 change scale by 100x and 1e-4x: carried pre-thresholds fail, segments are
@@ -66,12 +75,18 @@ def test_error_feedback_chain_matches_oracle(dtype):
             idx, val = tb.rank_pairs(r)
             assert np.array_equal(idx, states[r].idx), (step, r)
             assert np.array_equal(val.view(np.uint32), states[r].val.view(np.uint32)), (step, r)
-            assert np.array_equal(tb.rank_bitmap(r), states[r].bitmap[:tb.sizes.bitmap_words])
-            got = tb.rank_acc(r)[:b.n_elems]
-            want = acc[r].view(got.dtype)
-            assert np.array_equal(got, want), (step, r, int(np.argmax(got != want)))
+            local = states[r].bitmap[:tb.sizes.bitmap_words]
+            assert np.array_equal(tb.rank_bitmap(r), O.index_widen4(local)
+                                  if index_mode == O.INDEX_ADD4 else local)
+            if apply_every_step or step == n_steps - 1:
+                tb.feedback_apply(r)
+                tb.feedback_apply(r)            # idempotent
+                torch.cuda.synchronize()
+                got = tb.rank_acc(r)[:b.n_elems]
+                want = acc[r].view(got.dtype)
+                assert np.array_equal(got, want), (step, r, int(np.argmax(got != want)))
         # the rest of the path on the same survivors: merged Index, sketch, decode
-        bitmap, U = O.index_or([s.bitmap for s in states])
+        bitmap, U = O.merge_index([s.bitmap for s in states], index_mode)
         assert tb.header()["U"] == U
 
 
