@@ -452,6 +452,27 @@ void tagco_encode(const uint32_t *idx, const float *val, uint64_t cnt,
     }
 }
 
+/*
+ * Quantised communication of the sketch (section 5: the inherited
+ * implementation is float32-only; combining the compression with
+ * quantisation of what is communicated, e.g. to bfloat16, is named as the
+ * next step).  This repository's reading: a rank builds its Count Sketch in
+ * float32 exactly as before and rounds every cell to the nearest bfloat16,
+ * ties to even, when it puts the sketch on the wire (16 bits per cell); the
+ * Reduce widens the cells back and adds them in float32 in rank order, and
+ * decoding is unchanged.  The cells are rounded in place and stay float32
+ * values (low 16 bits zero).  Non-finite cells are not expected.
+ */
+void tagco_quantize_cells_bf16(float *sketch, uint64_t m)
+{
+    for (uint64_t c = 0; c < m; ++c) {
+        uint32_t b;
+        memcpy(&b, &sketch[c], 4);
+        b = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
+        memcpy(&sketch[c], &b, 4);
+    }
+}
+
 /* Reduce(local_count_sketch, d): element-wise float32 sum in rank order,
  * ((C_0 + C_1) + C_2) + ...  (Algorithm 1; section 3.1). */
 void tagco_sum(const float *const *sketches, uint32_t n_ranks, uint64_t m,

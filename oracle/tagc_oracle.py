@@ -85,6 +85,8 @@ def lib():
         L.tagco_encode.restype = None
         L.tagco_encode.argtypes = [u32p, f32p, C.c_uint64, u32p, C.c_uint64,
                                    C.c_uint64, C.c_uint64, C.c_int, u32p, f32p]
+        L.tagco_quantize_cells_bf16.restype = None
+        L.tagco_quantize_cells_bf16.argtypes = [f32p, C.c_uint64]
         L.tagco_index_add.restype = C.c_uint64
         L.tagco_index_add.argtypes = [C.POINTER(u32p), C.c_uint32, C.c_uint64, C.c_uint32,
                                       u32p]
@@ -135,6 +137,7 @@ class Config:
     part_unknowns: int = 8192    # P_cap
     part_cells: int = 12288      # T_cap (multiple of 3)
     index_mode: int = 0          # INDEX_OR1 | INDEX_ADD1 | INDEX_ADD4
+    cell_type: int = 0           # CELL_F32 | CELL_BF16: what a sketch cell is on the wire
 
 
 def c_offsets(segments):
@@ -305,6 +308,18 @@ def encode(idx, val, bnd, A, m_sub, seed, plus_only=False, mask=None):
     return sk[:m]
 
 
+CELL_F32, CELL_BF16 = 0, 1
+
+
+def quantize_cells_bf16(sketch):
+    """A rank's sketch as it goes on the wire with 16-bit cells: every cell rounded to the
+    nearest bfloat16, ties to even (returned as float32 values)."""
+    out = np.array(sketch, np.float32, copy=True)
+    if out.size:
+        lib().tagco_quantize_cells_bf16(_f32p(out), out.size)
+    return out
+
+
 def sketch_sum(sketches):
     n = len(sketches)
     m = sketches[0].size
@@ -404,6 +419,8 @@ def run_bucket(grads, cfg: Config, segments, plus_only=False,
     mask = None if cfg.index_mode == INDEX_OR1 else bitmap
     for r in ranks:
         r.sketch = encode(r.idx, r.val, bnd, A, m_sub, cfg.seed, plus_only, mask)
+        if cfg.cell_type == CELL_BF16:
+            r.sketch = quantize_cells_bf16(r.sketch)
     total = sketch_sum([r.sketch for r in ranks])
     if decode_mode == DECODE_PEEL:
         dec = peel(bitmap, n_c, U, A, m_sub, cfg.seed, total, plus_only)
