@@ -74,6 +74,9 @@ def parse_args():
     ap.add_argument("--keep-ppm", type=int, default=0,
                     help="survivors per million for every compressed segment (Table 1: "
                          "(1 - theta) * 10^6); 0 = the workload's dynamic ratios")
+    ap.add_argument("--cell-bits", type=int, default=32, choices=[32, 16],
+                    help="a rank's sketch cells on the wire: float32, or rounded to bfloat16 "
+                         "(section 5: quantised communication)")
     ap.add_argument("--decode-mode", type=int, default=0, choices=[0, 1, 2],
                     help="0 peeling only (the headline), 1 peeling + estimation of what it "
                          "leaves, 2 estimation only (section 2.2's two decompression algorithms)")
@@ -114,7 +117,7 @@ def make_buckets(args):
     return bs
 
 
-def alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1):
+def alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1, cell=4):
     """Algorithmic bytes per stage for one bucket: one read of the gradient (with error
     feedback also one read and one write of the accumulator), every message
     materialised once; work-lists, histograms and degree tables are not credited."""
@@ -124,13 +127,13 @@ def alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1):
     return {
         "S1+S2 sparsify+index": passes * N * z.n_real * e + 8 * k_total + wire * N * n_c // 8,
         "S3a index OR": wire * N * n_c // 8 + n_c // 8,
-        "S2' encode": 8 * k_total + N * 4 * m,
-        "S3b sketch sum": (N + 1) * 4 * m,
+        "S2' encode": 8 * k_total + N * cell * m,
+        "S3b sketch sum": (N * cell + 4) * m,
         "S4 decode": n_c // 8 + 4 * m + 8 * U + (4 * n_c if dense else 0),
     }
 
 
-def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1):
+def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1, cell=4):
     """Bytes each bandwidth-relevant kernel must itself move per bucket (all its
     launches together).  hist1 and compact each read the gradient once, so their sum
     exceeds the stage's algorithmic bytes: the stage figure shows the cost of the
@@ -146,8 +149,8 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1):
         "finish": 8 * k_total + N * n_c // 8,
         "index_or": (wire * N + 1) * n_c // 8,
         "widen4": (1 + 4) * N * n_c // 8,
-        "encode": 8 * k_total + N * 4 * m,
-        "sketch_sum": (N + 1) * 4 * m,
+        "encode": 8 * k_total + N * cell * m,
+        "sketch_sum": (N * cell + 4) * m,
         "enumerate": n_c // 8 + 4 * U,
         "peel": 4 * m + 8 * U,
         "dense": n_c // 8 + 4 * U + 4 * n_c,
@@ -231,7 +234,8 @@ def main():
         cfg = B.tagc_config(dtype=b.dtype, n_ranks=N, n_hash=3, sizing=sizing,
                             sizing_milli=b.sizing_milli, index_mode=args.index_mode,
                             part_unknowns=args.part_unknowns, part_cells=args.part_cells,
-                            seed=args.seed, decode_mode=args.decode_mode)
+                            seed=args.seed, decode_mode=args.decode_mode,
+                            cell_type=int(args.cell_bits == 16))
         plan = B.tagc_plan(cfg, [tuple(s[:4]) for s in b.segments])
         z = B.tagc_plan_sizes(plan)
         for k, f in fields.items():
@@ -246,7 +250,7 @@ def main():
                               part_unknowns=args.part_unknowns, part_cells=args.part_cells,
                               error_feedback=args.error_feedback,
                               decode_mode=args.decode_mode, index_mode=args.index_mode,
-                              sizing=sizing,
+                              sizing=sizing, cell_type=int(args.cell_bits == 16),
                               share=None if first else tbs[i % lanes],
                               min_bytes=need if first else None))
     stream = torch.cuda.current_stream()
@@ -273,6 +277,7 @@ def main():
     kalg = {}
     unresolved = estimated = rounds = 0
     wire = 4 if args.index_mode == B.TAGC_INDEX_ADD4 else 1
+    cell = args.cell_bits // 8
     U_tot = m_tot = k_tot = 0
     flags = 0
     facts = []
@@ -285,9 +290,9 @@ def main():
         flags |= st["flags"]
         for r in range(N):
             flags |= tbs[i].rank_counts(r)["flags"]
-        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire).items():
+        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire, cell).items():
             balg[k] += v
-        for k, v in kernel_alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire).items():
+        for k, v in kernel_alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire, cell).items():
             kalg[k] = kalg.get(k, 0) + v
         input_bytes += N * tbs[i].sizes.n_real * buckets[i].elem_bytes
         unresolved += st["n_unresolved"]
@@ -384,7 +389,7 @@ def main():
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,
-                   "index_mode": args.index_mode,
+                   "index_mode": args.index_mode, "cell_bits": args.cell_bits,
                    "peel_rounds_max": rounds, "input_generation_s": round(t_gen, 2)},
         "hbm_frac_end_to_end": round(balg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "alg_bytes_per_step": balg_total,

@@ -86,8 +86,22 @@ typedef struct tagc_config {
                                0 = default                                      */
     uint64_t seed;          /* hash seed; all ranks must use the same           */
     uint32_t decode_mode;   /* TAGC_DECODE_*; 0 = peeling only                  */
-    uint32_t reserved;      /* must be 0                                        */
+    uint32_t cell_type;     /* TAGC_CELL_*: what a cell of a rank's sketch is on
+                               the wire; 0 = float32                            */
 } tagc_config;
+
+/*
+ * Section 5 names quantised communication as the step beyond the float32-only
+ * implementation.  TAGC_CELL_BF16: a rank builds its Count Sketch in float32
+ * as always and rounds each cell to the nearest bfloat16 (ties to even) when
+ * it writes rank->sketch, which then holds 16-bit cells; PHASE_SKETCH of
+ * tagc_aggregate widens them and adds in float32 in rank order; the summed
+ * sketch and everything after it stay float32.  Halves the sketch's volume;
+ * decoded values carry the rounding noise of the cells they passed through
+ * (lossless only when the cells are bfloat16 numbers anyway).
+ */
+#define TAGC_CELL_F32 0u
+#define TAGC_CELL_BF16 1u
 
 /*
  * Index modes (section 2.2).  The paper's implementation cannot OR over NCCL
@@ -191,7 +205,9 @@ typedef struct tagc_rank_buffers {
                            wire: bit j in word j>>5, bit j&31 (bitmap_words
                            words), or 4-bit counters with TAGC_INDEX_ADD4       */
     float *sketch;      /* [sketch_cells_capacity] local Count Sketch; cells
-                           [0, m) are written, the rest untouched              */
+                           [0, m) are written, the rest untouched.  16-bit
+                           cells (rank_sketch_bytes covers either) with
+                           TAGC_CELL_BF16                                      */
     void *workspace;    /* [rank_workspace_bytes] scratch, may be shared by ranks
                            processed one after another on one stream           */
     void *acc;          /* NULL, or [grad_elems] of the plan's dtype: the rank's

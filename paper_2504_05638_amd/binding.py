@@ -23,6 +23,7 @@ TAGC_HDR_U, TAGC_HDR_A, TAGC_HDR_MSUB, TAGC_HDR_M, TAGC_HDR_WORDS = 0, 1, 2, 3, 
 TAGC_ST_UNRESOLVED, TAGC_ST_ROUNDS, TAGC_ST_FLAGS, TAGC_ST_WORDS = 0, 1, 2, 8
 TAGC_ST_ESTIMATED = 3
 TAGC_DECODE_PEEL, TAGC_DECODE_PEEL_ESTIMATE, TAGC_DECODE_ESTIMATE = 0, 1, 2
+TAGC_CELL_F32, TAGC_CELL_BF16 = 0, 1
 TAGC_FLAG_SPIN_LIMIT, TAGC_FLAG_OVERFLOW = 1, 2
 
 EXPORTS = ["tagc_plan", "tagc_plan_destroy", "tagc_plan_sizes",
@@ -42,7 +43,7 @@ class tagc_config(C.Structure):
                 ("sizing_milli", C.c_uint32), ("index_mode", C.c_uint32),
                 ("part_unknowns", C.c_uint32), ("part_cells", C.c_uint32),
                 ("seed", C.c_uint64), ("decode_mode", C.c_uint32),
-                ("reserved", C.c_uint32)]
+                ("cell_type", C.c_uint32)]
 
 
 _SIZE_FIELDS = [

@@ -29,7 +29,7 @@ class TagcBucket:
                  sizing=B.TAGC_SIZE_LOAD_FACTOR, seed=0, part_unknowns=0,
                  part_cells=0, device="cuda", dense=False, share=None, min_bytes=None,
                  error_feedback=False, decode_mode=B.TAGC_DECODE_PEEL,
-                 index_mode=B.TAGC_INDEX_OR1):
+                 index_mode=B.TAGC_INDEX_OR1, cell_type=B.TAGC_CELL_F32):
         if not torch.cuda.is_available():
             raise RuntimeError("libtagc needs a GPU: no CPU path exists")
         self.device = torch.device(device)
@@ -38,7 +38,7 @@ class TagcBucket:
                                  index_mode=index_mode,
                                  part_unknowns=part_unknowns,
                                  part_cells=part_cells, seed=seed,
-                                 decode_mode=decode_mode)
+                                 decode_mode=decode_mode, cell_type=cell_type)
         self.segments = [tuple(s[:4]) for s in segments]
         self.plan = B.tagc_plan(self.cfg, self.segments)
         self.sizes = B.tagc_plan_sizes(self.plan)
@@ -206,7 +206,12 @@ class TagcBucket:
                         wire * self.sizes.bitmap_words)
 
     def rank_sketch(self, r):
-        return self._np(self._rk_tensors[r]["sketch"], np.float32, self.header()["m"])
+        """The rank's sketch as float32 values (16-bit wire cells widened)."""
+        m = self.header()["m"]
+        if self.cfg.cell_type == B.TAGC_CELL_BF16:
+            half = self._np(self._rk_tensors[r]["sketch"], np.uint16, m)
+            return (half.astype(np.uint32) << 16).view(np.float32)
+        return self._np(self._rk_tensors[r]["sketch"], np.float32, m)
 
     def shared_bitmap(self):
         return self._np(self.sh_bitmap, np.uint32, self.sizes.bitmap_words)

@@ -132,6 +132,14 @@ __device__ inline void st_stream(float4 *p, float4 v)
     __builtin_nontemporal_store(x, reinterpret_cast<f32x4_t *>(p));
 }
 
+// float32 -> bfloat16 bits, round to nearest, ties to even; a NaN keeps a mantissa bit
+__device__ inline uint32_t round_to_bf16(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    if ((b & 0x7F800000u) == 0x7F800000u && (b & 0x007FFFFFu)) return (b >> 16) | 0x0040u;
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
 __device__ inline uint64_t ld_agent(const uint64_t *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

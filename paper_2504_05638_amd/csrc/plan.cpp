@@ -29,7 +29,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     if (cfg->sizing != TAGC_SIZE_LOAD_FACTOR && cfg->sizing != TAGC_SIZE_FIXED_RATIO)
         return TAGC_EINVAL;
     if (cfg->index_mode > TAGC_INDEX_ADD4) return TAGC_EUNSUPPORTED;
-    if (cfg->decode_mode > TAGC_DECODE_ESTIMATE || cfg->reserved) return TAGC_EINVAL;
+    if (cfg->decode_mode > TAGC_DECODE_ESTIMATE || cfg->cell_type > TAGC_CELL_BF16)
+        return TAGC_EINVAL;
     uint32_t P_cap = cfg->part_unknowns ? cfg->part_unknowns : kDefaultPartUnknowns;
     uint32_t T_cap = cfg->part_cells ? cfg->part_cells : kDefaultPartCells;
     if (P_cap > kMaxPartUnknowns || T_cap > kMaxPartCells || T_cap < 3 || T_cap % 3 ||
@@ -177,10 +178,11 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     z.rank_cnt_bytes = round_up(4 * (p->cnt_ranges + p->A_cap + 2), 16);
     const uint64_t wire = cfg->index_mode == TAGC_INDEX_ADD4 ? 4 : 1;  // bits per parameter
     z.rank_bitmap_bytes = round_up(4 * wire * std::max<uint64_t>(words, 1), 16);
-    z.rank_sketch_bytes = round_up(4 * p->m_cap, 16);
+    const uint64_t cell_bytes = cfg->cell_type == TAGC_CELL_BF16 ? 2 : 4;  // on the wire
+    z.rank_sketch_bytes = round_up(cell_bytes * p->m_cap, 16);
     z.rank_workspace_bytes = w.total;
     z.shared_bitmap_bytes = round_up(4 * std::max<uint64_t>(words, 1), 16);
-    z.shared_sketch_bytes = z.rank_sketch_bytes;
+    z.shared_sketch_bytes = round_up(4 * p->m_cap, 16);
     z.shared_header_bytes = 4 * TAGC_HDR_WORDS;
     z.shared_bounds_bytes = round_up(4 * (p->A_cap + 1), 16);
     // chunk prefixes; behind them, when the 4-bit Index of more ranks than one pass takes is
@@ -195,7 +197,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     if (n_real) {
         z.wire_index_bits = 2.0 * double(wire) * double(p->n_c) / double(n_real);
         double cells = cfg->sizing == TAGC_SIZE_LOAD_FACTOR ? double(p->m_cap) : double(M_max);
-        z.wire_sketch_bits = 32.0 * cells / double(n_real);
+        z.wire_sketch_bits = 8.0 * double(cell_bytes) * cells / double(n_real);
         z.wire_total_bits = z.wire_index_bits + z.wire_sketch_bits;
     }
     *out = p;

@@ -19,7 +19,8 @@ __global__ void __launch_bounds__(256)
 encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
               const uint32_t *__restrict__ cnt, const uint32_t *__restrict__ header,
               float *__restrict__ sketch, uint32_t sw0, uint32_t sw1, uint32_t sw2,
-              uint32_t ranges_off, uint32_t pair_cap, const uint32_t *__restrict__ mask)
+              uint32_t ranges_off, uint32_t pair_cap, const uint32_t *__restrict__ mask,
+              uint32_t cells16)
 {
     extern __shared__ float tile[];
     const uint32_t A = header[TAGC_HDR_A], m_sub = header[TAGC_HDR_MSUB];
@@ -62,8 +63,27 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
         lds_add_f32(&tile[slot], neg ? -v : v);
     }
     __syncthreads();
-    // the tile leaves in 16-byte stores where the sketch is aligned for them
     const uint64_t b0 = (uint64_t(a) * 3 + j) * m_sub;
+    if (cells16) {
+        // 16-bit cells on the wire: each cell rounded to the nearest bfloat16, ties to even;
+        // eight to a 16-byte store where the sketch is aligned for them
+        uint16_t *out = reinterpret_cast<uint16_t *>(sketch) + b0;
+        const uint32_t head = min(m_sub, uint32_t((8u - uint32_t(b0 & 7u)) & 7u));
+        const uint32_t n8 = (m_sub - head) / 8;
+        if (threadIdx.x < head) out[threadIdx.x] = uint16_t(round_to_bf16(tile[threadIdx.x]));
+        for (uint32_t v = threadIdx.x; v < n8; v += 256) {
+            const float *t = tile + head + 8 * v;
+            st_stream(reinterpret_cast<uint4 *>(out + head + 8 * v),
+                      make_uint4(round_to_bf16(t[0]) | (round_to_bf16(t[1]) << 16),
+                                 round_to_bf16(t[2]) | (round_to_bf16(t[3]) << 16),
+                                 round_to_bf16(t[4]) | (round_to_bf16(t[5]) << 16),
+                                 round_to_bf16(t[6]) | (round_to_bf16(t[7]) << 16)));
+        }
+        for (uint32_t c = head + 8 * n8 + threadIdx.x; c < m_sub; c += 256)
+            out[c] = uint16_t(round_to_bf16(tile[c]));
+        return;
+    }
+    // the tile leaves in 16-byte stores where the sketch is aligned for them
     float *out = sketch + b0;
     const uint32_t head = min(m_sub, uint32_t((4u - uint32_t(b0 & 3u)) & 3u));
     const uint32_t n4 = (m_sub - head) / 4;
@@ -126,6 +146,58 @@ sketch_sum_kernel(RankPtrs rp, uint32_t n_in, float *__restrict__ out,
     }
 }
 
+// The same sum over ranks whose cells are bfloat16 on the wire: eight cells (one 16-byte
+// load) per rank and thread, widened and added in float32 in rank order.
+__global__ void __launch_bounds__(256)
+sketch_sum16_kernel(RankPtrs rp, uint32_t n_in, float *__restrict__ out,
+                    const uint32_t *__restrict__ header, int accumulate)
+{
+    const uint32_t m = header[TAGC_HDR_M];
+    const uint32_t m8 = m / 8;
+    const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+    if (c < m8) {
+        float acc[8];
+        if (accumulate) {
+            const float4 a = reinterpret_cast<const float4 *>(out)[2 * c];
+            const float4 b = reinterpret_cast<const float4 *>(out)[2 * c + 1];
+            acc[0] = a.x; acc[1] = a.y; acc[2] = a.z; acc[3] = a.w;
+            acc[4] = b.x; acc[5] = b.y; acc[6] = b.z; acc[7] = b.w;
+        }
+        for (uint32_t r0 = 0; r0 < n_in; r0 += kSumBatch) {
+            uint4 v[kSumBatch];
+#pragma unroll
+            for (uint32_t i = 0; i < kSumBatch; ++i)
+                if (r0 + i < n_in) v[i] = ld_stream(static_cast<const uint4 *>(rp.p[r0 + i]) + c);
+#pragma unroll
+            for (uint32_t i = 0; i < kSumBatch; ++i) {
+                if (r0 + i >= n_in) continue;
+                const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+                const bool first = r0 + i == 0 && !accumulate;
+#pragma unroll
+                for (uint32_t e = 0; e < 8; ++e) {
+                    const float x = __uint_as_float(e & 1u ? w[e >> 1] & 0xFFFF0000u : w[e >> 1] << 16);
+                    acc[e] = first ? x : acc[e] + x;
+                }
+            }
+        }
+        st_stream(reinterpret_cast<float4 *>(out) + 2 * c, make_float4(acc[0], acc[1], acc[2], acc[3]));
+        st_stream(reinterpret_cast<float4 *>(out) + 2 * c + 1,
+                  make_float4(acc[4], acc[5], acc[6], acc[7]));
+    }
+    if (blockIdx.x == 0) {
+        const uint32_t t = m8 * 8 + threadIdx.x;
+        if (t < m) {
+            float acc = accumulate ? out[t] : 0.0f;
+            for (uint32_t r = 0; r < n_in; ++r) {
+                const float x =
+                    __uint_as_float(uint32_t(static_cast<const uint16_t *>(rp.p[r])[t]) << 16);
+                acc = (r == 0 && !accumulate) ? x : acc + x;
+            }
+            out[t] = acc;
+        }
+    }
+}
+
 }  // namespace
 
 int launch_encode(const tagc_plan_t *p, const tagc_rank_buffers *rk, const tagc_shared_buffers *sh,
@@ -137,7 +209,8 @@ int launch_encode(const tagc_plan_t *p, const tagc_rank_buffers *rk, const tagc_
     encode_kernel<<<grid, 256, lds, s>>>(rk->idx, rk->val, rk->cnt, sh->header, rk->sketch,
                                          p->seed_word[0], p->seed_word[1], p->seed_word[2],
                                          p->cnt_ranges, uint32_t(p->K),
-                                         p->cfg.index_mode == TAGC_INDEX_OR1 ? nullptr : sh->bitmap);
+                                         p->cfg.index_mode == TAGC_INDEX_OR1 ? nullptr : sh->bitmap,
+                                         p->cfg.cell_type == TAGC_CELL_BF16);
     return hip_ok(hipGetLastError());
 }
 
@@ -151,7 +224,11 @@ int launch_sketch_sum(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint
         RankPtrs rp{};
         const uint32_t n_in = std::min(kMaxRanksPerPass, n_ranks - r0);
         for (uint32_t r = 0; r < n_in; ++r) rp.p[r] = ranks[r0 + r].sketch;
-        sketch_sum_kernel<<<grid, 256, 0, s>>>(rp, n_in, sh->sketch, sh->header, r0 != 0);
+        if (p->cfg.cell_type == TAGC_CELL_BF16)
+            sketch_sum16_kernel<<<(grid + 1) / 2, 256, 0, s>>>(rp, n_in, sh->sketch, sh->header,
+                                                                r0 != 0);
+        else
+            sketch_sum_kernel<<<grid, 256, 0, s>>>(rp, n_in, sh->sketch, sh->header, r0 != 0);
     }
     return hip_ok(hipGetLastError());
 }

@@ -71,12 +71,6 @@ __device__ inline uint32_t vec_elem_bits(const uint32_t (&w)[4], uint32_t e)
 // g + acc in the gradient's own type (Algorithm 1, line 1; section 3.2, local gradient
 // accumulation): one float32 add per entry; a bf16 result is rounded to nearest-even (a NaN
 // keeps a mantissa bit).  `g`, `a`: one 32-bit word of each buffer (two bf16 entries).
-__device__ inline uint32_t round_to_bf16(float x)
-{
-    const uint32_t b = __float_as_uint(x);
-    if ((b & 0x7F800000u) == 0x7F800000u && (b & 0x007FFFFFu)) return (b >> 16) | 0x0040u;
-    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
-}
 template <int DTYPE>
 __device__ inline uint32_t sum_word(uint32_t g, uint32_t a)
 {

@@ -12,9 +12,11 @@ def oracle_segments(bucket):
     return [O.Segment(s.offset, s.length, s.keep_ppm, s.flags) for s in bucket.segments]
 
 
-def oracle_config(bucket, sizing=O.SIZE_LOAD_FACTOR, seed=0, P=8192, T=12288, index_mode=0):
+def oracle_config(bucket, sizing=O.SIZE_LOAD_FACTOR, seed=0, P=8192, T=12288, index_mode=0,
+                  cell_type=0):
     return O.Config(dtype=bucket.dtype, sizing=sizing, sizing_milli=bucket.sizing_milli,
-                    seed=seed, part_unknowns=P, part_cells=T, index_mode=index_mode)
+                    seed=seed, part_unknowns=P, part_cells=T, index_mode=index_mode,
+                    cell_type=cell_type)
 
 
 def segment_of(c_index, bucket):
@@ -67,18 +69,18 @@ def estimate_tolerance(ores, seed, rel=1e-5):
 
 
 def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTOR, dense=True,
-             decode_mode=0, index_mode=0):
+             decode_mode=0, index_mode=0, cell_type=0):
     """Runs oracle and library on the same inputs; returns (oracle result, TagcBucket)."""
     import torch
     from paper_2504_05638_amd.bucket import TagcBucket
 
-    ocfg = oracle_config(bucket, sizing, seed, P or 8192, T or 12288, index_mode)
+    ocfg = oracle_config(bucket, sizing, seed, P or 8192, T or 12288, index_mode, cell_type)
     ores = O.run_bucket([G.to_numpy_raw(g) for g in grads_torch_cpu], ocfg,
                         oracle_segments(bucket), decode_mode=decode_mode)
     tb = TagcBucket(bucket.segments, bucket.dtype, len(grads_torch_cpu),
                     sizing_milli=bucket.sizing_milli, sizing=sizing, seed=seed,
                     part_unknowns=P, part_cells=T, dense=dense, decode_mode=decode_mode,
-                    index_mode=index_mode)
+                    index_mode=index_mode, cell_type=cell_type)
     dev = [g.cuda() for g in grads_torch_cpu]
     tb.run(dev)
     torch.cuda.synchronize()
@@ -117,6 +119,13 @@ def compare_all(bucket, ores, tb, exact_values=False, rel=1e-5):
         got, want = tb.rank_sketch(r), ores.ranks[r].sketch
         if exact_values:
             assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        elif tb.cfg.cell_type:
+            # 16-bit wire cells: the float32 cell behind it may differ in its last bits with
+            # the order of the adds, which now and then tips the rounding to the neighbouring
+            # bfloat16 (one unit in the 8th significant bit)
+            d = np.abs(got.astype(np.float64) - want)
+            assert np.all(d <= 2.0 ** -7 * np.abs(want) + 1e-37)
+            assert got.size == 0 or np.mean(got.view(np.uint32) == want.view(np.uint32)) > 0.995
         else:
             mag = O.encode(ores.ranks[r].idx, np.abs(ores.ranks[r].val), ores.bnd, ores.A,
                            ores.m_sub, tb.cfg.seed, plus_only=True,
@@ -142,6 +151,13 @@ def compare_all(bucket, ores, tb, exact_values=False, rel=1e-5):
         assert np.array_equal(val, ores.decoded.val)
     else:
         tol = value_tolerance(ores, rel)
+        if tb.cfg.cell_type:
+            # a wire cell that rounded the other way moves what was decoded through it by one
+            # bfloat16 unit of the cell; rare (checked above), but it has to be allowed for
+            loose = value_tolerance(ores, 2.0 ** -6)
+            err_q = np.abs(val.astype(np.float64) - ores.decoded.val.astype(np.float64))
+            assert np.all(err_q <= loose) and np.mean(err_q <= tol) > 0.97
+            tol = loose
         if mode and unresolved.any():
             tol[unresolved] = estimate_tolerance(ores, tb.cfg.seed, rel)[unresolved]
         err = np.abs(val.astype(np.float64) - ores.decoded.val.astype(np.float64))
