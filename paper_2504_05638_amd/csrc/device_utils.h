@@ -132,6 +132,17 @@ __device__ inline void st_stream(float4 *p, float4 v)
     __builtin_nontemporal_store(x, reinterpret_cast<f32x4_t *>(p));
 }
 
+// bit p of the result = nibble p of x is not 0 (4-bit Index counters -> Index bits)
+__device__ inline uint32_t nibbles_set(uint32_t x)
+{
+    x |= x >> 2;
+    x |= x >> 1;
+    x &= 0x11111111u;  // bit 4p = nibble p != 0
+    x = (x | (x >> 3)) & 0x03030303u;
+    x = (x | (x >> 6)) & 0x000F000Fu;
+    return (x | (x >> 12)) & 0xFFu;
+}
+
 // float32 -> bfloat16 bits, round to nearest, ties to even; a NaN keeps a mantissa bit
 __device__ inline uint32_t round_to_bf16(float x)
 {

@@ -17,16 +17,6 @@ namespace {
 // being set where the summed counter is not 0.  Sums wrap as unsigned 32-bit adds do.  With
 // more ranks than one launch takes, the running result is carried in `out` (OR, 1-bit add)
 // or, for the counters, in `sum4`.
-__device__ __forceinline__ uint32_t nonzero_nibbles(uint32_t x)  // bit p = nibble p != 0
-{
-    x |= x >> 2;
-    x |= x >> 1;
-    x &= 0x11111111u;             // bit 4p = nibble p != 0
-    x = (x | (x >> 3)) & 0x03030303u;
-    x = (x | (x >> 6)) & 0x000F000Fu;
-    return (x | (x >> 12)) & 0xFFu;
-}
-
 template <int MODE>
 __global__ void __launch_bounds__(256)
 index_merge_kernel(RankPtrs rp, uint32_t n_in, uint32_t *__restrict__ out, uint32_t n_words,
@@ -55,8 +45,8 @@ index_merge_kernel(RankPtrs rp, uint32_t n_in, uint32_t *__restrict__ out, uint3
             if (!last) {
                 *reinterpret_cast<uint4 *>(sum4 + q) = acc;
             } else {
-                const uint32_t m = nonzero_nibbles(acc.x) | (nonzero_nibbles(acc.y) << 8) |
-                                   (nonzero_nibbles(acc.z) << 16) | (nonzero_nibbles(acc.w) << 24);
+                const uint32_t m = nibbles_set(acc.x) | (nibbles_set(acc.y) << 8) |
+                                   (nibbles_set(acc.z) << 16) | (nibbles_set(acc.w) << 24);
                 out[w] = m;
                 pc += __popc(m);
             }

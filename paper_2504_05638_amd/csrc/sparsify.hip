@@ -27,11 +27,18 @@
 //    finish       (first part) ordered pass over the candidates only: pairs + every Index
 //                 word
 //
-//  dense route (segments that are short, unaligned, or re-routed; two reads)
+//  dense route (segments that are short, unaligned, keep more than ~3 %, or were re-routed;
+//  two reads)
 //    hist1        exact histogram of the top 15 key bits of every entry, in LDS; the
 //                 workgroup that completes a segment's histogram selects its threshold
 //    hist2/select2 fp32 only, as above
 //    finish       (second part) ordered pass over the gradient: pairs + Index words
+//
+// With a gradient accumulator (error feedback: Algorithm 1, lines 1-2) what is sparsified is
+// grad + acc: scan_spill, and accumulate for the segments it does not read, write the sums
+// back to acc, from which the dense route then reads; which of them were sent is recorded
+// by the rank's own Index and applied when acc is read next (see SentMap).  With 4-bit
+// counters on the wire (section 2.2) widen4 turns the Index into them at the end.
 //
 // Ordered output across workgroups: every item publishes its counts as soon as it has
 // them and learns its offset from the counts of earlier items only, which belong to
@@ -103,16 +110,6 @@ struct SentMap {
     const uint32_t *map;  // the rank's Index buffer as the previous call left it
     uint32_t wire4;       // 4-bit counters instead of bits
 };
-
-__device__ inline uint32_t nibbles_set(uint32_t x)  // bit p = nibble p of x != 0
-{
-    x |= x >> 2;
-    x |= x >> 1;
-    x &= 0x11111111u;
-    x = (x | (x >> 3)) & 0x03030303u;
-    x = (x | (x >> 6)) & 0x000F000Fu;
-    return (x | (x >> 12)) & 0xFFu;
-}
 
 // bit e <=> parameter ci + e was sent, for the VEC parameters of one 16-byte vector
 // (ci a multiple of VEC, VEC = 4 or 8)
