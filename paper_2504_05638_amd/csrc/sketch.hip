@@ -1,12 +1,12 @@
 // Count Sketch encode and aggregation.
 //
 // encode: local_count_sketch <- compress(g_shard, index) of Algorithm 1.  The merged Index
-//   enters through the layout (and, when it was merged by addition, as a mask): partition a owns the pairs whose c-index lies in
-//   [bounds[a], bounds[a+1]) -- a contiguous run of the rank's sorted pair list, whose ends
-//   the Index aggregation leaves in the rank's cnt buffer -- and the
-//   3*m_sub cells starting at a*3*m_sub.  One workgroup builds one sub-table (partition a,
-//   hash function j) in LDS and writes it out once, so the sketch is produced with
-//   coalesced stores and no global atomics.
+//   enters through the layout (and, when it was merged by addition, as a mask): partition a
+//   owns the pairs whose c-index lies in [bounds[a], bounds[a+1]) -- a contiguous run of the
+//   rank's sorted pair list, whose ends the Index aggregation leaves in the rank's cnt
+//   buffer -- and the 3*m_sub cells starting at a*3*m_sub.  One workgroup builds the
+//   partition's three sub-tables in LDS, reading the pairs once, and writes them out as one
+//   contiguous run, so the sketch is produced with coalesced stores and no global atomics.
 // sum: Reduce(local_count_sketch, d) as an element-wise float32 sum in rank order.
 #include "device_utils.h"
 #include "tagc_internal.h"
@@ -15,63 +15,68 @@ namespace tagc {
 
 namespace {
 
-__global__ void __launch_bounds__(256)
+constexpr uint32_t kEncodeThreads = 512;
+
+__global__ void __launch_bounds__(kEncodeThreads)
 encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
               const uint32_t *__restrict__ cnt, const uint32_t *__restrict__ header,
               float *__restrict__ sketch, uint32_t sw0, uint32_t sw1, uint32_t sw2,
               uint32_t ranges_off, uint32_t pair_cap, const uint32_t *__restrict__ mask,
               uint32_t cells16)
 {
-    extern __shared__ float tile[];
+    constexpr uint32_t NT = kEncodeThreads;
+    extern __shared__ float tile[];  // the partition's three sub-tables, as in the sketch
     const uint32_t A = header[TAGC_HDR_A], m_sub = header[TAGC_HDR_MSUB];
-    const uint32_t a = blockIdx.x, j = blockIdx.y;
+    const uint32_t a = blockIdx.x;
     if (a >= A) return;
-    const uint32_t sw = j == 0 ? sw0 : (j == 1 ? sw1 : sw2);
+    const uint32_t cells = 3 * m_sub;
     // the partition's run of the sorted pair list, found when the Index was aggregated
     const uint32_t lo = min(cnt[ranges_off + a], pair_cap);
     const uint32_t hi = min(cnt[ranges_off + a + 1], pair_cap);
-    // a thread's first pairs (all of them for a partition of up to 1024 pairs of this rank)
-    // are requested together, before the tile is cleared
     // after an addition-simulated Index All-Reduce (section 2.2) the merged Index need not
     // hold every pair: only the positions it names are encoded (mask = merged Index then)
     auto named = [&](uint32_t i) { return !mask || ((mask[i >> 5] >> (i & 31)) & 1u); };
+    auto add = [&](uint32_t i, float v) {
+        uint32_t neg;
+        uint32_t slot = hash_slot(i, sw0, m_sub, &neg);
+        lds_add_f32(&tile[slot], neg ? -v : v);
+        slot = hash_slot(i, sw1, m_sub, &neg);
+        lds_add_f32(&tile[m_sub + slot], neg ? -v : v);
+        slot = hash_slot(i, sw2, m_sub, &neg);
+        lds_add_f32(&tile[2 * m_sub + slot], neg ? -v : v);
+    };
+    // a thread's first pairs (all of them for a partition of up to 1024 pairs of this rank)
+    // are requested together, before the tiles are cleared
     constexpr uint32_t PRE = 4;
     uint32_t pi[PRE];
     float pv[PRE];
 #pragma unroll
     for (uint32_t u = 0; u < PRE; ++u) {
-        const uint32_t t = lo + threadIdx.x + u * 256;
+        const uint32_t t = lo + threadIdx.x + u * NT;
         pi[u] = t < hi ? idx[t] : 0u;
         pv[u] = t < hi ? val[t] : 0.0f;
     }
-    for (uint32_t c = threadIdx.x; c < m_sub; c += 256) tile[c] = 0.0f;
+    for (uint32_t c = threadIdx.x; c < cells; c += NT) tile[c] = 0.0f;
     __syncthreads();
 #pragma unroll
-    for (uint32_t u = 0; u < PRE; ++u) {
-        if (lo + threadIdx.x + u * 256 < hi && named(pi[u])) {
-            uint32_t neg;
-            const uint32_t slot = hash_slot(pi[u], sw, m_sub, &neg);
-            lds_add_f32(&tile[slot], neg ? -pv[u] : pv[u]);
-        }
-    }
-    for (uint32_t t = lo + threadIdx.x + PRE * 256; t < hi; t += 256) {
+    for (uint32_t u = 0; u < PRE; ++u)
+        if (lo + threadIdx.x + u * NT < hi && named(pi[u])) add(pi[u], pv[u]);
+    for (uint32_t t = lo + threadIdx.x + PRE * NT; t < hi; t += NT) {
         const uint32_t i = idx[t];
         const float v = val[t];
-        if (!named(i)) continue;
-        uint32_t neg;
-        const uint32_t slot = hash_slot(i, sw, m_sub, &neg);
-        lds_add_f32(&tile[slot], neg ? -v : v);
+        if (named(i)) add(i, v);
     }
     __syncthreads();
-    const uint64_t b0 = (uint64_t(a) * 3 + j) * m_sub;
+    // the partition's cells are one contiguous run of the sketch
+    const uint64_t b0 = uint64_t(a) * cells;
     if (cells16) {
         // 16-bit cells on the wire: each cell rounded to the nearest bfloat16, ties to even;
         // eight to a 16-byte store where the sketch is aligned for them
         uint16_t *out = reinterpret_cast<uint16_t *>(sketch) + b0;
-        const uint32_t head = min(m_sub, uint32_t((8u - uint32_t(b0 & 7u)) & 7u));
-        const uint32_t n8 = (m_sub - head) / 8;
+        const uint32_t head = min(cells, uint32_t((8u - uint32_t(b0 & 7u)) & 7u));
+        const uint32_t n8 = (cells - head) / 8;
         if (threadIdx.x < head) out[threadIdx.x] = uint16_t(round_to_bf16(tile[threadIdx.x]));
-        for (uint32_t v = threadIdx.x; v < n8; v += 256) {
+        for (uint32_t v = threadIdx.x; v < n8; v += NT) {
             const float *t = tile + head + 8 * v;
             st_stream(reinterpret_cast<uint4 *>(out + head + 8 * v),
                       make_uint4(round_to_bf16(t[0]) | (round_to_bf16(t[1]) << 16),
@@ -79,21 +84,21 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
                                  round_to_bf16(t[4]) | (round_to_bf16(t[5]) << 16),
                                  round_to_bf16(t[6]) | (round_to_bf16(t[7]) << 16)));
         }
-        for (uint32_t c = head + 8 * n8 + threadIdx.x; c < m_sub; c += 256)
+        for (uint32_t c = head + 8 * n8 + threadIdx.x; c < cells; c += NT)
             out[c] = uint16_t(round_to_bf16(tile[c]));
         return;
     }
-    // the tile leaves in 16-byte stores where the sketch is aligned for them
+    // 16-byte stores where the sketch is aligned for them
     float *out = sketch + b0;
-    const uint32_t head = min(m_sub, uint32_t((4u - uint32_t(b0 & 3u)) & 3u));
-    const uint32_t n4 = (m_sub - head) / 4;
+    const uint32_t head = min(cells, uint32_t((4u - uint32_t(b0 & 3u)) & 3u));
+    const uint32_t n4 = (cells - head) / 4;
     if (threadIdx.x < head) out[threadIdx.x] = tile[threadIdx.x];
-    for (uint32_t v = threadIdx.x; v < n4; v += 256) {
+    for (uint32_t v = threadIdx.x; v < n4; v += NT) {
         const float *t = tile + head + 4 * v;
         st_stream(reinterpret_cast<float4 *>(out + head + 4 * v),
                   make_float4(t[0], t[1], t[2], t[3]));
     }
-    for (uint32_t c = head + 4 * n4 + threadIdx.x; c < m_sub; c += 256) out[c] = tile[c];
+    for (uint32_t c = head + 4 * n4 + threadIdx.x; c < cells; c += NT) out[c] = tile[c];
 }
 
 // One float4 of cells per thread: the loads of up to kSumBatch ranks are issued together
@@ -204,13 +209,20 @@ int launch_encode(const tagc_plan_t *p, const tagc_rank_buffers *rk, const tagc_
                   hipStream_t s)
 {
     ProfileScope ps("encode", s);
-    const size_t lds = size_t(p->T_cap / 3) * sizeof(float);
-    dim3 grid(uint32_t(p->A_cap), 3, 1);
-    encode_kernel<<<grid, 256, lds, s>>>(rk->idx, rk->val, rk->cnt, sh->header, rk->sketch,
-                                         p->seed_word[0], p->seed_word[1], p->seed_word[2],
-                                         p->cnt_ranges, uint32_t(p->K),
-                                         p->cfg.index_mode == TAGC_INDEX_OR1 ? nullptr : sh->bitmap,
-                                         p->cfg.cell_type == TAGC_CELL_BF16);
+    const size_t lds = size_t(p->T_cap) * sizeof(float);
+    static size_t attr_bytes = 0;
+    if (lds > attr_bytes) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(encode_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(lds)) != hipSuccess)
+            return TAGC_EHIP;
+        attr_bytes = lds;
+    }
+    encode_kernel<<<uint32_t(p->A_cap), kEncodeThreads, lds, s>>>(
+        rk->idx, rk->val, rk->cnt, sh->header, rk->sketch, p->seed_word[0], p->seed_word[1],
+        p->seed_word[2], p->cnt_ranges, uint32_t(p->K),
+        p->cfg.index_mode == TAGC_INDEX_OR1 ? nullptr : sh->bitmap,
+        p->cfg.cell_type == TAGC_CELL_BF16);
     return hip_ok(hipGetLastError());
 }
 
