@@ -1,6 +1,9 @@
-"""GPU parity at the benchmark's full size: one 7B-shaped bucket (config5, block 0: 202 M
-bf16 entries x 16 ranks, load factor 1.5, default partitions, dense output), run exactly as
-bench.py runs it.  The oracle cannot redo all of it in test time, so: sampled (rank, segment)
+"""GPU parity at the workloads' full sizes: one 7B-shaped bucket of the benchmark (config5,
+block 0: 202 M bf16 entries x 16 ranks, load factor 1.5, default partitions, dense output),
+run exactly as bench.py runs it; one bucket of the sharded 7B workload (config4); the 64 M
+heavy-tailed bucket with half-shared supports (config3) at two of its (keep, load factor)
+points, one of which takes the two-read route.  The oracle cannot redo all of it in test
+time, so: sampled (rank, segment)
 pairs go through the oracle's sparsifier bit for bit; one rank's whole sketch and a slice of
 the summed one go through the oracle's encode and sum; the cheap stages (Index merge, layout,
 bounds) are redone in full; everything else is checked through what must hold at any size --
@@ -21,18 +24,15 @@ def _say(msg):
     print("[fullsize] " + msg, flush=True)
 
 
-def test_config5_bucket_as_the_benchmark_runs_it():
+def _check_full_size(b, data, seed=0, oracle_ranks=(0,), max_unresolved=20):
     from paper_2504_05638_amd.bucket import TagcBucket
-    print("\n[case] config5 block 0 at full size", flush=True)
-    b = G.config5(0)[0]
     N = b.n_ranks
-    assert N == 16 and b.n_elems > 200_000_000
+    bf16 = b.dtype == G.BF16
     segs = [s for s in b.segments if s.flags & 1]
     offs, n_c = O.c_offsets(oracle_segments(b))
     c_off = [o for o, s in zip(offs, b.segments) if s.flags & 1]
     k = [O.keep_count(s.length, s.keep_ppm) for s in segs]
-    data = [G.rank_gradient(b, r, "cuda") for r in range(N)]
-    tb = TagcBucket(b.segments, b.dtype, N, sizing_milli=b.sizing_milli, seed=0, dense=True)
+    tb = TagcBucket(b.segments, b.dtype, N, sizing_milli=b.sizing_milli, seed=seed, dense=True)
     tb.run(data)
     torch.cuda.synchronize()
     z = tb.sizes
@@ -50,18 +50,20 @@ def test_config5_bucket_as_the_benchmark_runs_it():
         pairs.append((idx, val))
     _say("counts and order of all ranks")
 
-    # ---- stage 1, sampled ranks: Index <-> pairs, values, magnitude rule; oracle on sampled
-    # segments (the largest, the smallest, one in between)
+    # ---- stage 1, sampled ranks: Index <-> pairs, values, and the selection rule, which
+    # with the count fixes the kept set: nothing left out is larger than anything kept, of
+    # the entries that tie with the smallest kept one the lowest positions are kept, zeros
+    # never.  Sampled segments (largest, smallest, one in between) also through the oracle.
     by_len = sorted(range(len(segs)), key=lambda l: segs[l].length)
     sampled_segs = {by_len[0], by_len[len(by_len) // 2], by_len[-1]}
-    for r in (0, 9):
+    for r in sorted({0, N // 2 + 1} | set(oracle_ranks)):
         idx, val = pairs[r]
         bits = np.zeros(n_c, bool)
         bits[idx] = True
         assert np.array_equal(np.packbits(bits, bitorder="little").view(np.uint32),
                               tb.rank_bitmap(r))
         del bits
-        raw = G.to_numpy_raw(data[r])                            # bf16 bit patterns
+        raw = G.to_numpy_raw(data[r])          # bf16 bit patterns, or float32
         pos = 0
         for l, s in enumerate(segs):
             i_l = idx[pos:pos + k[l]].astype(np.int64) - c_off[l]
@@ -69,26 +71,31 @@ def test_config5_bucket_as_the_benchmark_runs_it():
             pos += k[l]
             assert i_l.min() >= 0 and i_l.max() < s.length
             seg_raw = raw[s.offset:s.offset + s.length]
-            wide = (seg_raw.astype(np.uint32) << 16)
+            wide = (seg_raw.astype(np.uint32) << 16) if bf16 else seg_raw.view(np.uint32)
             assert np.array_equal(v_l.view(np.uint32), wide[i_l])        # the entries themselves
             key = wide & 0x7FFFFFFF
-            kept_min = key[i_l].min()
+            T = key[i_l].min()
+            assert T > 0
+            tie_pos = np.flatnonzero(key == T)
+            kept_ties = np.isin(tie_pos, i_l, assume_unique=True)
+            assert kept_ties[0] and not np.any(np.diff(kept_ties.astype(np.int8)) > 0)
             key[i_l] = 0
-            assert key.max() <= kept_min                                  # the k largest magnitudes
-            if l in sampled_segs:
+            assert key.max() <= T
+            del key
+            if l in sampled_segs and r in oracle_ranks:
                 one = [O.Segment(0, s.length, s.keep_ppm, 1)]
-                st = O.sparsify(np.ascontiguousarray(seg_raw), O.Config(dtype=O.BF16), one)
-                assert np.array_equal(st.idx.astype(np.int64), i_l)      # ties included
+                st = O.sparsify(np.ascontiguousarray(seg_raw), O.Config(dtype=b.dtype), one)
+                assert np.array_equal(st.idx.astype(np.int64), i_l)
                 assert np.array_equal(st.val.view(np.uint32), v_l.view(np.uint32))
         del raw
-        _say("rank %d against its gradient and the oracle" % r)
+        _say("rank %d against its gradient%s" % (r, " and the oracle" if r in oracle_ranks else ""))
 
     # ---- stage 3a in full: merged Index, U, layout, bounds
     maps = [tb.rank_bitmap(r) for r in range(N)]
     merged, U = O.index_or(maps)
     assert np.array_equal(tb.shared_bitmap(), merged)
     hdr = tb.header()
-    cfg = O.Config(dtype=O.BF16, sizing_milli=b.sizing_milli, seed=0)
+    cfg = O.Config(dtype=b.dtype, sizing_milli=b.sizing_milli, seed=seed)
     A, m_sub, m = O.layout(U, cfg, z.n_real)
     assert hdr == dict(U=U, A=A, m_sub=m_sub, m=m)
     bnd = O.bounds(merged, n_c, U, A)
@@ -96,9 +103,9 @@ def test_config5_bucket_as_the_benchmark_runs_it():
     _say("Index merge, layout, bounds: U=%d A=%d m=%d" % (U, A, m))
 
     # ---- stage 2': one rank's whole sketch through the oracle's encode
-    r = 5
-    want = O.encode(pairs[r][0], pairs[r][1], bnd, A, m_sub, 0)
-    mag = O.encode(pairs[r][0], np.abs(pairs[r][1]), bnd, A, m_sub, 0, plus_only=True)
+    r = N // 3
+    want = O.encode(pairs[r][0], pairs[r][1], bnd, A, m_sub, seed)
+    mag = O.encode(pairs[r][0], np.abs(pairs[r][1]), bnd, A, m_sub, seed, plus_only=True)
     got = tb.rank_sketch(r)
     assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-5 * mag.astype(np.float64))
     assert np.mean(got.view(np.uint32) == want.view(np.uint32)) > 0.99
@@ -106,7 +113,8 @@ def test_config5_bucket_as_the_benchmark_runs_it():
     _say("rank %d sketch" % r)
 
     # ---- stage 3b: a slice of the summed sketch (the ranks' sketches are still on the device)
-    c0, c1 = m // 3, m // 3 + (1 << 20)
+    c0 = m // 3
+    c1 = min(m, c0 + (1 << 20))
     parts = [tb.rank_sketch(q)[c0:c1].copy() for q in range(N)]
     want = O.sketch_sum(parts)
     got = tb.shared_sketch()[c0:c1]
@@ -118,7 +126,7 @@ def test_config5_bucket_as_the_benchmark_runs_it():
     big = np.zeros(n_c, np.float64)
     for idx, val in pairs:
         ref[idx] += val                  # a rank's indices are distinct: plain fancy add is exact
-        np.maximum.at(big, idx, np.abs(val).astype(np.float64))
+        big[idx] = np.maximum(big[idx], np.abs(val))
     st = tb.status()
     out_idx, out_val = tb.outputs()
     assert st["flags"] == 0 and out_idx.size == U
@@ -130,7 +138,7 @@ def test_config5_bucket_as_the_benchmark_runs_it():
     err = np.abs(out_val.astype(np.float64) - ref[out_idx])
     bad = err > 1e-5 * scale[part]
     # what peeling could not recover is reported as 0 and counted, nothing else is off
-    assert bad.sum() <= st["n_unresolved"] <= 20
+    assert bad.sum() <= st["n_unresolved"] <= max_unresolved
     assert np.all(out_val[bad] == 0)
     dense = tb.dense()
     want = np.zeros(n_c, np.float32)
@@ -138,3 +146,37 @@ def test_config5_bucket_as_the_benchmark_runs_it():
     assert np.array_equal(dense.view(np.uint32), want.view(np.uint32))
     _say("decode against the definition: %d unresolved of %d, %d rounds"
          % (st["n_unresolved"], U, st["rounds"]))
+    return tb
+
+
+def test_config5_bucket_as_the_benchmark_runs_it():
+    print("\n[case] config5 block 0 at full size", flush=True)
+    b = G.config5(0)[0]
+    assert b.n_ranks == 16 and b.n_elems > 200_000_000
+    data = [G.rank_gradient(b, r, "cuda") for r in range(b.n_ranks)]
+    tb = _check_full_size(b, data, oracle_ranks=(0, 9))
+    assert all(tb.rank_counts(r)["dense_segments"] == 0 for r in range(1, b.n_ranks))
+
+
+def test_config4_sharded_7b_bucket():
+    print("\n[case] config4 block 0 at full size", flush=True)
+    b = G.config4(0)[0]
+    assert b.n_ranks == 8 and b.n_elems > 25_000_000
+    data = [G.rank_gradient(b, r, "cuda") for r in range(b.n_ranks)]
+    _check_full_size(b, data, oracle_ranks=(0, 5))
+
+
+@pytest.mark.parametrize("keep_ppm,lf,dense_route", [(10_000, 1500, False), (100_000, 3000, True)])
+def test_config3_heavy_tails_shared_supports(keep_ppm, lf, dense_route):
+    """64 M Student-t entries per rank, half of every rank's support shared with all others;
+    at 10 % kept the plan takes the two-read route."""
+    print("\n[case] config3 at full size keep=%d lf=%d" % (keep_ppm, lf), flush=True)
+    b = G.config3(0, keep_ppm=keep_ppm, sizing_milli=lf)
+    assert b.n_elems == 1 << 26 and b.n_ranks == 8
+    data = [G.config3_rank_gradient(b, r, "cuda") for r in range(b.n_ranks)]
+    tb = _check_full_size(b, data, oracle_ranks=(3,))
+    assert (tb.rank_counts(0)["dense_segments"] == 1) == dense_route
+    k = (b.n_elems * keep_ppm) // 10 ** 6
+    # 8 ranks, half of each support shared: k/2 + 8 * k/2 positions, less what the private
+    # halves happen to share at 10 %
+    assert 3.5 * k < tb.header()["U"] < 4.6 * k
