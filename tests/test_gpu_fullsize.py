@@ -180,3 +180,51 @@ def test_config3_heavy_tails_shared_supports(keep_ppm, lf, dense_route):
     # 8 ranks, half of each support shared: k/2 + 8 * k/2 positions, less what the private
     # halves happen to share at 10 %
     assert 3.5 * k < tb.header()["U"] < 4.6 * k
+
+
+def test_one_segment_of_almost_two_to_the_31_entries():
+    """The largest segment the format allows (just under 2^31 entries, 4.3 GB of bf16), one
+    rank, through the whole path.  Too large for the oracle or for host-side checks: the
+    selection rule, the Index and the decoded values are verified with torch's own device
+    primitives (count, gather, compare), which is all the rule needs."""
+    from paper_2504_05638_amd.bucket import TagcBucket
+    print("\n[case] one segment of 2^31 - 4096 entries", flush=True)
+    n = (1 << 31) - 4096
+    b = G.Bucket("max", G.BF16, 1, [G.Seg(0, n, 10_000, 1, "w")], n, 1500, {"w": 1e-3})
+    g = G.rank_gradient(b, 0, "cuda")
+    k = (n * 10_000) // 10 ** 6
+    tb = TagcBucket(b.segments, b.dtype, 1, sizing_milli=b.sizing_milli, seed=0, dense=False)
+    tb.run([g])
+    torch.cuda.synchronize()
+    cnt = tb.rank_counts(0)
+    assert cnt["flags"] == 0 and cnt["nonfinite"] == 0 and cnt["total"] == k and cnt["seg"] == [k]
+    t = tb._rk_tensors[0]
+    idx = t["idx"].view(torch.int32)[:k].to(torch.int64)
+    val = t["val"].view(torch.float32)[:k]
+    assert bool((idx >= 0).all()) and int(idx[-1]) < n
+    assert bool((idx[1:] > idx[:-1]).all())
+    assert torch.equal(val, g[idx].to(torch.float32))                  # the entries themselves
+    mag = g.abs()
+    T = val.abs().min().to(torch.bfloat16)
+    assert float(T) > 0
+    assert int((mag > T).sum()) <= k <= int((mag >= T).sum())         # the k largest
+    ties = torch.nonzero(mag == T).flatten()
+    kept = torch.isin(ties, idx, assume_unique=True)
+    n_kept = int(kept.sum())
+    assert n_kept >= 1 and bool(kept[:n_kept].all())                   # the lowest positions
+    del mag
+    _say("selection rule: %d ties at the threshold, %d kept" % (ties.numel(), n_kept))
+    lut = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device="cuda")
+    words = tb.sizes.bitmap_words
+    bm = t["bitmap"][:4 * words]
+    assert int(lut[bm.to(torch.int64)].sum()) == k
+    assert bool(((bm[idx >> 3].to(torch.int64) >> (idx & 7)) & 1).all())  # Index <-> pairs
+    hdr, st = tb.header(), tb.status()
+    assert hdr["U"] == k and st["flags"] == 0 and st["n_unresolved"] <= 20
+    out_idx = tb.out_idx.view(torch.int32)[:k].to(torch.int64)
+    out_val = tb.out_val.view(torch.float32)[:k]
+    assert torch.equal(out_idx, idx)
+    off = out_val != val                   # one rank: the decoded sum is what it sent
+    rel = (out_val - val).abs() / val.abs()
+    assert int((off & (rel > 1e-5)).sum()) <= st["n_unresolved"]
+    _say("decode: %d unresolved of %d, %d rounds" % (st["n_unresolved"], k, st["rounds"]))
