@@ -8,7 +8,7 @@
  *   tagc_plan            host only, once per bucket shape
  *   tagc_plan_upload     copies the segment table to the device, once
  *   for each rank r:  tagc_compress(PHASE_INDEX)    sparsify + create_index
- *   tagc_aggregate(PHASE_INDEX)                     All-Reduce(index) as OR
+ *   tagc_aggregate(PHASE_INDEX)                     All-Reduce(index) as OR (or add)
  *   for each rank r:  tagc_compress(PHASE_SKETCH)   compress -> Count Sketch
  *   tagc_aggregate(PHASE_SKETCH)                    Reduce as element-wise sum
  *   tagc_decompress                                 peeling_decompress
@@ -299,13 +299,15 @@ int tagc_feedback_apply(const tagc_plan_t *plan, const tagc_rank_buffers *rank,
 /*
  * Stands in for the two collectives of Algorithm 1 on one GPU.
  * PHASE_INDEX : shared->bitmap = OR over ranks[r].bitmap (section 2.2: OR is
- *   the operation the Index needs); counts its non-zeros U, derives the sketch
+ *   the operation the Index needs), or what adding the ranks' wire Indexes
+ *   gives (see "Index modes"); counts its non-zeros U, derives the sketch
  *   layout (A, m_sub, m) and the partition bounds; writes shared->header,
  *   shared->bounds; clears shared->status; locates the bounds in every given
  *   rank's pair list (ranks[r].idx, ranks[r].cnt are read, the ranges written
  *   behind the counts in ranks[r].cnt).
  * PHASE_SKETCH: shared->sketch[c] = ((ranks[0].sketch[c] + ranks[1].sketch[c])
- *   + ...) in rank order, float32, for c < m.
+ *   + ...) in rank order, float32, for c < m (16-bit wire cells are widened
+ *   first).
  * `ranks` is a host array of n_ranks structs (1 <= n_ranks <= config.n_ranks).
  */
 int tagc_aggregate(const tagc_plan_t *plan, uint32_t phase,
