@@ -1102,8 +1102,16 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb,
             const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
             uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_state,
             uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
-            uint32_t *__restrict__ bitmap, uint32_t *cnt)
+            uint32_t *__restrict__ bitmap, uint32_t *cnt, uint64_t *stamps)
 {
+#ifdef TAGC_PHASE_TIMING
+    // per-workgroup time stamps (100 MHz counter) in the look-back area of the dense route,
+    // which a plan without dense-route work leaves unused
+#define EMIT_STAMP(i) do { if (threadIdx.x == 0) stamps[8 * bid + (i)] = wall_clock64(); } while (0)
+#else
+#define EMIT_STAMP(i) do { } while (0)
+#endif
+    EMIT_STAMP(0);
     constexpr uint32_t VEC = DTYPE == kBF16 ? 8 : 4;
     constexpr uint32_t CHUNK = 64 * VEC * kCandRows;
     constexpr uint32_t SC_ELEMS = CHUNK * kCandChunksPerSuper;
@@ -1224,6 +1232,7 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb,
             n_gt += key > T;
             n_eq += (key == T) && quota;
         });
+        EMIT_STAMP(1);
         // ---- order inside the item (its 128 threads are in position order), publish
         const uint32_t inc_gt = wave_incl_scan<uint32_t>(n_gt);
         const uint32_t inc_eq = wave_incl_scan<uint32_t>(n_eq);
@@ -1238,6 +1247,7 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb,
         uint32_t eb = inc_eq - n_eq + ((wave & 1u) ? lo_eq : 0u);
         if (live && tt == 0)
             st_agent(&sc_state[sc], kStAgg | (uint64_t(it_gt) << 31) | uint64_t(it_eq));
+        EMIT_STAMP(2);
         // ---- prefix over the segment's earlier super-chunks: four words requested at a
         // time, then each is waited for (bounded) only if it has not been published yet
         uint64_t sum = 0;
@@ -1268,6 +1278,7 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb,
         sum = wave_sum<uint64_t>(sum);
         if (lane == 0) s_sum[wave] = sum;
         __syncthreads();  // also orders the clearing of `bits` before the ORs below
+        EMIT_STAMP(3);
         sum = s_sum[2 * k] + s_sum[2 * k + 1];
         // output position (within the segment) of the item's first survivor, and how many
         // survivors the item has: entries above T all survive, ties while the quota lasts
@@ -1313,6 +1324,7 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb,
             });
         }
         __syncthreads();
+        EMIT_STAMP(4);
         if (live) {
             const uint32_t n_st = min(item_n, kEmitStage);
             for (uint32_t i = tt; i < n_st; i += 128) {
@@ -1327,8 +1339,10 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb,
                 if (sc_rel0 + i * 32 < n_seg) bitmap[w0 + i] = bits[k][i];
         }
         __syncthreads();  // LDS is reused by the next iteration
+        EMIT_STAMP(5);
     }
 }
+#undef EMIT_STAMP
 
 // ---------------------------------------------------------------- compact
 
@@ -1537,7 +1551,7 @@ finish_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ ta
 {
     if (blockIdx.x < n_emit)
         emit_body<DTYPE>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
-                         CAP, sc_state, idx_out, val_out, bitmap, cnt);
+                         CAP, sc_state, idx_out, val_out, bitmap, cnt, tile_state);
     else
         compact_body<DTYPE>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, table, sel,
                             tile_state, idx_out, val_out, bitmap, cnt, ticket);
