@@ -4,7 +4,7 @@
 One "step" is one pass of the whole hot path (sparsify + index, Index OR, sketch
 encode, sketch sum, peeling decode) over one full synthetic gradient of the
 workload: every bucket, every simulated rank.  Inputs are resident in HBM before
-the timed region starts.  Prints ONE JSON line (see README/DESIGN for the fields).
+the timed region starts.  Prints ONE JSON line (the fields are described in README.md).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config5]
 """

@@ -35,7 +35,7 @@ def test_small_mixed_bucket(dtype, lf):
 
 
 def test_config1_full_size():
-    """BASELINE config 1: 4 ranks x 1,048,576 fp32 ~ N(0, 1e-3), top 1 %, lf 3."""
+    """Benchmark configuration 1: 4 ranks x 1,048,576 fp32 ~ N(0, 1e-3), top 1 %, lf 3."""
     _announce("config1")
     b = G.config1(seed=0)
     ores, tb = run_both(b, _grads(b), seed=0)
@@ -90,7 +90,7 @@ def test_heavy_ties_and_zeros(dtype, kind):
 
 
 def test_gpt2_block_shapes_fp32():
-    """One GPT-2-small block of BASELINE config 2 (4 compressed linear layers, biases
+    """One GPT-2-small block of benchmark configuration 2 (4 compressed linear layers, biases
     and LayerNorms skipped, per-layer keep ratio), 3 ranks."""
     _announce("config2 block0")
     b = G.config2(seed=0, n_ranks=3)[0]
@@ -101,7 +101,7 @@ def test_gpt2_block_shapes_fp32():
 
 def test_bf16_many_tiles_ragged_tail_student_t():
     """bf16, heavy-tailed values, length not a multiple of the tile or the vector,
-    load factor 1.5 (BASELINE config 3 at reduced length, with its overlap recipe)."""
+    load factor 1.5 (benchmark configuration 3 at reduced length, with its overlap recipe)."""
     _announce("config3 reduced")
     b = G.config3(seed=0, n=(1 << 21) + 4321, n_ranks=4, keep_ppm=10_000, sizing_milli=1500)
     grads = [G.config3_rank_gradient(b, r, "cpu") for r in range(4)]
