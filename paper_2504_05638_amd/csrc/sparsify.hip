@@ -1092,7 +1092,7 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // workgroup, which the hardware has dispatched before this one: the wait ends however few
 // workgroups are resident at a time (other streams may be using the device).
 constexpr int kEmitItems = 2;
-constexpr uint32_t kEmitStage = 1280;  // survivors of an item that go through LDS
+constexpr uint32_t kEmitStage = 800;  // survivors of an item that go through LDS
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
 template <int DTYPE>
@@ -1541,7 +1541,7 @@ __device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad,
 static_assert(kEmitThreads == kCompactThreads, "one launch for both parts");
 
 template <int DTYPE>
-__global__ void __launch_bounds__(kEmitThreads) __attribute__((amdgpu_waves_per_eu(6, 8)))
+__global__ void __launch_bounds__(kEmitThreads) __attribute__((amdgpu_waves_per_eu(7, 8)))
 finish_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ table,
               const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
               const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
