@@ -44,12 +44,36 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     p->T_cap = T_cap;
     p->elem_bytes = cfg->dtype == TAGC_F32 ? 4 : 2;
     p->vec_elems = 16 / p->elem_bytes;
-    p->tile_elems = kCompactThreads * p->vec_elems * kCompactRows;
     p->chunk_elems = 64 * p->vec_elems * kCandRows;
     p->cand_cap = 32;
     p->static_dense = false;
     p->any_nonfast = false;
     for (uint32_t j = 0; j < 3; ++j) p->seed_word[j] = seed_word(cfg->seed, j);
+
+    // Candidate route: slots per chunk for 1.3 x the kept fraction plus six standard
+    // deviations.  Its second pass costs in proportion to the candidates; measured on
+    // 7B-shaped buckets it beats reading the gradient twice up to about 3 % kept (4 % of a
+    // chunk expected as candidates), beyond that (Table 1's 2x and 4x regimes) the dense
+    // route is several times faster.  Returns the slots a chunk needs, 0 = dense route.
+    auto fast_slots = [&](const tagc_segment &s) -> uint32_t {
+        const uint64_t k = uint64_t((unsigned __int128)s.length * s.keep_ppm / 1000000u);
+        if (s.offset % p->vec_elems || s.length < kFastMinElems || k < kFastMinKeep) return 0;
+        const double mu = 1.3 * double(k) / double(s.length) * p->chunk_elems;
+        if (mu > kFastMaxCandFrac * p->chunk_elems) return 0;
+        return uint32_t(round_up(uint64_t(mu + 6.0 * sqrt(mu) + 16.0), 32));
+    };
+    // Compaction tile of the dense route: four 16-byte vectors per thread where that route
+    // is planned work, two where it is only the safety net of re-routed segments -- the
+    // kernel it shares with the candidate route's last pass then needs few enough
+    // registers for one more workgroup per CU.
+    for (uint32_t l = 0; l < n_seg; ++l) {
+        const tagc_segment &s = segs[l];
+        if (!(s.flags & TAGC_SEG_COMPRESS) || s.keep_ppm > 1000000u || s.length == 0) continue;
+        if ((unsigned __int128)s.length * s.keep_ppm / 1000000u && !fast_slots(s))
+            p->static_dense = true;
+    }
+    p->compact_rows = p->static_dense ? 4 : 2;
+    p->tile_elems = kCompactThreads * p->vec_elems * p->compact_rows;
 
     uint64_t c = 0, n_real = 0, K = 0, tiles = 0, grad_elems = 0, scs = 0;
     try {
@@ -73,20 +97,10 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
             d.k = uint32_t((unsigned __int128)s.length * s.keep_ppm / 1000000u);
             d.tile_start = uint32_t(tiles);
             d.flags = (s.offset % p->vec_elems) == 0 ? kSegAligned : 0;
-            // Candidate route: slots per chunk for 1.3 x the kept fraction plus six
-            // standard deviations.  Its second pass costs in proportion to the candidates;
-            // measured on 7B-shaped buckets it beats reading the gradient twice up to about
-            // 3 % kept (4 % of a chunk expected as candidates), beyond that (Table 1's 2x and
-            // 4x regimes) the dense route is several times faster.
-            if ((d.flags & kSegAligned) && d.n >= kFastMinElems && d.k >= kFastMinKeep) {
-                const double mu = 1.3 * double(d.k) / double(d.n) * p->chunk_elems;
-                const uint32_t cap = uint32_t(round_up(uint64_t(mu + 6.0 * sqrt(mu) + 16.0), 32));
-                if (mu <= kFastMaxCandFrac * p->chunk_elems) {
-                    d.flags |= kSegFast;
-                    p->cand_cap = std::max(p->cand_cap, cap);
-                }
+            if (const uint32_t cap = fast_slots(s)) {
+                d.flags |= kSegFast;
+                p->cand_cap = std::max(p->cand_cap, cap);
             }
-            if (d.k && d.n && !(d.flags & kSegFast)) p->static_dense = true;
             if (d.n && !(d.flags & kSegFast)) p->any_nonfast = true;
             d.sc_start = uint32_t(scs);
             scs += ceil_div(s.length, uint64_t(p->chunk_elems) * kCandChunksPerSuper);

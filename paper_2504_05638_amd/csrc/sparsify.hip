@@ -1096,7 +1096,7 @@ constexpr uint32_t kEmitStage = 800;  // survivors of an item that go through LD
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
 template <int DTYPE>
-__device__ inline void emit_body(uint32_t bid, uint32_t nb,
+__device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
                                  const uint32_t *__restrict__ table,
                                  const SelDev *__restrict__ sel,
             const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
@@ -1347,8 +1347,8 @@ __device__ inline void emit_body(uint32_t bid, uint32_t nb,
 // ---------------------------------------------------------------- compact
 
 // Dense route, final pass over the gradient itself.
-template <int DTYPE>
-__device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad,
+template <int DTYPE, uint32_t ROWS>
+__device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const char *grad,
                                     const uint32_t *__restrict__ table,
                const SelDev *__restrict__ sel, uint64_t *tile_state,
                uint32_t *__restrict__ idx_out,
@@ -1357,7 +1357,6 @@ __device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad,
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
-    constexpr uint32_t ROWS = kCompactRows;
     constexpr uint32_t ROW_ELEMS = kCompactThreads * VEC;
     constexpr uint32_t TILE = ROW_ELEMS * ROWS;
     constexpr uint32_t LPW = 32 / VEC;  // lanes that share one Index word
@@ -1540,8 +1539,9 @@ __device__ inline void compact_body(uint32_t bid, uint32_t nb, const char *grad,
 // dispatched in order, so inside each part a workgroup still only waits for earlier ones.
 static_assert(kEmitThreads == kCompactThreads, "one launch for both parts");
 
-template <int DTYPE>
-__global__ void __launch_bounds__(kEmitThreads) __attribute__((amdgpu_waves_per_eu(7, 8)))
+template <int DTYPE, uint32_t COMPACT_ROWS>
+__global__ void __launch_bounds__(kEmitThreads)
+    __attribute__((amdgpu_waves_per_eu(COMPACT_ROWS == 2 ? 7 : 6, 8)))
 finish_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ table,
               const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
               const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
@@ -1553,7 +1553,7 @@ finish_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ ta
         emit_body<DTYPE>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
                          CAP, sc_state, idx_out, val_out, bitmap, cnt, tile_state);
     else
-        compact_body<DTYPE>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, table, sel,
+        compact_body<DTYPE, COMPACT_ROWS>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, table, sel,
                             tile_state, idx_out, val_out, bitmap, cnt, ticket);
 }
 
@@ -1670,7 +1670,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     const int cus = device_cu_count();
     const size_t lds_hist = kBins1 * sizeof(uint32_t);
     static bool a_sample = false, a_hist = false;
-    static int occ_finish = 0;
+    static int occ_finish[2] = {0, 0};
 
     if (L == 0) {  // nothing is compressed: only the counts have to read zero
         ProfileScope ps("fill_zero", s);
@@ -1724,8 +1724,10 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     if (p->total_sc || p->total_tiles) {
         ProfileScope ps("finish", s);  // emit + compact
-        const int occ =
-            resident_blocks_per_cu(finish_kernel<DTYPE>, kEmitThreads, 0, &occ_finish);
+        // the plan fixed the compaction tile's height, and with it which kernel this is
+        auto kernel = p->compact_rows == 4 ? finish_kernel<DTYPE, 4> : finish_kernel<DTYPE, 2>;
+        const int occ = resident_blocks_per_cu(kernel, kEmitThreads, 0,
+                                               &occ_finish[p->compact_rows == 4]);
         if (occ <= 0) return TAGC_EHIP;
         const uint32_t n_emit = (p->total_sc + kEmitItems - 1) / kEmitItems;
         // Compaction: one tile per workgroup when dense-route work is certain: a tile's
@@ -1739,7 +1741,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
             p->static_dense ? p->total_tiles
                             : std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
         uint32_t *ticket = p->static_dense ? nullptr : arrive + L;
-        finish_kernel<DTYPE><<<n_emit + n_compact, kEmitThreads, 0, s>>>(
+        kernel<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
             n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state,
             tile_state,
             rk->idx, rk->val, bitmap1, rk->cnt, ticket);

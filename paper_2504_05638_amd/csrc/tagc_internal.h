@@ -16,7 +16,6 @@ constexpr uint32_t kBins1 = 32768;   // top 15 key bits: all of a bf16 key, key>
 constexpr uint32_t kBins2 = 65536;   // low 16 key bits (fp32 only)
 constexpr uint32_t kHistThreads = 1024;
 constexpr uint32_t kCompactThreads = 256;
-constexpr uint32_t kCompactRows = 2;  // 16-byte vectors per thread per tile
 constexpr uint32_t kCandRows = 4;        // 16-byte vectors per lane per candidate chunk
 constexpr uint32_t kCandChunksPerSuper = 32;  // chunks one emit workgroup handles
 constexpr uint32_t kEmitThreads = 256;
@@ -82,6 +81,7 @@ struct tagc_plan_s {
     std::vector<tagc_segment> segments;       // as given
     std::vector<tagc::SegDev> table;          // compressed segments only
     uint32_t elem_bytes, vec_elems;
+    uint32_t compact_rows;                    // 16-byte vectors per thread per compaction tile (2 or 4)
     uint32_t tile_elems;                      // elements per compaction tile
     uint32_t total_tiles;
     uint32_t total_sc;                        // super-chunks of the candidate path
