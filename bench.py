@@ -84,6 +84,10 @@ def parse_args():
                     help="capture each bucket's call sequence in a HIP graph after the warm-up "
                          "and replay it in the timed steps (the library only enqueues kernels, so "
                          "a caller may do that); helps where many small launches bind the host")
+    ap.add_argument("--grad-sets", type=int, default=0,
+                    help="distinct gradients per bucket data set, one per step in turn (0 = 3 "
+                         "with --error-feedback, where feeding the same gradient every step "
+                         "would double the accumulator's scale from step to step, else 1)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="before the timed region, copy this many MiB device to device three "
@@ -220,7 +224,13 @@ def main():
 
     # ---- inputs resident in HBM (pool of distinct bucket data sets)
     t0 = time.perf_counter()
-    data = [[gen(buckets[d], r, "cuda") for r in range(N)] for d in range(pool)]
+    import dataclasses
+    n_sets = args.grad_sets or (3 if args.error_feedback else 1)
+    if args.graph:
+        n_sets = 1  # a captured graph reads the buffers it was captured with
+    data_sets = [[[gen(dataclasses.replace(buckets[d], seed=buckets[d].seed + 7919 * v), r, "cuda")
+                   for r in range(N)] for d in range(pool)] for v in range(n_sets)]
+    data = data_sets[0]
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t0
 
@@ -260,9 +270,13 @@ def main():
     stream = torch.cuda.current_stream()
     streams = [stream] + [torch.cuda.Stream() for _ in range(lanes - 1)]
 
+    step_no = [0]
+
     def step(one_stream=False):
+        cur = data_sets[step_no[0] % n_sets]  # every step a different gradient, in turn
+        step_no[0] += 1
         for i in range(n_b):
-            tbs[i].run(data[i % pool], stream if one_stream else streams[i % lanes])
+            tbs[i].run(cur[i % pool], stream if one_stream else streams[i % lanes])
 
     for _ in range(args.warmup):
         step()
@@ -346,7 +360,7 @@ def main():
             bad |= tbs[i].rank_counts(r)["flags"]
         # (with error feedback every pass starts from different accumulators, so U and the
         # residue legitimately change from pass to pass: only the flags are checked then)
-        if bad or (not args.error_feedback and (hdr, st) != facts[i]):
+        if bad or (not args.error_feedback and n_sets == 1 and (hdr, st) != facts[i]):
             sys.stderr.write("bench.py: bucket %d differs when run with %d buckets in flight "
                              "(flags %d)\n" % (i, lanes, bad))
             sys.exit(1)
@@ -415,7 +429,7 @@ def main():
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,
                    "index_mode": args.index_mode, "cell_bits": args.cell_bits,
-                   "graph_replay": bool(args.graph),
+                   "graph_replay": bool(args.graph), "gradient_sets": n_sets,
                    "peel_rounds_max": rounds, "input_generation_s": round(t_gen, 2)},
         "hbm_frac_end_to_end": round(balg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "alg_bytes_per_step": balg_total,

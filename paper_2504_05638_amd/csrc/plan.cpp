@@ -153,8 +153,9 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     off += round_up(tiles * 8, 16);
     w.sc_state = off;
     off += round_up(scs * 8, 16);
-    w.counters = off;  // one arrival counter per segment, one tile ticket
-    off += round_up(4 * (L + 1), 64);
+    // one arrival counter per segment, one tile ticket, one raised pre-threshold per segment
+    w.counters = off;
+    off += round_up(4 * (2 * L + 1), 64);
     p->zero_bytes = off;
     w.sel = off;
     off += round_up(L * sizeof(SelDev), 16);

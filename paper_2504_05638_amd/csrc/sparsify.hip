@@ -199,13 +199,14 @@ accumulate_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ ta
 // holds fewer than `need`; *total_out is the histogram's sum either way.  A second count
 // `need2` (0 = none) is located in the same pass: *bin2_out is the largest bin with at
 // least need2 entries at or above it, or 0xFFFFFFFF if the histogram holds fewer.  So is,
-// on request, the number of entries in the bins from `tail_from` upwards.
+// on request, the number of entries in the bins from `tail_from` upwards.  Bins below
+// `floor_bin` count as empty.
 template <int BPT>
 __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t *bin_out,
                                    uint32_t *above_out, uint32_t *at_out, uint32_t *total_out,
                                    uint32_t *smem /* >= 24 words */, uint32_t need2 = 0,
                                    uint32_t *bin2_out = nullptr, uint32_t tail_from = 0,
-                                   uint32_t *tail_out = nullptr)
+                                   uint32_t *tail_out = nullptr, uint32_t floor_bin = 0)
 {
     const uint32_t t = threadIdx.x;
     const uint4 *hv = reinterpret_cast<const uint4 *>(hist + uint64_t(t) * BPT);
@@ -215,7 +216,13 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
     for (int i = 0; i < BPT / 4; ++i) {
         const uint4 v = hv[i];
         bins[4 * i] = v.x; bins[4 * i + 1] = v.y; bins[4 * i + 2] = v.z; bins[4 * i + 3] = v.w;
-        s += v.x + v.y + v.z + v.w;
+    }
+    // bins below `floor_bin` are read as empty (their counts are incomplete when part of the
+    // scan ran with a higher pre-threshold)
+#pragma unroll
+    for (int b = 0; b < BPT; ++b) {
+        if (t * BPT + b < floor_bin) bins[b] = 0;
+        s += bins[b];
     }
     uint32_t total;
     uint32_t prefix = block_excl_scan<uint32_t, kHistThreads / 64>(s, &total, smem);
@@ -399,14 +406,15 @@ constexpr uint32_t kSpillWindow = 768;
 constexpr uint32_t kSpillThreads = 512;
 constexpr uint32_t kSpillStage = 512;  // staged slots per wave
 constexpr uint32_t kSpillList = 16;    // staged chunks per wave
+constexpr uint32_t kSpillRaise = 6;    // bins (1/128 octave each) a wave's pre-threshold goes up per try
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kSpillThreads)
 scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                   const uint32_t *__restrict__ table,
-                  SelDev *sel, const uint32_t *__restrict__ binlo, uint32_t *__restrict__ hist,
-                  uint32_t *__restrict__ cand, uint32_t *__restrict__ chunk_cnt,
-                  uint64_t n_slots_total, uint32_t CAP)
+                  SelDev *sel, const uint32_t *__restrict__ binlo, uint32_t *raised,
+                  uint32_t *__restrict__ hist, uint32_t *__restrict__ cand,
+                  uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP)
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
@@ -503,7 +511,9 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
         if (!route || acc) {
             const char *base = grad + sd.offset * EB;
             char *abase = acc ? acc + sd.offset * EB : nullptr;
-            const uint32_t swar_add = (0x8000u - blo) * 0x10001u;
+            // The wave's own pre-threshold: starts at the segment's and goes up when a chunk
+            // holds more candidates than it has slots (see below).
+            uint32_t blo_w = blo, swar_add = (0x8000u - blo) * 0x10001u;
             bool overflow = false;
             // the lane's four vectors of chunk `ch`; entries past the segment's end read as 0
             auto load_chunk = [&](const char *base, uint32_t ch, uint32_t (&w)[ROWS][4]) {
@@ -611,7 +621,7 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                     } else {
 #pragma unroll
                         for (uint32_t e = 0; e < VEC; ++e)
-                            f |= uint32_t(((w[r][e] & 0x7FFFFFFFu) >> 16) >= blo) << e;
+                            f |= uint32_t(((w[r][e] & 0x7FFFFFFFu) >> 16) >= blo_w) << e;
                         c[r] = __popc(f);
                     }
                     mask |= f << (r * VEC);
@@ -625,15 +635,55 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                 }
                 // slot of each lane's first candidate per row: one scan over the four
                 // row counts packed in 16-bit fields (a row holds at most 512 candidates)
-                const uint32_t ia = wave_incl_scan<uint32_t>(c[0] | (c[1] << 16));
-                const uint32_t ib = wave_incl_scan<uint32_t>(c[2] | (c[3] << 16));
-                const uint32_t ta = __builtin_amdgcn_readlane(ia, 63);
-                const uint32_t tb = __builtin_amdgcn_readlane(ib, 63);
-                const uint32_t t0 = ta & 0xFFFFu, t1 = ta >> 16, t2 = tb & 0xFFFFu, t3 = tb >> 16;
-                // exclusive positions, again two per register: rows 0,1 and rows 2,3
-                const uint32_t p01 = ia - (c[0] | (c[1] << 16)) + (t0 << 16);
-                const uint32_t p23 = ib - (c[2] | (c[3] << 16)) + (t0 + t1) * 0x10001u + (t2 << 16);
-                const uint32_t total = t0 + t1 + t2 + t3;
+                uint32_t p01, p23, total;
+                auto place = [&]() {
+                    const uint32_t ia = wave_incl_scan<uint32_t>(c[0] | (c[1] << 16));
+                    const uint32_t ib = wave_incl_scan<uint32_t>(c[2] | (c[3] << 16));
+                    const uint32_t ta = __builtin_amdgcn_readlane(ia, 63);
+                    const uint32_t tb = __builtin_amdgcn_readlane(ib, 63);
+                    const uint32_t t0 = ta & 0xFFFFu, t1 = ta >> 16, t2 = tb & 0xFFFFu,
+                                   t3 = tb >> 16;
+                    // exclusive positions, again two per register: rows 0,1 and rows 2,3
+                    p01 = ia - (c[0] | (c[1] << 16)) + (t0 << 16);
+                    p23 = ib - (c[2] | (c[3] << 16)) + (t0 + t1) * 0x10001u + (t2 << 16);
+                    total = t0 + t1 + t2 + t3;
+                };
+                place();
+                // More candidates than the chunk has slots: the pre-threshold this call was
+                // given is too low (the gradient's scale went up since it was tuned; with
+                // error feedback it does every step).  Rather than giving the segment up to
+                // the two-read route, the wave raises its own pre-threshold -- for this chunk,
+                // classified again from its LDS copy, and for the chunks it takes after it --
+                // until the chunk fits.  Nothing has been counted or stored for the chunk yet.
+                // The highest pre-threshold any wave used is recorded: the histogram is only
+                // complete from there upwards, which is where the selection then looks.
+                while (total > CAP && blo_w < 0x7F7Fu) {
+                    blo_w = min(blo_w + kSpillRaise, 0x7F7Fu);
+                    swar_add = (0x8000u - blo_w) * 0x10001u;
+                    mask = 0;
+#pragma unroll
+                    for (uint32_t r = 0; r < ROWS; ++r) {
+                        const uint4 v = dw[r * 64 + lane];
+                        const uint32_t x[4] = {v.x, v.y, v.z, v.w};
+                        uint32_t f = 0;
+                        if (DTYPE == kBF16) {
+#pragma unroll
+                            for (uint32_t j = 0; j < 4; ++j) {
+                                const uint32_t t = ((x[j] & 0x7FFF7FFFu) + swar_add) & 0x80008000u;
+                                f |= (t >> 15) << (2 * j);
+                            }
+                            c[r] = __popc(f);
+                            f = (f & 0xFFFFu) | ((f >> 16) << 1);
+                        } else {
+#pragma unroll
+                            for (uint32_t e = 0; e < VEC; ++e)
+                                f |= uint32_t(((x[e] & 0x7FFFFFFFu) >> 16) >= blo_w) << e;
+                            c[r] = __popc(f);
+                        }
+                        mask |= f << (r * VEC);
+                    }
+                    place();
+                }
                 const uint32_t chunk_id = uint32_t(s0) + ch;
                 const uint32_t need = min((total + 31u) & ~31u, CAP);
                 if (staged && (n_list == kSpillList || fill + need > kSpillStage)) flush();
@@ -692,6 +742,7 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
             SPILL_STAMP(2);
             if (staged) flush();
             SPILL_STAMP(3);
+            if (blo_w > blo && lane == 0) atomicMax(&raised[l], blo_w);
             if (overflow && lane == 0)  // a chunk denser than its slots: take the dense route
                 atomicOr(&sel[l].route, 1u);
         }
@@ -755,8 +806,8 @@ __device__ inline void hist_elem(uint32_t f32bits, uint32_t *h)
 template <int DTYPE>
 __device__ inline void select1_segment(uint32_t l, const SegDev &sd, const uint32_t *hist,
                                        SelDev *sel, uint32_t *cnt, uint32_t dense,
-                                       const uint32_t *binlo, uint32_t *hint,
-                                       uint32_t *smem /* >= 32 words */)
+                                       const uint32_t *binlo, const uint32_t *raised,
+                                       uint32_t *hint, uint32_t *smem /* >= 32 words */)
 {
     SelDev r = sel[l];
     if (r.route != dense) {
@@ -777,14 +828,17 @@ __device__ inline void select1_segment(uint32_t l, const SegDev &sd, const uint3
     const bool fast = (sd.flags & kSegFast) != 0;
     const uint32_t want = fast ? uint32_t(1.3f * float(sd.k)) + 1u : 0u;
     // nf: inputs with an all-ones exponent fall into bins >= 0x7F80
+    // Candidate route: the histogram is complete from the highest pre-threshold any wave of
+    // the scan used (the segment's, or what a wave raised it to when a chunk overflowed).
+    const uint32_t floor_bin = dense ? 0u : max(binlo[l], raised[l]);
     const bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem, want, &bin2,
-                                       0x7F80u, &nf);
+                                       0x7F80u, &nf, floor_bin);
     if (threadIdx.x != 0) return;
     if (fast) {
         uint32_t nh;
         if (bin2 != 0xFFFFFFFFu) nh = max(bin2, 1u);
         else if (dense) nh = 1u;  // fewer non-zeros than that in the whole segment
-        else nh = found ? max(binlo[l], 2u) - 1u : 0u;
+        else nh = found ? max(floor_bin, 2u) - 1u : 0u;
         hint[l] = nh;
     }
     if (!found && !dense) {  // the candidates hold fewer than k entries: dense route
@@ -819,12 +873,13 @@ __device__ inline void select1_segment(uint32_t l, const SegDev &sd, const uint3
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads)
 select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ hist,
-               SelDev *sel, uint32_t *cnt, const uint32_t *__restrict__ binlo, uint32_t *hint)
+               SelDev *sel, uint32_t *cnt, const uint32_t *__restrict__ binlo,
+               const uint32_t *__restrict__ raised, uint32_t *hint)
 {
     __shared__ uint32_t smem[32];
     const uint32_t l = blockIdx.x;
     const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
-    select1_segment<DTYPE>(l, sd, hist, sel, cnt, 0, binlo, hint, smem);
+    select1_segment<DTYPE>(l, sd, hist, sel, cnt, 0, binlo, raised, hint, smem);
 }
 
 // Dense route: one workgroup per CU, 32768 LDS counters, all entries of every dense-route
@@ -895,7 +950,7 @@ hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, 
         __syncthreads();
         if (s_last) {  // uniform
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            select1_segment<DTYPE>(l, sd, hist, sel, cnt, 1, binlo, hint, s_sel);
+            select1_segment<DTYPE>(l, sd, hist, sel, cnt, 1, binlo, nullptr, hint, s_sel);
         }
         __syncthreads();
     }
@@ -1648,6 +1703,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     uint32_t *hist1 = reinterpret_cast<uint32_t *>(ws + p->ws.hist1);
     uint32_t *hist1d = reinterpret_cast<uint32_t *>(ws + p->ws.hist1d);
     uint32_t *arrive = reinterpret_cast<uint32_t *>(ws + p->ws.counters);
+    uint32_t *raised = arrive + L + 1;  // behind the arrival counters and the tile ticket
     uint32_t *hist2 = reinterpret_cast<uint32_t *>(ws + p->ws.hist2);
     uint64_t *tile_state = reinterpret_cast<uint64_t *>(ws + p->ws.tile_state);
     uint64_t *sc_state = reinterpret_cast<uint64_t *>(ws + p->ws.sc_state);
@@ -1697,11 +1753,12 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
         scan_spill_kernel<DTYPE><<<cus * 2, kSpillThreads, 0, s>>>(
-            g, acc, sent, table, sel, binlo, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
+            g, acc, sent, table, sel, binlo, raised, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
     }
     {
         ProfileScope ps("select1", s);
-        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt, binlo, hint);
+        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt, binlo, raised,
+                                                         hint);
     }
     {
         ProfileScope ps("hist1", s);

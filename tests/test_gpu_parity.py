@@ -264,8 +264,12 @@ def test_candidate_route_fallbacks(dtype, kind):
     grads = [torch.from_numpy(v).to(td), torch.from_numpy(np.roll(v, 7777)).to(td)]
     ores, tb = run_both(b, grads, seed=2)
     compare_all(b, ores, tb, exact_values=kind in ("all_equal", "two_valued", "ints"))
-    if kind != "ints":   # (a 2 % tie class at the threshold still fits the slots)
-        assert tb.rank_counts(0)["dense_segments"] == 1     # the shortcut was abandoned
+    # Whether the shortcut was abandoned.  A pre-threshold that is merely far too low is
+    # not a reason any more: the scan raises it as it goes.  Tie classes larger than the
+    # slots, and a cluster that drives one wave's pre-threshold above the true threshold,
+    # still are.  (With "ints" the 2 % tie class at the threshold fits the slots.)
+    if kind != "ints":
+        assert tb.rank_counts(0)["dense_segments"] == (0 if kind == "sample_low" else 1)
 
 
 def test_buckets_in_flight_on_separate_streams():
@@ -306,7 +310,7 @@ def test_buckets_in_flight_on_separate_streams():
 def test_pre_threshold_carried_between_calls_never_changes_results(dtype):
     """A plan keeps each segment's pre-threshold from one PHASE_INDEX call to the next.
     Here consecutive calls see the same distribution (the hint holds), then gradients 100x
-    larger (far too many candidates: the slots overflow), then 10000x smaller (no
+    larger (far too many candidates for the slots), then 10000x smaller (no
     candidate at all), then the first scale again with one rank that is mostly zeros.
     Whatever the hint is worth, every rank's survivors must be exactly the oracle's."""
     _announce("pre-threshold hints dtype=%d" % dtype)
@@ -325,7 +329,8 @@ def test_pre_threshold_carried_between_calls_never_changes_results(dtype):
     compare_all(b, ores, tb)
     dense = [tb.rank_counts(r)["dense_segments"] for r in range(len(scales))]
     assert dense[0] == 0 and dense[1] == 0      # sampled, then the carried hint
-    assert dense[2] == 1 and dense[3] == 1      # the hint failed both ways: exact fallback
+    assert dense[2] == 0      # hint far too low: the scan raises it as it goes
+    assert dense[3] == 1      # hint far too high, no candidates: exact two-read fallback
     assert dense[6] == 0                        # and recovered (rank 5 still pays for rank 4)
 
 
