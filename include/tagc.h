@@ -221,9 +221,10 @@ typedef struct tagc_rank_buffers {
 /* Device buffers shared by the bucket (all dev, caller-owned). */
 typedef struct tagc_shared_buffers {
     const void *table;  /* [table_bytes] filled by tagc_plan_upload; PHASE_INDEX
-                           also keeps one pre-threshold per segment there, carried
-                           from call to call (a speed hint only: results do not
-                           depend on it)                                         */
+                           also keeps one pre-threshold per segment there (and a
+                           count of calls that still sample beside it), carried
+                           from call to call (speed hints only: results do not
+                           depend on them)                                       */
     uint32_t *bitmap;   /* [bitmap_words] merged Index                          */
     float *sketch;      /* [sketch_cells_capacity] summed Count Sketch          */
     uint32_t *header;   /* [TAGC_HDR_WORDS]                                     */

@@ -183,8 +183,9 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     z.part_unknowns = P_cap;
     z.part_cells = T_cap;
     z.grad_elems = grad_elems;
-    // header, one row per compressed segment, one pre-threshold hint per segment
-    z.table_bytes = 32 + 32 * std::max<uint64_t>(L, 1) + round_up(4 * std::max<uint64_t>(L, 1), 16);
+    // header, one row per compressed segment, then per segment one pre-threshold hint and one
+    // count of calls that still sample beside it
+    z.table_bytes = 32 + 32 * std::max<uint64_t>(L, 1) + round_up(8 * std::max<uint64_t>(L, 1), 16);
     z.rank_idx_bytes = round_up(4 * std::max<uint64_t>(K, 1), 16);
     z.rank_val_bytes = z.rank_idx_bytes;
     // counts first, then (from the Index aggregation on) the A+1 positions at which the
@@ -246,7 +247,7 @@ extern "C" int tagc_plan_upload(const tagc_plan_t *p, void *table_dev, void *str
     // no pre-threshold is known yet: the first PHASE_INDEX call samples
     if (!p->table.empty() &&
         hipMemsetAsync(static_cast<char *>(table_dev) + 32 + p->table.size() * sizeof(SegDev), 0,
-                       p->table.size() * 4, s) != hipSuccess)
+                       p->table.size() * 8, s) != hipSuccess)
         return TAGC_EHIP;
     return TAGC_OK;
 }

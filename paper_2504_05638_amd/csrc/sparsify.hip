@@ -327,8 +327,13 @@ sample_kernel(const char *__restrict__ grad, const char *acc, const SentMap sent
     // A pre-threshold left by the previous call on this plan (another rank, or the last
     // training step) is used as it is: the select kernels keep it tuned and withdraw it
     // when it fails, and whatever it is worth the result stays exact.
+    // After a call whose candidates came out short (the scale dropped since the hint was
+    // tuned; nothing in the scan can repair that direction) the next few calls sample as
+    // well and take the lower of the two.
     const uint32_t hb = hint[l];
-    if (hb) {
+    uint32_t *watch = hint + L;
+    const uint32_t wt = watch[l];
+    if (hb && !wt) {
         if (tid == 0) {
             sel[l] = r;
             binlo[l] = hb;
@@ -368,7 +373,9 @@ sample_kernel(const char *__restrict__ grad, const char *acc, const SentMap sent
     if (tid == 0) {
         if (!found) r.route = 1;  // the sample holds too few non-zeros to say anything
         sel[l] = r;
-        binlo[l] = max(bin, 1u);  // bin 0 (|g| < 2^-133) is never a candidate
+        bin = max(bin, 1u);  // bin 0 (|g| < 2^-133) is never a candidate
+        binlo[l] = hb && found ? min(hb, bin) : bin;
+        if (wt) watch[l] = wt - 1;
     }
 }
 
@@ -406,6 +413,7 @@ constexpr uint32_t kSpillWindow = 768;
 constexpr uint32_t kSpillThreads = 512;
 constexpr uint32_t kSpillStage = 512;  // staged slots per wave
 constexpr uint32_t kSpillList = 16;    // staged chunks per wave
+constexpr uint32_t kWatchCalls = 8;    // calls that sample beside the carried pre-threshold after a miss
 constexpr uint32_t kSpillRaise = 6;    // bins (1/128 octave each) a wave's pre-threshold goes up per try
 
 template <int DTYPE>
@@ -804,7 +812,8 @@ __device__ inline void hist_elem(uint32_t f32bits, uint32_t *h)
 // candidates only (a miss re-routes the segment); 1: segment on the dense route, histogram
 // of everything.
 template <int DTYPE>
-__device__ inline void select1_segment(uint32_t l, const SegDev &sd, const uint32_t *hist,
+__device__ inline void select1_segment(uint32_t n_seg, uint32_t l, const SegDev &sd,
+                                       const uint32_t *hist,
                                        SelDev *sel, uint32_t *cnt, uint32_t dense,
                                        const uint32_t *binlo, const uint32_t *raised,
                                        uint32_t *hint, uint32_t *smem /* >= 32 words */)
@@ -843,6 +852,7 @@ __device__ inline void select1_segment(uint32_t l, const SegDev &sd, const uint3
     }
     if (!found && !dense) {  // the candidates hold fewer than k entries: dense route
         sel[l].route = 1;
+        if (fast) hint[n_seg + l] = kWatchCalls;  // and the next calls sample beside the hint
         return;
     }
     if (nf) atomicAdd(&cnt[TAGC_CNT_NONFINITE], nf);
@@ -879,7 +889,7 @@ select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     __shared__ uint32_t smem[32];
     const uint32_t l = blockIdx.x;
     const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
-    select1_segment<DTYPE>(l, sd, hist, sel, cnt, 0, binlo, raised, hint, smem);
+    select1_segment<DTYPE>(table[0], l, sd, hist, sel, cnt, 0, binlo, raised, hint, smem);
 }
 
 // Dense route: one workgroup per CU, 32768 LDS counters, all entries of every dense-route
@@ -950,7 +960,7 @@ hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, 
         __syncthreads();
         if (s_last) {  // uniform
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            select1_segment<DTYPE>(l, sd, hist, sel, cnt, 1, binlo, nullptr, hint, s_sel);
+            select1_segment<DTYPE>(L, l, sd, hist, sel, cnt, 1, binlo, nullptr, hint, s_sel);
         }
         __syncthreads();
     }

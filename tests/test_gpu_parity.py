@@ -334,6 +334,26 @@ def test_pre_threshold_carried_between_calls_never_changes_results(dtype):
     assert dense[6] == 0                        # and recovered (rank 5 still pays for rank 4)
 
 
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+def test_falling_scale_costs_one_fallback_not_one_per_call(dtype):
+    """Every call sees gradients 12 % smaller than the one before: the carried pre-threshold
+    is too high each time.  The first such call falls back to the two-read route; after it
+    the plan samples beside the carried value for a few calls and takes the lower of the
+    two, so the following calls do not.  Results exact throughout."""
+    _announce("falling scale dtype=%d" % dtype)
+    n = (1 << 19) + 40
+    rng = np.random.default_rng(5)
+    scales = [1e-3 * 0.88 ** r for r in range(7)]
+    td = torch.float32 if dtype == G.F32 else torch.bfloat16
+    grads = [torch.from_numpy((rng.standard_normal(n) * sc).astype(np.float32)).to(td)
+             for sc in scales]
+    b = G.Bucket("falling", dtype, len(scales), [G.Seg(0, n, 10_000, 1, "w")], n, 3000)
+    ores, tb = run_both(b, grads, seed=4)
+    compare_all(b, ores, tb)
+    dense = [tb.rank_counts(r)["dense_segments"] for r in range(len(scales))]
+    assert dense == [0, 1, 0, 0, 0, 0, 0]
+
+
 def test_more_than_64_candidate_route_segments():
     """70 segments that all take the candidate route (the final kernel reads the segment
     tables lane-parallel for up to 64 segments and falls back to a search beyond), with
