@@ -553,28 +553,31 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                     }
                 }
             };
-            // the sums of chunk `ch` back to the accumulator (entries inside the segment only)
-            auto store_chunk = [&](uint32_t ch, const uint32_t (&w)[ROWS][4]) {
+            // The sums of chunk `ch` back to the accumulator (entries inside the segment only),
+            // from the chunk's LDS copy: the stores are issued after the next chunk's loads,
+            // whose registers the sums no longer occupy, so that waiting for those loads does
+            // not mean waiting for the stores' acknowledgements as well.
+            auto store_chunk = [&](uint32_t ch) {
                 const uint32_t rel0 = ch * CHUNK;
                 if (rel0 + CHUNK <= sd.n) {
                     uint4 *q = reinterpret_cast<uint4 *>(abase + uint64_t(rel0) * EB) + lane;
 #pragma unroll
-                    for (uint32_t r = 0; r < ROWS; ++r)
-                        st_stream(q + 64 * r, make_uint4(w[r][0], w[r][1], w[r][2], w[r][3]));
+                    for (uint32_t r = 0; r < ROWS; ++r) st_stream(q + 64 * r, dw[r * 64 + lane]);
                 } else {
 #pragma unroll
                     for (uint32_t r = 0; r < ROWS; ++r) {
                         const uint32_t rel = rel0 + r * ROW_ELEMS + lane * VEC;
+                        const uint4 v = dw[r * 64 + lane];
+                        const uint32_t x[4] = {v.x, v.y, v.z, v.w};
                         if (rel + VEC <= sd.n) {
-                            *reinterpret_cast<uint4 *>(abase + uint64_t(rel) * EB) =
-                                make_uint4(w[r][0], w[r][1], w[r][2], w[r][3]);
+                            *reinterpret_cast<uint4 *>(abase + uint64_t(rel) * EB) = v;
                         } else if (rel < sd.n) {
 #pragma unroll
                             for (uint32_t e = 0; e < VEC; ++e) {
                                 if (rel + e >= sd.n) continue;
                                 const uint32_t b = DTYPE == kBF16
-                                                       ? (w[r][e >> 1] >> (16 * (e & 1))) & 0xFFFFu
-                                                       : w[r][e];
+                                                       ? (x[e >> 1] >> (16 * (e & 1))) & 0xFFFFu
+                                                       : x[e];
                                 store_elem(abase, uint64_t(rel) + e, b, DTYPE);
                             }
                         }
@@ -606,7 +609,6 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
 #pragma unroll
                         for (uint32_t j = 0; j < 4; ++j)
                             w[r][j] = sum_word<DTYPE>(w[r][j], unsent_word<DTYPE>(aw[r][j], sb[r], j));
-                    store_chunk(ch, w);
                 }
                 // Keep the chunk in LDS (a lane only ever reads back what it wrote itself).
                 // Branch-free classification: bit r*VEC + e of `mask` <=> entry e of the
@@ -641,6 +643,7 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                         load_sent(ch + NW, sb);
                     }
                 }
+                if (acc) store_chunk(ch);
                 // slot of each lane's first candidate per row: one scan over the four
                 // row counts packed in 16-bit fields (a row holds at most 512 candidates)
                 uint32_t p01, p23, total;
