@@ -228,3 +228,14 @@ def test_one_segment_of_almost_two_to_the_31_entries():
     rel = (out_val - val).abs() / val.abs()
     assert int((off & (rel > 1e-5)).sum()) <= st["n_unresolved"]
     _say("decode: %d unresolved of %d, %d rounds" % (st["n_unresolved"], k, st["rounds"]))
+
+
+def test_7b_shaped_bucket_in_fp32():
+    """The same block shapes with float32 gradients (4 ranks): the path that needs the low 16
+    key bits as well (a second histogram over the candidates of the threshold bin)."""
+    import dataclasses
+    print("\n[case] config5 block 0 shapes, fp32, 4 ranks", flush=True)
+    b = dataclasses.replace(G.config5(0)[0], dtype=G.F32, n_ranks=4)
+    data = [G.rank_gradient(b, r, "cuda") for r in range(b.n_ranks)]
+    assert data[0].dtype == torch.float32
+    _check_full_size(b, data, oracle_ranks=(1,))
