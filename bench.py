@@ -53,9 +53,14 @@ def parse_args():
     ap.add_argument("--dense", type=int, default=1, help="also write the dense summed gradient")
     ap.add_argument("--buckets", type=int, default=0,
                     help="only the first B buckets of the workload (0 = all; for experiments)")
-    ap.add_argument("--lanes", type=int, default=6,
+    ap.add_argument("--lanes", type=int, default=12,
                     help="buckets in flight at once: bucket i runs on HIP stream i %% lanes with "
                          "that lane's own buffers (buckets are independent of each other)")
+    ap.add_argument("--decode-workgroups", type=int, default=64,
+                    help="with more than one bucket in flight: most workgroups of the peeling "
+                         "kernel at once (it needs a compute unit's whole local memory, so "
+                         "this leaves the other compute units to the other buckets' "
+                         "bandwidth-bound kernels); 0 = one per compute unit")
     ap.add_argument("--part-unknowns", type=int, default=0,
                     help="non-zeros per sketch partition (0 = library default)")
     ap.add_argument("--part-cells", type=int, default=0,
@@ -256,6 +261,7 @@ def main():
             need[k] = max(need[k], getattr(z, f))
         B.tagc_plan_destroy(plan)
     lanes = max(1, min(args.lanes, n_b))
+    peel_wgs = args.decode_workgroups if lanes > 1 else 0
     tbs = []
     for i, b in enumerate(buckets):
         first = i < lanes  # a lane's first bucket owns the buffers the lane's others reuse
@@ -265,6 +271,7 @@ def main():
                               error_feedback=args.error_feedback,
                               decode_mode=args.decode_mode, index_mode=args.index_mode,
                               sizing=sizing, cell_type=int(args.cell_bits == 16),
+                              decode_workgroups=peel_wgs,
                               share=None if first else tbs[i % lanes],
                               min_bytes=need if first else None))
     stream = torch.cuda.current_stream()
@@ -276,7 +283,8 @@ def main():
         cur = data_sets[step_no[0] % n_sets]  # every step a different gradient, in turn
         step_no[0] += 1
         for i in range(n_b):
-            tbs[i].run(cur[i % pool], stream if one_stream else streams[i % lanes])
+            tbs[i].run(cur[i % pool], stream if one_stream else streams[i % lanes],
+                       whole_device_decode=one_stream)
 
     for _ in range(args.warmup):
         step()
@@ -336,7 +344,7 @@ def main():
         def step(one_stream=False):  # noqa: F811 -- the timed steps replay the graphs
             if one_stream:
                 for i in range(n_b):
-                    tbs[i].run(data[i % pool], stream)
+                    tbs[i].run(data[i % pool], stream, whole_device_decode=True)
                 return
             for i in range(n_b):
                 with torch.cuda.stream(streams[i % lanes]):
@@ -403,8 +411,8 @@ def main():
                     "traffic": MEASURED_TRAFFIC.get((args.workload, dom)),
                     "avg_launch_ms": round(avg_ms, 5), "launches": d_n,
                     "alg_bytes_per_launch": int(per_launch),
-                    "events_pass": "same steps, one bucket in flight, HIP events around "
-                                   "every kernel on its stream",
+                    "events_pass": "same steps, one bucket in flight (so decode on the whole "
+                                   "device), HIP events around every kernel on its stream",
                     "events_pass_ms_per_step": round(1e3 * t_prof / args.steps, 3),
                     "kernels_ms_per_step": {k: round(v[0] / args.steps, 4)
                                             for k, v in sorted(prof.items(),
@@ -424,7 +432,7 @@ def main():
                                   buckets[0].sizing_milli / 1000.0,
                                   "sparse+dense output" if args.dense else "sparse output"),
                    "input_bytes_per_step": input_bytes, "distinct_bucket_data_sets": pool,
-                   "buckets_in_flight": lanes,
+                   "buckets_in_flight": lanes, "decode_workgroups": peel_wgs,
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,

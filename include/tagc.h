@@ -88,6 +88,16 @@ typedef struct tagc_config {
     uint32_t decode_mode;   /* TAGC_DECODE_*; 0 = peeling only                  */
     uint32_t cell_type;     /* TAGC_CELL_*: what a cell of a rank's sketch is on
                                the wire; 0 = float32                            */
+    uint32_t decode_workgroups; /* most workgroups the peeling kernel of
+                               tagc_decompress runs at once; 0 = one per compute
+                               unit.  A peeling workgroup needs a compute unit's
+                               whole local memory, so a caller that keeps other
+                               buckets' work in flight on other streams leaves
+                               the rest of the device to them with a value
+                               like a quarter of the compute units.  Results
+                               and buffer sizes do not depend on it: plans that
+                               differ in nothing else work on the same buffers  */
+    uint32_t reserved;      /* must be 0                                        */
 } tagc_config;
 
 /*

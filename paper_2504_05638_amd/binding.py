@@ -43,7 +43,8 @@ class tagc_config(C.Structure):
                 ("sizing_milli", C.c_uint32), ("index_mode", C.c_uint32),
                 ("part_unknowns", C.c_uint32), ("part_cells", C.c_uint32),
                 ("seed", C.c_uint64), ("decode_mode", C.c_uint32),
-                ("cell_type", C.c_uint32)]
+                ("cell_type", C.c_uint32), ("decode_workgroups", C.c_uint32),
+                ("reserved", C.c_uint32)]
 
 
 _SIZE_FIELDS = [

@@ -29,7 +29,8 @@ class TagcBucket:
                  sizing=B.TAGC_SIZE_LOAD_FACTOR, seed=0, part_unknowns=0,
                  part_cells=0, device="cuda", dense=False, share=None, min_bytes=None,
                  error_feedback=False, decode_mode=B.TAGC_DECODE_PEEL,
-                 index_mode=B.TAGC_INDEX_OR1, cell_type=B.TAGC_CELL_F32):
+                 index_mode=B.TAGC_INDEX_OR1, cell_type=B.TAGC_CELL_F32,
+                 decode_workgroups=0):
         if not torch.cuda.is_available():
             raise RuntimeError("libtagc needs a GPU: no CPU path exists")
         self.device = torch.device(device)
@@ -38,9 +39,18 @@ class TagcBucket:
                                  index_mode=index_mode,
                                  part_unknowns=part_unknowns,
                                  part_cells=part_cells, seed=seed,
-                                 decode_mode=decode_mode, cell_type=cell_type)
+                                 decode_mode=decode_mode, cell_type=cell_type,
+                                 decode_workgroups=decode_workgroups)
         self.segments = [tuple(s[:4]) for s in segments]
         self.plan = B.tagc_plan(self.cfg, self.segments)
+        # decode_workgroups only shapes tagc_decompress's launch: a plan that differs in
+        # nothing else works on the same buffers (for a caller that sometimes decodes with
+        # the device to itself)
+        self.plan_whole = None
+        if decode_workgroups:
+            cfg0 = B.tagc_config.from_buffer_copy(self.cfg)
+            cfg0.decode_workgroups = 0
+            self.plan_whole = B.tagc_plan(cfg0, self.segments)
         self.sizes = B.tagc_plan_sizes(self.plan)
         self.n_ranks = n_ranks
         z, dev = self.sizes, self.device
@@ -106,6 +116,9 @@ class TagcBucket:
         if self.plan is not None:
             B.tagc_plan_destroy(self.plan)
             self.plan = None
+        if getattr(self, "plan_whole", None) is not None:
+            B.tagc_plan_destroy(self.plan_whole)
+            self.plan_whole = None
 
     def __del__(self):
         try:
@@ -145,13 +158,14 @@ class TagcBucket:
                          self.rk[:n_ranks or self.n_ranks], self.shared,
                          _stream_ptr(stream))
 
-    def decompress(self, stream=None):
-        B.tagc_decompress(self.plan, self.shared, self.out_idx.data_ptr(),
+    def decompress(self, stream=None, whole_device=False):
+        plan = self.plan_whole if whole_device and self.plan_whole is not None else self.plan
+        B.tagc_decompress(plan, self.shared, self.out_idx.data_ptr(),
                           self.out_val.data_ptr(),
                           self.out_dense.data_ptr() if self.out_dense is not None else None,
                           _stream_ptr(stream))
 
-    def run(self, grads, stream=None):
+    def run(self, grads, stream=None, whole_device_decode=False):
         """The whole hot path for one bucket; grads[r] is rank r's buffer."""
         n = len(grads)
         for r in range(n):
@@ -160,7 +174,7 @@ class TagcBucket:
         for r in range(n):
             self.compress_sketch(r, stream)
         self.aggregate_sketch(n, stream)
-        self.decompress(stream)
+        self.decompress(stream, whole_device_decode)
 
     # ---------------------------------------------------------- read-backs
 

@@ -394,7 +394,9 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
     {
         ProfileScope ps("peel", s);
         const size_t lds = decode_lds_bytes(p->T_cap, p->P_cap);
-        const uint32_t grid = uint32_t(std::min<uint64_t>(p->A_cap, uint64_t(device_cu_count())));
+        // a workgroup takes partitions b, b + grid, ...: any grid size gives the same result
+        uint32_t grid = uint32_t(std::min<uint64_t>(p->A_cap, uint64_t(device_cu_count())));
+        if (p->cfg.decode_workgroups) grid = std::min(grid, p->cfg.decode_workgroups);
         // the default partition size gets an instantiation that holds exactly its data
         constexpr uint32_t kC0 = (kDefaultPartCells + kDecodeThreads - 1) / kDecodeThreads;
         constexpr uint32_t kI0 = (kDefaultPartUnknowns + kDecodeThreads - 1) / kDecodeThreads;

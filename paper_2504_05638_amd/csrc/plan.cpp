@@ -29,7 +29,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     if (cfg->sizing != TAGC_SIZE_LOAD_FACTOR && cfg->sizing != TAGC_SIZE_FIXED_RATIO)
         return TAGC_EINVAL;
     if (cfg->index_mode > TAGC_INDEX_ADD4) return TAGC_EUNSUPPORTED;
-    if (cfg->decode_mode > TAGC_DECODE_ESTIMATE || cfg->cell_type > TAGC_CELL_BF16)
+    if (cfg->decode_mode > TAGC_DECODE_ESTIMATE || cfg->cell_type > TAGC_CELL_BF16 ||
+        cfg->reserved != 0)
         return TAGC_EINVAL;
     uint32_t P_cap = cfg->part_unknowns ? cfg->part_unknowns : kDefaultPartUnknowns;
     uint32_t T_cap = cfg->part_cells ? cfg->part_cells : kDefaultPartCells;

@@ -69,7 +69,7 @@ def estimate_tolerance(ores, seed, rel=1e-5):
 
 
 def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTOR, dense=True,
-             decode_mode=0, index_mode=0, cell_type=0):
+             decode_mode=0, index_mode=0, cell_type=0, decode_workgroups=0):
     """Runs oracle and library on the same inputs; returns (oracle result, TagcBucket)."""
     import torch
     from paper_2504_05638_amd.bucket import TagcBucket
@@ -80,7 +80,8 @@ def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTO
     tb = TagcBucket(bucket.segments, bucket.dtype, len(grads_torch_cpu),
                     sizing_milli=bucket.sizing_milli, sizing=sizing, seed=seed,
                     part_unknowns=P, part_cells=T, dense=dense, decode_mode=decode_mode,
-                    index_mode=index_mode, cell_type=cell_type)
+                    index_mode=index_mode, cell_type=cell_type,
+                    decode_workgroups=decode_workgroups)
     dev = [g.cuda() for g in grads_torch_cpu]
     tb.run(dev)
     torch.cuda.synchronize()

@@ -306,6 +306,36 @@ def test_buckets_in_flight_on_separate_streams():
         compare_all(b, ores, tb)
 
 
+@pytest.mark.parametrize("wgs", [1, 4, 64])
+def test_decode_on_a_limited_number_of_workgroups(wgs):
+    """A caller with other buckets in flight limits the peeling kernel's grid; a workgroup
+    then takes several partitions in turn (18 here, so 1 -> all of them, 4 -> a ragged
+    deal, 64 -> some workgroups idle).  Integer inputs: bit for bit, sparse and dense;
+    then the same buffers decoded by the sibling plan without the limit."""
+    _announce("decode_workgroups=%d" % wgs)
+    rng = np.random.default_rng(21)
+    n, N = 400_000, 4
+    segs = [G.Seg(0, 150_000, 30_000, 1, "a"), G.Seg(150_000, 250_000, 20_000, 1, "b")]
+    b = G.Bucket("ints", G.BF16, N, segs, n, 1500)
+    grads = [torch.from_numpy(rng.integers(-100, 101, n).astype(np.float32)).to(torch.bfloat16)
+             for _ in range(N)]
+    ores, tb = run_both(b, grads, seed=2, P=2048, T=3072, decode_workgroups=wgs)
+    hdr, st = compare_all(b, ores, tb, exact_values=True)
+    assert hdr["A"] > 16 and hdr["A"] % 4 and st["n_unresolved"] == 0
+    nv, nd = 4 * hdr["U"], 4 * tb.sizes.n_c      # bytes the decoder writes
+    f32 = lambda t, nb: t[:nb].view(torch.float32)   # as numbers: a sum that cancels may
+    val, dense = f32(tb.out_val, nv).clone(), f32(tb.out_dense, nd).clone()  # be +0 or -0
+    tb.out_val.zero_()
+    tb.out_dense.zero_()
+    tb.decompress(whole_device=True)
+    torch.cuda.synchronize()
+    assert torch.equal(f32(tb.out_val, nv), val) and torch.equal(f32(tb.out_dense, nd), dense)
+    # random floats too, against the oracle within the usual tolerance
+    b2 = G.small_mixed_bucket(seed=5, dtype=G.F32, n_ranks=3, sizing_milli=1500)
+    ores, tb = run_both(b2, _grads(b2), seed=6, P=256, T=768, decode_workgroups=wgs)
+    compare_all(b2, ores, tb)
+
+
 @pytest.mark.parametrize("dtype", [G.F32, G.BF16])
 def test_pre_threshold_carried_between_calls_never_changes_results(dtype):
     """A plan keeps each segment's pre-threshold from one PHASE_INDEX call to the next.

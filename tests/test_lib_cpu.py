@@ -90,7 +90,7 @@ def test_argument_errors():
     seg = [(0, 1000, 10_000, 1)]
     for bad in (dict(dtype=7), dict(n_hash=2), dict(n_ranks=0), dict(sizing=9),
                 dict(sizing_milli=0), dict(part_cells=100), dict(part_cells=3 * 6000),
-                dict(part_unknowns=1 << 20)):
+                dict(part_unknowns=1 << 20), dict(reserved=1)):
         with pytest.raises(B.TagcError) as e:
             B.tagc_plan(_cfg(**bad), seg)
         assert e.value.code == -1
@@ -105,6 +105,10 @@ def test_argument_errors():
     with pytest.raises(B.TagcError):
         B.tagc_plan(_cfg(), [(0, 1000, 2_000_000, 1)])
     assert B.strerror(-2).startswith("size")
+    # any limit on the peeling grid is a valid plan, with the same sizes
+    z0 = B.tagc_plan_sizes(B.tagc_plan(_cfg(), seg))
+    z1 = B.tagc_plan_sizes(B.tagc_plan(_cfg(decode_workgroups=1 << 30), seg))
+    assert bytes(z0) == bytes(z1)
     # null / misaligned device pointers are rejected before anything is launched
     plan = B.tagc_plan(_cfg(), seg)
     rk, sh = B.tagc_rank_buffers(), B.tagc_shared_buffers()
