@@ -203,7 +203,8 @@ enum {
     TAGC_ST_ESTIMATED = 3,  /* entries whose value is an estimate                */
     TAGC_ST_WORDS = 8
 };
-#define TAGC_FLAG_SPIN_LIMIT 1u /* an internal bounded wait gave up: results invalid */
+#define TAGC_FLAG_SPIN_LIMIT 1u /* reserved: no wait between workgroups can fail, see
+                                   tagc_test_help_after                              */
 #define TAGC_FLAG_OVERFLOW 2u   /* a capacity was exceeded: results invalid          */
 
 /* Device buffers of one simulated rank (all dev, caller-owned). */
@@ -350,6 +351,17 @@ int tagc_decompress(const tagc_plan_t *plan, const tagc_shared_buffers *shared,
 int tagc_profile_enable(int on);
 int tagc_profile_read(const char **names, double *total_ms, uint64_t *launches,
                       uint32_t cap);
+
+/*
+ * For tests.  Where a workgroup of PHASE_INDEX's last kernel needs a count that
+ * another workgroup publishes, it polls for it `polls` times and then computes it
+ * itself from the same input (the other workgroup may not have started: other
+ * streams' kernels can hold its place), so results never depend on the value.
+ * The default is a few hundred; 0 makes every count that is not there at the
+ * first look be recomputed, which is how the tests reach that path.  Process-wide,
+ * takes effect at the next tagc_compress; returns the previous value.
+ */
+uint32_t tagc_test_help_after(uint32_t polls);
 
 /* Hash function j (0..2) of c-index i for a sub-table of m_sub cells, as the
  * device code computes it (host helper for tests and tools). */

@@ -29,7 +29,7 @@ TAGC_FLAG_SPIN_LIMIT, TAGC_FLAG_OVERFLOW = 1, 2
 EXPORTS = ["tagc_plan", "tagc_plan_destroy", "tagc_plan_sizes",
            "tagc_plan_upload", "tagc_compress", "tagc_feedback_apply", "tagc_aggregate",
            "tagc_decompress", "tagc_profile_enable", "tagc_profile_read",
-           "tagc_hash_host", "tagc_strerror"]
+           "tagc_test_help_after", "tagc_hash_host", "tagc_strerror"]
 
 
 class tagc_segment(C.Structure):
@@ -123,6 +123,8 @@ def lib():
         L.tagc_decompress.restype = C.c_int
         L.tagc_decompress.argtypes = [vp, C.POINTER(tagc_shared_buffers), vp,
                                       vp, vp, vp]
+        L.tagc_test_help_after.restype = C.c_uint32
+        L.tagc_test_help_after.argtypes = [C.c_uint32]
         L.tagc_profile_enable.restype = C.c_int
         L.tagc_profile_enable.argtypes = [C.c_int]
         L.tagc_profile_read.restype = C.c_int
@@ -200,6 +202,11 @@ def tagc_decompress(plan, shared: tagc_shared_buffers, idx_out, val_out,
                     dense_out=None, stream: int = 0):
     _check(lib().tagc_decompress(plan, C.byref(shared), idx_out, val_out,
                                  dense_out, stream), "tagc_decompress")
+
+
+def tagc_test_help_after(polls: int) -> int:
+    """Sets after how many polls a missing count is recomputed; returns the old value."""
+    return int(lib().tagc_test_help_after(int(polls)))
 
 
 def tagc_profile_enable(on: bool):

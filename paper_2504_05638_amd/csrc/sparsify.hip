@@ -41,8 +41,9 @@
 // counters on the wire (section 2.2) widen4 turns the Index into them at the end.
 //
 // Ordered output across workgroups: every item publishes its counts as soon as it has
-// them and learns its offset from the counts of earlier items only, which belong to
-// workgroups dispatched before its own; no kernel needs the device to itself.
+// them and learns its offset from the counts of earlier items only; counts that are not
+// there after a bounded number of polls it computes itself, so no workgroup depends on
+// another one's progress and no kernel needs the device to itself.
 #include "device_utils.h"
 #include "tagc_internal.h"
 
@@ -1072,15 +1073,19 @@ select2_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
 
 constexpr uint64_t kStAgg = 1ull << 62, kStPre = 2ull << 62, kStMask = 3ull << 62;
 
-// Decoupled look-back over the work items (tiles / super-chunks) of one segment, run by
-// the first wave of the workgroup.  state word = status(2) | count(key > T)(31) |
-// count(key == T)(31).  Workgroup b takes items b, b+G, b+2G, ... of a grid of G.  With one
-// item per workgroup every predecessor belongs to a lower-numbered workgroup, dispatched
-// earlier, which publishes its counts without waiting for any later item; with several
-// items per workgroup the same holds only while the whole grid is resident.  The wait is
-// bounded all the same: after kSpinLimit polls it gives up and raises a flag.
+// Decoupled look-back over the tiles of one segment, run by the first wave of the
+// workgroup.  state word = status(2) | count(key > T)(31) | count(key == T)(31).  A tile
+// publishes its counts without waiting for any other tile, so a predecessor that is
+// running is never waited for long.  One that has not started may take arbitrarily long:
+// the device's dies hand out their shares of a grid independently of each other, so with
+// other kernels in flight a lower-numbered workgroup can still be waiting for room on its
+// die while higher-numbered ones hold theirs, and two kernels that wait like this can hold
+// each other's room for good.  So the wait never decides anything: after `help_after`
+// polls the wave recounts the missing tile itself (`recount(tile)`, wave-uniform, from the
+// same input) and goes on.
+template <typename Recount>
 __device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, uint64_t agg,
-                                    uint32_t *flags)
+                                    uint32_t help_after, Recount &&recount)
 {
     const uint32_t l = lane_id();
     if (t == t0) {
@@ -1096,9 +1101,14 @@ __device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, ui
         const bool real = i >= int64_t(t0);
         uint64_t s = real ? ld_agent(&state[i]) : kStPre;
         while (__any((s & kStMask) == 0)) {
-            if (++spins > kSpinLimit) {
-                if (l == 0) atomicOr(flags, TAGC_FLAG_SPIN_LIMIT);
-                s |= kStPre;  // give up: result invalid, but every wave still exits
+            if (spins++ >= help_after) {
+                uint64_t miss = __ballot((s & kStMask) == 0);
+                while (miss) {  // one missing tile at a time, by the whole wave
+                    const uint32_t src = uint32_t(__builtin_ctzll(miss));
+                    miss &= miss - 1;
+                    const uint64_t a = recount(uint32_t(j - int64_t(src)));
+                    if (l == src) s = kStAgg | a;
+                }
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
@@ -1153,13 +1163,14 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // only what exceeds that (items keeping more than about 2 %) is stored directly.
 //
 // The prefix over earlier super-chunks has no chain: an item publishes its own counts,
-// then its threads add up the counts of all predecessors in its segment, each thread
-// waiting (bounded) only for the words it reads.  A predecessor publishes right after
-// counting and waits for nobody before that.  The launch has one workgroup per
-// kEmitItems adjacent items, so a predecessor always belongs to this or a lower-numbered
-// workgroup, which the hardware has dispatched before this one: the wait ends however few
-// workgroups are resident at a time (other streams may be using the device).
-constexpr int kEmitItems = 2;
+// then its threads add up the counts of all predecessors in its segment.  A predecessor
+// publishes right after counting and waits for nobody before that, so a word that is not
+// there yet is polled for -- but only `help_after` times: a predecessor's workgroup may
+// not have started (see lookback), and after that the thread counts the predecessor's
+// slots itself.  No workgroup depends on another one's progress.  (Handing the items out
+// in order by ticket instead, so that a predecessor has always started, was measured: one
+// counter for the ~1500 workgroups of a 200 M-entry bucket costs 30 ns per ticket, 44 us
+// on a 31 us kernel; one counter per segment still 14 us.)
 constexpr uint32_t kEmitStage = 800;  // survivors of an item that go through LDS
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
@@ -1170,7 +1181,8 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
             const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
             uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_state,
             uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
-            uint32_t *__restrict__ bitmap, uint32_t *cnt, uint64_t *stamps)
+            uint32_t *__restrict__ bitmap, uint32_t *cnt, uint32_t help_after,
+            uint64_t *stamps)
 {
 #ifdef TAGC_PHASE_TIMING
     // per-workgroup time stamps (100 MHz counter) in the look-back area of the dense route,
@@ -1317,7 +1329,25 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
             st_agent(&sc_state[sc], kStAgg | (uint64_t(it_gt) << 31) | uint64_t(it_eq));
         EMIT_STAMP(2);
         // ---- prefix over the segment's earlier super-chunks: four words requested at a
-        // time, then each is waited for (bounded) only if it has not been published yet
+        // time, then each is polled for only if it has not been published yet
+        // what super-chunk j of this segment publishes, from its slots
+        auto count_item = [&](uint32_t j) -> uint64_t {
+            uint32_t gt = 0, eq = 0;
+            const uint32_t rel0 = (j - sc_first) * SC_ELEMS;
+            for (uint32_t c = 0; c < kCandChunksPerSuper; ++c) {
+                if (se_cnt == 0 || rel0 + c * CHUNK >= n_seg) break;
+                const uint32_t gg = j * kCandChunksPerSuper + c;
+                const uint32_t n = min(chunk_cnt[gg], CAP);
+                const uint32_t *slots = cand + uint64_t(gg) * CAP;
+                for (uint32_t i = 0; i < n; ++i) {
+                    const uint32_t vb = DTYPE == kBF16 ? slots[i] & 0xFFFF0000u : slots[i];
+                    const uint32_t key = vb & 0x7FFFFFFFu;
+                    gt += key > T;
+                    eq += (key == T) && quota;
+                }
+            }
+            return (uint64_t(gt) << 31) | uint64_t(eq);
+        };
         uint64_t sum = 0;
         if (live) {
             for (uint32_t j0 = sc_first + tt; j0 < sc; j0 += 4 * 128) {
@@ -1332,8 +1362,8 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
                     const uint32_t j = j0 + u * 128;
                     uint32_t spins = 0;
                     while ((v[u] & kStMask) == 0) {  // an earlier workgroup, still counting
-                        if (++spins > kSpinLimit) {
-                            atomicOr(&cnt[TAGC_CNT_FLAGS], TAGC_FLAG_SPIN_LIMIT);
+                        if (spins++ >= help_after) {     // or not even started
+                            v[u] = count_item(j);
                             break;
                         }
                         __builtin_amdgcn_s_sleep(1);
@@ -1421,7 +1451,7 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
                const SelDev *__restrict__ sel, uint64_t *tile_state,
                uint32_t *__restrict__ idx_out,
                float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt,
-               uint32_t *ticket)
+               uint32_t *ticket, uint32_t help_after)
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
@@ -1533,8 +1563,22 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
         }
         // ---- look-back across the tiles of this segment + pair offset of the segment
         if (tid < 64) {
+            // the counts tile `ti` of this segment publishes, from the input itself
+            auto recount = [&](uint32_t ti) -> uint64_t {
+                uint32_t gt = 0, eq = 0;
+                if (se.cnt != 0) {
+                    const uint32_t r0 = (ti - sd.tile_start) * TILE;
+                    const uint32_t r1 = min(r0 + TILE, sd.n);
+                    for (uint32_t rel = r0 + tid; rel < r1; rel += 64) {
+                        const uint32_t key = load_elem_bits(base, rel, DTYPE) & 0x7FFFFFFFu;
+                        gt += key > se.T;
+                        eq += key == se.T && se.quota;
+                    }
+                }
+                return (uint64_t(wave_sum<uint32_t>(gt)) << 31) | wave_sum<uint32_t>(eq);
+            };
             uint64_t ex = lookback(tile_state, t, sd.tile_start, (uint64_t(Gt) << 31) | Et,
-                                   &cnt[TAGC_CNT_FLAGS]);
+                                   help_after, recount);
             uint32_t sb = 0;
             for (uint32_t i = tid; i < l; i += 64) sb += sel[i].cnt;
             sb = wave_sum<uint32_t>(sb);
@@ -1603,8 +1647,7 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
 // The last kernel of PHASE_INDEX: its first `n_emit` workgroups emit the candidate-route
 // segments, the rest compact the dense-route ones (both write pairs and Index words, of
 // different segments).  One launch instead of two: when a bucket has no dense-route work
-// the second part costs nothing, not even an empty kernel's turn-around.  Workgroups are
-// dispatched in order, so inside each part a workgroup still only waits for earlier ones.
+// the second part costs nothing, not even an empty kernel's turn-around.
 static_assert(kEmitThreads == kCompactThreads, "one launch for both parts");
 
 template <int DTYPE, uint32_t COMPACT_ROWS>
@@ -1615,14 +1658,14 @@ finish_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ ta
               const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
               uint64_t *sc_state, uint64_t *tile_state, uint32_t *__restrict__ idx_out,
               float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt,
-              uint32_t *ticket)
+              uint32_t *ticket, uint32_t help_after)
 {
     if (blockIdx.x < n_emit)
         emit_body<DTYPE>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
-                         CAP, sc_state, idx_out, val_out, bitmap, cnt, tile_state);
+                         CAP, sc_state, idx_out, val_out, bitmap, cnt, help_after, tile_state);
     else
         compact_body<DTYPE, COMPACT_ROWS>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, table, sel,
-                            tile_state, idx_out, val_out, bitmap, cnt, ticket);
+                            tile_state, idx_out, val_out, bitmap, cnt, ticket, help_after);
 }
 
 template <typename K>
@@ -1800,13 +1843,11 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
                                                &occ_finish[p->compact_rows == 4]);
         if (occ <= 0) return TAGC_EHIP;
         const uint32_t n_emit = (p->total_sc + kEmitItems - 1) / kEmitItems;
-        // Compaction: one tile per workgroup when dense-route work is certain: a tile's
-        // look-back then only ever waits for lower-numbered workgroups, which were
-        // dispatched before it, so it ends no matter how few workgroups the device can hold
-        // at the moment.  When no segment is planned for this route the part is only a
-        // safety net for re-routed segments and nearly always exits at once; a small
-        // persistent grid keeps that cheap, and deals its tiles out by ticket so that the
-        // same guarantee holds (one atomic per tile is affordable on that rare path).
+        // Compaction: one tile per workgroup when dense-route work is certain.  When no
+        // segment is planned for this route the part is only a safety net for re-routed
+        // segments and nearly always exits at once; a small persistent grid keeps that
+        // cheap, and deals its tiles out by ticket, in order (one atomic per tile is
+        // affordable on that rare path).
         const uint32_t n_compact =
             p->static_dense ? p->total_tiles
                             : std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
@@ -1814,7 +1855,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         kernel<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
             n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state,
             tile_state,
-            rk->idx, rk->val, bitmap1, rk->cnt, ticket);
+            rk->idx, rk->val, bitmap1, rk->cnt, ticket, help_after_polls());
     }
     if (wide && p->n_c) {
         ProfileScope ps("widen4", s);

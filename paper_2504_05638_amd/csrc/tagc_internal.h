@@ -19,6 +19,7 @@ constexpr uint32_t kCompactThreads = 256;
 constexpr uint32_t kCandRows = 4;        // 16-byte vectors per lane per candidate chunk
 constexpr uint32_t kCandChunksPerSuper = 32;  // chunks one emit workgroup handles
 constexpr uint32_t kEmitThreads = 256;
+constexpr int kEmitItems = 2;  // super-chunks per workgroup of the candidate route's last pass
 constexpr uint32_t kSampleVectors = 4096;     // 16-byte vectors sampled per segment
 constexpr uint32_t kFastMinElems = 1u << 17;  // shorter segments take the dense path
 constexpr uint32_t kFastMinKeep = 64;
@@ -33,7 +34,11 @@ constexpr uint32_t kMaxPartUnknowns = 16384;   // local ranks fit 14 bits
 constexpr uint32_t kDecodeThreads = 1024;
 constexpr uint32_t kLdsBytes = 160 * 1024;
 constexpr uint32_t kMaxRanksPerPass = 32;
-constexpr uint32_t kSpinLimit = 1u << 20;
+// polls (about half a microsecond each) for a count another workgroup is expected to
+// publish before the waiting one computes it itself: far longer than a running workgroup
+// takes to count, short against what a workgroup that has not started can take
+constexpr uint32_t kHelpAfterPolls = 1u << 9;
+uint32_t help_after_polls();  // kHelpAfterPolls unless a test lowered it
 
 // Device copy of one compressed segment.
 struct SegDev {

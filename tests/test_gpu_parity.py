@@ -306,6 +306,43 @@ def test_buckets_in_flight_on_separate_streams():
         compare_all(b, ores, tb)
 
 
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+def test_counts_of_other_workgroups_recomputed_instead_of_waited_for(dtype):
+    """The last kernel of the sparsifier orders its output through counts that workgroups
+    publish for each other; one that is not there in time (its workgroup may not even have
+    started when other streams hold the device) is recomputed by whoever needs it.  With
+    the patience set to zero polls that happens for every count not there at first sight:
+    same pairs, same Index, on the candidate route (many super-chunks per segment, ties at
+    the threshold) and on the dense route (many tiles per segment, ragged and unaligned
+    ones, Table 1's 20 % regime)."""
+    from paper_2504_05638_amd import binding as B
+    _announce("recount dtype=%d" % dtype)
+    old = B.tagc_test_help_after(0)
+    try:
+        assert old >= 256
+        segs = [G.Seg(0, (1 << 21) + 13, 10_000, 1, "long_ragged"),
+                G.Seg(2_097_176, 5000, 20_000, 1, "short"),
+                G.Seg(2_102_184, (1 << 20), 200_000, 1, "keeps_a_fifth"),
+                G.Seg(3_150_763, (1 << 19) + 64, 10_000, 1, "long_unaligned"),
+                G.Seg(3_675_120, 3 << 20, 12_500, 1, "long")]
+        n = 3_675_120 + (3 << 20)
+        b = G.Bucket("recount", dtype, 2, segs, n, 1500,
+                     {"long_ragged": 1e-3, "short": 1e-2, "keeps_a_fifth": 1e-4,
+                      "long_unaligned": 3e-3, "long": 1e-3})
+        ores, tb = run_both(b, _grads(b), seed=6)
+        compare_all(b, ores, tb)
+        assert tb.rank_counts(0)["dense_segments"] == 3
+        # integers: heavy ties at every threshold, bit for bit
+        rng = np.random.default_rng(5)
+        td = torch.float32 if dtype == G.F32 else torch.bfloat16
+        grads = [torch.from_numpy(rng.integers(-40, 41, n).astype(np.float32)).to(td)
+                 for _ in range(2)]
+        ores, tb = run_both(b, grads, seed=7)
+        compare_all(b, ores, tb, exact_values=True)
+    finally:
+        B.tagc_test_help_after(old)
+
+
 @pytest.mark.parametrize("wgs", [1, 4, 64])
 def test_decode_on_a_limited_number_of_workgroups(wgs):
     """A caller with other buckets in flight limits the peeling kernel's grid; a workgroup
