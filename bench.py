@@ -357,6 +357,7 @@ def main():
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    t_issue = time.perf_counter() - t0   # the host has enqueued everything
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
     ms_per_step = 1e3 * t_total / args.steps
@@ -433,6 +434,7 @@ def main():
                                   "sparse+dense output" if args.dense else "sparse output"),
                    "input_bytes_per_step": input_bytes, "distinct_bucket_data_sets": pool,
                    "buckets_in_flight": lanes, "decode_workgroups": peel_wgs,
+                   "host_issue_ms_per_step": round(1e3 * t_issue / args.steps, 3),
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,

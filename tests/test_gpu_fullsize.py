@@ -24,7 +24,8 @@ def _say(msg):
     print("[fullsize] " + msg, flush=True)
 
 
-def _check_full_size(b, data, seed=0, oracle_ranks=(0,), max_unresolved=20):
+def _check_full_size(b, data, seed=0, oracle_ranks=(0,), max_unresolved=20,
+                     decode_workgroups=0):
     from paper_2504_05638_amd.bucket import TagcBucket
     N = b.n_ranks
     bf16 = b.dtype == G.BF16
@@ -32,7 +33,8 @@ def _check_full_size(b, data, seed=0, oracle_ranks=(0,), max_unresolved=20):
     offs, n_c = O.c_offsets(oracle_segments(b))
     c_off = [o for o, s in zip(offs, b.segments) if s.flags & 1]
     k = [O.keep_count(s.length, s.keep_ppm) for s in segs]
-    tb = TagcBucket(b.segments, b.dtype, N, sizing_milli=b.sizing_milli, seed=seed, dense=True)
+    tb = TagcBucket(b.segments, b.dtype, N, sizing_milli=b.sizing_milli, seed=seed, dense=True,
+                    decode_workgroups=decode_workgroups)
     tb.run(data)
     torch.cuda.synchronize()
     z = tb.sizes
@@ -154,8 +156,56 @@ def test_config5_bucket_as_the_benchmark_runs_it():
     b = G.config5(0)[0]
     assert b.n_ranks == 16 and b.n_elems > 200_000_000
     data = [G.rank_gradient(b, r, "cuda") for r in range(b.n_ranks)]
-    tb = _check_full_size(b, data, oracle_ranks=(0, 9))
+    tb = _check_full_size(b, data, oracle_ranks=(0, 9), decode_workgroups=64)  # as bench.py
     assert all(tb.rank_counts(r)["dense_segments"] == 0 for r in range(1, b.n_ranks))
+
+
+def test_config5_buckets_in_flight_as_the_benchmark_keeps_them():
+    """Three 7B-shaped buckets (blocks 0, 1, 2; 8 ranks to fit the test's time) issued
+    round-robin on three streams, each with its own buffers and the peeling kernel limited
+    to 64 workgroups, twice over: every bucket must come out as it does alone on an idle
+    device -- same counts, pairs, Index, layout and decoded indices bit for bit; decoded
+    values within the float tolerance (the order of peeling's float subtractions inside a
+    round is free)."""
+    from paper_2504_05638_amd.bucket import TagcBucket
+    print("\n[case] three config5 buckets in flight", flush=True)
+    buckets = G.config5(0, n_ranks=8)[:3]
+    data = [[G.rank_gradient(b, r, "cuda") for r in range(b.n_ranks)] for b in buckets]
+    tbs = [TagcBucket(b.segments, b.dtype, b.n_ranks, sizing_milli=b.sizing_milli, seed=3,
+                      dense=False, decode_workgroups=64) for b in buckets]
+
+    def snapshot(tb):
+        hdr, st = tb.header(), tb.status()
+        U = hdr["U"]
+        ranks = [(tb.rank_counts(r), tb._rk_tensors[r]["idx"].clone(),
+                  tb._rk_tensors[r]["val"].clone()) for r in (0, tb.n_ranks - 1)]
+        return (hdr, st, ranks, tb.sh_bitmap.clone(), tb.out_idx[:4 * U].clone(),
+                tb.out_val[:4 * U].view(torch.float32).clone())
+
+    alone = []
+    for tb, d in zip(tbs, data):
+        tb.run(d)
+        torch.cuda.synchronize()
+        alone.append(snapshot(tb))
+        assert alone[-1][1]["flags"] == 0 and alone[-1][1]["n_unresolved"] <= 20
+    _say("alone done")
+    streams = [torch.cuda.Stream() for _ in tbs]
+    torch.cuda.synchronize()
+    for _ in range(2):
+        for tb, d, s in zip(tbs, data, streams):
+            tb.run(d, s)
+    torch.cuda.synchronize()
+    for i, (tb, ref) in enumerate(zip(tbs, alone)):
+        hdr, st, ranks, bitmap, oidx, oval = snapshot(tb)
+        assert hdr == ref[0] and st["flags"] == 0
+        assert st["n_unresolved"] == ref[1]["n_unresolved"] and st["rounds"] == ref[1]["rounds"]
+        for (c, ix, vl), (rc, rix, rvl) in zip(ranks, ref[2]):
+            k = 4 * c["total"]
+            assert c == rc and torch.equal(ix[:k], rix[:k]) and torch.equal(vl[:k], rvl[:k])
+        assert torch.equal(bitmap, ref[3]) and torch.equal(oidx, ref[4])
+        scale = float(ref[5].abs().max())
+        assert float((oval - ref[5]).abs().max()) <= 1e-5 * scale
+        _say("bucket %d in flight == alone (U = %d)" % (i, hdr["U"]))
 
 
 def test_config4_sharded_7b_bucket():
