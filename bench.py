@@ -43,8 +43,8 @@ MEASURED_TRAFFIC = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="config5",
                     choices=["config1", "config2", "config3", "config4", "config5"])
     ap.add_argument("--pool", type=int, default=8,
