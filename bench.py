@@ -36,7 +36,7 @@ STAGES = {
 # WRITE_SIZE runs (see profiles/); None until measured for a workload.
 MEASURED_TRAFFIC = {
     # (workload, kernel): bytes per launch = (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE) KiB * 1024
-    ("config5", "scan_spill"): int((2.0 * 197716.1 + 16817.8) * 1024),
+    ("config5", "scan_spill"): int((2.0 * 197722.4 + 16817.2) * 1024),
 }
 
 
