@@ -362,11 +362,14 @@ def main():
     t_total = time.perf_counter() - t0
     ms_per_step = 1e3 * t_total / args.steps
     # the buffers now hold each lane's last bucket: it must have come out as it did alone
+    recounts = 0
     for i in range(n_b - lanes, n_b):
         hdr, st = tbs[i].header(), tbs[i].status()
         bad = st["flags"]
         for r in range(N):
-            bad |= tbs[i].rank_counts(r)["flags"]
+            rc = tbs[i].rank_counts(r)
+            bad |= rc["flags"]
+            recounts += rc["recounts"]
         # (with error feedback every pass starts from different accumulators, so U and the
         # residue legitimately change from pass to pass: only the flags are checked then)
         if bad or (not args.error_feedback and n_sets == 1 and (hdr, st) != facts[i]):
@@ -435,6 +438,9 @@ def main():
                    "input_bytes_per_step": input_bytes, "distinct_bucket_data_sets": pool,
                    "buckets_in_flight": lanes, "decode_workgroups": peel_wgs,
                    "host_issue_ms_per_step": round(1e3 * t_issue / args.steps, 3),
+                   # counts a workgroup recomputed instead of waiting for another one, in the
+                   # last bucket of every lane (diagnostic: stalls between kernels in flight)
+                   "recounts_in_last_buckets": recounts,
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,

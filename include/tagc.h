@@ -181,7 +181,10 @@ enum {
                                unspecified but memory-safe)                      */
     TAGC_CNT_FLAGS = 2,     /* TAGC_FLAG_* bits                                  */
     TAGC_CNT_DENSE = 3,     /* segments that took the two-read route (diagnostic) */
-    TAGC_CNT_SEG0 = 4       /* [4 + l] = pairs of compressed segment l           */
+    TAGC_CNT_RECOUNTS = 4,  /* counts of another workgroup that were recomputed
+                               instead of waited for, see tagc_test_help_after
+                               (diagnostic)                                      */
+    TAGC_CNT_SEG0 = 5       /* [5 + l] = pairs of compressed segment l           */
 };
 /* Behind the counts (rank_cnt_bytes covers it) tagc_aggregate(PHASE_INDEX) leaves,
  * for every rank it is given, the A + 1 positions at which that rank's sorted

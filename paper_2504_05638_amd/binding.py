@@ -18,7 +18,8 @@ TAGC_SIZE_LOAD_FACTOR, TAGC_SIZE_FIXED_RATIO = 0, 1
 TAGC_INDEX_OR1, TAGC_INDEX_ADD1, TAGC_INDEX_ADD4 = 0, 1, 2
 TAGC_PHASE_INDEX, TAGC_PHASE_SKETCH = 1, 2
 TAGC_SEG_COMPRESS = 1
-TAGC_CNT_TOTAL, TAGC_CNT_NONFINITE, TAGC_CNT_FLAGS, TAGC_CNT_DENSE, TAGC_CNT_SEG0 = 0, 1, 2, 3, 4
+TAGC_CNT_TOTAL, TAGC_CNT_NONFINITE, TAGC_CNT_FLAGS, TAGC_CNT_DENSE = 0, 1, 2, 3
+TAGC_CNT_RECOUNTS, TAGC_CNT_SEG0 = 4, 5
 TAGC_HDR_U, TAGC_HDR_A, TAGC_HDR_MSUB, TAGC_HDR_M, TAGC_HDR_WORDS = 0, 1, 2, 3, 8
 TAGC_ST_UNRESOLVED, TAGC_ST_ROUNDS, TAGC_ST_FLAGS, TAGC_ST_WORDS = 0, 1, 2, 8
 TAGC_ST_ESTIMATED = 3

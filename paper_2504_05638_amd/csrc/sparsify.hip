@@ -1085,7 +1085,8 @@ constexpr uint64_t kStAgg = 1ull << 62, kStPre = 2ull << 62, kStMask = 3ull << 6
 // same input) and goes on.
 template <typename Recount>
 __device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, uint64_t agg,
-                                    uint32_t help_after, Recount &&recount)
+                                    uint32_t help_after, uint32_t *n_recounts,
+                                    Recount &&recount)
 {
     const uint32_t l = lane_id();
     if (t == t0) {
@@ -1107,7 +1108,10 @@ __device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, ui
                     const uint32_t src = uint32_t(__builtin_ctzll(miss));
                     miss &= miss - 1;
                     const uint64_t a = recount(uint32_t(j - int64_t(src)));
-                    if (l == src) s = kStAgg | a;
+                    if (l == src) {
+                        s = kStAgg | a;
+                        atomicAdd(n_recounts, 1u);
+                    }
                 }
                 break;
             }
@@ -1363,6 +1367,7 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
                     uint32_t spins = 0;
                     while ((v[u] & kStMask) == 0) {  // an earlier workgroup, still counting
                         if (spins++ >= help_after) {     // or not even started
+                            atomicAdd(&cnt[TAGC_CNT_RECOUNTS], 1u);
                             v[u] = count_item(j);
                             break;
                         }
@@ -1578,7 +1583,7 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
                 return (uint64_t(wave_sum<uint32_t>(gt)) << 31) | wave_sum<uint32_t>(eq);
             };
             uint64_t ex = lookback(tile_state, t, sd.tile_start, (uint64_t(Gt) << 31) | Et,
-                                   help_after, recount);
+                                   help_after, &cnt[TAGC_CNT_RECOUNTS], recount);
             uint32_t sb = 0;
             for (uint32_t i = tid; i < l; i += 64) sb += sel[i].cnt;
             sb = wave_sum<uint32_t>(sb);

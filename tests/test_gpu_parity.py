@@ -332,6 +332,7 @@ def test_counts_of_other_workgroups_recomputed_instead_of_waited_for(dtype):
         ores, tb = run_both(b, _grads(b), seed=6)
         compare_all(b, ores, tb)
         assert tb.rank_counts(0)["dense_segments"] == 3
+        assert min(tb.rank_counts(r)["recounts"] for r in range(2)) > 100   # the path was taken
         # integers: heavy ties at every threshold, bit for bit
         rng = np.random.default_rng(5)
         td = torch.float32 if dtype == G.F32 else torch.bfloat16
