@@ -221,6 +221,12 @@ def main():
     from paper_2504_05638_amd import binding as B
     from paper_2504_05638_amd.bucket import TagcBucket
 
+    if args.error_feedback and args.workload == "config5" and not args.buckets:
+        # every bucket's ranks keep an accumulator of the gradient's size: all 32 blocks x 16
+        # ranks (207 GB) plus three gradient sets do not fit the device
+        args.buckets, args.pool = 12, min(args.pool, 2)
+        sys.stderr.write("bench.py: --error-feedback on config5 runs the first 12 buckets "
+                         "(accumulators of all 32 do not fit beside the inputs)\n")
     buckets = make_buckets(args)
     n_b = len(buckets)
     pool = max(1, min(args.pool, n_b))
