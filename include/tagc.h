@@ -360,7 +360,7 @@ int tagc_profile_read(const char **names, double *total_ms, uint64_t *launches,
  * another workgroup publishes, it polls for it `polls` times and then computes it
  * itself from the same input (the other workgroup may not have started: other
  * streams' kernels can hold its place), so results never depend on the value.
- * The default is a few hundred; 0 makes every count that is not there at the
+ * The default is a few thousand; 0 makes every count that is not there at the
  * first look be recomputed, which is how the tests reach that path.  Process-wide,
  * takes effect at the next tagc_compress; returns the previous value.
  */

@@ -99,6 +99,14 @@ def lib():
             raise RuntimeError(
                 "libtagc.so is missing: build it with "
                 "`python -m paper_2504_05638_amd.build` (there is no fallback)")
+        # libtagc uses whatever HIP runtime the process has loaded.  A caller that hands it
+        # torch's device memory and streams needs that to be torch's own copy, so torch (when
+        # there is one) is loaded first: the other order ends in HIP errors at the first
+        # call that takes a stream.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.tagc_plan.restype = C.c_int

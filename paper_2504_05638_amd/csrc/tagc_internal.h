@@ -35,9 +35,11 @@ constexpr uint32_t kDecodeThreads = 1024;
 constexpr uint32_t kLdsBytes = 160 * 1024;
 constexpr uint32_t kMaxRanksPerPass = 32;
 // polls (about half a microsecond each) for a count another workgroup is expected to
-// publish before the waiting one computes it itself: far longer than a running workgroup
-// takes to count, short against what a workgroup that has not started can take
-constexpr uint32_t kHelpAfterPolls = 1u << 9;
+// publish before the waiting one computes it itself.  Far longer than a running workgroup
+// takes to count even with the device shared (with 512 polls a run with error feedback
+// recomputed tens of thousands of counts that were merely late, each at many times the cost
+// of waiting; with 4096 none), short against what a workgroup that has not started can take
+constexpr uint32_t kHelpAfterPolls = 1u << 12;
 uint32_t help_after_polls();  // kHelpAfterPolls unless a test lowered it
 
 // Device copy of one compressed segment.
