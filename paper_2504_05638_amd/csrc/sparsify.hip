@@ -1069,68 +1069,20 @@ select2_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     atomicAdd(&cnt[TAGC_CNT_TOTAL], r.cnt);
 }
 
-// --------------------------------------------------------------- look-back
+// ---------------------------------------------------------- ordered output
 
-constexpr uint64_t kStAgg = 1ull << 62, kStPre = 2ull << 62, kStMask = 3ull << 62;
+constexpr uint64_t kStAgg = 1ull << 62, kStMask = 3ull << 62;  // published / status bits
 
-// Decoupled look-back over the tiles of one segment, run by the first wave of the
-// workgroup.  state word = status(2) | count(key > T)(31) | count(key == T)(31).  A tile
-// publishes its counts without waiting for any other tile, so a predecessor that is
-// running is never waited for long.  One that has not started may take arbitrarily long:
-// the device's dies hand out their shares of a grid independently of each other, so with
-// other kernels in flight a lower-numbered workgroup can still be waiting for room on its
-// die while higher-numbered ones hold theirs, and two kernels that wait like this can hold
-// each other's room for good.  So the wait never decides anything: after `help_after`
-// polls the wave recounts the missing tile itself (`recount(tile)`, wave-uniform, from the
-// same input) and goes on.
-template <typename Recount>
-__device__ inline uint64_t lookback(uint64_t *state, uint32_t t, uint32_t t0, uint64_t agg,
-                                    uint32_t help_after, uint32_t *n_recounts,
-                                    Recount &&recount)
-{
-    const uint32_t l = lane_id();
-    if (t == t0) {
-        if (l == 0) st_agent(&state[t], kStPre | agg);
-        return 0;
-    }
-    if (l == 0) st_agent(&state[t], kStAgg | agg);
-    uint64_t excl = 0;
-    int64_t j = int64_t(t) - 1;
-    uint32_t spins = 0;
-    while (true) {
-        const int64_t i = j - l;
-        const bool real = i >= int64_t(t0);
-        uint64_t s = real ? ld_agent(&state[i]) : kStPre;
-        while (__any((s & kStMask) == 0)) {
-            if (spins++ >= help_after) {
-                uint64_t miss = __ballot((s & kStMask) == 0);
-                while (miss) {  // one missing tile at a time, by the whole wave
-                    const uint32_t src = uint32_t(__builtin_ctzll(miss));
-                    miss &= miss - 1;
-                    const uint64_t a = recount(uint32_t(j - int64_t(src)));
-                    if (l == src) {
-                        s = kStAgg | a;
-                        atomicAdd(n_recounts, 1u);
-                    }
-                }
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
-            if ((s & kStMask) == 0) s = ld_agent(&state[i]);
-        }
-        const uint64_t pm = __ballot((s & kStMask) == kStPre);
-        const uint64_t v = s & ~kStMask;
-        if (pm) {
-            const uint32_t first = __builtin_ctzll(pm);
-            excl += wave_sum<uint64_t>(l <= first ? v : 0ull);
-            break;
-        }
-        excl += wave_sum<uint64_t>(v);
-        j -= 64;
-    }
-    if (l == 0) st_agent(&state[t], kStPre | (excl + agg));
-    return excl;
-}
+// Ordered output (emit's items, compaction's tiles).  state word = status(2) |
+// count(key > T)(31) | count(key == T)(31).  An item publishes its counts as soon as it has
+// them, without waiting for anything, and then adds up the counts of all earlier items of its
+// segment: no chain from item to item.  A predecessor that is running is never waited for
+// long.  One that has not started may take arbitrarily long: the device's dies hand out their
+// shares of a grid independently of each other, so with other kernels in flight a
+// lower-numbered workgroup can still be waiting for room on its die while higher-numbered
+// ones hold theirs, and two kernels that wait like this can hold each other's room for
+// good.  So a wait never decides anything: after `help_after` polls whoever needs a count
+// computes it from the same input and goes on.
 
 // last l with start(l) <= t, start() read through `field` (tile_start or sc_start)
 template <typename F>
@@ -1170,7 +1122,7 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // then its threads add up the counts of all predecessors in its segment.  A predecessor
 // publishes right after counting and waits for nobody before that, so a word that is not
 // there yet is polled for -- but only `help_after` times: a predecessor's workgroup may
-// not have started (see lookback), and after that the thread counts the predecessor's
+// not have started (see "Ordered output" above), and after that the thread counts the predecessor's
 // slots itself.  No workgroup depends on another one's progress.  (Handing the items out
 // in order by ticket instead, so that a predecessor has always started, was measured: one
 // counter for the ~1500 workgroups of a 200 M-entry bucket costs 30 ns per ticket, 44 us
@@ -1189,7 +1141,7 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
             uint64_t *stamps)
 {
 #ifdef TAGC_PHASE_TIMING
-    // per-workgroup time stamps (100 MHz counter) in the look-back area of the dense route,
+    // per-workgroup time stamps (100 MHz counter) in the tile state area of the dense route,
     // which a plan without dense-route work leaves unused
 #define EMIT_STAMP(i) do { if (threadIdx.x == 0) stamps[8 * bid + (i)] = wall_clock64(); } while (0)
 #else
@@ -1566,15 +1518,18 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
             Gt += Gr[r];
             Et += Er[r];
         }
-        // ---- look-back across the tiles of this segment + pair offset of the segment
-        if (tid < 64) {
-            // the counts tile `ti` of this segment publishes, from the input itself
+        // ---- publish the tile's counts, add up those of the segment's earlier tiles (up to a
+        // few thousand words, 256 per step; they come from the L2), pair offset of the segment
+        if (tid == 0) st_agent(&tile_state[t], kStAgg | (uint64_t(Gt) << 31) | Et);
+        {
+            const uint32_t lane = tid & 63;
+            // the counts tile `ti` of this segment publishes, from the input itself (by a wave)
             auto recount = [&](uint32_t ti) -> uint64_t {
                 uint32_t gt = 0, eq = 0;
                 if (se.cnt != 0) {
                     const uint32_t r0 = (ti - sd.tile_start) * TILE;
                     const uint32_t r1 = min(r0 + TILE, sd.n);
-                    for (uint32_t rel = r0 + tid; rel < r1; rel += 64) {
+                    for (uint32_t rel = r0 + lane; rel < r1; rel += 64) {
                         const uint32_t key = load_elem_bits(base, rel, DTYPE) & 0x7FFFFFFFu;
                         gt += key > se.T;
                         eq += key == se.T && se.quota;
@@ -1582,13 +1537,38 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
                 }
                 return (uint64_t(wave_sum<uint32_t>(gt)) << 31) | wave_sum<uint32_t>(eq);
             };
-            uint64_t ex = lookback(tile_state, t, sd.tile_start, (uint64_t(Gt) << 31) | Et,
-                                   help_after, &cnt[TAGC_CNT_RECOUNTS], recount);
+            uint64_t sum = 0;
+            for (uint32_t j0 = sd.tile_start; j0 < t; j0 += kCompactThreads) {
+                const uint32_t j = j0 + tid;
+                uint64_t v = j < t ? ld_agent(&tile_state[j]) : kStAgg;
+                uint32_t spins = 0;
+                while (__any((v & kStMask) == 0)) {  // an earlier workgroup, still counting
+                    if (spins++ >= help_after) {     // or not even started
+                        uint64_t miss = __ballot((v & kStMask) == 0);
+                        while (miss) {  // one missing tile at a time, by the whole wave
+                            const uint32_t src = uint32_t(__builtin_ctzll(miss));
+                            miss &= miss - 1;
+                            const uint64_t a = recount(j0 + (tid & ~63u) + src);
+                            if (lane == src) {
+                                v = kStAgg | a;
+                                atomicAdd(&cnt[TAGC_CNT_RECOUNTS], 1u);
+                            }
+                        }
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                    if ((v & kStMask) == 0) v = ld_agent(&tile_state[j]);
+                }
+                sum += v & ~kStMask;
+            }
+            sum = block_sum<uint64_t, kCompactThreads / 64>(sum, s_scan);
             uint32_t sb = 0;
-            for (uint32_t i = tid; i < l; i += 64) sb += sel[i].cnt;
-            sb = wave_sum<uint32_t>(sb);
+            if (tid < 64) {
+                for (uint32_t i = tid; i < l; i += 64) sb += sel[i].cnt;
+                sb = wave_sum<uint32_t>(sb);
+            }
             if (tid == 0) {
-                s_excl = ex;
+                s_excl = sum;
                 s_base = sb;
             }
         }
