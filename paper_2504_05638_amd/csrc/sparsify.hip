@@ -1122,11 +1122,11 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // then its threads add up the counts of all predecessors in its segment.  A predecessor
 // publishes right after counting and waits for nobody before that, so a word that is not
 // there yet is polled for -- but only `help_after` times: a predecessor's workgroup may
-// not have started (see "Ordered output" above), and after that the thread counts the predecessor's
-// slots itself.  No workgroup depends on another one's progress.  (Handing the items out
-// in order by ticket instead, so that a predecessor has always started, was measured: one
-// counter for the ~1500 workgroups of a 200 M-entry bucket costs 30 ns per ticket, 44 us
-// on a 31 us kernel; one counter per segment still 14 us.)
+// not have started (see "Ordered output" above), and after that the thread counts the
+// predecessor's slots itself.  No workgroup depends on another one's progress.  (Handing
+// the items out in order by ticket instead, so that a predecessor has always started, was
+// measured: one counter for the ~1500 workgroups of a 200 M-entry bucket costs 30 ns per
+// ticket, 44 us on a 31 us kernel; one counter per segment still 14 us.)
 constexpr uint32_t kEmitStage = 800;  // survivors of an item that go through LDS
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
