@@ -118,6 +118,23 @@ def test_argument_errors():
         B.tagc_decompress(plan, sh, 256, 256)
 
 
+def test_bench_refuses_more_than_one_gpu_and_fails_loudly_without_one():
+    """bench.py measures one GPU: asked for more it says so and exits; without a GPU it
+    must not fall back to anything (there is no CPU path)."""
+    import subprocess
+    import sys
+    bench = os.path.join(ROOT, "bench.py")
+    r = subprocess.run([sys.executable, bench, "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, bench, "--steps", "1", "--warmup", "0",
+                            "--workload", "config1", "--no-cpu-baseline"],
+                           capture_output=True, text=True, timeout=300)
+        assert r.returncode != 0 and not r.stdout.strip().startswith("{")
+
+
 def test_help_after_hook_swaps_values():
     """The test hook for the recount fallback is plain host state: it hands back what was
     set before (the library's default first)."""
