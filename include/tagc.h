@@ -302,6 +302,28 @@ int tagc_compress(const tagc_plan_t *plan, uint32_t phase, const void *grad_dev,
                   const tagc_shared_buffers *shared, void *stream);
 
 /*
+ * tagc_compress for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and errors as
+ * tagc_compress, except that rank->workspace is ignored (it may be NULL):
+ * PHASE_INDEX works on an array of TAGC_STATIC_WORKSPACE_BYTES that is part
+ * of the library's device code, one copy per GPU, held until the process
+ * ends.  Returns TAGC_ESIZE, before anything is enqueued, when the plan's
+ * rank_workspace_bytes exceed that size.  The call allocates nothing (no
+ * hipMalloc / hipFree, no allocating library routine); its first call on a
+ * device looks the array's address up (do that call outside a graph capture).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams, threads or plans) race, exactly like
+ * tagc_compress calls sharing one rank->workspace.  The array keeps the last
+ * call's contents; PHASE_INDEX clears what it needs clear, as it does for a
+ * caller's workspace.
+ */
+#define TAGC_STATIC_WORKSPACE_BYTES (16u << 20)
+int tagc_compress_static(const tagc_plan_t *plan, uint32_t phase, const void *grad_dev,
+                         const tagc_rank_buffers *rank,
+                         const tagc_shared_buffers *shared, void *stream);
+
+/*
  * Error feedback, optional: clears in rank->acc the entries that rank->bitmap
  * names, after which rank->acc alone is acc_next of Algorithm 1 (line 2).  For
  * inspection and checkpoints; idempotent, and the following PHASE_INDEX call

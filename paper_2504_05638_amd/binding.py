@@ -26,9 +26,10 @@ TAGC_ST_ESTIMATED = 3
 TAGC_DECODE_PEEL, TAGC_DECODE_PEEL_ESTIMATE, TAGC_DECODE_ESTIMATE = 0, 1, 2
 TAGC_CELL_F32, TAGC_CELL_BF16 = 0, 1
 TAGC_FLAG_SPIN_LIMIT, TAGC_FLAG_OVERFLOW = 1, 2
+TAGC_STATIC_WORKSPACE_BYTES = 16 << 20
 
 EXPORTS = ["tagc_plan", "tagc_plan_destroy", "tagc_plan_sizes",
-           "tagc_plan_upload", "tagc_compress", "tagc_feedback_apply", "tagc_aggregate",
+           "tagc_plan_upload", "tagc_compress", "tagc_compress_static", "tagc_feedback_apply", "tagc_aggregate",
            "tagc_decompress", "tagc_profile_enable", "tagc_profile_read",
            "tagc_test_help_after", "tagc_hash_host", "tagc_strerror"]
 
@@ -122,6 +123,8 @@ def lib():
         L.tagc_compress.argtypes = [vp, C.c_uint32, vp,
                                     C.POINTER(tagc_rank_buffers),
                                     C.POINTER(tagc_shared_buffers), vp]
+        L.tagc_compress_static.restype = C.c_int
+        L.tagc_compress_static.argtypes = L.tagc_compress.argtypes
         L.tagc_aggregate.restype = C.c_int
         L.tagc_feedback_apply.restype = C.c_int
         L.tagc_feedback_apply.argtypes = [vp, C.POINTER(tagc_rank_buffers),
@@ -192,6 +195,13 @@ def tagc_compress(plan, phase, grad_dev, rank: tagc_rank_buffers,
                   shared: tagc_shared_buffers, stream: int = 0):
     _check(lib().tagc_compress(plan, phase, grad_dev, C.byref(rank),
                                C.byref(shared), stream), "tagc_compress")
+
+
+def tagc_compress_static(plan, phase, grad_dev, rank: tagc_rank_buffers,
+                         shared: tagc_shared_buffers, stream: int = 0):
+    """tagc_compress on the library's own workspace (rank.workspace is ignored)."""
+    _check(lib().tagc_compress_static(plan, phase, grad_dev, C.byref(rank),
+                                      C.byref(shared), stream), "tagc_compress_static")
 
 
 def tagc_feedback_apply(plan, rank: tagc_rank_buffers, shared: tagc_shared_buffers,

@@ -294,6 +294,19 @@ extern "C" int tagc_compress(const tagc_plan_t *p, uint32_t phase, const void *g
     return TAGC_EINVAL;
 }
 
+extern "C" int tagc_compress_static(const tagc_plan_t *p, uint32_t phase, const void *grad,
+                                    const tagc_rank_buffers *rk, const tagc_shared_buffers *sh,
+                                    void *stream)
+{
+    if (!p || !rk) return TAGC_EINVAL;
+    if (p->sizes.rank_workspace_bytes > TAGC_STATIC_WORKSPACE_BYTES) return TAGC_ESIZE;
+    tagc_rank_buffers r = *rk;
+    r.workspace = nullptr;
+    const int rc = static_workspace(&r.workspace);
+    if (rc) return rc;
+    return tagc_compress(p, phase, grad, &r, sh, stream);
+}
+
 extern "C" int tagc_feedback_apply(const tagc_plan_t *p, const tagc_rank_buffers *rk,
                                    const tagc_shared_buffers *sh, void *stream)
 {

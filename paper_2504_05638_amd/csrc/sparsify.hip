@@ -44,6 +44,8 @@
 // them and learns its offset from the counts of earlier items only; counts that are not
 // there after a bounded number of polls it computes itself, so no workgroup depends on
 // another one's progress and no kernel needs the device to itself.
+#include <mutex>
+
 #include "device_utils.h"
 #include "tagc_internal.h"
 
@@ -1870,6 +1872,30 @@ int launch_sparsify(const tagc_plan_t *p, const void *grad, const tagc_rank_buff
 {
     return p->cfg.dtype == TAGC_BF16 ? launch_sparsify_t<kBF16>(p, grad, rk, sh, s)
                                      : launch_sparsify_t<kF32>(p, grad, rk, sh, s);
+}
+
+// ------------------------------------------------ workspace without a caller
+//
+// For callers that cannot hand over (or allocate) a rank workspace: the same kernels work
+// on this array instead.  In host code `scratch` is only a stand-in for the symbol, not a
+// device address; the address on the current device is looked up once per device and kept.
+// Every GPU holds its own copy of the array at its own address until the process ends.
+static __device__ __align__(256) unsigned char scratch[TAGC_STATIC_WORKSPACE_BYTES];
+
+int static_workspace(void **out)
+{
+    static std::mutex mu;
+    static void *ptr[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return TAGC_EHIP;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TAGC_EHIP;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return TAGC_OK;
 }
 
 }  // namespace tagc

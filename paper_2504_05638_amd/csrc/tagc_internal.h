@@ -168,6 +168,10 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
 
 size_t decode_lds_bytes(uint32_t T_cap, uint32_t P_cap);
 
+// device address, on the current device, of the library's own rank workspace
+// (TAGC_STATIC_WORKSPACE_BYTES); looked up on the first call per device, never allocated
+int static_workspace(void **out);
+
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? TAGC_OK : TAGC_EHIP; }
 
 }  // namespace tagc

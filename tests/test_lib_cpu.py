@@ -118,6 +118,22 @@ def test_argument_errors():
         B.tagc_decompress(plan, sh, 256, 256)
 
 
+def test_static_workspace_variant_rejects_a_plan_that_does_not_fit_before_touching_anything():
+    """tagc_compress_static checks the plan's workspace size first: no device is needed to
+    be told that a 7B-shaped bucket does not fit the library's own array."""
+    b = G.config5()[0]
+    plan = B.tagc_plan(_cfg(dtype=b.dtype, n_ranks=1, sizing_milli=1500), b.segments)
+    assert B.tagc_plan_sizes(plan).rank_workspace_bytes > B.TAGC_STATIC_WORKSPACE_BYTES
+    rk, sh = B.tagc_rank_buffers(), B.tagc_shared_buffers()
+    with pytest.raises(B.TagcError) as e:
+        B.tagc_compress_static(plan, B.TAGC_PHASE_INDEX, 4096, rk, sh, 0)
+    assert e.value.code == -2
+    with pytest.raises(B.TagcError) as e:
+        B.tagc_compress_static(None, B.TAGC_PHASE_INDEX, 4096, rk, sh, 0)
+    assert e.value.code == -1
+    B.tagc_plan_destroy(plan)
+
+
 def test_bench_refuses_more_than_one_gpu_and_fails_loudly_without_one():
     """bench.py measures one GPU: asked for more it says so and exits; without a GPU it
     must not fall back to anything (there is no CPU path)."""
