@@ -60,14 +60,14 @@ __device__ inline Cells cells_of(uint32_t i, uint32_t m_sub, uint32_t sw0, uint3
 }
 
 // Appends `value` to the queue for every active lane with `pred`; one LDS atomic per wave.
-__device__ inline void queue_push(bool pred, uint32_t value, uint32_t *tail, uint16_t *queue)
+__device__ inline void queue_push(bool pred, uint32_t value, uint32_t *count, uint16_t *queue)
 {
     const uint64_t bal = __ballot(pred);
     if (bal == 0) return;
     const uint32_t lane = lane_id();
     const uint32_t leader = __builtin_ctzll(bal);
     uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(tail, uint32_t(__popcll(bal)));
+    if (lane == leader) base = atomicAdd(count, uint32_t(__popcll(bal)));
     base = __shfl(base, leader, 64);
     if (pred) queue[base + uint32_t(__popcll(bal & ((1ull << lane) - 1ull)))] = uint16_t(value);
 }
@@ -120,9 +120,10 @@ enumerate_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
 }
 
 // Appends up to three values per lane (those whose predicate holds) with one LDS atomic
-// per wave.  Safe in divergent code: only the active lanes take part.
+// per wave; `queue` points at the first free slot of the round, `count` at the number of
+// slots the round has taken so far.  Safe in divergent code: only the active lanes take part.
 __device__ inline void queue_push3(bool p0, uint32_t v0, bool p1, uint32_t v1, bool p2,
-                                   uint32_t v2, uint32_t *tail, uint16_t *queue)
+                                   uint32_t v2, uint32_t *count, uint16_t *queue)
 {
     const uint64_t b0 = __ballot(p0), b1 = __ballot(p1), b2 = __ballot(p2);
     const uint32_t n0 = __popcll(b0), n1 = __popcll(b1), n2 = __popcll(b2);
@@ -131,7 +132,7 @@ __device__ inline void queue_push3(bool p0, uint32_t v0, bool p1, uint32_t v1, b
     const uint64_t lt = (1ull << lane) - 1ull;
     const uint32_t leader = __builtin_ctzll(__ballot(true));
     uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(tail, n0 + n1 + n2);
+    if (lane == leader) base = atomicAdd(count, n0 + n1 + n2);
     base = __shfl(base, leader, 64);
     if (p0) queue[base + uint32_t(__popcll(b0 & lt))] = uint16_t(v0);
     if (p1) queue[base + n0 + uint32_t(__popcll(b1 & lt))] = uint16_t(v1);
@@ -163,7 +164,12 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     uint32_t *claimed = idx + P_cap;                 // [P_cap/32 + 1] resolved unknowns
     uint32_t *scratch = claimed + (P_cap / 32 + 1);  // [32]
     uint16_t *queue = reinterpret_cast<uint16_t *>(scratch + 32);  // [T_cap] cells of degree 1
-    __shared__ uint32_t s_tail, s_any;
+    // Per round: the number of cells the round queued for the next one, and whether it
+    // resolved anything.  Three of each, used in turn: round r reads what round r-1 left
+    // in slot r%3 (n) resp. (r-1)%3 (any) and writes slot (r+1)%3 resp. r%3, so a wave that
+    // is late into round r never sees what faster waves of the same round already write;
+    // the slot nobody touches in round r is cleared by thread 0 for its next use.
+    __shared__ uint32_t s_n[3], s_any[3];
     const uint32_t tid = threadIdx.x;
     const uint32_t U = header[TAGC_HDR_U], A = header[TAGC_HDR_A];
     const uint32_t m_sub = header[TAGC_HDR_MSUB];
@@ -189,9 +195,8 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
         }
     };
     if (blockIdx.x < A) prefetch(blockIdx.x);
-    if (tid == 0) s_any = 0;  // ordered before its first use by the barriers below
 
-    uint32_t sweep = 1, max_rounds = 0;  // s_any starts at 0: no round has number 0 or 1
+    uint32_t max_rounds = 0;
     for (uint32_t a = blockIdx.x; a < A; a += gridDim.x) {
     PHASE_INIT();
     const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
@@ -204,7 +209,7 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
         if (c < cells) cell[c] = __float_as_uint(pre_cell[q]);
     }
     for (uint32_t c = tid; c < P_cap / 32 + 1; c += kDecodeThreads) claimed[c] = 0;
-    if (tid == 0) s_tail = 0;
+    if (tid < 3) s_n[tid] = s_any[tid] = 0;
     __syncthreads();
     PHASE_MARK(0);
 
@@ -227,7 +232,7 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     if (mode != TAGC_DECODE_ESTIMATE) {  // estimation alone: the queue stays empty
         for (uint32_t c0 = 0; c0 < cells; c0 += kDecodeThreads) {
             const uint32_t c = c0 + tid;
-            queue_push(c < cells && (meta_hi[2 * c] & kDegMask) == 1u, c, &s_tail, queue);
+            queue_push(c < cells && (meta_hi[2 * c] & kDegMask) == 1u, c, &s_n[1], queue);
         }
     }
     PHASE_MARK(1);
@@ -238,16 +243,19 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     // every other cell is only ever changed by compare-and-swap.  Removals of a round run
     // concurrently with its claims, which changes neither the set of unknowns the round
     // resolves (a cell that reaches degree 1 now is queued for the next round) nor, beyond
-    // rounding order, their values.  "Did the round resolve anything" travels through an
-    // LDS word stamped with the round's number (`sweep` keeps counting across partitions,
-    // so a stale stamp never matches).
+    // rounding order, their values.
     uint32_t rounds = 0, head = 0;
-    while (true) {
-        ++sweep;
-        __syncthreads();  // queue, s_tail and cells of the previous round are complete
-        if (s_any == sweep - 1) ++rounds;
-        const uint32_t tail = s_tail;
+    for (uint32_t r = 1;; ++r) {
+        __syncthreads();  // queue, counts and cells of the previous round are complete
+        const uint32_t cur = r % 3, nxt = (r + 1) % 3, idle = (r + 2) % 3;
+        if (s_any[idle]) ++rounds;  // slot (r-1)%3: did round r-1 resolve anything
+        const uint32_t tail = head + s_n[cur];
         if (tail == head) break;
+        if (tid == 0) {
+            s_n[idle] = 0;     // read in round r-1, added to again in round r+1
+            s_any[nxt] = 0;    // read in round r-1 (as its idle slot), set again in round r+1
+        }
+        uint16_t *next_queue = queue + tail;
         for (uint32_t e = head + tid; e < tail; e += kDecodeThreads) {
             const uint32_t q = queue[e];
             const unsigned long long oq = cell[q];
@@ -255,7 +263,7 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
             if ((m & kDegMask) != 1u) continue;  // emptied since it was queued
             const uint32_t u = m >> 15, bit = 1u << (u & 31);
             if (atomicOr(&claimed[u >> 5], bit) & bit) continue;  // reached through another cell
-            s_any = sweep;
+            s_any[cur] = 1;
             const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
             const uint32_t c[3] = {cl.c[0], cl.c[1], cl.c[2]};
             const uint32_t neg = cl.neg;
@@ -284,7 +292,7 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
             }
             queue_push3((uint32_t(o[0] >> 32) & kDegMask) == 2u, c[0],
                         (uint32_t(o[1] >> 32) & kDegMask) == 2u, c[1],
-                        (uint32_t(o[2] >> 32) & kDegMask) == 2u, c[2], &s_tail, queue);
+                        (uint32_t(o[2] >> 32) & kDegMask) == 2u, c[2], &s_n[nxt], next_queue);
         }
         head = tail;
     }
