@@ -85,10 +85,12 @@ def parse_args():
     ap.add_argument("--decode-mode", type=int, default=0, choices=[0, 1, 2],
                     help="0 peeling only (the headline), 1 peeling + estimation of what it "
                          "leaves, 2 estimation only (section 2.2's two decompression algorithms)")
-    ap.add_argument("--graph", action="store_true",
-                    help="capture each bucket's call sequence in a HIP graph after the warm-up "
-                         "and replay it in the timed steps (the library only enqueues kernels, so "
-                         "a caller may do that); helps where many small launches bind the host")
+    ap.add_argument("--graph", type=int, default=1, choices=[0, 1],
+                    help="1 (default): capture each bucket's call sequence in a HIP graph after "
+                         "the warm-up and replay it in the timed steps (the library only enqueues "
+                         "kernels, so a caller may do that), which keeps the result independent "
+                         "of how fast the host issues launches; 0: issue every launch eagerly.  "
+                         "Off with --error-feedback, whose steps take a different gradient each")
     ap.add_argument("--grad-sets", type=int, default=0,
                     help="distinct gradients per bucket data set, one per step in turn (0 = 3 "
                          "with --error-feedback, where feeding the same gradient every step "
@@ -237,8 +239,8 @@ def main():
     t0 = time.perf_counter()
     import dataclasses
     n_sets = args.grad_sets or (3 if args.error_feedback else 1)
-    if args.graph:
-        n_sets = 1  # a captured graph reads the buffers it was captured with
+    if n_sets > 1:
+        args.graph = 0  # a captured graph reads the buffers it was captured with
     data_sets = [[[gen(dataclasses.replace(buckets[d], seed=buckets[d].seed + 7919 * v), r, "cuda")
                    for r in range(N)] for d in range(pool)] for v in range(n_sets)]
     data = data_sets[0]
