@@ -173,38 +173,44 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1, cell=4):
 
 
 def cpu_baseline(args):
-    """The oracle, as it stands, timed on this machine's host cores on a bounded sample
-    of the same workload."""
+    """The oracle, as it stands, timed on this machine's host cores on a bounded sample of the
+    same workload: the first bucket whole (config5: all seven segments of block 0) for all
+    its ranks, the per-rank steps spread over the host's threads."""
     from concurrent.futures import ThreadPoolExecutor
+    import torch
     from oracle import tagc_oracle as O
     from synth import gradients as G
     b = make_buckets(args)[0]
-    seg = max((s for s in b.segments if s.flags & 1), key=lambda s: s.length)  # largest
-    n = min(seg.length, 1 << 26)
     n_ranks = min(b.n_ranks, 16)
-    sub = G.Bucket("sample", b.dtype, n_ranks, [G.Seg(0, n, seg.keep_ppm, 1, seg.name)], n,
-                   b.sizing_milli, {seg.name: b.sigma.get(seg.name, 1e-3)}, b.kind,
-                   b.seed, b.bucket_id)
-    grads = [G.to_numpy_raw(G.rank_gradient(sub, r, "cpu")) for r in range(n_ranks)]
-    cfg = O.Config(dtype=sub.dtype, sizing_milli=sub.sizing_milli, seed=args.seed)
-    segs = [O.Segment(0, n, seg.keep_ppm, 1)]
+    gen = G.config3_rank_gradient if args.workload == "config3" else G.rank_gradient
+    # generated on the device and copied over (faster than the host's generator; the
+    # oracle's input is host memory either way)
+    grads = [G.to_numpy_raw(gen(b, r, "cuda" if torch.cuda.is_available() else "cpu"))
+             for r in range(n_ranks)]
+    cfg = O.Config(dtype=b.dtype, sizing_milli=b.sizing_milli, seed=args.seed)
+    segs = [O.Segment(s.offset, s.length, s.keep_ppm, s.flags) for s in b.segments]
+    offs, n_c = O.c_offsets(segs)
+    n_real = b.compressed_elems()
     threads = min(n_ranks, os.cpu_count() or 1, 16)
     O.lib()
     t0 = time.perf_counter()
     with ThreadPoolExecutor(threads) as ex:   # ranks are independent until the OR
         ranks = list(ex.map(lambda g: O.sparsify(g, cfg, segs), grads))
     bitmap, U = O.index_or([r.bitmap for r in ranks])
-    A, m_sub, m = O.layout(U, cfg, n)
-    bnd = O.bounds(bitmap, n, U, A)
+    A, m_sub, m = O.layout(U, cfg, n_real)
+    bnd = O.bounds(bitmap, n_c, U, A)
+    salt = O.salts(bitmap, n_c, U, A, m_sub, cfg.seed)
     with ThreadPoolExecutor(threads) as ex:
-        sks = list(ex.map(lambda r: O.encode(r.idx, r.val, bnd, A, m_sub, cfg.seed), ranks))
+        sks = list(ex.map(lambda r: O.encode(r.idx, r.val, bnd, A, m_sub, cfg.seed, salt=salt),
+                          ranks))
     total = O.sketch_sum(sks)
-    dec = O.peel(bitmap, n, U, A, m_sub, cfg.seed, total)
+    dec = O.peel(bitmap, n_c, U, A, m_sub, cfg.seed, total, salt=salt)
     dt = time.perf_counter() - t0
-    nbytes = n_ranks * n * sub.elem_bytes
+    nbytes = n_ranks * n_real * b.elem_bytes
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "%s segment %s (%d elements) x %d ranks, whole path, %.1f s"
-                      % (b.name, seg.name, n, n_ranks, dt),
+            "sample": "%s whole (%d compressed segments, %d elements) x %d ranks, whole path, "
+                      "%.1f s" % (b.name, sum(1 for s in segs if s.flags & 1), n_real,
+                                  n_ranks, dt),
             "n_unresolved": dec.n_unresolved}
 
 

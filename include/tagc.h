@@ -242,7 +242,10 @@ typedef struct tagc_shared_buffers {
     uint32_t *bitmap;   /* [bitmap_words] merged Index                          */
     float *sketch;      /* [sketch_cells_capacity] summed Count Sketch          */
     uint32_t *header;   /* [TAGC_HDR_WORDS]                                     */
-    uint32_t *bounds;   /* [partition_capacity + 1] first c-index per partition */
+    uint32_t *bounds;   /* [shared_bounds_bytes / 4] first c-index of each partition
+                           (A + 1 words, the last one n_c), then, from word
+                           partition_capacity + 1 on, the partitions' hash
+                           salts (A words), see tagc_aggregate             */
     void *workspace;    /* [shared_workspace_bytes]                             */
     uint32_t *status;   /* [TAGC_ST_WORDS]                                      */
 } tagc_shared_buffers;
@@ -338,7 +341,10 @@ int tagc_feedback_apply(const tagc_plan_t *plan, const tagc_rank_buffers *rank,
  * PHASE_INDEX : shared->bitmap = OR over ranks[r].bitmap (section 2.2: OR is
  *   the operation the Index needs), or what adding the ranks' wire Indexes
  *   gives (see "Index modes"); counts its non-zeros U, derives the sketch
- *   layout (A, m_sub, m) and the partition bounds; writes shared->header,
+ *   layout (A, m_sub, m), the partition bounds and, per partition, the hash
+ *   salt: the smallest of 0..15 under which no two non-zeros of the partition
+ *   get the same three cells (such a pair could never be decoded; section
+ *   2.2 and Table 1 call the compression lossless); writes shared->header,
  *   shared->bounds; clears shared->status; locates the bounds in every given
  *   rank's pair list (ranks[r].idx, ranks[r].cnt are read, the ranges written
  *   behind the counts in ranks[r].cnt).
@@ -387,11 +393,6 @@ int tagc_profile_read(const char **names, double *total_ms, uint64_t *launches,
  * takes effect at the next tagc_compress; returns the previous value.
  */
 uint32_t tagc_test_help_after(uint32_t polls);
-
-/* Hash function j (0..2) of c-index i for a sub-table of m_sub cells, as the
- * device code computes it (host helper for tests and tools). */
-void tagc_hash_host(uint32_t i, uint64_t seed, uint32_t j, uint32_t m_sub,
-                    uint32_t *slot, int32_t *sign);
 
 const char *tagc_strerror(int err);
 

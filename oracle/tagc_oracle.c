@@ -391,34 +391,116 @@ uint32_t tagco_seed_word(uint64_t seed, uint32_t j)
 /*
  * Hash function j of c-index i (a Count Sketch has, per hash function, a
  * bucket hash and a +-1 sign hash; the paper cites the structure by name
- * only, section 2.2):
- *   h    = mix32(i xor seed_word(j))
+ * only, section 2.2), under the salt of i's partition (tagco_salts below;
+ * salt 0 for nearly every partition):
+ *   h    = mix32(i xor seed_word(j + 3*salt))
  *   slot = floor(h * m_sub / 2^32)   within sub-table j of i's partition
  *   sign = -1 if h is odd else +1
  */
-void tagco_hash(uint32_t i, uint64_t seed, uint32_t j, uint32_t m_sub,
-                uint32_t *slot, int32_t *sign)
+void tagco_hash(uint32_t i, uint64_t seed, uint32_t j, uint32_t salt,
+                uint32_t m_sub, uint32_t *slot, int32_t *sign)
 {
-    uint32_t h = tagco_mix32(i ^ tagco_seed_word(seed, j));
+    uint32_t h = tagco_mix32(i ^ tagco_seed_word(seed, j + 3 * salt));
     *slot = (uint32_t)(((uint64_t)h * m_sub) >> 32);
     *sign = (h & 1u) ? -1 : 1;
 }
 
 static uint64_t cell_of(uint32_t i, uint64_t a, uint32_t j, uint64_t m_sub,
-                        uint64_t seed, int plus_only, float *sgn)
+                        uint64_t seed, uint32_t salt, int plus_only,
+                        float *sgn)
 {
     uint32_t slot;
     int32_t s;
-    tagco_hash(i, seed, j, (uint32_t)m_sub, &slot, &s);
+    tagco_hash(i, seed, j, salt, (uint32_t)m_sub, &slot, &s);
     *sgn = plus_only ? 1.0f : (float)s;
     return a * 3 * m_sub + (uint64_t)j * m_sub + slot;
+}
+
+/* ------------------------------------------------------------------ salts */
+
+static int cmp_u64_asc(const void *a, const void *b)
+{
+    uint64_t x = *(const uint64_t *)a, y = *(const uint64_t *)b;
+    return x < y ? -1 : (x > y);
+}
+
+/*
+ * The paper calls the compression lossless (section 2.2, Table 1).  Peeling
+ * can never separate two non-zeros that fall into the same three cells, and
+ * with the three cells confined to one partition of m_sub cells per hash
+ * function that happens to some pair of a partition's P non-zeros with
+ * probability about P^2 / (2 m_sub^3): a few pairs per 10^8 non-zeros at this
+ * format's partition sizes, each costing two entries of the gradient.
+ *
+ * This repository's remedy uses what Algorithm 1 already provides: the merged
+ * Index reaches every rank before compress(g_shard, index) runs, so encoder
+ * and decoder can both derive, from the Index alone, a per-partition salt for
+ * the hash functions:
+ *
+ *   salt[a] = the smallest s in [0, TAGCO_SALT_LIMIT) under which no two
+ *             non-zeros of partition a have the same (slot_0, slot_1, slot_2);
+ *             TAGCO_SALT_LIMIT - 1 if there is none (then peeling reports the
+ *             entries it cannot recover, as always).
+ *
+ * Written out as the definition: for each s in turn, the triples of the
+ * partition's non-zeros are sorted and neighbours compared.  Nothing travels:
+ * the salts are a function of the merged Index and the seed.
+ */
+#define TAGCO_SALT_LIMIT 16
+
+int tagco_salts(const uint32_t *bitmap, uint64_t n_c, uint64_t U, uint64_t A,
+                uint64_t m_sub, uint64_t seed, uint32_t *salt_out)
+{
+    if (U == 0 || A == 0)
+        return 0;
+    uint32_t *idx = (uint32_t *)malloc(U * sizeof(uint32_t));
+    uint64_t *key = (uint64_t *)malloc(U * sizeof(uint64_t));
+    if (!idx || !key) {
+        free(idx);
+        free(key);
+        return -1;
+    }
+    uint64_t t = 0;
+    for (uint64_t i = 0; i < n_c; ++i)
+        if ((bitmap[i >> 5] >> (i & 31)) & 1u)
+            idx[t++] = (uint32_t)i;
+    for (uint64_t a = 0; a < A; ++a) {
+        uint64_t r0 = tagco_part_start(a, U, A), r1 = tagco_part_start(a + 1, U, A);
+        uint64_t n = r1 - r0;
+        salt_out[a] = TAGCO_SALT_LIMIT - 1;
+        for (uint32_t s = 0; s < TAGCO_SALT_LIMIT; ++s) {
+            for (uint64_t u = 0; u < n; ++u) {
+                uint64_t k = 0;
+                for (uint32_t j = 0; j < 3; ++j) {
+                    uint32_t slot;
+                    int32_t sign;
+                    tagco_hash(idx[r0 + u], seed, j, s, (uint32_t)m_sub, &slot, &sign);
+                    k = (k << 21) | slot; /* m_sub < 2^21 */
+                }
+                key[u] = k;
+            }
+            qsort(key, n, sizeof(uint64_t), cmp_u64_asc);
+            int dup = 0;
+            for (uint64_t u = 1; u < n; ++u)
+                if (key[u] == key[u - 1])
+                    dup = 1;
+            if (!dup) {
+                salt_out[a] = s;
+                break;
+            }
+        }
+    }
+    free(idx);
+    free(key);
+    return 0;
 }
 
 /* ---------------------------------------------------------------- encode */
 
 /*
  * local_count_sketch <- compress(g_shard, index)  (Algorithm 1).  The merged
- * Index enters only through the layout (A, m_sub) and the partition bounds.
+ * Index enters only through the layout (A, m_sub), the partition bounds and
+ * the partitions' salts (`salt`, A entries).
  * Pairs are taken in ascending c-index, hash functions j = 0,1,2 in order,
  * each update one float32 add.  `plus_only` replaces every sign by +1 (used
  * by a test that shows signs do not matter to peeling).
@@ -431,8 +513,8 @@ static uint64_t cell_of(uint32_t i, uint64_t a, uint32_t j, uint64_t m_sub,
  */
 void tagco_encode(const uint32_t *idx, const float *val, uint64_t cnt,
                   const uint32_t *bnd, uint64_t A, uint64_t m_sub,
-                  uint64_t seed, int plus_only, const uint32_t *mask,
-                  float *sketch)
+                  uint64_t seed, const uint32_t *salt, int plus_only,
+                  const uint32_t *mask, float *sketch)
 {
     uint64_t m = 3 * A * m_sub;
     for (uint64_t c = 0; c < m; ++c)
@@ -446,7 +528,7 @@ void tagco_encode(const uint32_t *idx, const float *val, uint64_t cnt,
             ++a;
         for (uint32_t j = 0; j < 3; ++j) {
             float s;
-            uint64_t c = cell_of(i, a, j, m_sub, seed, plus_only, &s);
+            uint64_t c = cell_of(i, a, j, m_sub, seed, salt[a], plus_only, &s);
             sketch[c] = sketch[c] + s * val[t];
         }
     }
@@ -504,10 +586,12 @@ void tagco_sum(const float *const *sketches, uint32_t n_ranks, uint64_t m,
  * whose summed value is 0.
  *
  * `sketch` is modified in place.  round_out[t] = round (1-based) in which
- * unknown t was resolved, 0 if never.
+ * unknown t was resolved, 0 if never.  `salt`: the partitions' salts (A
+ * entries), the same the encoders used.
  */
 int tagco_peel(const uint32_t *bitmap, uint64_t n_c, uint64_t U, uint64_t A,
-               uint64_t m_sub, uint64_t seed, int plus_only, float *sketch,
+               uint64_t m_sub, uint64_t seed, const uint32_t *salt,
+               int plus_only, float *sketch,
                uint32_t *idx_out, float *val_out, uint32_t *round_out,
                uint32_t *rounds, uint64_t *n_unresolved)
 {
@@ -543,7 +627,8 @@ int tagco_peel(const uint32_t *bitmap, uint64_t n_c, uint64_t U, uint64_t A,
         round_out[t] = 0;
         for (uint32_t j = 0; j < 3; ++j) {
             float s;
-            deg[cell_of(idx_out[t], part[t], j, m_sub, seed, plus_only, &s)]++;
+            deg[cell_of(idx_out[t], part[t], j, m_sub, seed, salt[part[t]],
+                        plus_only, &s)]++;
         }
     }
     uint64_t resolved = 0;
@@ -556,7 +641,7 @@ int tagco_peel(const uint32_t *bitmap, uint64_t n_c, uint64_t U, uint64_t A,
             for (uint32_t j = 0; j < 3; ++j) {
                 float s;
                 uint64_t c = cell_of(idx_out[t], part[t], j, m_sub, seed,
-                                     plus_only, &s);
+                                     salt[part[t]], plus_only, &s);
                 if (deg[c] == 1) {
                     val_out[t] = s * sketch[c]; /* snapshot: no write yet */
                     picked[t] = 1;
@@ -573,7 +658,7 @@ int tagco_peel(const uint32_t *bitmap, uint64_t n_c, uint64_t U, uint64_t A,
             for (uint32_t j = 0; j < 3; ++j) {
                 float s;
                 uint64_t c = cell_of(idx_out[t], part[t], j, m_sub, seed,
-                                     plus_only, &s);
+                                     salt[part[t]], plus_only, &s);
                 sketch[c] = sketch[c] - s * val_out[t];
                 deg[c]--;
             }
@@ -606,7 +691,8 @@ int tagco_peel(const uint32_t *bitmap, uint64_t n_c, uint64_t U, uint64_t A,
  */
 uint64_t tagco_estimate(const uint32_t *idx, const uint32_t *round_in,
                         uint64_t U, uint64_t A, uint64_t m_sub, uint64_t seed,
-                        const float *sketch, float *val_out)
+                        const uint32_t *salt, const float *sketch,
+                        float *val_out)
 {
     uint64_t a = 0, n_est = 0;
     for (uint64_t t = 0; t < U; ++t) {
@@ -617,7 +703,7 @@ uint64_t tagco_estimate(const uint32_t *idx, const uint32_t *round_in,
         float r[3];
         for (uint32_t j = 0; j < 3; ++j) {
             float s;
-            uint64_t c = cell_of(idx[t], a, j, m_sub, seed, 0, &s);
+            uint64_t c = cell_of(idx[t], a, j, m_sub, seed, salt[a], 0, &s);
             r[j] = s * sketch[c];
         }
         /* sort the three readings ascending, take the middle one */

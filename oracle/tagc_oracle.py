@@ -80,11 +80,14 @@ def lib():
         L.tagco_seed_word.restype = C.c_uint32
         L.tagco_seed_word.argtypes = [C.c_uint64, C.c_uint32]
         L.tagco_hash.restype = None
-        L.tagco_hash.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32,
+        L.tagco_hash.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32,
                                  C.c_uint32, u32p, C.POINTER(C.c_int32)]
+        L.tagco_salts.restype = C.c_int
+        L.tagco_salts.argtypes = [u32p, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
+                                  C.c_uint64, u32p]
         L.tagco_encode.restype = None
         L.tagco_encode.argtypes = [u32p, f32p, C.c_uint64, u32p, C.c_uint64,
-                                   C.c_uint64, C.c_uint64, C.c_int, u32p, f32p]
+                                   C.c_uint64, C.c_uint64, u32p, C.c_int, u32p, f32p]
         L.tagco_quantize_cells_bf16.restype = None
         L.tagco_quantize_cells_bf16.argtypes = [f32p, C.c_uint64]
         L.tagco_index_add.restype = C.c_uint64
@@ -96,11 +99,11 @@ def lib():
         L.tagco_sum.argtypes = [C.POINTER(f32p), C.c_uint32, C.c_uint64, f32p]
         L.tagco_peel.restype = C.c_int
         L.tagco_peel.argtypes = [u32p, C.c_uint64, C.c_uint64, C.c_uint64,
-                                 C.c_uint64, C.c_uint64, C.c_int, f32p, u32p,
+                                 C.c_uint64, C.c_uint64, u32p, C.c_int, f32p, u32p,
                                  f32p, u32p, u32p, u64p]
         L.tagco_estimate.restype = C.c_uint64
         L.tagco_estimate.argtypes = [u32p, u32p, C.c_uint64, C.c_uint64, C.c_uint64,
-                                     C.c_uint64, f32p, f32p]
+                                     C.c_uint64, u32p, f32p, f32p]
         L.tagco_wire_bits_per_param.restype = C.c_double
         L.tagco_wire_bits_per_param.argtypes = [C.c_double, C.c_double,
                                                 C.c_int]
@@ -291,20 +294,42 @@ def bounds(bitmap, n_c, U, A):
     return bnd
 
 
-def hash_slot(i, seed, j, m_sub):
+def hash_slot(i, seed, j, m_sub, salt=0):
     slot, sign = C.c_uint32(), C.c_int32()
-    lib().tagco_hash(i, seed, j, m_sub, C.byref(slot), C.byref(sign))
+    lib().tagco_hash(i, seed, j, salt, m_sub, C.byref(slot), C.byref(sign))
     return int(slot.value), int(sign.value)
 
 
-def encode(idx, val, bnd, A, m_sub, seed, plus_only=False, mask=None):
+SALT_LIMIT = 16
+
+
+def salts(bitmap, n_c, U, A, m_sub, seed):
+    """Per-partition hash salts, a function of the merged Index and the seed alone: the
+    smallest salt under which no two non-zeros of the partition share all three cells."""
+    out = np.zeros(max(A, 1), np.uint32)
+    if lib().tagco_salts(_u32p(bitmap), n_c, U, A, m_sub, seed, _u32p(out)) != 0:
+        raise MemoryError("oracle allocation failed")
+    return out[:A]
+
+
+def _salt_arg(salt, A):
+    """`salt=None` stands for the all-zero salts (every partition hashed as it is)."""
+    if salt is None:
+        return np.zeros(max(A, 1), np.uint32)
+    s = np.ascontiguousarray(salt, np.uint32)
+    if s.size < A:
+        raise ValueError("one salt per partition expected")
+    return s if s.size else np.zeros(1, np.uint32)
+
+
+def encode(idx, val, bnd, A, m_sub, seed, plus_only=False, mask=None, salt=None):
     m = 3 * A * m_sub
     sk = np.zeros(max(m, 1), np.float32)
     idx = np.ascontiguousarray(idx, np.uint32)
     val = np.ascontiguousarray(val, np.float32)
     lib().tagco_encode(_u32p(idx), _f32p(val), idx.size, _u32p(bnd), A, m_sub,
-                       seed, int(plus_only), None if mask is None else _u32p(mask),
-                       _f32p(sk))
+                       seed, _u32p(_salt_arg(salt, A)), int(plus_only),
+                       None if mask is None else _u32p(mask), _f32p(sk))
     return sk[:m]
 
 
@@ -341,7 +366,7 @@ class Decoded:
     residual: np.ndarray = field(default=None, repr=False)
 
 
-def peel(bitmap, n_c, U, A, m_sub, seed, sketch, plus_only=False) -> Decoded:
+def peel(bitmap, n_c, U, A, m_sub, seed, sketch, plus_only=False, salt=None) -> Decoded:
     idx = np.zeros(max(U, 1), np.uint32)
     val = np.zeros(max(U, 1), np.float32)
     rnd = np.zeros(max(U, 1), np.uint32)
@@ -350,6 +375,7 @@ def peel(bitmap, n_c, U, A, m_sub, seed, sketch, plus_only=False) -> Decoded:
         work = np.zeros(1, np.float32)
     rounds, unres = C.c_uint32(), C.c_uint64()
     rc = lib().tagco_peel(_u32p(bitmap), n_c, U, A, m_sub, seed,
+                          _u32p(_salt_arg(salt, A)),
                           int(plus_only), _f32p(work), _u32p(idx), _f32p(val),
                           _u32p(rnd), C.byref(rounds), C.byref(unres))
     if rc != 0:
@@ -361,7 +387,7 @@ def peel(bitmap, n_c, U, A, m_sub, seed, sketch, plus_only=False) -> Decoded:
 DECODE_PEEL, DECODE_PEEL_ESTIMATE, DECODE_ESTIMATE = 0, 1, 2
 
 
-def estimate(dec: Decoded, A, m_sub, seed, sketch, only_unresolved=True) -> int:
+def estimate(dec: Decoded, A, m_sub, seed, sketch, only_unresolved=True, salt=None) -> int:
     """Count Sketch point queries (median of the three signed readings) for the unknowns
     of `dec` that peeling left (or for all of them), on `sketch`; fills dec.val in place
     and returns how many were estimated (section 2.2, the estimation algorithm)."""
@@ -372,10 +398,11 @@ def estimate(dec: Decoded, A, m_sub, seed, sketch, only_unresolved=True) -> int:
     rnd = np.ascontiguousarray(dec.round, np.uint32)
     return int(lib().tagco_estimate(
         _u32p(dec.idx), _u32p(rnd) if only_unresolved else None, U, A, m_sub, seed,
-        _f32p(sk), _f32p(dec.val)))
+        _u32p(_salt_arg(salt, A)), _f32p(sk), _f32p(dec.val)))
 
 
-def decompress(bitmap, n_c, U, A, m_sub, seed, sketch, mode=DECODE_PEEL) -> Decoded:
+def decompress(bitmap, n_c, U, A, m_sub, seed, sketch, mode=DECODE_PEEL,
+               salt=None) -> Decoded:
     """peeling_decompress of Algorithm 1, optionally followed by estimation of what it
     could not recover (mode 1), or estimation alone on the raw sketch (mode 2)."""
     if mode == DECODE_ESTIMATE:
@@ -385,11 +412,11 @@ def decompress(bitmap, n_c, U, A, m_sub, seed, sketch, mode=DECODE_PEEL) -> Deco
         assert idx.size == U
         dec = Decoded(idx, np.zeros(U, np.float32), np.zeros(U, np.uint32), 0, U,
                       np.array(sketch, np.float32, copy=True))
-        estimate(dec, A, m_sub, seed, dec.residual, only_unresolved=False)
+        estimate(dec, A, m_sub, seed, dec.residual, only_unresolved=False, salt=salt)
         return dec
-    dec = peel(bitmap, n_c, U, A, m_sub, seed, sketch)
+    dec = peel(bitmap, n_c, U, A, m_sub, seed, sketch, salt=salt)
     if mode == DECODE_PEEL_ESTIMATE and dec.n_unresolved:
-        estimate(dec, A, m_sub, seed, dec.residual)
+        estimate(dec, A, m_sub, seed, dec.residual, salt=salt)
     return dec
 
 
@@ -405,29 +432,33 @@ class BucketResult:
     sketch: np.ndarray
     decoded: Decoded
     n_c: int
+    salt: np.ndarray = None
 
 
 def run_bucket(grads, cfg: Config, segments, plus_only=False,
-               decode_mode=DECODE_PEEL) -> BucketResult:
-    """Algorithm 1 for one bucket and len(grads) simulated ranks."""
+               decode_mode=DECODE_PEEL, salted=True) -> BucketResult:
+    """Algorithm 1 for one bucket and len(grads) simulated ranks.  `salted=False` leaves
+    every partition's salt at 0 (for tests that show what the salts are for)."""
     offs, n_c = c_offsets(segments)
     n_real = sum(s.length for s in segments if s.flags & FLAG_COMPRESS)
     ranks = [sparsify(g, cfg, segments) for g in grads]
     bitmap, U = merge_index([r.bitmap for r in ranks], cfg.index_mode)
     A, m_sub, m = layout(U, cfg, n_real)
     bnd = bounds(bitmap, n_c, U, A)
+    salt = (salts(bitmap, n_c, U, A, m_sub, cfg.seed) if salted
+            else np.zeros(A, np.uint32))
     mask = None if cfg.index_mode == INDEX_OR1 else bitmap
     for r in ranks:
-        r.sketch = encode(r.idx, r.val, bnd, A, m_sub, cfg.seed, plus_only, mask)
+        r.sketch = encode(r.idx, r.val, bnd, A, m_sub, cfg.seed, plus_only, mask, salt)
         if cfg.cell_type == CELL_BF16:
             r.sketch = quantize_cells_bf16(r.sketch)
     total = sketch_sum([r.sketch for r in ranks])
     if decode_mode == DECODE_PEEL:
-        dec = peel(bitmap, n_c, U, A, m_sub, cfg.seed, total, plus_only)
+        dec = peel(bitmap, n_c, U, A, m_sub, cfg.seed, total, plus_only, salt)
     else:
         assert not plus_only
-        dec = decompress(bitmap, n_c, U, A, m_sub, cfg.seed, total, decode_mode)
-    return BucketResult(ranks, bitmap, U, A, m_sub, m, bnd, total, dec, n_c)
+        dec = decompress(bitmap, n_c, U, A, m_sub, cfg.seed, total, decode_mode, salt)
+    return BucketResult(ranks, bitmap, U, A, m_sub, m, bnd, total, dec, n_c, salt)
 
 
 def wire_bits_per_param(index_bits, ratio, lhc=False):

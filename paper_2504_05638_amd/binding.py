@@ -144,7 +144,7 @@ def lib():
                                         C.POINTER(C.c_double),
                                         C.POINTER(C.c_uint64), C.c_uint32]
         L.tagc_hash_host.restype = None
-        L.tagc_hash_host.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32,
+        L.tagc_hash_host.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32,
                                      C.c_uint32, C.POINTER(C.c_uint32),
                                      C.POINTER(C.c_int32)]
         L.tagc_strerror.restype = C.c_char_p
@@ -243,7 +243,7 @@ def tagc_profile_read(cap: int = 64):
     return {names[i].decode(): (ms[i], int(cnt[i])) for i in range(n)}
 
 
-def tagc_hash_host(i, seed, j, m_sub):
+def tagc_hash_host(i, seed, j, m_sub, salt=0):
     slot, sign = C.c_uint32(), C.c_int32()
-    lib().tagc_hash_host(i, seed, j, m_sub, C.byref(slot), C.byref(sign))
+    lib().tagc_hash_host(i, seed, j, salt, m_sub, C.byref(slot), C.byref(sign))
     return int(slot.value), int(sign.value)

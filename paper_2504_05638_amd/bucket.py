@@ -237,6 +237,11 @@ class TagcBucket:
     def bounds(self):
         return self._np(self.sh_bounds, np.uint32, self.header()["A"] + 1)
 
+    def salts(self):
+        """The partitions' hash salts (behind the bounds in the same buffer)."""
+        A, cap = self.header()["A"], self.sizes.partition_capacity
+        return self._np(self.sh_bounds, np.uint32)[cap + 1:cap + 1 + A].copy()
+
     def outputs(self):
         U = self.header()["U"]
         return self._np(self.out_idx, np.uint32, U), self._np(self.out_val, np.float32, U)

@@ -155,7 +155,7 @@ template <uint32_t kCellPre, uint32_t kIdxPre>
 __global__ void __launch_bounds__(kDecodeThreads)
 peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ header,
             const uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
-            uint32_t *status, uint32_t sw0, uint32_t sw1, uint32_t sw2, uint32_t T_cap,
+            uint32_t *status, uint64_t seed, const uint32_t *__restrict__ salt, uint32_t T_cap,
             uint32_t P_cap, uint32_t mode)
 {
     extern __shared__ uint64_t lds64[];
@@ -201,6 +201,10 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     PHASE_INIT();
     const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
     const uint32_t Pa = uint32_t(uint64_t(a + 1) * U / A) - rho0;
+    // the partition's hash functions: the seed under the salt the encoders used
+    const uint32_t sa = salt[a];
+    const uint32_t sw0 = seed_word(seed, 3 * sa), sw1 = seed_word(seed, 3 * sa + 1),
+                   sw2 = seed_word(seed, 3 * sa + 2);
 
     // ---- stage the partition's cells from the registers, clear state
 #pragma unroll
@@ -421,8 +425,8 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
             attr_bytes[small] = lds;
         }
         kernel<<<grid, kDecodeThreads, lds, s>>>(
-            sh->sketch, sh->header, idx_out, val_out, sh->status, p->seed_word[0],
-            p->seed_word[1], p->seed_word[2], p->T_cap, p->P_cap, p->cfg.decode_mode);
+            sh->sketch, sh->header, idx_out, val_out, sh->status, p->cfg.seed,
+            sh->bounds + p->A_cap + 1, p->T_cap, p->P_cap, p->cfg.decode_mode);
     }
     if (dense_out && n_chunks) {
         ProfileScope ps("dense", s);

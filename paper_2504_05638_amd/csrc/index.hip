@@ -219,7 +219,138 @@ ranges_kernel(RankPtrs idx, RankPtrs cnt, uint32_t n_in, const uint32_t *__restr
     c[ranges_off + a] = lo;
 }
 
+// Per-partition hash salts (the compression is to be lossless, section 2.2 and Table 1).
+// Two non-zeros of a partition that fall into the same three cells can never be peeled
+// apart, and with the cells of a non-zero confined to its partition that happens to a few
+// pairs per 10^8 non-zeros.  The merged Index reaches every rank before compress(g_shard,
+// index) runs (Algorithm 1), so encoder and decoder can both derive from it, for every
+// partition, the smallest salt under which all of the partition's (slot_0, slot_1, slot_2)
+// are distinct; nothing travels.  Nearly every partition keeps salt 0.
+//
+// One workgroup per partition at a time, two workgroups per compute unit.  The partition's
+// non-zeros are the set bits of the merged Index in [bounds[a], bounds[a+1]).  Each gets a
+// number t (any order; a wave takes a run of numbers with one LDS add), its three slots under
+// the salt being tried, and is pushed on the list of its slot_0 (an LDS exchange of the
+// list's head); afterwards it walks what was on that list before it and compares the other
+// two slots.  LDS per non-zero: a 32-bit tag (slot_1, slot_2) and a 16-bit link; per cell of
+// a sub-table a 32-bit list head -- little enough for two partitions per compute unit, whose
+// phases (hashing on the vector units, list building and walking in LDS) then overlap.
+constexpr uint32_t kSaltThreads = 1024;
+constexpr uint32_t kSaltLimit = 16;       // salts tried: 0 .. 15
+constexpr uint32_t kNoLink = 0xFFFFu;
+constexpr uint32_t kSaltPre = 4;          // Index words per thread requested a partition ahead
+
+__global__ void __launch_bounds__(kSaltThreads)
+salt_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
+            const uint32_t *__restrict__ header, const uint32_t *__restrict__ bounds,
+            uint32_t *__restrict__ salt_out, uint64_t seed, uint32_t P_cap, uint32_t q_cap)
+{
+    extern __shared__ uint32_t lds_salt[];
+    uint32_t *tag = lds_salt;                        // [P_cap] c-index, then slot_1 | slot_2 << 16
+    uint32_t *head = tag + P_cap;                                   // [q_cap]
+    uint16_t *link = reinterpret_cast<uint16_t *>(head + q_cap);    // [P_cap]
+    __shared__ uint32_t s_n, s_dup;
+    const uint32_t A = header[TAGC_HDR_A], m_sub = min(header[TAGC_HDR_MSUB], q_cap);
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    // word `w` of partition [lo, hi), bits outside the partition cleared
+    auto load_word = [&](uint32_t w, uint32_t lo, uint32_t hi) -> uint32_t {
+        if (lo >= hi || w > ((hi - 1) >> 5) || w >= n_words) return 0u;
+        uint32_t word = bitmap[w];
+        if (w == (lo >> 5)) word &= 0xFFFFFFFFu << (lo & 31);
+        if (w == ((hi - 1) >> 5) && (hi & 31)) word &= (1u << (hi & 31)) - 1u;
+        return word;
+    };
+    // Requests run ahead of the work: the bounds of the partition after the next, and the
+    // first Index words of the next one, are on their way while this one is checked.
+    uint32_t pre[kSaltPre], lo = 0, hi = 0, lo2 = 0, hi2 = 0;
+    const uint32_t G = gridDim.x;
+    if (blockIdx.x < A) {
+        lo = bounds[blockIdx.x];
+        hi = bounds[blockIdx.x + 1];
+#pragma unroll
+        for (uint32_t k = 0; k < kSaltPre; ++k)
+            pre[k] = load_word((lo >> 5) + k * kSaltThreads + tid, lo, hi);
+    }
+    if (blockIdx.x + G < A) {
+        lo2 = bounds[blockIdx.x + G];
+        hi2 = bounds[blockIdx.x + G + 1];
+    }
+    for (uint32_t a = blockIdx.x; a < A; a += G) {
+        const uint32_t w_lo = lo >> 5, w_hi = lo < hi ? (hi - 1) >> 5 : 0;
+        const uint32_t cur_lo = lo, cur_hi = hi;
+        uint32_t cur[kSaltPre];
+#pragma unroll
+        for (uint32_t k = 0; k < kSaltPre; ++k) cur[k] = pre[k];
+        lo = lo2;
+        hi = hi2;
+        if (a + G < A) {
+#pragma unroll
+            for (uint32_t k = 0; k < kSaltPre; ++k)
+                pre[k] = load_word((lo >> 5) + k * kSaltThreads + tid, lo, hi);
+        }
+        if (a + 2 * G < A) {
+            lo2 = bounds[a + 2 * G];
+            hi2 = bounds[a + 2 * G + 1];
+        }
+        uint32_t salt = 0;
+        if (cur_lo < cur_hi) {
+            for (salt = 0; salt < kSaltLimit; ++salt) {
+                const uint32_t sw0 = seed_word(seed, 3 * salt), sw1 = seed_word(seed, 3 * salt + 1),
+                               sw2 = seed_word(seed, 3 * salt + 2);
+                for (uint32_t c = tid; c < m_sub; c += kSaltThreads) head[c] = kNoLink;
+                if (tid == 0) s_n = s_dup = 0;
+                __syncthreads();
+                uint32_t k = 0;
+                for (uint32_t base = w_lo + (tid - lane); base <= w_hi; base += kSaltThreads, ++k) {
+                    // (wave-uniform loop: the numbering below is a wave-wide scan)
+                    uint32_t word = k < kSaltPre ? cur[k < kSaltPre ? k : 0]
+                                                 : load_word(base + lane, cur_lo, cur_hi);
+                    const uint32_t pc = __popc(word);
+                    const uint32_t inc = wave_incl_scan<uint32_t>(pc);
+                    const uint32_t tot = __builtin_amdgcn_readlane(inc, 63);
+                    if (tot == 0) continue;
+                    uint32_t start = 0;
+                    if (lane == 0) start = atomicAdd(&s_n, tot);
+                    start = __builtin_amdgcn_readfirstlane(start);
+                    uint32_t t = start + inc - pc;
+                    for (; word; word &= word - 1, ++t)  // (a partition holds <= P_cap)
+                        if (t < P_cap) tag[t] = (base + lane) * 32 + uint32_t(__builtin_ctz(word));
+                }
+                __syncthreads();
+                // every lane busy: the numbered non-zeros are hashed in number order (a
+                // lane's own Index word holds anything from none to a dozen of them)
+                for (uint32_t t = tid; t < min(s_n, P_cap); t += kSaltThreads) {
+                    const uint32_t i = tag[t];
+                    uint32_t neg;
+                    const uint32_t c0 = hash_slot(i, sw0, m_sub, &neg);
+                    tag[t] = hash_slot(i, sw1, m_sub, &neg) | (hash_slot(i, sw2, m_sub, &neg) << 16);
+                    link[t] = uint16_t(atomicExch(&head[c0], t));
+                }
+                __syncthreads();
+                const uint32_t n = min(s_n, P_cap);
+                bool dup = false;
+                for (uint32_t t = tid; t < n; t += kSaltThreads) {
+                    const uint32_t mine = tag[t];
+                    for (uint32_t p = link[t]; p != kNoLink; p = link[p]) dup |= tag[p] == mine;
+                }
+                if (dup) s_dup = 1;
+                __syncthreads();
+                const bool again = s_dup != 0;
+                __syncthreads();  // s_dup is cleared by the next try
+                if (!again) break;
+            }
+            salt = min(salt, kSaltLimit - 1);
+        }
+        if (tid == 0) salt_out[a] = salt;
+    }
+}
+
 }  // namespace
+
+size_t salt_lds_bytes(uint32_t T_cap, uint32_t P_cap)
+{
+    return size_t(P_cap) * 4 + size_t(T_cap / 3) * 4 + size_t(P_cap) * 2 + 16;
+}
 
 int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32_t n_ranks,
                     const tagc_shared_buffers *sh, hipStream_t s)
@@ -256,6 +387,24 @@ int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32
         const uint32_t grid = uint32_t((p->A_cap + 1 + 3) / 4);
         bounds_kernel<<<grid, 256, 0, s>>>(sh->bitmap, n_words, uint32_t(p->n_c), chunk, n_chunks,
                                            sh->header, sh->bounds);
+    }
+    if (n_chunks) {
+        ProfileScope ps("salt", s);
+        const size_t lds = salt_lds_bytes(p->T_cap, p->P_cap);
+        static size_t attr_bytes = 0;
+        if (lds > attr_bytes) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(salt_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(lds)) != hipSuccess)
+                return TAGC_EHIP;
+            attr_bytes = lds;
+        }
+        // as many workgroups as fit the device at once, each taking partitions b, b + grid, ...
+        const uint32_t per_cu = uint32_t(std::max<size_t>(1, std::min<size_t>(2, kLdsBytes / (lds + 1024))));
+        const uint32_t grid = uint32_t(std::min<uint64_t>(p->A_cap, uint64_t(device_cu_count()) * per_cu));
+        salt_kernel<<<grid, kSaltThreads, lds, s>>>(sh->bitmap, n_words, sh->header, sh->bounds,
+                                                    sh->bounds + p->A_cap + 1, p->cfg.seed,
+                                                    p->P_cap, p->T_cap / 3);
     }
     if (n_chunks) {
         ProfileScope ps("ranges", s);

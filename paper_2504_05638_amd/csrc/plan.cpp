@@ -7,6 +7,7 @@
 #include <new>
 
 #include "tagc_internal.h"
+#include "tagc_test.h"
 
 using namespace tagc;
 
@@ -49,7 +50,6 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     p->cand_cap = 32;
     p->static_dense = false;
     p->any_nonfast = false;
-    for (uint32_t j = 0; j < 3; ++j) p->seed_word[j] = seed_word(cfg->seed, j);
 
     // Candidate route: slots per chunk for 1.3 x the kept fraction plus six standard
     // deviations.  Its second pass costs in proportion to the candidates; measured on
@@ -201,7 +201,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     z.shared_bitmap_bytes = round_up(4 * std::max<uint64_t>(words, 1), 16);
     z.shared_sketch_bytes = round_up(4 * p->m_cap, 16);
     z.shared_header_bytes = 4 * TAGC_HDR_WORDS;
-    z.shared_bounds_bytes = round_up(4 * (p->A_cap + 1), 16);
+    // the partitions' first c-indices (A + 1), then their hash salts (A)
+    z.shared_bounds_bytes = round_up(4 * (2 * p->A_cap + 1), 16);
     // chunk prefixes; behind them, when the 4-bit Index of more ranks than one pass takes is
     // summed, the running 4-bit sum
     z.shared_workspace_bytes = round_up(4 * (p->n_chunks + 1), 16);
@@ -347,11 +348,11 @@ extern "C" int tagc_decompress(const tagc_plan_t *p, const tagc_shared_buffers *
     return launch_decode(p, sh, idx_out, val_out, dense_out, static_cast<hipStream_t>(stream));
 }
 
-extern "C" void tagc_hash_host(uint32_t i, uint64_t seed, uint32_t j, uint32_t m_sub,
-                               uint32_t *slot, int32_t *sign)
+extern "C" void tagc_hash_host(uint32_t i, uint64_t seed, uint32_t j, uint32_t salt,
+                               uint32_t m_sub, uint32_t *slot, int32_t *sign)
 {
     uint32_t neg;
-    *slot = hash_slot(i, seed_word(seed, j), m_sub, &neg);
+    *slot = hash_slot(i, seed_word(seed, j + 3 * salt), m_sub, &neg);
     *sign = neg ? -1 : 1;
 }
 

@@ -4,7 +4,8 @@
 //   enters through the layout (and, when it was merged by addition, as a mask): partition a
 //   owns the pairs whose c-index lies in [bounds[a], bounds[a+1]) -- a contiguous run of the
 //   rank's sorted pair list, whose ends the Index aggregation leaves in the rank's cnt
-//   buffer -- and the 3*m_sub cells starting at a*3*m_sub.  One workgroup builds the
+//   buffer -- the 3*m_sub cells starting at a*3*m_sub, and its own salt for the hash functions
+//   (also left by the Index aggregation, behind the bounds).  One workgroup builds the
 //   partition's three sub-tables in LDS, reading the pairs once, and writes them out as one
 //   contiguous run, so the sketch is produced with coalesced stores and no global atomics.
 // sum: Reduce(local_count_sketch, d) as an element-wise float32 sum in rank order.
@@ -20,7 +21,7 @@ constexpr uint32_t kEncodeThreads = 512;
 __global__ void __launch_bounds__(kEncodeThreads)
 encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
               const uint32_t *__restrict__ cnt, const uint32_t *__restrict__ header,
-              float *__restrict__ sketch, uint32_t sw0, uint32_t sw1, uint32_t sw2,
+              float *__restrict__ sketch, uint64_t seed, const uint32_t *__restrict__ salt,
               uint32_t ranges_off, uint32_t pair_cap, const uint32_t *__restrict__ mask,
               uint32_t cells16)
 {
@@ -30,6 +31,10 @@ encode_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ val,
     const uint32_t a = blockIdx.x;
     if (a >= A) return;
     const uint32_t cells = 3 * m_sub;
+    // the partition's hash functions: the seed under the salt the Index aggregation chose
+    const uint32_t sa = salt[a];
+    const uint32_t sw0 = seed_word(seed, 3 * sa), sw1 = seed_word(seed, 3 * sa + 1),
+                   sw2 = seed_word(seed, 3 * sa + 2);
     // the partition's run of the sorted pair list, found when the Index was aggregated
     const uint32_t lo = min(cnt[ranges_off + a], pair_cap);
     const uint32_t hi = min(cnt[ranges_off + a + 1], pair_cap);
@@ -219,8 +224,8 @@ int launch_encode(const tagc_plan_t *p, const tagc_rank_buffers *rk, const tagc_
         attr_bytes = lds;
     }
     encode_kernel<<<uint32_t(p->A_cap), kEncodeThreads, lds, s>>>(
-        rk->idx, rk->val, rk->cnt, sh->header, rk->sketch, p->seed_word[0], p->seed_word[1],
-        p->seed_word[2], p->cnt_ranges, uint32_t(p->K),
+        rk->idx, rk->val, rk->cnt, sh->header, rk->sketch, p->cfg.seed,
+        sh->bounds + p->A_cap + 1, p->cnt_ranges, uint32_t(p->K),
         p->cfg.index_mode == TAGC_INDEX_OR1 ? nullptr : sh->bitmap,
         p->cfg.cell_type == TAGC_CELL_BF16);
     return hip_ok(hipGetLastError());

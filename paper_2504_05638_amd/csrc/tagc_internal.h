@@ -98,7 +98,6 @@ struct tagc_plan_s {
     bool static_dense;                        // some segment with k > 0 never takes the candidate route
     uint64_t n_real, n_c, K, U_cap, A_cap, m_cap;
     uint32_t P_cap, T_cap;
-    uint32_t seed_word[3];
     tagc::Workspace ws;
     uint64_t zero_bytes;                      // prefix of the rank workspace cleared per call
     uint64_t n_chunks;                        // popcount chunks of the Index
@@ -167,6 +166,7 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
                   float *val_out, float *dense_out, hipStream_t s);
 
 size_t decode_lds_bytes(uint32_t T_cap, uint32_t P_cap);
+size_t salt_lds_bytes(uint32_t T_cap, uint32_t P_cap);
 
 // device address, on the current device, of the library's own rank workspace
 // (TAGC_STATIC_WORKSPACE_BYTES); looked up on the first call per device, never allocated

@@ -109,13 +109,11 @@ def test_integer_inputs_decode_bit_exactly_to_the_definition(lf, n_ranks):
     assert r.A > 1                       # several partitions
     assert np.array_equal(r.decoded.idx, idx)
     ok = r.decoded.round > 0
-    assert r.decoded.n_unresolved == np.count_nonzero(~ok)
-    assert r.decoded.n_unresolved <= 4   # duplicate triples only, see below
-    assert np.array_equal(r.decoded.val[ok].astype(np.float64), val[ok])
-    assert np.all(r.decoded.val[~ok] == 0)
+    assert r.decoded.n_unresolved == 0   # lossless (section 2.2)
+    assert np.array_equal(r.decoded.val.astype(np.float64), val)
+    assert ok.all()
     # after a complete peel nothing is left in the sketch
-    if r.decoded.n_unresolved == 0:
-        assert not r.decoded.residual[:r.m].any()
+    assert not r.decoded.residual[:r.m].any()
 
 
 @pytest.mark.parametrize("dtype", [O.F32, O.BF16])
@@ -180,7 +178,8 @@ def test_resolved_set_is_the_complement_of_the_two_core(lf):
     cells = {}
     for k, a in zip(keys, part):
         cells[k] = [int(a) * 3 * r.m_sub + j * r.m_sub
-                    + O.hash_slot(k, cfg.seed, j, r.m_sub)[0] for j in range(3)]
+                    + O.hash_slot(k, cfg.seed, j, r.m_sub, int(r.salt[a]))[0]
+                    for j in range(3)]
     peeled = _worklist_two_core(keys, cells)
     got = set(np.asarray(keys)[r.decoded.round > 0].tolist())
     assert got == peeled
@@ -205,7 +204,7 @@ def test_exhaustive_tiny_cases_against_brute_force_rounds():
         keys = r.decoded.idx.tolist()
         part = np.searchsorted(r.bnd[1:r.A], r.decoded.idx, side="right")
         cells = {k: [int(a) * 3 * r.m_sub + j * r.m_sub
-                     + O.hash_slot(k, cfg.seed, j, r.m_sub)[0]
+                     + O.hash_slot(k, cfg.seed, j, r.m_sub, int(r.salt[a]))[0]
                      for j in range(3)] for k, a in zip(keys, part)}
         alive, rnd, t = set(keys), {}, 0
         while True:
@@ -239,9 +238,7 @@ def test_peeling_threshold_of_three_hash_sketches(lf, expect_ok):
     r = O.run_bucket(g, cfg, segs)
     assert r.U > 100_000
     if expect_ok:
-        # a partition of P unknowns fails only through two indices sharing all
-        # three cells: expected pairs ~ 13.5 U / (lf^3 P^2) << 1 here
-        assert r.decoded.n_unresolved <= 2
+        assert r.decoded.n_unresolved == 0
     else:
         assert r.decoded.n_unresolved > 0.5 * r.U
 
@@ -261,11 +258,10 @@ def test_table1_regimes_are_lossless_for_two_ranks(ratio_milli, theta_ppm):
     r = O.run_bucket(grads, cfg, segs)
     assert r.m <= n * 1000 // ratio_milli
     assert r.m / r.U > 1.25
-    assert r.decoded.n_unresolved <= 2
+    assert r.decoded.n_unresolved == 0
     idx, val = D.sparse_sum(grads, O.F32, segs)
-    ok = r.decoded.round > 0
     assert np.array_equal(r.decoded.idx, idx)
-    assert np.array_equal(r.decoded.val[ok].astype(np.float64), val[ok])
+    assert np.array_equal(r.decoded.val.astype(np.float64), val)
 
 
 # ------------------------------------------------------- signs (P9), edges
