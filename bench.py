@@ -24,9 +24,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # Kernels of the library grouped into the stages of the path.
 STAGES = {
-    "S1+S2 sparsify+index": ["fill_zero", "accumulate", "sample", "scan_spill", "select1", "hist1",
-                             "hist2c", "hist2", "select2", "finish", "widen4"],
-    "S3a index OR": ["index_or", "header", "bounds", "ranges"],
+    "S1+S2 sparsify+index": ["fill_zero", "accumulate", "prepare", "scan_spill", "hist1",
+                             "hist2c", "hist2", "select2", "count", "place", "widen4"],
+    "S3a index OR": ["index_or", "header", "bounds", "salt", "ranges"],
     "S2' encode": ["encode"],
     "S3b sketch sum": ["sketch_sum"],
     "S4 decode": ["enumerate", "peel", "dense"],
@@ -159,9 +159,11 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1, cell=4):
         "scan_spill": (3 if ef else 1) * N * z.n_real * e,
         "hist1": N * z.n_real * e,
         "hist2": N * z.n_real * e,
-        # finish = emit (candidate route) + compact (dense route: reads the gradient again);
-        # priced as emit, which is all it is for a bucket without dense-route segments
-        "finish": 8 * k_total + N * n_c // 8,
+        # place = the candidate route's last pass + the dense route's (which reads the gradient
+        # again); priced as the former, which is all it is for a bucket without dense-route
+        # segments; count reads the candidate slots (about 1.3 x 4 bytes per pair)
+        "place": 8 * k_total + N * n_c // 8,
+        "count": int(1.3 * 4 * k_total),
         "index_or": (wire * N + 1) * n_c // 8,
         "widen4": (1 + 4) * N * n_c // 8,
         "encode": 8 * k_total + N * cell * m,
@@ -376,14 +378,11 @@ def main():
     t_total = time.perf_counter() - t0
     ms_per_step = 1e3 * t_total / args.steps
     # the buffers now hold each lane's last bucket: it must have come out as it did alone
-    recounts = 0
     for i in range(n_b - lanes, n_b):
         hdr, st = tbs[i].header(), tbs[i].status()
         bad = st["flags"]
         for r in range(N):
-            rc = tbs[i].rank_counts(r)
-            bad |= rc["flags"]
-            recounts += rc["recounts"]
+            bad |= tbs[i].rank_counts(r)["flags"]
         # (with error feedback every pass starts from different accumulators, so U and the
         # residue legitimately change from pass to pass: only the flags are checked then)
         if bad or (not args.error_feedback and n_sets == 1 and (hdr, st) != facts[i]):
@@ -452,9 +451,6 @@ def main():
                    "input_bytes_per_step": input_bytes, "distinct_bucket_data_sets": pool,
                    "buckets_in_flight": lanes, "decode_workgroups": peel_wgs,
                    "host_issue_ms_per_step": round(1e3 * t_issue / args.steps, 3),
-                   # counts a workgroup recomputed instead of waiting for another one, in the
-                   # last bucket of every lane (diagnostic: stalls between kernels in flight)
-                   "recounts_in_last_buckets": recounts,
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,

@@ -181,9 +181,7 @@ enum {
                                unspecified but memory-safe)                      */
     TAGC_CNT_FLAGS = 2,     /* TAGC_FLAG_* bits                                  */
     TAGC_CNT_DENSE = 3,     /* segments that took the two-read route (diagnostic) */
-    TAGC_CNT_RECOUNTS = 4,  /* counts of another workgroup that were recomputed
-                               instead of waited for, see tagc_test_help_after
-                               (diagnostic)                                      */
+    TAGC_CNT_RESERVED = 4,  /* 0                                                 */
     TAGC_CNT_SEG0 = 5       /* [5 + l] = pairs of compressed segment l           */
 };
 /* Behind the counts (rank_cnt_bytes covers it) tagc_aggregate(PHASE_INDEX) leaves,
@@ -206,8 +204,6 @@ enum {
     TAGC_ST_ESTIMATED = 3,  /* entries whose value is an estimate                */
     TAGC_ST_WORDS = 8
 };
-#define TAGC_FLAG_SPIN_LIMIT 1u /* reserved: no wait between workgroups can fail, see
-                                   tagc_test_help_after                              */
 #define TAGC_FLAG_OVERFLOW 2u   /* a capacity was exceeded: results invalid          */
 
 /* Device buffers of one simulated rank (all dev, caller-owned). */
@@ -382,17 +378,6 @@ int tagc_decompress(const tagc_plan_t *plan, const tagc_shared_buffers *shared,
 int tagc_profile_enable(int on);
 int tagc_profile_read(const char **names, double *total_ms, uint64_t *launches,
                       uint32_t cap);
-
-/*
- * For tests.  Where a workgroup of PHASE_INDEX's last kernel needs a count that
- * another workgroup publishes, it polls for it `polls` times and then computes it
- * itself from the same input (the other workgroup may not have started: other
- * streams' kernels can hold its place), so results never depend on the value.
- * The default is a few thousand; 0 makes every count that is not there at the
- * first look be recomputed, which is how the tests reach that path.  Process-wide,
- * takes effect at the next tagc_compress; returns the previous value.
- */
-uint32_t tagc_test_help_after(uint32_t polls);
 
 const char *tagc_strerror(int err);
 

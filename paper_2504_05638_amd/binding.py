@@ -19,19 +19,19 @@ TAGC_INDEX_OR1, TAGC_INDEX_ADD1, TAGC_INDEX_ADD4 = 0, 1, 2
 TAGC_PHASE_INDEX, TAGC_PHASE_SKETCH = 1, 2
 TAGC_SEG_COMPRESS = 1
 TAGC_CNT_TOTAL, TAGC_CNT_NONFINITE, TAGC_CNT_FLAGS, TAGC_CNT_DENSE = 0, 1, 2, 3
-TAGC_CNT_RECOUNTS, TAGC_CNT_SEG0 = 4, 5
+TAGC_CNT_RESERVED, TAGC_CNT_SEG0 = 4, 5
 TAGC_HDR_U, TAGC_HDR_A, TAGC_HDR_MSUB, TAGC_HDR_M, TAGC_HDR_WORDS = 0, 1, 2, 3, 8
 TAGC_ST_UNRESOLVED, TAGC_ST_ROUNDS, TAGC_ST_FLAGS, TAGC_ST_WORDS = 0, 1, 2, 8
 TAGC_ST_ESTIMATED = 3
 TAGC_DECODE_PEEL, TAGC_DECODE_PEEL_ESTIMATE, TAGC_DECODE_ESTIMATE = 0, 1, 2
 TAGC_CELL_F32, TAGC_CELL_BF16 = 0, 1
-TAGC_FLAG_SPIN_LIMIT, TAGC_FLAG_OVERFLOW = 1, 2
+TAGC_FLAG_OVERFLOW = 2
 TAGC_STATIC_WORKSPACE_BYTES = 16 << 20
 
 EXPORTS = ["tagc_plan", "tagc_plan_destroy", "tagc_plan_sizes",
            "tagc_plan_upload", "tagc_compress", "tagc_compress_static", "tagc_feedback_apply", "tagc_aggregate",
            "tagc_decompress", "tagc_profile_enable", "tagc_profile_read",
-           "tagc_test_help_after", "tagc_hash_host", "tagc_strerror"]
+           "tagc_hash_host", "tagc_strerror"]
 
 
 class tagc_segment(C.Structure):
@@ -135,8 +135,6 @@ def lib():
         L.tagc_decompress.restype = C.c_int
         L.tagc_decompress.argtypes = [vp, C.POINTER(tagc_shared_buffers), vp,
                                       vp, vp, vp]
-        L.tagc_test_help_after.restype = C.c_uint32
-        L.tagc_test_help_after.argtypes = [C.c_uint32]
         L.tagc_profile_enable.restype = C.c_int
         L.tagc_profile_enable.argtypes = [C.c_int]
         L.tagc_profile_read.restype = C.c_int
@@ -221,11 +219,6 @@ def tagc_decompress(plan, shared: tagc_shared_buffers, idx_out, val_out,
                     dense_out=None, stream: int = 0):
     _check(lib().tagc_decompress(plan, C.byref(shared), idx_out, val_out,
                                  dense_out, stream), "tagc_decompress")
-
-
-def tagc_test_help_after(polls: int) -> int:
-    """Sets after how many polls a missing count is recomputed; returns the old value."""
-    return int(lib().tagc_test_help_after(int(polls)))
 
 
 def tagc_profile_enable(on: bool):

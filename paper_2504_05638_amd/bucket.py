@@ -199,7 +199,6 @@ class TagcBucket:
         L = self.sizes.n_seg_compressed
         return dict(total=int(c[B.TAGC_CNT_TOTAL]), nonfinite=int(c[B.TAGC_CNT_NONFINITE]),
                     flags=int(c[B.TAGC_CNT_FLAGS]), dense_segments=int(c[B.TAGC_CNT_DENSE]),
-                    recounts=int(c[B.TAGC_CNT_RECOUNTS]),
                     seg=c[B.TAGC_CNT_SEG0:B.TAGC_CNT_SEG0 + L].tolist())
 
     def rank_pairs(self, r):

@@ -140,28 +140,22 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     const uint64_t words = p->n_c / 32;
     p->n_chunks = ceil_div(words, kChunkWords);
 
-    // rank workspace: a prefix that every PHASE_INDEX call clears, then uncleared scratch
+    // rank workspace: the histograms that are added to by atomics (a prefix that every
+    // PHASE_INDEX call clears before use), then plain scratch that is written before it is read
     Workspace &w = p->ws;
     const uint64_t chunks = scs * kCandChunksPerSuper;
     uint64_t off = 0;
-    w.hist1 = off;
-    off += L * kBins1 * 4;
     w.hist1d = off;
     off += L * kBins1 * 4;
     w.hist2 = off;
     off += (cfg->dtype == TAGC_F32 ? L * kBins2 * 4 : 0);
-    w.tile_state = off;
-    off += round_up(tiles * 8, 16);
-    w.sc_state = off;
-    off += round_up(scs * 8, 16);
-    // one arrival counter per segment, one tile ticket, one raised pre-threshold per segment
-    w.counters = off;
-    off += round_up(4 * (2 * L + 1), 64);
     p->zero_bytes = off;
     w.sel = off;
     off += round_up(L * sizeof(SelDev), 16);
-    w.binlo = off;
-    off += round_up(L * 4, 16);
+    w.tile_cnt = off;
+    off += round_up(tiles * 8, 16);
+    w.sc_cnt = off;
+    off += round_up(scs * 8, 16);
     w.chunk_cnt = off;
     off += round_up(chunks * 4, 16);
     off = round_up(off, 128);  // a chunk's slots then start on a cache-line boundary
@@ -184,9 +178,10 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     z.part_unknowns = P_cap;
     z.part_cells = T_cap;
     z.grad_elems = grad_elems;
-    // header, one row per compressed segment, then per segment one pre-threshold hint and one
-    // count of calls that still sample beside it
-    z.table_bytes = 32 + 32 * std::max<uint64_t>(L, 1) + round_up(8 * std::max<uint64_t>(L, 1), 16);
+    // header, one row per compressed segment, then the plan's device state (pre-thresholds,
+    // arrival counters, candidate histograms: see TableState)
+    z.table_bytes = 32 + 32 * std::max<uint64_t>(L, 1) +
+                    round_up(4 * table_state_words(std::max<uint64_t>(L, 1)), 16);
     z.rank_idx_bytes = round_up(4 * std::max<uint64_t>(K, 1), 16);
     z.rank_val_bytes = z.rank_idx_bytes;
     // counts first, then (from the Index aggregation on) the A+1 positions at which the
@@ -246,11 +241,13 @@ extern "C" int tagc_plan_upload(const tagc_plan_t *p, void *table_dev, void *str
                        p->table.size() * sizeof(SegDev), hipMemcpyHostToDevice,
                        s) != hipSuccess)
         return TAGC_EHIP;
-    // no pre-threshold is known yet: the first PHASE_INDEX call samples
+    // the plan's device state starts at zero; no pre-threshold is known yet, so the first
+    // PHASE_INDEX call samples
     if (!p->table.empty() &&
         hipMemsetAsync(static_cast<char *>(table_dev) + 32 + p->table.size() * sizeof(SegDev), 0,
-                       p->table.size() * 8, s) != hipSuccess)
+                       4 * table_state_words(p->table.size()), s) != hipSuccess)
         return TAGC_EHIP;
+    p->sample_pending.store(1, std::memory_order_relaxed);
     return TAGC_OK;
 }
 

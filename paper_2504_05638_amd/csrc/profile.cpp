@@ -76,18 +76,6 @@ int device_cu_count()
 
 using namespace tagc;
 
-namespace {
-std::atomic<uint32_t> g_help_after{tagc::kHelpAfterPolls};
-}
-namespace tagc {
-uint32_t help_after_polls() { return g_help_after.load(std::memory_order_relaxed); }
-}  // namespace tagc
-
-extern "C" uint32_t tagc_test_help_after(uint32_t polls)
-{
-    return g_help_after.exchange(polls, std::memory_order_relaxed);
-}
-
 extern "C" int tagc_profile_enable(int on)
 {
     std::lock_guard<std::mutex> lk(g_mu);

@@ -13,26 +13,30 @@
 // Two routes per segment, both exact:
 //
 //  candidate route (one read of the gradient)
-//    sample       only when the plan knows no pre-threshold for the segment yet: a strided
-//                 sample gives a conservative pre-threshold bin `binlo`; otherwise the bin
-//                 the previous call on the plan left behind is taken (the launch also
-//                 clears the per-call workspace)
-//    scan_spill   streams the segment once: entries with key bin >= binlo ("candidates",
-//                 ~1.3 x k of them) are histogrammed in LDS and spilled, in position
-//                 order, into fixed slots per 4 KiB chunk -- no cross-wave dependency
-//    select1      exact threshold from the candidate histogram, and the pre-threshold for
-//                 the next call; if the candidates do not contain k entries (the
+//    prepare      only on the first call after the plan's table was uploaded: a strided
+//                 sample gives every segment a conservative pre-threshold bin; afterwards
+//                 each call leaves the pre-threshold for the next one in the table
+//    scan_spill   streams the segment once: entries with key bin >= the pre-threshold
+//                 ("candidates", ~1.3 x k of them) are histogrammed and spilled, in position
+//                 order, into fixed slots per 4 KiB chunk -- no cross-wave dependency.  The
+//                 workgroup that finishes a segment last selects its exact threshold from
+//                 the candidate histogram; if the candidates do not contain k entries (the
 //                 pre-threshold misled) the segment is re-routed
 //    hist2c/select2  fp32 only: low 16 key bits inside the threshold bin
-//    finish       (first part) ordered pass over the candidates only: pairs + every Index
-//                 word
+//    count        survivors of every super-chunk of candidates (32 chunks)
+//    place        ordered pass over the candidates only: pairs + every Index word
 //
-//  dense route (segments that are short, unaligned, keep more than ~3 %, or were re-routed;
-//  two reads)
+//  dense route (segments that are short, unaligned, keep more than ~3 %, have no
+//  pre-threshold yet, or were re-routed; three reads)
 //    hist1        exact histogram of the top 15 key bits of every entry, in LDS; the
 //                 workgroup that completes a segment's histogram selects its threshold
 //    hist2/select2 fp32 only, as above
-//    finish       (second part) ordered pass over the gradient: pairs + Index words
+//    count        survivors of every tile of the gradient
+//    place        ordered pass over the gradient: pairs + Index words
+//
+// count and place are one launch each for both routes.  Ordered output across workgroups
+// needs no waiting: place starts when every count is there, and every item adds up the counts
+// of the earlier items of its segment by itself.
 //
 // With a gradient accumulator (error feedback: Algorithm 1, lines 1-2) what is sparsified is
 // grad + acc: scan_spill, and accumulate for the segments it does not read, write the sums
@@ -40,10 +44,9 @@
 // by the rank's own Index and applied when acc is read next (see SentMap).  With 4-bit
 // counters on the wire (section 2.2) widen4 turns the Index into them at the end.
 //
-// Ordered output across workgroups: every item publishes its counts as soon as it has
-// them and learns its offset from the counts of earlier items only; counts that are not
-// there after a bounded number of polls it computes itself, so no workgroup depends on
-// another one's progress and no kernel needs the device to itself.
+// Counters that must start at zero (arrivals, the candidate histograms) live in the plan's
+// table, which only the library writes: whoever reads them last puts them back to zero, so
+// no call spends a launch on clearing (see TableState).
 #include <mutex>
 
 #include "device_utils.h"
@@ -276,19 +279,21 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
     return total >= need;
 }
 
-// ----------------------------------------------------------------- sample
+// ---------------------------------------------------------------- prepare
 
-// One workgroup per compressed segment.  Initialises the segment's SelDev (route) and,
-// for segments on the candidate route, picks `binlo` from a strided sample of 16-byte
-// vectors: the sample bin above which  k*S/n + 5*sqrt(k*S/n) + 16  sampled entries lie.
-// The margin makes it very unlikely that fewer than k entries of the whole segment pass
-// the pre-threshold; if that still happens select1 notices and re-routes the segment.
+// First call after the table's upload (and plans without a scan to clear for them).  One
+// workgroup per compressed segment: segments on the candidate route that have no
+// pre-threshold yet get one from a strided sample of 16-byte vectors: the sample bin above
+// which  k*S/n + 5*sqrt(k*S/n) + 16  sampled entries lie.  The margin makes it very unlikely
+// that fewer than k entries of the whole segment pass the pre-threshold; if that still
+// happens the selection notices and re-routes the segment.  A sample that holds too few
+// non-zeros to say anything leaves the segment without one: it takes the dense route this
+// time, whose histogram then provides it.  The remaining workgroups clear the histograms of
+// the dense route when there is no scan to do it.
 template <int DTYPE>
 __global__ void __launch_bounds__(kHistThreads)
-sample_kernel(const char *__restrict__ grad, const char *acc, const SentMap sent,
-              const uint32_t *__restrict__ table, SelDev *__restrict__ sel,
-              uint32_t *__restrict__ binlo, uint32_t *hint, uint4 *zero_base, uint64_t zero_n16,
-              uint32_t *cnt, uint32_t n_cnt)
+prepare_kernel(const char *__restrict__ grad, const char *acc, const SentMap sent,
+               uint32_t *table, uint4 *zero_base, uint64_t zero_n16)
 {
     extern __shared__ uint32_t h[];
     __shared__ uint32_t smem[32];
@@ -297,52 +302,17 @@ sample_kernel(const char *__restrict__ grad, const char *acc, const SentMap sent
     const uint32_t L = table[0];
     const uint32_t tid = threadIdx.x;
     if (blockIdx.x >= L) {
-        // the remaining workgroups clear the per-call part of the workspace and the counts
         const uint32_t fb = blockIdx.x - L, nfb = gridDim.x - L;
         const uint4 z = make_uint4(0, 0, 0, 0);
         for (uint64_t i = uint64_t(fb) * kHistThreads + tid; i < zero_n16;
              i += uint64_t(nfb) * kHistThreads)
             zero_base[i] = z;
-        if (fb == 0)
-            for (uint32_t i = tid; i < n_cnt; i += kHistThreads) cnt[i] = 0;
         return;
     }
     const uint32_t l = blockIdx.x;
     const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
-    SelDev r{};
-    r.route = (sd.flags & kSegFast) ? 0u : 1u;
-    if (sd.k == 0 || sd.n == 0) {  // nothing survives: no pass needs to read this segment
-        r.T = 0xFFFFFFFFu;
-        r.route = 0;
-        if (tid == 0) {
-            sel[l] = r;
-            binlo[l] = 0x7FFFFFFFu;
-        }
-        return;
-    }
-    if (r.route) {
-        if (tid == 0) {
-            sel[l] = r;
-            binlo[l] = 1;
-        }
-        return;
-    }
-    // A pre-threshold left by the previous call on this plan (another rank, or the last
-    // training step) is used as it is: the select kernels keep it tuned and withdraw it
-    // when it fails, and whatever it is worth the result stays exact.
-    // After a call whose candidates came out short (the scale dropped since the hint was
-    // tuned; nothing in the scan can repair that direction) the next few calls sample as
-    // well and take the lower of the two.
-    const uint32_t hb = hint[l];
-    uint32_t *watch = hint + L;
-    const uint32_t wt = watch[l];
-    if (hb && !wt) {
-        if (tid == 0) {
-            sel[l] = r;
-            binlo[l] = hb;
-        }
-        return;
-    }
+    const TableState ts = table_state(table, L);
+    if (sd.k == 0 || sd.n == 0 || !(sd.flags & kSegFast) || ts.hint[l]) return;
     for (uint32_t i = tid; i < kBins1; i += kHistThreads) h[i] = 0;
     __syncthreads();
     const uint32_t nvec = sd.n / VEC;
@@ -373,13 +343,8 @@ sample_kernel(const char *__restrict__ grad, const char *acc, const SentMap sent
     const uint32_t need = uint32_t(ks + 5.0f * sqrtf(ks) + 16.0f) + 1u;
     uint32_t bin, above, at, total;
     const bool found = select_bins<32>(h, need, &bin, &above, &at, &total, smem);
-    if (tid == 0) {
-        if (!found) r.route = 1;  // the sample holds too few non-zeros to say anything
-        sel[l] = r;
-        bin = max(bin, 1u);  // bin 0 (|g| < 2^-133) is never a candidate
-        binlo[l] = hb && found ? min(hb, bin) : bin;
-        if (wt) watch[l] = wt - 1;
-    }
+    // bin 0 (|g| < 2^-133) is never a candidate
+    if (tid == 0 && found) ts.hint[l] = max(bin, 1u);
 }
 
 // ------------------------------------------------------------- scan_spill
@@ -408,24 +373,135 @@ sample_kernel(const char *__restrict__ grad, const char *acc, const SentMap sent
 // 32 MB of requests outstanding, enough to saturate HBM; more only lengthens the queue the
 // last workgroups to start wait in, and they keep that lag to the end of the kernel.  The
 // LDS pays for the chunk buffer (candidates are fetched from it by position instead of
-// being selected out of sixteen registers) and the staging area.  The LDS histogram only
-// covers the kSpillWindow bins from binlo upwards (6 octaves of magnitude); anything above
-// goes straight to the global one.  Slot order inside a chunk comes from a wave-local scan
-// of the per-lane counts, so a wave never waits on another.
-constexpr uint32_t kSpillWindow = 768;
+// being selected out of sixteen registers) and the staging area.  The histogram covers the
+// kWinBins bins from the segment's pre-threshold upwards (12 octaves of magnitude); what lies
+// above them is only counted (it survives whenever the threshold is inside the window, and
+// otherwise the segment is re-routed).  Slot order inside a chunk comes from a wave-local
+// scan of the per-lane counts, so a wave never waits on another.
+//
+// A workgroup that is done with its part of a segment adds its histogram to the segment's
+// in the plan's table and counts itself as arrived; the one that arrives last selects the
+// segment's threshold on the spot (select_window) and puts the table words back to zero.
+// The kernel's workgroups also clear, as they start, the dense route's histograms in the
+// rank workspace, which nothing touches before the kernels after this one.
 constexpr uint32_t kSpillThreads = 512;
 constexpr uint32_t kSpillStage = 512;  // staged slots per wave
 constexpr uint32_t kSpillList = 16;    // staged chunks per wave
-constexpr uint32_t kWatchCalls = 8;    // calls that sample beside the carried pre-threshold after a miss
+constexpr uint32_t kWatchCalls = 8;    // calls that extrapolate a falling pre-threshold after a miss
 constexpr uint32_t kSpillRaise = 6;    // bins (1/128 octave each) a wave's pre-threshold goes up per try
+
+// Threshold of one candidate-route segment from its candidate histogram `win` (table), by
+// the kSpillThreads threads of the scan's last workgroup on the segment.  Leaves SelDev,
+// the segment's count, the pre-threshold for the next call, and the table words at zero.
+// pre-threshold for the next call from `bin2`, the bin above which 1.3 k entries lie now:
+// that bin itself, or, in the calls after a miss (the scale fell by more than the margin
+// since the hint was tuned), lower by the factor it fell by since the call before (at most
+// half an octave) and 1.5 % more.  Bins are float32 bit patterns >> 16: the magnitudes are
+// extrapolated, not the bin numbers, whose width in relative terms varies twofold across an
+// octave.
+__device__ inline uint32_t next_hint(uint32_t bin2, uint32_t prev, uint32_t watch)
+{
+    if (!watch || prev <= bin2) return max(bin2, 1u);
+    const float now = __uint_as_float(bin2 << 16), before = __uint_as_float(prev << 16);
+    const float fall = fmaxf(now / before, 0.7071f);
+    return max(__float_as_uint(now * fall * 0.985f) >> 16, 1u);
+}
+
+template <int DTYPE>
+__device__ inline void select_window(uint32_t l, const SegDev &sd, uint32_t blo,
+                                     const TableState ts, SelDev *sel, uint32_t *smem /* >= 32 */)
+{
+    constexpr uint32_t BPT = kWinBins / kSpillThreads;  // consecutive bins per thread
+    static_assert(BPT * kSpillThreads == kWinBins, "every thread owns BPT bins of the window");
+    const uint32_t tid = threadIdx.x;
+    uint32_t *win = ts.win + size_t(l) * kWinWords;
+    uint32_t c[BPT];
+#pragma unroll
+    for (uint32_t b = 0; b < BPT; ++b) {
+        c[b] = win[tid * BPT + b];
+        win[tid * BPT + b] = 0;
+    }
+    const uint32_t above_w = win[kWinBins], nf = win[kWinBins + 1];
+    const uint32_t raised = ts.raised[l], overflow = ts.reroute[l];
+    __syncthreads();  // everybody has read what thread 0 clears next
+    if (tid == 0) {
+        win[kWinBins] = win[kWinBins + 1] = 0;
+        ts.raised[l] = ts.reroute[l] = ts.arrive[l] = 0;
+    }
+    // the histogram is complete from the highest pre-threshold any wave used upwards
+    const uint32_t floor_bin = max(blo, raised), floor_w = floor_bin - blo;
+    uint32_t s = 0;
+#pragma unroll
+    for (uint32_t b = 0; b < BPT; ++b) {
+        if (tid * BPT + b < floor_w) c[b] = 0;
+        s += c[b];
+    }
+    uint32_t total;
+    const uint32_t prefix = block_excl_scan<uint32_t, kSpillThreads / 64>(s, &total, smem);
+    const uint32_t suffix = total - prefix + above_w;  // this thread's bins and everything higher
+    // largest bin with at least `need` entries at or above it; twice: the threshold (k), and
+    // the pre-threshold for the next call (1.3 k, what the slots per chunk are sized for)
+    const uint32_t want = uint32_t(1.3f * float(sd.k)) + 1u;
+    if (tid == 0) smem[16] = smem[19] = 0xFFFFFFFFu;
+    __syncthreads();
+    auto locate = [&](uint32_t need, uint32_t *bin_out, uint32_t *above_out) {
+        if (!(s && suffix >= need && suffix - s < need)) return;
+        uint32_t acc = suffix - s;  // entries in the bins above the one looked at
+#pragma unroll
+        for (int b = int(BPT) - 1; b >= 0; --b) {
+            if (acc + c[b] >= need) {
+                *bin_out = tid * BPT + uint32_t(b);
+                if (above_out) *above_out = acc;
+                return;
+            }
+            acc += c[b];
+        }
+    };
+    locate(sd.k, &smem[16], &smem[17]);
+    locate(want, &smem[19], nullptr);
+    __syncthreads();
+    if (tid != 0) return;
+    const uint32_t bin_w = smem[16], above = smem[17], bin2_w = smem[19];
+    const bool found = bin_w != 0xFFFFFFFFu && !overflow && blo != 0;
+    SelDev r{};
+    if (!found) {
+        // The candidates hold fewer than k entries (the scale fell since the pre-threshold
+        // was tuned), the threshold lies above the window, slots overflowed, or there was no
+        // pre-threshold: dense route, whose histogram also provides the next pre-threshold.
+        r.route = 1;
+        if (blo != 0 && !overflow && above_w < sd.k) ts.watch[l] = kWatchCalls;
+        ts.hint[l] = 0;
+        sel[l] = r;
+        return;
+    }
+    // The window may not reach down to 1.3 k entries; then one bin below what this call
+    // could see.
+    const uint32_t bin2 = bin2_w != 0xFFFFFFFFu ? max(blo + bin2_w, 1u) : max(floor_bin, 2u) - 1u;
+    const uint32_t wt = ts.watch[l];
+    ts.hint[l] = next_hint(bin2, ts.prev[l], wt);
+    ts.prev[l] = bin2;
+    if (wt) ts.watch[l] = wt - 1;
+    if (nf) atomicAdd(&ts.glob[1], nf);
+    const uint32_t T_bin = blo + bin_w;
+    if (DTYPE == kBF16) {
+        r.T = T_bin << 16;
+        r.G = above;
+        r.quota = sd.k - above;
+        r.cnt = sd.k;
+    } else {
+        r.bin1 = T_bin;
+        r.G1 = above;
+        r.need2 = 1;
+    }
+    sel[l] = r;
+}
 
 template <int DTYPE>
 __global__ void __launch_bounds__(kSpillThreads)
 scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
-                  const uint32_t *__restrict__ table,
-                  SelDev *sel, const uint32_t *__restrict__ binlo, uint32_t *raised,
-                  uint32_t *__restrict__ hist, uint32_t *__restrict__ cand,
-                  uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP)
+                  uint32_t *table, SelDev *sel, uint32_t *__restrict__ cand,
+                  uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
+                  uint4 *zero_base, uint64_t zero_n16)
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
@@ -435,33 +511,31 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
     constexpr uint32_t NW = kSpillThreads / 64;
     constexpr uint32_t STAGE_WORDS = kSpillStage * (DTYPE == kBF16 ? 1 : 2);
     static_assert(ROWS == 4 && ROWS * VEC <= 32, "packed masks and row counts below");
-    __shared__ uint32_t h[kSpillWindow];
+    __shared__ uint32_t h[kWinWords];
+    __shared__ uint32_t s_sel[32];
+    __shared__ uint32_t s_last;
     __shared__ uint32_t stage[NW][STAGE_WORDS];
     __shared__ uint32_t list[NW][3][kSpillList];  // chunk number, staging offset, count
     __shared__ uint4 data[NW][ROWS * 64];         // each wave's current chunk
     const uint32_t L = table[0];
     const uint32_t total_chunks = table[4] * kCandChunksPerSuper;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    const TableState ts = table_state(table, L);
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     // wave-uniform by construction; saying so keeps chunk addresses in scalar registers
     const uint32_t wib = __builtin_amdgcn_readfirstlane(tid >> 6);
+    {   // the dense route's histograms start at zero (nobody reads them before this kernel ends)
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        for (uint64_t i = uint64_t(blockIdx.x) * kSpillThreads + tid; i < zero_n16;
+             i += uint64_t(gridDim.x) * kSpillThreads)
+            zero_base[i] = z;
+    }
     uint32_t span = (total_chunks + gridDim.x - 1) / gridDim.x;
     span = (span + NW - 1) / NW * NW;
     const uint64_t g0 = uint64_t(blockIdx.x) * span;
     if (g0 >= total_chunks) return;
     const uint64_t g1 = min(g0 + span, uint64_t(total_chunks));
-#ifdef TAGC_PHASE_TIMING
-    // per-workgroup time stamps (100 MHz counter) in the unused dense-route histogram area:
-    // start, first chunk classified, streaming done, histogram flushed
-    unsigned long long *stamp =
-        reinterpret_cast<unsigned long long *>(hist + uint64_t(L) * kBins1) + 8 * blockIdx.x;
-    bool first_done = false;
-    if (tid == 0) stamp[0] = wall_clock64();
-#define SPILL_STAMP(k) do { if (tid == 0) stamp[k] = wall_clock64(); } while (0)
-#else
-#define SPILL_STAMP(k) do { } while (0)
-#endif
-    for (uint32_t i = tid; i < kSpillWindow; i += kSpillThreads) h[i] = 0;
+    for (uint32_t i = tid; i < kWinWords; i += kSpillThreads) h[i] = 0;
     __syncthreads();
     // last segment whose first chunk is not beyond the span's start
     uint32_t l0 = 0;
@@ -509,17 +583,14 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
         const uint32_t lo = g0 > s0 ? uint32_t(g0 - s0) : 0u;
         const uint32_t hi = uint32_t(min(uint64_t(n_chunks), g1 - s0));
         if (lo >= hi) continue;
-        // Another workgroup may re-route the segment while we look.  Waves that disagree
-        // about it do no harm: a re-routed segment's candidates are never read, and the
-        // barriers below do not depend on the answer.
-        const uint32_t route = __builtin_amdgcn_readfirstlane(
-            __hip_atomic_load(&sel[l].route, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        const uint32_t blo = binlo[l];  // 1 <= blo <= 0x7FFF on this route
-        uint32_t *gh = hist + uint64_t(l) * kBins1;
-        // With an accumulator (error feedback) the segment is streamed whatever its route:
-        // this pass is also the one that turns acc into grad + acc, which the dense route
-        // then reads instead of the gradient.
-        if (!route || acc) {
+        // No pre-threshold (the sample could not tell, or the last call withdrew it): the
+        // segment takes the dense route this time.
+        // With an accumulator (error feedback) the segment is streamed all the same: this
+        // pass is also the one that turns acc into grad + acc, which the dense route then
+        // reads instead of the gradient.  Its candidates are then never used.
+        const uint32_t hint = ts.hint[l];
+        const uint32_t blo = hint ? hint : 0x7F7Fu;  // 1 <= blo <= 0x7FFF
+        if (hint || acc) {
             const char *base = grad + sd.offset * EB;
             char *abase = acc ? acc + sd.offset * EB : nullptr;
             // The wave's own pre-threshold: starts at the segment's and goes up when a chunk
@@ -719,9 +790,9 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                         bits = uint32_t(reinterpret_cast<const uint16_t *>(dw)[rel]) << 16;
                     else
                         bits = reinterpret_cast<const uint32_t *>(dw)[rel];
-                    const uint32_t bin = (bits & 0x7FFFFFFFu) >> 16, wi = bin - blo;
-                    if (wi < kSpillWindow) atomicAdd(&h[wi], 1u);
-                    else atomicAdd(&gh[bin], 1u);
+                    const uint32_t bin = (bits & 0x7FFFFFFFu) >> 16;
+                    atomicAdd(&h[min(bin - blo, kWinBins)], 1u);      // in the window, or above it
+                    if (bin >= 0x7F80u) atomicAdd(&h[kWinBins + 1], 1u);  // all-ones exponent
                     if (ps < CAP) {
                         if (DTYPE == kBF16) {
                             if (staged) stc[ps] = bits | rel;
@@ -749,120 +820,138 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                     chunk_cnt[chunk_id] = total;
                 }
                 overflow |= total > CAP;
-#ifdef TAGC_PHASE_TIMING
-                if (!first_done) { SPILL_STAMP(1); first_done = true; }
-#endif
             }
-            SPILL_STAMP(2);
             if (staged) flush();
-            SPILL_STAMP(3);
-            if (blo_w > blo && lane == 0) atomicMax(&raised[l], blo_w);
+            if (blo_w > blo && lane == 0) atomicMax(&ts.raised[l], blo_w);
             if (overflow && lane == 0)  // a chunk denser than its slots: take the dense route
-                atomicOr(&sel[l].route, 1u);
+                atomicOr(&ts.reroute[l], 1u);
         }
         __syncthreads();
-        for (uint32_t i = tid; i < kSpillWindow; i += kSpillThreads) {
+        uint32_t *win = ts.win + size_t(l) * kWinWords;
+        for (uint32_t i = tid; i < kWinWords; i += kSpillThreads) {
             const uint32_t c = h[i];
             if (c) {
-                atomicAdd(&gh[blo + i], c);
+                atomicAdd(&win[i], c);
                 h[i] = 0;
             }
         }
+        // The table updates are device-scope atomics, performed where every CU sees them; a
+        // thread only has to wait until its own have been acknowledged before the workgroup
+        // counts as arrived.  (A device-scope release fence would also write back every dirty
+        // line of the L2, at many times the cost.)  The workgroup that arrives last drops
+        // what it may hold of the table in its caches and selects.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
-        SPILL_STAMP(4);
+        if (tid == 0) {
+            const uint64_t c_last = s0 + n_chunks - 1;  // segment's chunks: one workgroup per span
+            const uint32_t expected = uint32_t(c_last / span) - uint32_t(s0 / span) + 1u;
+            s_last = atomicAdd(&ts.arrive[l], 1u) == expected - 1u;
+        }
+        __syncthreads();
+        if (s_last) {  // uniform
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            select_window<DTYPE>(l, sd, hint, ts, sel, s_sel);
+        }
+        __syncthreads();
     }
 }
-#undef SPILL_STAMP
+
+// Whether segment l is on the dense route: by plan (not eligible for the candidate route), or
+// because the scan's selection sent it there (no pre-threshold, too few candidates, a chunk
+// denser than its slots).  sel[l] of a candidate-route segment has been written by the scan.
+__device__ inline bool on_dense_route(const SegDev &sd, const SelDev *sel, uint32_t l)
+{
+    if (sd.k == 0 || sd.n == 0) return false;
+    return !(sd.flags & kSegFast) || sel[l].route != 0;
+}
 
 // true iff some segment is on the dense route.  Every thread reads the same words, so the
 // loads are scalar and the answer is uniform without a barrier.
-__device__ inline bool any_dense_route(const SelDev *sel, uint32_t L)
+__device__ inline bool any_dense_route(const SegDev *segs, const SelDev *sel, uint32_t L)
 {
-    uint32_t any = 0;
-    for (uint32_t l = 0; l < L; ++l) any |= sel[l].route;
-    return any != 0;
+    bool any = false;
+    for (uint32_t l = 0; l < L; ++l) any |= on_dense_route(segs[l], sel, l);
+    return any;
 }
 
 // ------------------------------------------------------------------ hist1
 
-template <int DTYPE>
-__device__ inline void hist_word(uint32_t w, uint32_t *h)
+// LDS histogram of the dense route: `WBINS` counters for the bins from `base` upwards; an
+// entry outside that window goes straight to the global histogram `gh`.
+template <uint32_t WBINS>
+struct HistWin {
+    uint32_t *h, *gh;
+    uint32_t base;
+    __device__ inline void add(uint32_t bin) const
+    {
+        if (WBINS == kBins1) {
+            atomicAdd(&h[bin], 1u);
+        } else {
+            const uint32_t wi = bin - base;
+            if (wi < WBINS) atomicAdd(&h[wi], 1u);
+            else atomicAdd(&gh[bin], 1u);
+        }
+    }
+};
+
+template <int DTYPE, uint32_t WBINS>
+__device__ inline void hist_word(uint32_t w, const HistWin<WBINS> &hw)
 {
     if (DTYPE == kBF16) {
         uint32_t a = w & 0x7FFFu, b = (w >> 16) & 0x7FFFu;
-        if (a) atomicAdd(&h[a], 1u);
-        if (b) atomicAdd(&h[b], 1u);
+        if (a) hw.add(a);
+        if (b) hw.add(b);
     } else {
         uint32_t key = w & 0x7FFFFFFFu;
-        if (key) atomicAdd(&h[key >> 16], 1u);
+        if (key) hw.add(key >> 16);
     }
 }
 
-template <int DTYPE>
-__device__ inline void hist_vec(uint4 v, uint32_t *h)
+template <int DTYPE, uint32_t WBINS>
+__device__ inline void hist_vec(uint4 v, const HistWin<WBINS> &hw)
 {
-    hist_word<DTYPE>(v.x, h);
-    hist_word<DTYPE>(v.y, h);
-    hist_word<DTYPE>(v.z, h);
-    hist_word<DTYPE>(v.w, h);
+    hist_word<DTYPE>(v.x, hw);
+    hist_word<DTYPE>(v.y, hw);
+    hist_word<DTYPE>(v.z, hw);
+    hist_word<DTYPE>(v.w, hw);
 }
 
-__device__ inline void hist_elem(uint32_t f32bits, uint32_t *h)
+template <uint32_t WBINS>
+__device__ inline void hist_elem(uint32_t f32bits, const HistWin<WBINS> &hw)
 {
     uint32_t key = f32bits & 0x7FFFFFFFu;
-    if (key) atomicAdd(&h[key >> 16], 1u);
+    if (key) hw.add(key >> 16);
 }
 
-// Threshold bin of one segment from its 32768-bin histogram, by a whole workgroup of
-// kHistThreads threads.  `dense` = 0: segment on the candidate route, histogram of
-// candidates only (a miss re-routes the segment); 1: segment on the dense route, histogram
-// of everything.
+// Threshold bin of one dense-route segment from the 32768-bin histogram of all its entries,
+// by a whole workgroup of kHistThreads threads.  Also leaves the pre-threshold for the next
+// call on this plan: the bin above which about 1.3 k entries lie (what the slots per chunk
+// are sized for).
 template <int DTYPE>
-__device__ inline void select1_segment(uint32_t n_seg, uint32_t l, const SegDev &sd,
-                                       const uint32_t *hist,
-                                       SelDev *sel, uint32_t *cnt, uint32_t dense,
-                                       const uint32_t *binlo, const uint32_t *raised,
-                                       uint32_t *hint, uint32_t *smem /* >= 32 words */)
+__device__ inline void select_dense(uint32_t l, const SegDev &sd, const uint32_t *hist,
+                                    SelDev *sel, const TableState ts,
+                                    uint32_t *smem /* >= 32 words */)
 {
-    SelDev r = sel[l];
-    if (r.route != dense) {
-        // a candidate-route segment that overflowed its slots: the pre-threshold was too low
-        if (!dense && (sd.flags & kSegFast) && sd.k && threadIdx.x == 0) hint[l] = 0;
-        return;
-    }
-    if (sd.k == 0 || sd.n == 0) {
-        if (threadIdx.x == 0) cnt[TAGC_CNT_SEG0 + l] = 0;
-        return;
-    }
     const uint32_t *h = hist + uint64_t(l) * kBins1;
-    // Besides the threshold bin: the pre-threshold for the next call on this plan, the bin
-    // above which about 1.3 k entries lie (what the slots per chunk are sized for).  The
-    // candidate histogram may not reach that far down; then one bin below this call's
-    // pre-threshold.  A miss withdraws the hint, so that the next call samples again.
     uint32_t bin, above, at, total, bin2, nf;
     const bool fast = (sd.flags & kSegFast) != 0;
     const uint32_t want = fast ? uint32_t(1.3f * float(sd.k)) + 1u : 0u;
     // nf: inputs with an all-ones exponent fall into bins >= 0x7F80
-    // Candidate route: the histogram is complete from the highest pre-threshold any wave of
-    // the scan used (the segment's, or what a wave raised it to when a chunk overflowed).
-    const uint32_t floor_bin = dense ? 0u : max(binlo[l], raised[l]);
     const bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem, want, &bin2,
-                                       0x7F80u, &nf, floor_bin);
+                                       0x7F80u, &nf);
     if (threadIdx.x != 0) return;
     if (fast) {
-        uint32_t nh;
-        if (bin2 != 0xFFFFFFFFu) nh = max(bin2, 1u);
-        else if (dense) nh = 1u;  // fewer non-zeros than that in the whole segment
-        else nh = found ? max(floor_bin, 2u) - 1u : 0u;
-        hint[l] = nh;
+        // fewer non-zeros than 1.3 k in the whole segment: everything is a candidate
+        const uint32_t b2 = bin2 != 0xFFFFFFFFu ? max(bin2, 1u) : 1u;
+        // after a miss (the scale fell below what the carried pre-threshold admits) the next
+        // calls extrapolate the fall instead of trusting the last value
+        ts.hint[l] = next_hint(b2, ts.prev[l], ts.watch[l]);
+        ts.prev[l] = b2;
     }
-    if (!found && !dense) {  // the candidates hold fewer than k entries: dense route
-        sel[l].route = 1;
-        if (fast) hint[n_seg + l] = kWatchCalls;  // and the next calls sample beside the hint
-        return;
-    }
-    if (nf) atomicAdd(&cnt[TAGC_CNT_NONFINITE], nf);
-    if (dense) atomicAdd(&cnt[TAGC_CNT_DENSE], 1u);
+    if (nf) atomicAdd(&ts.glob[1], nf);
+    atomicAdd(&ts.glob[2], 1u);
+    SelDev r{};
+    r.route = 1;
     if (!found) {  // fewer non-zeros than k: keep every non-zero
         r.T = 0;
         r.quota = 0;
@@ -879,34 +968,24 @@ __device__ inline void select1_segment(uint32_t n_seg, uint32_t l, const SegDev 
         r.need2 = 1;
     }
     sel[l] = r;
-    if (!r.need2) {
-        cnt[TAGC_CNT_SEG0 + l] = r.cnt;
-        atomicAdd(&cnt[TAGC_CNT_TOTAL], r.cnt);
-    }
 }
 
-// Candidate route: one workgroup per segment, after scan_spill.
-template <int DTYPE>
-__global__ void __launch_bounds__(kHistThreads)
-select1_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ hist,
-               SelDev *sel, uint32_t *cnt, const uint32_t *__restrict__ binlo,
-               const uint32_t *__restrict__ raised, uint32_t *hint)
-{
-    __shared__ uint32_t smem[32];
-    const uint32_t l = blockIdx.x;
-    const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
-    select1_segment<DTYPE>(table[0], l, sd, hist, sel, cnt, 0, binlo, raised, hint, smem);
-}
+// Dense route: one workgroup per CU, all entries of every dense-route segment.  Leaves at
+// once when no segment is on the dense route.  The workgroup that completes a segment's
+// histogram selects its threshold right away, while the others go on with the next segment:
+// no separate selection launch.
+//
+// WBINS = 32768: all counters in LDS (128 KiB), for plans with dense-route segments.  A plan
+// without any launches the kernel only as the safety net of re-routed segments, and a
+// workgroup that needs most of a compute unit's LDS has to wait, on a busy device, until
+// one is that free -- just to find that there is nothing to do.  Such plans use WBINS = 4096
+// (16 KiB): the 32 octaves around the segment's last pre-threshold, where all but a
+// vanishing part of a gradient lies; the rest is added to the global histogram directly.
+constexpr uint32_t kHistWindow = 4096;
 
-// Dense route: one workgroup per CU, 32768 LDS counters, all entries of every dense-route
-// segment.  Leaves at once when no segment is on the dense route.  The workgroup that
-// completes a segment's histogram selects its threshold right away, while the others go on
-// with the next segment: no separate selection launch.
-template <int DTYPE>
+template <int DTYPE, uint32_t WBINS>
 __global__ void __launch_bounds__(kHistThreads)
-hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, SelDev *sel,
-             uint32_t *hist, uint32_t *cnt, const uint32_t *__restrict__ binlo, uint32_t *hint,
-             uint32_t *arrive)
+hist1_kernel(const char *__restrict__ grad, uint32_t *table, SelDev *sel, uint32_t *hist)
 {
     extern __shared__ uint32_t h[];
     __shared__ uint32_t s_sel[32];
@@ -914,15 +993,23 @@ hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, 
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
     const uint32_t L = table[0];
-    if (!any_dense_route(sel, L)) return;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    if (!any_dense_route(segs, sel, L)) return;
+    const TableState ts = table_state(table, L);
     const uint32_t tid = threadIdx.x;
-    for (uint32_t i = tid; i < kBins1; i += kHistThreads) h[i] = 0;
+    for (uint32_t i = tid; i < WBINS; i += kHistThreads) h[i] = 0;
     __syncthreads();
     for (uint32_t l = 0; l < L; ++l) {
         const SegDev sd = segs[l];
-        if (sd.k == 0 || sd.n == 0 || !sel[l].route) continue;
+        if (!on_dense_route(sd, sel, l)) continue;
         const char *base = grad + sd.offset * EB;
+        uint32_t *gh = hist + uint64_t(l) * kBins1;
+        // window: 24 octaves below to 8 above the bin the last call's 1.3 k largest entries
+        // began at; without one, magnitudes from 2^-30 to 4
+        const uint32_t prev = ts.prev[l];
+        const HistWin<WBINS> hw{h, gh, WBINS == kBins1 ? 0u
+                                          : (prev ? (prev > 3072u ? min(prev - 3072u, kBins1 - WBINS) : 0u)
+                                                  : 97u * 128u)};
         if (sd.flags & kSegAligned) {
             const uint4 *vp = reinterpret_cast<const uint4 *>(base);
             const uint64_t nvec = sd.n / VEC;
@@ -931,27 +1018,26 @@ hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, 
             for (; v + 3 * stride < nvec; v += 4 * stride) {
                 const uint4 a = ld_stream(vp + v), b = ld_stream(vp + v + stride),
                             c = ld_stream(vp + v + 2 * stride), d = ld_stream(vp + v + 3 * stride);
-                hist_vec<DTYPE>(a, h);
-                hist_vec<DTYPE>(b, h);
-                hist_vec<DTYPE>(c, h);
-                hist_vec<DTYPE>(d, h);
+                hist_vec<DTYPE>(a, hw);
+                hist_vec<DTYPE>(b, hw);
+                hist_vec<DTYPE>(c, hw);
+                hist_vec<DTYPE>(d, hw);
             }
-            for (; v < nvec; v += stride) hist_vec<DTYPE>(ld_stream(vp + v), h);
+            for (; v < nvec; v += stride) hist_vec<DTYPE>(ld_stream(vp + v), hw);
             if (blockIdx.x == 0) {
                 uint64_t i = nvec * VEC + tid;
-                if (i < sd.n) hist_elem(load_elem_bits(base, i, DTYPE), h);
+                if (i < sd.n) hist_elem(load_elem_bits(base, i, DTYPE), hw);
             }
         } else {
             for (uint64_t i = uint64_t(blockIdx.x) * kHistThreads + tid; i < sd.n;
                  i += uint64_t(gridDim.x) * kHistThreads)
-                hist_elem(load_elem_bits(base, i, DTYPE), h);
+                hist_elem(load_elem_bits(base, i, DTYPE), hw);
         }
         __syncthreads();
-        uint32_t *gh = hist + uint64_t(l) * kBins1;
-        for (uint32_t i = tid; i < kBins1; i += kHistThreads) {
+        for (uint32_t i = tid; i < WBINS; i += kHistThreads) {
             uint32_t c = h[i];
             if (c) {
-                atomicAdd(&gh[i], c);
+                atomicAdd(&gh[hw.base + i], c);
                 h[i] = 0;
             }
         }
@@ -962,11 +1048,12 @@ hist1_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table, 
         // arrives last drops what it may hold of the histogram in its caches and selects.
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
-        if (tid == 0) s_last = atomicAdd(&arrive[l], 1u) == gridDim.x - 1;
+        if (tid == 0) s_last = atomicAdd(&ts.arrive_d[l], 1u) == gridDim.x - 1;
         __syncthreads();
         if (s_last) {  // uniform
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            select1_segment<DTYPE>(L, l, sd, hist, sel, cnt, 1, binlo, nullptr, hint, s_sel);
+            if (tid == 0) ts.arrive_d[l] = 0;  // for the next call
+            select_dense<DTYPE>(l, sd, hist, sel, ts, s_sel);
         }
         __syncthreads();
     }
@@ -978,12 +1065,12 @@ hist2_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
              const SelDev *__restrict__ sel, uint32_t *__restrict__ hist2)
 {
     const uint32_t L = table[0];
-    if (!any_dense_route(sel, L)) return;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    if (!any_dense_route(segs, sel, L)) return;
     const uint32_t tid = threadIdx.x;
     for (uint32_t l = 0; l < L; ++l) {
-        if (!sel[l].need2 || !sel[l].route) continue;
         const SegDev sd = segs[l];
+        if (!on_dense_route(sd, sel, l) || !sel[l].need2) continue;
         const uint32_t bin1 = sel[l].bin1;
         uint32_t *gh = hist2 + uint64_t(l) * kBins2;
         const char *base = grad + sd.offset * 4;
@@ -1027,8 +1114,8 @@ hist2c_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
     for (uint32_t l = 0; l < L; ++l) {
-        if (!sel[l].need2 || sel[l].route) continue;
         const SegDev sd = segs[l];
+        if (sd.k == 0 || sd.n == 0 || on_dense_route(sd, sel, l) || !sel[l].need2) continue;
         const uint32_t bin1 = sel[l].bin1;
         uint32_t *gh = hist2 + uint64_t(l) * kBins2;
         const uint32_t n_chunks = (sd.n + CHUNK - 1) / CHUNK;
@@ -1044,14 +1131,14 @@ hist2c_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel
 }
 
 __global__ void __launch_bounds__(kHistThreads)
-select2_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ hist2,
-               SelDev *__restrict__ sel, uint32_t *__restrict__ cnt)
+select2_kernel(uint32_t *table, const uint32_t *__restrict__ hist2, SelDev *__restrict__ sel)
 {
     __shared__ uint32_t smem[32];
     const uint32_t l = blockIdx.x;
+    const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
+    if (sd.k == 0 || sd.n == 0) return;
     SelDev r = sel[l];
     if (!r.need2) return;
-    const SegDev sd = reinterpret_cast<const SegDev *>(table + 8)[l];
     uint32_t bin, above, at, total;
     bool found =
         select_bins<64>(hist2 + uint64_t(l) * kBins2, sd.k - r.G1, &bin, &above, &at, &total, smem);
@@ -1059,7 +1146,7 @@ select2_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     if (!found) {  // cannot happen when both histograms saw the same data
         bin = 0;
         above = total;
-        atomicOr(&cnt[TAGC_CNT_FLAGS], TAGC_FLAG_OVERFLOW);
+        atomicOr(&table_state(table, table[0]).glob[0], TAGC_FLAG_OVERFLOW);
     }
     r.T = (r.bin1 << 16) | bin;
     r.G = r.G1 + above;
@@ -1067,24 +1154,16 @@ select2_kernel(const uint32_t *__restrict__ table, const uint32_t *__restrict__ 
     r.cnt = sd.k;
     r.need2 = 0;
     sel[l] = r;
-    cnt[TAGC_CNT_SEG0 + l] = r.cnt;
-    atomicAdd(&cnt[TAGC_CNT_TOTAL], r.cnt);
 }
 
 // ---------------------------------------------------------- ordered output
 
-constexpr uint64_t kStAgg = 1ull << 62, kStMask = 3ull << 62;  // published / status bits
-
-// Ordered output (emit's items, compaction's tiles).  state word = status(2) |
-// count(key > T)(31) | count(key == T)(31).  An item publishes its counts as soon as it has
-// them, without waiting for anything, and then adds up the counts of all earlier items of its
-// segment: no chain from item to item.  A predecessor that is running is never waited for
-// long.  One that has not started may take arbitrarily long: the device's dies hand out their
-// shares of a grid independently of each other, so with other kernels in flight a
-// lower-numbered workgroup can still be waiting for room on its die while higher-numbered
-// ones hold theirs, and two kernels that wait like this can hold each other's room for
-// good.  So a wait never decides anything: after `help_after` polls whoever needs a count
-// computes it from the same input and goes on.
+// Ordered output (the candidate route's super-chunks, the dense route's tiles) takes two
+// launches and no waiting.  `count` leaves, per item, count(key > T) << 31 | count(key == T);
+// `place` starts when all of them are there: every item adds up the counts of the earlier
+// items of its segment by itself (a few hundred to a few thousand words from the L2) and puts
+// its survivors where they belong.  No workgroup ever depends on another one's progress, so
+// neither the order in which the device starts them nor other kernels in flight matter.
 
 // last l with start(l) <= t, start() read through `field` (tile_start or sc_start)
 template <typename F>
@@ -1098,17 +1177,49 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
     return lo;
 }
 
+// pairs segment i emits, as the selection left it (segments that keep nothing have none)
+__device__ inline uint32_t segment_count(const SegDev &sd, const SelDev *sel, uint32_t i)
+{
+    return sd.k == 0 || sd.n == 0 ? 0u : sel[i].cnt;
+}
+
+// The rank's count words, from the selections and what the call's kernels accumulated in
+// the table (which goes back to zero); by one workgroup of the last kernel.
+__device__ inline void write_rank_counts(uint32_t *table, const SelDev *sel, uint32_t *cnt,
+                                         uint32_t *smem /* >= 8 */)
+{
+    const uint32_t L = table[0];
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    uint32_t total = 0;
+    for (uint32_t l = threadIdx.x; l < L; l += kEmitThreads) {
+        const uint32_t c = segment_count(segs[l], sel, l);
+        cnt[TAGC_CNT_SEG0 + l] = c;
+        total += c;
+    }
+    total = block_sum<uint32_t, kEmitThreads / 64>(total, smem);
+    if (threadIdx.x == 0) {
+        const TableState ts = table_state(table, L);
+        cnt[TAGC_CNT_TOTAL] = total;
+        cnt[TAGC_CNT_FLAGS] = ts.glob[0];
+        cnt[TAGC_CNT_NONFINITE] = ts.glob[1];
+        cnt[TAGC_CNT_DENSE] = ts.glob[2];
+        cnt[TAGC_CNT_RESERVED] = 0;
+        ts.glob[0] = ts.glob[1] = ts.glob[2] = 0;
+    }
+}
+
 // ------------------------------------------------------------------- emit
 
-// Candidate route, final pass.  A workgroup handles kEmitItems adjacent super-chunks (32
+// Candidate route, count and place.  A workgroup handles kEmitItems adjacent super-chunks (32
 // chunks each), two waves per super-chunk: 4 threads per chunk share the chunk's slots
-// evenly, in order, and classify them against the exact threshold twice -- once to count,
-// once (after the scan over the item's threads and the prefix over the segment's earlier
-// super-chunks) to place the survivors in ascending c-index.  A super-chunk's Index words
-// are assembled in LDS and written whole, zeros included.
+// evenly, in order, and classify them against the exact threshold.  `count` (PLACE = false)
+// stops there and stores the item's totals.  `place` classifies again, scans over the item's
+// threads, adds up the earlier super-chunks of the segment and places the survivors in
+// ascending c-index.  A super-chunk's Index words are assembled in LDS and written whole,
+// zeros included.
 //
 // Every step is latency-bound (a dependent memory access costs 1-3 us under load), so the
-// kernel is built to need few of them in a row and to be resident all at once (one item's
+// kernels are built to need few of them in a row and to be resident all at once (one item's
 // state per thread keeps the register count low enough for that).  Everything whose
 // address follows from the workgroup number alone is requested at once: the chunk counts,
 // and -- lane i taking segment i -- the whole segment and selection tables, from which the
@@ -1119,47 +1230,28 @@ __device__ inline uint32_t segment_of(uint32_t L, uint32_t t, F start)
 // instruction would touch 64 different cache lines (measured: 60 % of the kernel's time);
 // so the first kEmitStage of them are placed in LDS and leave as contiguous stores, and
 // only what exceeds that (items keeping more than about 2 %) is stored directly.
-//
-// The prefix over earlier super-chunks has no chain: an item publishes its own counts,
-// then its threads add up the counts of all predecessors in its segment.  A predecessor
-// publishes right after counting and waits for nobody before that, so a word that is not
-// there yet is polled for -- but only `help_after` times: a predecessor's workgroup may
-// not have started (see "Ordered output" above), and after that the thread counts the
-// predecessor's slots itself.  No workgroup depends on another one's progress.  (Handing
-// the items out in order by ticket instead, so that a predecessor has always started, was
-// measured: one counter for the ~1500 workgroups of a 200 M-entry bucket costs 30 ns per
-// ticket, 44 us on a 31 us kernel; one counter per segment still 14 us.)
 constexpr uint32_t kEmitStage = 800;  // survivors of an item that go through LDS
 static_assert(kEmitThreads == 128 * kEmitItems, "two waves per item");
 
-template <int DTYPE>
+template <int DTYPE, bool PLACE>
 __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
                                  const uint32_t *__restrict__ table,
                                  const SelDev *__restrict__ sel,
             const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
-            uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_state,
+            uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_cnt,
             uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
-            uint32_t *__restrict__ bitmap, uint32_t *cnt, uint32_t help_after,
-            uint64_t *stamps)
+            uint32_t *__restrict__ bitmap)
 {
-#ifdef TAGC_PHASE_TIMING
-    // per-workgroup time stamps (100 MHz counter) in the tile state area of the dense route,
-    // which a plan without dense-route work leaves unused
-#define EMIT_STAMP(i) do { if (threadIdx.x == 0) stamps[8 * bid + (i)] = wall_clock64(); } while (0)
-#else
-#define EMIT_STAMP(i) do { } while (0)
-#endif
-    EMIT_STAMP(0);
     constexpr uint32_t VEC = DTYPE == kBF16 ? 8 : 4;
     constexpr uint32_t CHUNK = 64 * VEC * kCandRows;
     constexpr uint32_t SC_ELEMS = CHUNK * kCandChunksPerSuper;
     constexpr uint32_t SC_WORDS = SC_ELEMS / 32;
     constexpr int NI = kEmitItems;
-    __shared__ uint32_t bits[NI][SC_WORDS];
+    __shared__ uint32_t bits[PLACE ? NI : 1][PLACE ? SC_WORDS : 1];
     // staged survivor: value bits and position in the super-chunk (16 bits); bf16 packs
     // both in one word, like a candidate slot
-    __shared__ uint32_t st_a[NI][kEmitStage];
-    __shared__ uint16_t st_b[NI][DTYPE == kF32 ? kEmitStage : 2];
+    __shared__ uint32_t st_a[PLACE ? NI : 1][PLACE ? kEmitStage : 1];
+    __shared__ uint16_t st_b[PLACE ? NI : 1][PLACE && DTYPE == kF32 ? kEmitStage : 2];
     static_assert(SC_ELEMS <= 65536, "a position in the super-chunk fits 16 bits");
     __shared__ uint32_t s_gt[2 * NI], s_eq[2 * NI];
     __shared__ uint64_t s_sum[2 * NI];
@@ -1178,7 +1270,7 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
         const uint32_t scc = live ? sc : 0u;
         const uint32_t g = scc * kCandChunksPerSuper + ch_in_sc;  // global chunk number
         const uint32_t *sp = cand + uint64_t(g) * CAP;
-        const uint32_t craw = chunk_cnt[g];
+        const uint32_t craw = chunk_cnt[g];  // (only meaningful for a chunk the scan has seen)
         // segment i's table rows in lane i
         uint32_t t_start = 0xFFFFFFFFu, t_n = 0, t_coff = 0, t_T = 0, t_quota = 0, t_cnt = 0,
                  t_route = 0;
@@ -1188,9 +1280,12 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
             const uint4 *e4 = reinterpret_cast<const uint4 *>(sel + lane);
             const uint4 sa = s4[0], sb = s4[1], ea = e4[0], eb = e4[1];
             t_n = sa.z; t_coff = sa.w; t_start = sb.w;                 // n, c_off, sc_start
-            t_T = ea.x; t_quota = ea.y; t_cnt = ea.w; t_route = eb.w;  // T, quota, cnt, route
+            if (sb.x != 0 && sa.z != 0) {   // k, n: a segment that keeps nothing has no selection
+                t_T = ea.x; t_quota = ea.y; t_cnt = ea.w; t_route = eb.w;  // T, quota, cnt, route
+            }
         }
-        for (uint32_t i = tt; i < SC_WORDS; i += 128) bits[k][i] = 0;
+        if (PLACE)
+            for (uint32_t i = tt; i < SC_WORDS; i += 128) bits[k][i] = 0;
 
         // ---- segment, threshold, pair offset of the segment (all wave-uniform)
         uint32_t l, c_off, n_seg, sc_first, T, quota, seg_base, se_cnt, se_route;
@@ -1208,11 +1303,12 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
         } else {
             l = segment_of(L, scc, [&](uint32_t i) { return segs[i].sc_start; });
             const SegDev sd = segs[l];
-            const SelDev se = sel[l];
+            SelDev se{};
+            if (sd.k != 0 && sd.n != 0) se = sel[l];
             n_seg = sd.n; c_off = sd.c_off; sc_first = sd.sc_start;
             T = se.T; quota = se.quota; se_cnt = se.cnt; se_route = se.route;
             uint32_t sum = 0;
-            for (uint32_t i = lane; i < l; i += 64) sum += sel[i].cnt;
+            for (uint32_t i = lane; i < l; i += 64) sum += segment_count(segs[i], sel, i);
             seg_base = wave_sum<uint32_t>(sum);
         }
         live = live && !se_route;  // the dense route writes re-routed segments
@@ -1270,8 +1366,7 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
             n_gt += key > T;
             n_eq += (key == T) && quota;
         });
-        EMIT_STAMP(1);
-        // ---- order inside the item (its 128 threads are in position order), publish
+        // ---- order inside the item (its 128 threads are in position order)
         const uint32_t inc_gt = wave_incl_scan<uint32_t>(n_gt);
         const uint32_t inc_eq = wave_incl_scan<uint32_t>(n_eq);
         if (lane == 63) {
@@ -1281,61 +1376,20 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
         __syncthreads();
         const uint32_t lo_gt = s_gt[2 * k], lo_eq = s_eq[2 * k];
         const uint32_t it_gt = lo_gt + s_gt[2 * k + 1], it_eq = lo_eq + s_eq[2 * k + 1];
+        if (!PLACE) {
+            if (sc < total_sc && tt == 0) sc_cnt[sc] = (uint64_t(it_gt) << 31) | uint64_t(it_eq);
+            __syncthreads();  // s_gt / s_eq are rewritten by the next iteration
+            continue;
+        }
         uint32_t gb = inc_gt - n_gt + ((wave & 1u) ? lo_gt : 0u);
         uint32_t eb = inc_eq - n_eq + ((wave & 1u) ? lo_eq : 0u);
-        if (live && tt == 0)
-            st_agent(&sc_state[sc], kStAgg | (uint64_t(it_gt) << 31) | uint64_t(it_eq));
-        EMIT_STAMP(2);
-        // ---- prefix over the segment's earlier super-chunks: four words requested at a
-        // time, then each is polled for only if it has not been published yet
-        // what super-chunk j of this segment publishes, from its slots
-        auto count_item = [&](uint32_t j) -> uint64_t {
-            uint32_t gt = 0, eq = 0;
-            const uint32_t rel0 = (j - sc_first) * SC_ELEMS;
-            for (uint32_t c = 0; c < kCandChunksPerSuper; ++c) {
-                if (se_cnt == 0 || rel0 + c * CHUNK >= n_seg) break;
-                const uint32_t gg = j * kCandChunksPerSuper + c;
-                const uint32_t n = min(chunk_cnt[gg], CAP);
-                const uint32_t *slots = cand + uint64_t(gg) * CAP;
-                for (uint32_t i = 0; i < n; ++i) {
-                    const uint32_t vb = DTYPE == kBF16 ? slots[i] & 0xFFFF0000u : slots[i];
-                    const uint32_t key = vb & 0x7FFFFFFFu;
-                    gt += key > T;
-                    eq += (key == T) && quota;
-                }
-            }
-            return (uint64_t(gt) << 31) | uint64_t(eq);
-        };
+        // ---- prefix over the segment's earlier super-chunks, whose counts are all there
         uint64_t sum = 0;
-        if (live) {
-            for (uint32_t j0 = sc_first + tt; j0 < sc; j0 += 4 * 128) {
-                uint64_t v[4];
-#pragma unroll
-                for (uint32_t u = 0; u < 4; ++u) {
-                    const uint32_t j = j0 + u * 128;
-                    v[u] = j < sc ? ld_agent(&sc_state[j]) : kStAgg;
-                }
-#pragma unroll
-                for (uint32_t u = 0; u < 4; ++u) {
-                    const uint32_t j = j0 + u * 128;
-                    uint32_t spins = 0;
-                    while ((v[u] & kStMask) == 0) {  // an earlier workgroup, still counting
-                        if (spins++ >= help_after) {     // or not even started
-                            atomicAdd(&cnt[TAGC_CNT_RECOUNTS], 1u);
-                            v[u] = count_item(j);
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
-                        v[u] = ld_agent(&sc_state[j]);
-                    }
-                    sum += v[u] & ~kStMask;
-                }
-            }
-        }
+        if (live)
+            for (uint32_t j = sc_first + tt; j < sc; j += 128) sum += sc_cnt[j];
         sum = wave_sum<uint64_t>(sum);
         if (lane == 0) s_sum[wave] = sum;
         __syncthreads();  // also orders the clearing of `bits` before the ORs below
-        EMIT_STAMP(3);
         sum = s_sum[2 * k] + s_sum[2 * k + 1];
         // output position (within the segment) of the item's first survivor, and how many
         // survivors the item has: entries above T all survive, ties while the quota lasts
@@ -1381,7 +1435,6 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
             });
         }
         __syncthreads();
-        EMIT_STAMP(4);
         if (live) {
             const uint32_t n_st = min(item_n, kEmitStage);
             for (uint32_t i = tt; i < n_st; i += 128) {
@@ -1396,21 +1449,20 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
                 if (sc_rel0 + i * 32 < n_seg) bitmap[w0 + i] = bits[k][i];
         }
         __syncthreads();  // LDS is reused by the next iteration
-        EMIT_STAMP(5);
     }
 }
-#undef EMIT_STAMP
 
 // ---------------------------------------------------------------- compact
 
-// Dense route, final pass over the gradient itself.
-template <int DTYPE, uint32_t ROWS>
+// Dense route, count and place, over the gradient itself: one tile of kCompactThreads x ROWS
+// 16-byte vectors per workgroup and turn.  Also writes the (all-zero) Index words of the
+// segments that keep nothing.
+template <int DTYPE, uint32_t ROWS, bool PLACE>
 __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const char *grad,
                                     const uint32_t *__restrict__ table,
-               const SelDev *__restrict__ sel, uint64_t *tile_state,
+               const SelDev *__restrict__ sel, uint64_t *tile_cnt,
                uint32_t *__restrict__ idx_out,
-               float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt,
-               uint32_t *ticket, uint32_t help_after)
+               float *__restrict__ val_out, uint32_t *__restrict__ bitmap)
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
     constexpr uint32_t VEC = 16 / EB;
@@ -1422,43 +1474,27 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
     __shared__ uint32_t s_base;
 
     const uint32_t L = table[0], total_tiles = table[1];
-    if (!any_dense_route(sel, L)) return;
     const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    // anything to do at all?  (uniform: every thread reads the same words)
+    bool any = false;
+    for (uint32_t l = 0; l < L; ++l) {
+        const SegDev sd = segs[l];
+        any |= on_dense_route(sd, sel, l) || (PLACE && sd.n != 0 && sd.k == 0);
+    }
+    if (!any) return;
     const uint32_t tid = threadIdx.x;
 
-    __shared__ uint32_t s_ticket;
-    for (uint32_t it = 0;; ++it) {
-        uint32_t t = 0, l = 0;
-        if (ticket) {
-            // Persistent grid: the tiles of the dense-route segments are dealt out in
-            // order, one ticket each, to whichever workgroup asks next.  A tile's
-            // predecessors then belong to workgroups that are running or done, however few
-            // of the grid are resident at a time.
-            if (tid == 0) s_ticket = atomicAdd(ticket, 1u);
-            __syncthreads();
-            uint32_t j = s_ticket;
-            bool found = false;
-            for (l = 0; l < L; ++l) {
-                if (!sel[l].route) continue;
-                const uint32_t t0 = segs[l].tile_start;
-                const uint32_t n_l = (l + 1 < L ? segs[l + 1].tile_start : total_tiles) - t0;
-                if (j < n_l) {
-                    t = t0 + j;
-                    found = true;
-                    break;
-                }
-                j -= n_l;
-            }
-            if (!found) break;
-        } else {  // one tile per workgroup (the loop runs again only on a smaller launch)
-            t = bid + it * nb;
-            if (t >= total_tiles) break;
-            l = segment_of(L, t, [&](uint32_t i) { return segs[i].tile_start; });
-        }
+    for (uint32_t t = bid; t < total_tiles; t += nb) {
+        const uint32_t l = segment_of(L, t, [&](uint32_t i) { return segs[i].tile_start; });
         const SegDev sd = segs[l];
-        const SelDev se = sel[l];
-        if (!se.route) continue;  // the candidate route writes this segment (uniform)
+        const bool dense = on_dense_route(sd, sel, l);
+        // (the candidate route writes the other segments that keep something; a segment that
+        // keeps nothing only needs its Index words, which place writes as zeros)
+        if (!dense && !(PLACE && sd.n != 0 && sd.k == 0)) continue;  // uniform
+        SelDev se{};
+        if (dense) se = sel[l];
         const uint32_t base_rel = (t - sd.tile_start) * TILE;
+        if (base_rel >= sd.n) continue;  // (tile_start of several empty segments coincides)
         const char *base = grad + sd.offset * EB;
 
         // ---- load (rows of 256 16-byte vectors, lane-contiguous)
@@ -1520,53 +1556,20 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
             Gt += Gr[r];
             Et += Er[r];
         }
-        // ---- publish the tile's counts, add up those of the segment's earlier tiles (up to a
-        // few thousand words, 256 per step; they come from the L2), pair offset of the segment
-        if (tid == 0) st_agent(&tile_state[t], kStAgg | (uint64_t(Gt) << 31) | Et);
+        if (!PLACE) {
+            if (tid == 0) tile_cnt[t] = (uint64_t(Gt) << 31) | Et;
+            continue;  // (block_excl_scan ends with a barrier: s_scan may be reused)
+        }
+        // ---- add up the counts of the segment's earlier tiles (up to a few thousand words,
+        // 256 per step; they come from the L2), pair offset of the segment
         {
-            const uint32_t lane = tid & 63;
-            // the counts tile `ti` of this segment publishes, from the input itself (by a wave)
-            auto recount = [&](uint32_t ti) -> uint64_t {
-                uint32_t gt = 0, eq = 0;
-                if (se.cnt != 0) {
-                    const uint32_t r0 = (ti - sd.tile_start) * TILE;
-                    const uint32_t r1 = min(r0 + TILE, sd.n);
-                    for (uint32_t rel = r0 + lane; rel < r1; rel += 64) {
-                        const uint32_t key = load_elem_bits(base, rel, DTYPE) & 0x7FFFFFFFu;
-                        gt += key > se.T;
-                        eq += key == se.T && se.quota;
-                    }
-                }
-                return (uint64_t(wave_sum<uint32_t>(gt)) << 31) | wave_sum<uint32_t>(eq);
-            };
             uint64_t sum = 0;
-            for (uint32_t j0 = sd.tile_start; j0 < t; j0 += kCompactThreads) {
-                const uint32_t j = j0 + tid;
-                uint64_t v = j < t ? ld_agent(&tile_state[j]) : kStAgg;
-                uint32_t spins = 0;
-                while (__any((v & kStMask) == 0)) {  // an earlier workgroup, still counting
-                    if (spins++ >= help_after) {     // or not even started
-                        uint64_t miss = __ballot((v & kStMask) == 0);
-                        while (miss) {  // one missing tile at a time, by the whole wave
-                            const uint32_t src = uint32_t(__builtin_ctzll(miss));
-                            miss &= miss - 1;
-                            const uint64_t a = recount(j0 + (tid & ~63u) + src);
-                            if (lane == src) {
-                                v = kStAgg | a;
-                                atomicAdd(&cnt[TAGC_CNT_RECOUNTS], 1u);
-                            }
-                        }
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(1);
-                    if ((v & kStMask) == 0) v = ld_agent(&tile_state[j]);
-                }
-                sum += v & ~kStMask;
-            }
+            if (dense)
+                for (uint32_t j = sd.tile_start + tid; j < t; j += kCompactThreads) sum += tile_cnt[j];
             sum = block_sum<uint64_t, kCompactThreads / 64>(sum, s_scan);
             uint32_t sb = 0;
             if (tid < 64) {
-                for (uint32_t i = tid; i < l; i += 64) sb += sel[i].cnt;
+                for (uint32_t i = tid; i < l; i += 64) sb += segment_count(segs[i], sel, i);
                 sb = wave_sum<uint32_t>(sb);
             }
             if (tid == 0) {
@@ -1629,30 +1632,48 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
     }
 }
 
-// ----------------------------------------------------------------- finish
+// --------------------------------------------------------- count and place
 
-// The last kernel of PHASE_INDEX: its first `n_emit` workgroups emit the candidate-route
-// segments, the rest compact the dense-route ones (both write pairs and Index words, of
-// different segments).  One launch instead of two: when a bucket has no dense-route work
-// the second part costs nothing, not even an empty kernel's turn-around.
+// The last two kernels of PHASE_INDEX.  In each, the first `n_emit` workgroups work on the
+// candidate-route segments and the rest on the dense-route ones (pairs and Index words of
+// different segments): one launch instead of two, and when a bucket has no dense-route work
+// that part costs nothing, not even an empty kernel's turn-around.
 static_assert(kEmitThreads == kCompactThreads, "one launch for both parts");
 
 template <int DTYPE, uint32_t COMPACT_ROWS>
 __global__ void __launch_bounds__(kEmitThreads)
-    __attribute__((amdgpu_waves_per_eu(COMPACT_ROWS == 2 ? 7 : 6, 8)))
-finish_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ table,
-              const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
-              const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
-              uint64_t *sc_state, uint64_t *tile_state, uint32_t *__restrict__ idx_out,
-              float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt,
-              uint32_t *ticket, uint32_t help_after)
+count_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ table,
+             const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
+             const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
+             uint64_t *sc_cnt, uint64_t *tile_cnt)
 {
     if (blockIdx.x < n_emit)
-        emit_body<DTYPE>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
-                         CAP, sc_state, idx_out, val_out, bitmap, cnt, help_after, tile_state);
+        emit_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
+                                CAP, sc_cnt, nullptr, nullptr, nullptr);
     else
-        compact_body<DTYPE, COMPACT_ROWS>(blockIdx.x - n_emit, gridDim.x - n_emit, grad, table, sel,
-                            tile_state, idx_out, val_out, bitmap, cnt, ticket, help_after);
+        compact_body<DTYPE, COMPACT_ROWS, false>(blockIdx.x - n_emit, gridDim.x - n_emit, grad,
+                                                 table, sel, tile_cnt, nullptr, nullptr, nullptr);
+}
+
+template <int DTYPE, uint32_t COMPACT_ROWS>
+__global__ void __launch_bounds__(kEmitThreads)
+    __attribute__((amdgpu_waves_per_eu(COMPACT_ROWS == 2 ? 7 : 6, 8)))
+place_kernel(uint32_t n_emit, const char *grad, uint32_t *table,
+             const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
+             const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
+             uint64_t *sc_cnt, uint64_t *tile_cnt, uint32_t *__restrict__ idx_out,
+             float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt)
+{
+    if (blockIdx.x == gridDim.x - 1) {  // (any one workgroup: the last has the least to do)
+        __shared__ uint32_t s_cnt[8];
+        write_rank_counts(table, sel, cnt, s_cnt);
+    }
+    if (blockIdx.x < n_emit)
+        emit_body<DTYPE, true>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
+                               CAP, sc_cnt, idx_out, val_out, bitmap);
+    else
+        compact_body<DTYPE, COMPACT_ROWS, true>(blockIdx.x - n_emit, gridDim.x - n_emit, grad,
+                                                table, sel, tile_cnt, idx_out, val_out, bitmap);
 }
 
 template <typename K>
@@ -1739,19 +1760,14 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
                       const tagc_shared_buffers *sh, hipStream_t s)
 {
     const uint32_t L = uint32_t(p->table.size());
-    const uint32_t *table = static_cast<const uint32_t *>(sh->table);
-    // behind the segment rows: one pre-threshold per segment, carried from call to call
-    uint32_t *hint = const_cast<uint32_t *>(table) + 8 + 8 * size_t(L);
+    // the table is the plan's device state as well (pre-thresholds, counters): written here
+    uint32_t *table = static_cast<uint32_t *>(const_cast<void *>(sh->table));
     char *ws = static_cast<char *>(rk->workspace);
-    uint32_t *hist1 = reinterpret_cast<uint32_t *>(ws + p->ws.hist1);
     uint32_t *hist1d = reinterpret_cast<uint32_t *>(ws + p->ws.hist1d);
-    uint32_t *arrive = reinterpret_cast<uint32_t *>(ws + p->ws.counters);
-    uint32_t *raised = arrive + L + 1;  // behind the arrival counters and the tile ticket
     uint32_t *hist2 = reinterpret_cast<uint32_t *>(ws + p->ws.hist2);
-    uint64_t *tile_state = reinterpret_cast<uint64_t *>(ws + p->ws.tile_state);
-    uint64_t *sc_state = reinterpret_cast<uint64_t *>(ws + p->ws.sc_state);
+    uint64_t *tile_cnt = reinterpret_cast<uint64_t *>(ws + p->ws.tile_cnt);
+    uint64_t *sc_cnt = reinterpret_cast<uint64_t *>(ws + p->ws.sc_cnt);
     SelDev *sel = reinterpret_cast<SelDev *>(ws + p->ws.sel);
-    uint32_t *binlo = reinterpret_cast<uint32_t *>(ws + p->ws.binlo);
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + p->ws.chunk_cnt);
     uint32_t *cand = reinterpret_cast<uint32_t *>(ws + p->ws.cand);
     const uint64_t n_slots = uint64_t(p->total_sc) * kCandChunksPerSuper * p->cand_cap;
@@ -1762,51 +1778,57 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     // Error feedback: scan_spill (candidate route) and accumulate_kernel (all other segments)
     // turn acc into grad + acc; whoever reads the input after them reads it from acc.  Both
     // read acc through the Index this rank's previous call left in rk->bitmap (what was
-    // sent reads as 0) before finish / widen4 overwrite that Index with the new one.
+    // sent reads as 0) before place / widen4 overwrite that Index with the new one.
     char *acc = static_cast<char *>(rk->acc);
     const char *src = acc ? acc : g;
     const SentMap sent{rk->bitmap, wide ? 1u : 0u};
     const int cus = device_cu_count();
     const size_t lds_hist = kBins1 * sizeof(uint32_t);
-    static bool a_sample = false, a_hist = false;
-    static int occ_finish[2] = {0, 0};
+    static bool a_prepare = false, a_hist = false;
+    static int occ_place[2] = {0, 0};
 
-    if (L == 0) {  // nothing is compressed: only the counts have to read zero
+    if (L == 0 || (p->total_sc == 0 && p->total_tiles == 0)) {
+        // nothing is compressed (or every compressed segment is empty): only the counts
+        // have to read zero
         ProfileScope ps("fill_zero", s);
         fill_zero_kernel<<<1, 256, 0, s>>>(reinterpret_cast<uint4 *>(ws), 0, rk->cnt,
-                                           TAGC_CNT_SEG0);
+                                           TAGC_CNT_SEG0 + L);
         return hip_ok(hipGetLastError());
     }
-    if (allow_lds(sample_kernel<DTYPE>, lds_hist, &a_sample) ||
-        allow_lds(hist1_kernel<DTYPE>, lds_hist, &a_hist))
+    if (allow_lds(prepare_kernel<DTYPE>, lds_hist, &a_prepare) ||
+        allow_lds(hist1_kernel<DTYPE, kBins1>, lds_hist, &a_hist))
         return TAGC_EHIP;
     if (acc && p->any_nonfast) {
         ProfileScope ps("accumulate", s);
         accumulate_kernel<DTYPE><<<cus * 4, 256, 0, s>>>(g, table, acc, sent);
     }
-    {
-        ProfileScope ps("sample", s);  // + clears the per-call workspace
-        const uint64_t n16 = p->zero_bytes / 16;
+    // the dense route's histograms are cleared by the scan as it starts, or, where there is
+    // no scan, by prepare; which also samples pre-thresholds on the first call after an upload
+    const uint64_t zero_n16 = p->zero_bytes / 16;
+    const bool sample = p->sample_pending.exchange(0, std::memory_order_relaxed) != 0;
+    if (sample || !p->total_sc) {
+        ProfileScope ps("prepare", s);
+        const uint64_t n16 = p->total_sc ? 0 : zero_n16;
         const uint32_t fill_blocks = uint32_t(
             std::max<uint64_t>(1, std::min<uint64_t>((n16 + kHistThreads - 1) / kHistThreads, cus)));
-        sample_kernel<DTYPE><<<L + fill_blocks, kHistThreads, lds_hist, s>>>(
-            g, acc, sent, table, sel, binlo, hint, reinterpret_cast<uint4 *>(ws), n16, rk->cnt,
-            TAGC_CNT_SEG0 + L);
+        prepare_kernel<DTYPE><<<L + fill_blocks, kHistThreads, lds_hist, s>>>(
+            g, acc, sent, table, reinterpret_cast<uint4 *>(ws), n16);
     }
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
         scan_spill_kernel<DTYPE><<<cus * 2, kSpillThreads, 0, s>>>(
-            g, acc, sent, table, sel, binlo, raised, hist1, cand, chunk_cnt, n_slots, p->cand_cap);
+            g, acc, sent, table, sel, cand, chunk_cnt, n_slots, p->cand_cap,
+            reinterpret_cast<uint4 *>(ws), zero_n16);
     }
     {
-        ProfileScope ps("select1", s);
-        select1_kernel<DTYPE><<<L, kHistThreads, 0, s>>>(table, hist1, sel, rk->cnt, binlo, raised,
-                                                         hint);
-    }
-    {
+        // leaves at once unless a segment is on the dense route (by plan, or because the
+        // scan's selection sent it there)
         ProfileScope ps("hist1", s);
-        hist1_kernel<DTYPE><<<cus, kHistThreads, lds_hist, s>>>(src, table, sel, hist1d, rk->cnt,
-                                                                binlo, hint, arrive);
+        if (p->static_dense)
+            hist1_kernel<DTYPE, kBins1><<<cus, kHistThreads, lds_hist, s>>>(src, table, sel, hist1d);
+        else
+            hist1_kernel<DTYPE, kHistWindow><<<cus, kHistThreads, kHistWindow * sizeof(uint32_t), s>>>(
+                src, table, sel, hist1d);
     }
     if (DTYPE == kF32) {
         if (p->total_sc) {
@@ -1819,30 +1841,35 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         }
         {
             ProfileScope ps("select2", s);
-            select2_kernel<<<L, kHistThreads, 0, s>>>(table, hist2, sel, rk->cnt);
+            select2_kernel<<<L, kHistThreads, 0, s>>>(table, hist2, sel);
         }
     }
-    if (p->total_sc || p->total_tiles) {
-        ProfileScope ps("finish", s);  // emit + compact
-        // the plan fixed the compaction tile's height, and with it which kernel this is
-        auto kernel = p->compact_rows == 4 ? finish_kernel<DTYPE, 4> : finish_kernel<DTYPE, 2>;
-        const int occ = resident_blocks_per_cu(kernel, kEmitThreads, 0,
-                                               &occ_finish[p->compact_rows == 4]);
+    {
+        // the plan fixed the compaction tile's height, and with it which kernels these are
+        const bool rows4 = p->compact_rows == 4;
+        auto count = rows4 ? count_kernel<DTYPE, 4> : count_kernel<DTYPE, 2>;
+        auto place = rows4 ? place_kernel<DTYPE, 4> : place_kernel<DTYPE, 2>;
+        const int occ = resident_blocks_per_cu(place, kEmitThreads, 0, &occ_place[rows4]);
         if (occ <= 0) return TAGC_EHIP;
         const uint32_t n_emit = (p->total_sc + kEmitItems - 1) / kEmitItems;
-        // Compaction: one tile per workgroup when dense-route work is certain.  When no
+        // Dense route: one tile per workgroup when dense-route work is certain.  When no
         // segment is planned for this route the part is only a safety net for re-routed
-        // segments and nearly always exits at once; a small persistent grid keeps that
-        // cheap, and deals its tiles out by ticket, in order (one atomic per tile is
-        // affordable on that rare path).
+        // segments and nearly always exits at once: a grid that fits the device takes the
+        // tiles in turns then.
         const uint32_t n_compact =
             p->static_dense ? p->total_tiles
                             : std::min<uint32_t>(p->total_tiles, uint32_t(cus) * uint32_t(occ));
-        uint32_t *ticket = p->static_dense ? nullptr : arrive + L;
-        kernel<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
-            n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_state,
-            tile_state,
-            rk->idx, rk->val, bitmap1, rk->cnt, ticket, help_after_polls());
+        {
+            ProfileScope ps("count", s);
+            count<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
+                n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_cnt, tile_cnt);
+        }
+        {
+            ProfileScope ps("place", s);
+            place<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
+                n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_cnt, tile_cnt,
+                rk->idx, rk->val, bitmap1, rk->cnt);
+        }
     }
     if (wide && p->n_c) {
         ProfileScope ps("widen4", s);

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <vector>
 
 #include "tagc.h"
@@ -34,13 +35,12 @@ constexpr uint32_t kMaxPartUnknowns = 16384;   // local ranks fit 14 bits
 constexpr uint32_t kDecodeThreads = 1024;
 constexpr uint32_t kLdsBytes = 160 * 1024;
 constexpr uint32_t kMaxRanksPerPass = 32;
-// polls (about half a microsecond each) for a count another workgroup is expected to
-// publish before the waiting one computes it itself.  Far longer than a running workgroup
-// takes to count even with the device shared (with 512 polls a run with error feedback
-// recomputed tens of thousands of counts that were merely late, each at many times the cost
-// of waiting; with 4096 none), short against what a workgroup that has not started can take
-constexpr uint32_t kHelpAfterPolls = 1u << 12;
-uint32_t help_after_polls();  // kHelpAfterPolls unless a test lowered it
+// Candidate histogram of the single-read route: the bins from a segment's pre-threshold
+// upwards (12 octaves of magnitude: a gradient may grow 4000-fold between two calls before
+// its threshold leaves the window); then one count of everything above them, one of the
+// non-finite entries, padding.
+constexpr uint32_t kWinBins = 1536;
+constexpr uint32_t kWinWords = 1544;
 
 // Device copy of one compressed segment.
 struct SegDev {
@@ -56,7 +56,9 @@ constexpr uint32_t kSegAligned = 1;  // offset is a multiple of the 16-byte vect
 constexpr uint32_t kSegFast = 2;     // eligible for the single-read candidate path
 static_assert(sizeof(SegDev) == 32, "SegDev layout");
 
-// Result of the threshold search for one segment (device memory).
+// Result of the threshold search for one segment (device memory).  Written for every
+// segment with k > 0 and n > 0: by the scan's last workgroup on the segment, by the dense
+// route's selection, and (fp32) completed by the second-level selection.
 struct SelDev {
     uint32_t T;       // threshold key; keep key > T, and `quota` lowest-position ties
     uint32_t quota;   // ties (key == T) to keep
@@ -76,10 +78,36 @@ struct RankPtrs {
 // ------------------------------------------------------------------- plan
 
 struct Workspace {  // byte offsets inside a rank workspace
-    uint64_t hist1, hist1d, hist2, tile_state, sc_state, counters;  // cleared per call
-    uint64_t sel, binlo, chunk_cnt, cand, bitmap1, total;
+    uint64_t hist1d, hist2;  // cleared by every PHASE_INDEX call before they are added to
+    uint64_t sel, tile_cnt, sc_cnt, chunk_cnt, cand, bitmap1, total;
 };
 
+// Device state of a plan, kept behind the segment rows of its table: all zero after
+// tagc_plan_upload, and every PHASE_INDEX call leaves it as it found it except for the
+// pre-thresholds, which are what is carried from call to call.  It lives with the table and
+// not in a rank workspace because nobody but the library writes the table: counters that
+// have to start at zero can rely on it without a clearing pass per call.
+struct TableState {
+    uint32_t *hint;      // [L] pre-threshold bin for the next call, 0 = none
+    uint32_t *watch;     // [L] calls that still follow the falling trend after a miss
+    uint32_t *prev;      // [L] the bin above which 1.3 k entries lay at the last call
+    uint32_t *arrive;    // [L] workgroups of the scan that are done with the segment
+    uint32_t *arrive_d;  // [L] the same for the dense route's histogram
+    uint32_t *raised;    // [L] highest pre-threshold a wave of the scan used
+    uint32_t *reroute;   // [L] a chunk overflowed its slots
+    uint32_t *glob;      // [8] flags, non-finite inputs, dense-route segments of the call
+    uint32_t *win;       // [L][kWinWords] candidate histograms
+};
+__host__ __device__ inline TableState table_state(uint32_t *table, uint32_t L)
+{
+    // behind the 32-byte rows: the histograms (a multiple of 32 bytes each), then the rest
+    uint32_t *w = table + 8 + 8 * size_t(L);
+    uint32_t *p = w + size_t(L) * kWinWords + 8;
+    return TableState{p,         p + L,     p + 2 * L, p + 3 * L, p + 4 * L,
+                      p + 5 * L, p + 6 * L, p - 8,     w};
+}
+static_assert(kWinWords % 8 == 0, "histograms stay 32-byte aligned");
+constexpr uint64_t table_state_words(uint64_t L) { return 7 * L + 8 + L * kWinWords; }
 
 }  // namespace tagc
 
@@ -100,6 +128,8 @@ struct tagc_plan_s {
     uint32_t P_cap, T_cap;
     tagc::Workspace ws;
     uint64_t zero_bytes;                      // prefix of the rank workspace cleared per call
+    // the table was uploaded and no PHASE_INDEX call has sampled pre-thresholds for it yet
+    mutable std::atomic<uint32_t> sample_pending{0};
     uint64_t n_chunks;                        // popcount chunks of the Index
     tagc_sizes sizes;
 };

@@ -301,8 +301,8 @@ def test_candidate_route_fallbacks(dtype, kind):
         sampled = (np.arange(4096) * stride + stride // 2)[:, None] * vec + np.arange(vec)
         if kind == "sample_high":       # the sample sees only the largest values
             v[sampled.ravel()] = rng.choice([-1.0, 1.0], sampled.size) * 0.5
-        elif kind == "sample_low":      # the sample sees only tiny values
-            v[sampled.ravel()] *= 1e-4
+        elif kind == "sample_low":      # the sample sees only tiny values (10 octaves down;
+            v[sampled.ravel()] *= 1e-3  # the candidate histogram spans 12)
         else:                           # 3000 large values inside one 2048-entry chunk
             v[100_000:103_000] = rng.choice([-1.0, 1.0], 3000) * (0.1 + rng.random(3000))
     td = torch.float32 if dtype == G.F32 else torch.bfloat16
@@ -358,41 +358,37 @@ def test_buckets_in_flight_on_separate_streams():
 
 
 @pytest.mark.parametrize("dtype", [G.F32, G.BF16])
-def test_counts_of_other_workgroups_recomputed_instead_of_waited_for(dtype):
-    """The last kernel of the sparsifier orders its output through counts that workgroups
-    publish for each other; one that is not there in time (its workgroup may not even have
-    started when other streams hold the device) is recomputed by whoever needs it.  With
-    the patience set to zero polls that happens for every count not there at first sight:
-    same pairs, same Index, on the candidate route (many super-chunks per segment, ties at
-    the threshold) and on the dense route (many tiles per segment, ragged and unaligned
-    ones, Table 1's 20 % regime)."""
-    from paper_2504_05638_amd import binding as B
-    _announce("recount dtype=%d" % dtype)
-    old = B.tagc_test_help_after(0)
-    try:
-        assert old >= 256
-        segs = [G.Seg(0, (1 << 21) + 13, 10_000, 1, "long_ragged"),
-                G.Seg(2_097_176, 5000, 20_000, 1, "short"),
-                G.Seg(2_102_184, (1 << 20), 200_000, 1, "keeps_a_fifth"),
-                G.Seg(3_150_763, (1 << 19) + 64, 10_000, 1, "long_unaligned"),
-                G.Seg(3_675_120, 3 << 20, 12_500, 1, "long")]
-        n = 3_675_120 + (3 << 20)
-        b = G.Bucket("recount", dtype, 2, segs, n, 1500,
-                     {"long_ragged": 1e-3, "short": 1e-2, "keeps_a_fifth": 1e-4,
-                      "long_unaligned": 3e-3, "long": 1e-3})
-        ores, tb = run_both(b, _grads(b), seed=6)
-        compare_all(b, ores, tb)
-        assert tb.rank_counts(0)["dense_segments"] == 3
-        assert min(tb.rank_counts(r)["recounts"] for r in range(2)) > 100   # the path was taken
-        # integers: heavy ties at every threshold, bit for bit
-        rng = np.random.default_rng(5)
-        td = torch.float32 if dtype == G.F32 else torch.bfloat16
-        grads = [torch.from_numpy(rng.integers(-40, 41, n).astype(np.float32)).to(td)
-                 for _ in range(2)]
-        ores, tb = run_both(b, grads, seed=7)
-        compare_all(b, ores, tb, exact_values=True)
-    finally:
-        B.tagc_test_help_after(old)
+def test_ordered_output_over_many_items_per_segment(dtype):
+    """The sparsifier's last two kernels order their output through per-item counts (count,
+    then place): same pairs, same Index as the oracle on the candidate route (many
+    super-chunks per segment, ties at the threshold) and on the dense route (many tiles per
+    segment, ragged and unaligned ones, Table 1's 20 % regime), twice in a row on the same
+    buffers (the counters the kernels keep in the plan's table must be back at zero)."""
+    _announce("ordered output dtype=%d" % dtype)
+    segs = [G.Seg(0, (1 << 21) + 13, 10_000, 1, "long_ragged"),
+            G.Seg(2_097_176, 5000, 20_000, 1, "short"),
+            G.Seg(2_102_184, (1 << 20), 200_000, 1, "keeps_a_fifth"),
+            G.Seg(3_150_763, (1 << 19) + 64, 10_000, 1, "long_unaligned"),
+            G.Seg(3_675_120, 3 << 20, 12_500, 1, "long")]
+    n = 3_675_120 + (3 << 20)
+    b = G.Bucket("ordered", dtype, 2, segs, n, 1500,
+                 {"long_ragged": 1e-3, "short": 1e-2, "keeps_a_fifth": 1e-4,
+                  "long_unaligned": 3e-3, "long": 1e-3})
+    grads = _grads(b)
+    ores, tb = run_both(b, grads, seed=6)
+    compare_all(b, ores, tb)
+    assert tb.rank_counts(0)["dense_segments"] == 3
+    tb.run([g.cuda() for g in grads])          # again, now from carried pre-thresholds
+    torch.cuda.synchronize()
+    compare_all(b, ores, tb)
+    assert tb.rank_counts(1)["dense_segments"] == 3
+    # integers: heavy ties at every threshold, bit for bit
+    rng = np.random.default_rng(5)
+    td = torch.float32 if dtype == G.F32 else torch.bfloat16
+    grads = [torch.from_numpy(rng.integers(-40, 41, n).astype(np.float32)).to(td)
+             for _ in range(2)]
+    ores, tb = run_both(b, grads, seed=7)
+    compare_all(b, ores, tb, exact_values=True)
 
 
 @pytest.mark.parametrize("wgs", [1, 4, 64])
@@ -459,8 +455,8 @@ def test_pre_threshold_carried_between_calls_never_changes_results(dtype):
 def test_falling_scale_costs_one_fallback_not_one_per_call(dtype):
     """Every call sees gradients 12 % smaller than the one before: the carried pre-threshold
     is too high each time.  The first such call falls back to the two-read route; after it
-    the plan samples beside the carried value for a few calls and takes the lower of the
-    two, so the following calls do not.  Results exact throughout."""
+    the plan lowers the carried value by what it fell since the call before, for a few
+    calls, so the following calls do not.  Results exact throughout."""
     _announce("falling scale dtype=%d" % dtype)
     n = (1 << 19) + 40
     rng = np.random.default_rng(5)

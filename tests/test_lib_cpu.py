@@ -152,18 +152,6 @@ def test_bench_refuses_more_than_one_gpu_and_fails_loudly_without_one():
         assert r.returncode != 0 and not r.stdout.strip().startswith("{")
 
 
-def test_help_after_hook_swaps_values():
-    """The test hook for the recount fallback is plain host state: it hands back what was
-    set before (the library's default first)."""
-    default = B.tagc_test_help_after(7)
-    try:
-        assert 64 <= default <= 1 << 16
-        assert B.tagc_test_help_after(0) == 7
-        assert B.tagc_test_help_after(default) == 0
-    finally:
-        B.tagc_test_help_after(default)
-
-
 def test_host_hash_helper_agrees_with_known_answers():
     path = os.path.join(ROOT, "tests", "golden", "hash_kat.txt")
     for line in open(path):
