@@ -32,12 +32,25 @@ STAGES = {
     "S4 decode": ["enumerate", "peel", "dense"],
 }
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC = {
-    # (workload, kernel): bytes per launch = (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE) KiB * 1024
-    ("config5", "scan_spill"): int((2.0 * 197722.4 + 16817.2) * 1024),
-}
+def profile_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` as the tracked rocprofv3 counter summary of this
+    workload has them (profiles/<workload>_all_kernels.txt, the table written from the
+    --pmc FETCH_SIZE / WRITE_SIZE runs; its column scaled_total_MB is already calibrated).
+    None when there is no such summary or it does not list the kernel."""
+    path = os.path.join(ROOT, "profiles", "%s_all_kernels.txt" % workload)
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    in_table = False
+    for line in lines:
+        if line.startswith("kernel") and "scaled_total_MB" in line:
+            in_table = True
+            continue
+        f = line.split()
+        if in_table and len(f) == 5 and f[0] == kernel:
+            return int(float(f[4]) * 1e6)
+    return None
 
 
 def parse_args():
@@ -425,7 +438,9 @@ def main():
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": MEASURED_TRAFFIC.get((args.workload, dom)),
+                    # HBM bytes per launch, from the tracked counter runs of this workload
+                    "traffic": profile_traffic(args.workload, dom),
+                    "traffic_source": "profiles/%s_all_kernels.txt" % args.workload,
                     "avg_launch_ms": round(avg_ms, 5), "launches": d_n,
                     "alg_bytes_per_launch": int(per_launch),
                     "events_pass": "same steps, one bucket in flight (so decode on the whole "

@@ -230,11 +230,14 @@ typedef struct tagc_rank_buffers {
 
 /* Device buffers shared by the bucket (all dev, caller-owned). */
 typedef struct tagc_shared_buffers {
-    const void *table;  /* [table_bytes] filled by tagc_plan_upload; PHASE_INDEX
-                           also keeps one pre-threshold per segment there (and a
-                           count of calls that still sample beside it), carried
-                           from call to call (speed hints only: results do not
-                           depend on them)                                       */
+    const void *table;  /* [table_bytes] filled by tagc_plan_upload and from then
+                           on written by the library only: behind the segment
+                           rows PHASE_INDEX keeps the plan's device state there
+                           (one pre-threshold per segment, carried from call to
+                           call as a speed hint that results never depend on;
+                           counters and candidate histograms that every call
+                           leaves at zero again).  PHASE_INDEX calls that share
+                           a table must not overlap in time                    */
     uint32_t *bitmap;   /* [bitmap_words] merged Index                          */
     float *sketch;      /* [sketch_cells_capacity] summed Count Sketch          */
     uint32_t *header;   /* [TAGC_HDR_WORDS]                                     */
@@ -263,8 +266,9 @@ void tagc_plan_destroy(tagc_plan_t *plan);
 /* Fills *out (host).  Never touches the device. */
 int tagc_plan_sizes(const tagc_plan_t *plan, tagc_sizes *out);
 
-/* Copies the plan's segment table into `table_dev` (table_bytes) on `stream`.
- * The plan must outlive the copy. */
+/* Copies the plan's segment table into `table_dev` (table_bytes) on `stream` and
+ * clears the device state behind it; the first PHASE_INDEX call on the plan
+ * after an upload also samples pre-thresholds.  The plan must outlive the copy. */
 int tagc_plan_upload(const tagc_plan_t *plan, void *table_dev, void *stream);
 
 /*
@@ -274,7 +278,8 @@ int tagc_plan_upload(const tagc_plan_t *plan, void *table_dev, void *stream);
  *   of largest magnitude, ties to the lower position, exact zeros never; writes
  *   the survivors as (c-index, float32 value) pairs in ascending c-index to
  *   rank->idx / rank->val, counts to rank->cnt, and the local Index to
- *   rank->bitmap (every word is written).  Uses rank->workspace.
+ *   rank->bitmap (every word is written).  Uses rank->workspace and the device
+ *   state in shared->table (see tagc_shared_buffers).
  *   With rank->acc set (Algorithm 1, lines 1-2; section 3.2, local gradient
  *   accumulation) the entries of the compressed segments are first replaced by
  *   grad + acc, added in the gradient's own type (bf16: one float32 add rounded

@@ -149,6 +149,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     off += L * kBins1 * 4;
     w.hist2 = off;
     off += (cfg->dtype == TAGC_F32 ? L * kBins2 * 4 : 0);
+    w.group_cnt = off;
+    off += round_up((tiles / kTileGroup + 1) * 8, 16);
     p->zero_bytes = off;
     w.sel = off;
     off += round_up(L * sizeof(SelDev), 16);

@@ -385,6 +385,10 @@ prepare_kernel(const char *__restrict__ grad, const char *acc, const SentMap sen
 // The kernel's workgroups also clear, as they start, the dense route's histograms in the
 // rank workspace, which nothing touches before the kernels after this one.
 constexpr uint32_t kSpillThreads = 512;
+#ifndef TAGC_SPILL_WGS
+#define TAGC_SPILL_WGS 2
+#endif
+constexpr uint32_t kSpillWgsPerCU = TAGC_SPILL_WGS;  // workgroups launched per compute unit
 constexpr uint32_t kSpillStage = 512;  // staged slots per wave
 constexpr uint32_t kSpillList = 16;    // staged chunks per wave
 constexpr uint32_t kWatchCalls = 8;    // calls that extrapolate a falling pre-threshold after a miss
@@ -1460,7 +1464,7 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
 template <int DTYPE, uint32_t ROWS, bool PLACE>
 __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const char *grad,
                                     const uint32_t *__restrict__ table,
-               const SelDev *__restrict__ sel, uint64_t *tile_cnt,
+               const SelDev *__restrict__ sel, uint64_t *tile_cnt, uint64_t *group_cnt,
                uint32_t *__restrict__ idx_out,
                float *__restrict__ val_out, uint32_t *__restrict__ bitmap)
 {
@@ -1557,15 +1561,31 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
             Et += Er[r];
         }
         if (!PLACE) {
-            if (tid == 0) tile_cnt[t] = (uint64_t(Gt) << 31) | Et;
+            // the tile's counts, and added to those of its group of kTileGroup tiles (groups
+            // are cut from the bucket's tile numbers, whatever the segments)
+            if (tid == 0) {
+                const uint64_t v = (uint64_t(Gt) << 31) | Et;
+                tile_cnt[t] = v;
+                atomicAdd(reinterpret_cast<unsigned long long *>(&group_cnt[t / kTileGroup]), v);
+            }
             continue;  // (block_excl_scan ends with a barrier: s_scan may be reused)
         }
-        // ---- add up the counts of the segment's earlier tiles (up to a few thousand words,
-        // 256 per step; they come from the L2), pair offset of the segment
+        // ---- add up the counts of the segment's earlier tiles: whole groups that lie inside
+        // the segment by their sums, the tiles before and after them one by one (a few
+        // hundred words at most, from the L2); pair offset of the segment
         {
             uint64_t sum = 0;
-            if (dense)
-                for (uint32_t j = sd.tile_start + tid; j < t; j += kCompactThreads) sum += tile_cnt[j];
+            if (dense) {
+                const uint32_t t0 = sd.tile_start;
+                const uint32_t g0 = (t0 + kTileGroup - 1) / kTileGroup, g1 = t / kTileGroup;
+                if (g0 < g1) {
+                    for (uint32_t j = t0 + tid; j < g0 * kTileGroup; j += kCompactThreads) sum += tile_cnt[j];
+                    for (uint32_t j = g0 + tid; j < g1; j += kCompactThreads) sum += group_cnt[j];
+                    for (uint32_t j = g1 * kTileGroup + tid; j < t; j += kCompactThreads) sum += tile_cnt[j];
+                } else {
+                    for (uint32_t j = t0 + tid; j < t; j += kCompactThreads) sum += tile_cnt[j];
+                }
+            }
             sum = block_sum<uint64_t, kCompactThreads / 64>(sum, s_scan);
             uint32_t sb = 0;
             if (tid < 64) {
@@ -1645,14 +1665,15 @@ __global__ void __launch_bounds__(kEmitThreads)
 count_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ table,
              const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
              const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
-             uint64_t *sc_cnt, uint64_t *tile_cnt)
+             uint64_t *sc_cnt, uint64_t *tile_cnt, uint64_t *group_cnt)
 {
     if (blockIdx.x < n_emit)
         emit_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
                                 CAP, sc_cnt, nullptr, nullptr, nullptr);
     else
         compact_body<DTYPE, COMPACT_ROWS, false>(blockIdx.x - n_emit, gridDim.x - n_emit, grad,
-                                                 table, sel, tile_cnt, nullptr, nullptr, nullptr);
+                                                 table, sel, tile_cnt, group_cnt, nullptr, nullptr,
+                                                 nullptr);
 }
 
 template <int DTYPE, uint32_t COMPACT_ROWS>
@@ -1661,8 +1682,9 @@ __global__ void __launch_bounds__(kEmitThreads)
 place_kernel(uint32_t n_emit, const char *grad, uint32_t *table,
              const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
              const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
-             uint64_t *sc_cnt, uint64_t *tile_cnt, uint32_t *__restrict__ idx_out,
-             float *__restrict__ val_out, uint32_t *__restrict__ bitmap, uint32_t *cnt)
+             uint64_t *sc_cnt, uint64_t *tile_cnt, uint64_t *group_cnt,
+             uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
+             uint32_t *__restrict__ bitmap, uint32_t *cnt)
 {
     if (blockIdx.x == gridDim.x - 1) {  // (any one workgroup: the last has the least to do)
         __shared__ uint32_t s_cnt[8];
@@ -1673,7 +1695,8 @@ place_kernel(uint32_t n_emit, const char *grad, uint32_t *table,
                                CAP, sc_cnt, idx_out, val_out, bitmap);
     else
         compact_body<DTYPE, COMPACT_ROWS, true>(blockIdx.x - n_emit, gridDim.x - n_emit, grad,
-                                                table, sel, tile_cnt, idx_out, val_out, bitmap);
+                                                table, sel, tile_cnt, group_cnt, idx_out, val_out,
+                                                bitmap);
 }
 
 template <typename K>
@@ -1766,6 +1789,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     uint32_t *hist1d = reinterpret_cast<uint32_t *>(ws + p->ws.hist1d);
     uint32_t *hist2 = reinterpret_cast<uint32_t *>(ws + p->ws.hist2);
     uint64_t *tile_cnt = reinterpret_cast<uint64_t *>(ws + p->ws.tile_cnt);
+    uint64_t *group_cnt = reinterpret_cast<uint64_t *>(ws + p->ws.group_cnt);
     uint64_t *sc_cnt = reinterpret_cast<uint64_t *>(ws + p->ws.sc_cnt);
     SelDev *sel = reinterpret_cast<SelDev *>(ws + p->ws.sel);
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + p->ws.chunk_cnt);
@@ -1816,7 +1840,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
-        scan_spill_kernel<DTYPE><<<cus * 2, kSpillThreads, 0, s>>>(
+        scan_spill_kernel<DTYPE><<<cus * kSpillWgsPerCU, kSpillThreads, 0, s>>>(
             g, acc, sent, table, sel, cand, chunk_cnt, n_slots, p->cand_cap,
             reinterpret_cast<uint4 *>(ws), zero_n16);
     }
@@ -1862,13 +1886,14 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         {
             ProfileScope ps("count", s);
             count<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
-                n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_cnt, tile_cnt);
+                n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_cnt, tile_cnt,
+                group_cnt);
         }
         {
             ProfileScope ps("place", s);
             place<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
                 n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_cnt, tile_cnt,
-                rk->idx, rk->val, bitmap1, rk->cnt);
+                group_cnt, rk->idx, rk->val, bitmap1, rk->cnt);
         }
     }
     if (wide && p->n_c) {

@@ -26,6 +26,7 @@ constexpr uint32_t kFastMinElems = 1u << 17;  // shorter segments take the dense
 constexpr uint32_t kFastMinKeep = 64;
 constexpr double kFastMaxCandFrac = 0.04;  // expected candidates per element beyond which the dense path wins
 constexpr uint32_t kChunkWords = 1024;  // Index words per popcount chunk
+constexpr uint32_t kTileGroup = 64;     // dense-route tiles whose counts are also kept as one sum
 // A partition keeps, in LDS, 10 bytes per cell (value, meta word, queue slot) and 4 per
 // unknown (its c-index): 12288 cells and 8192 unknowns fill the 160 KiB.
 constexpr uint32_t kDefaultPartCells = 12288;
@@ -78,7 +79,7 @@ struct RankPtrs {
 // ------------------------------------------------------------------- plan
 
 struct Workspace {  // byte offsets inside a rank workspace
-    uint64_t hist1d, hist2;  // cleared by every PHASE_INDEX call before they are added to
+    uint64_t hist1d, hist2, group_cnt;  // cleared by every PHASE_INDEX call before they are added to
     uint64_t sel, tile_cnt, sc_cnt, chunk_cnt, cand, bitmap1, total;
 };
 
