@@ -151,6 +151,19 @@ __device__ inline uint32_t round_to_bf16(float x)
     return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
 }
 
+// Waits until every vector memory operation this thread has issued -- stores and atomics
+// without a return value included -- has been acknowledged by the memory system.  Used
+// before a workgroup announces, through another device-scope atomic, that its updates are
+// there: a workgroup-scope release fence does not wait for them (it compiles to no wait
+// on the vector memory counter), so the announcement could overtake the updates; and a
+// device-scope release fence would also write back every dirty line of the L2, at many
+// times the cost.  (s_waitcnt vmcnt(0); the other counters are left alone.)
+__device__ inline void wait_own_memory_ops()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
 __device__ inline uint64_t ld_agent(const uint64_t *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -427,6 +427,7 @@ __device__ inline void select_window(uint32_t l, const SegDev &sd, uint32_t blo,
     }
     const uint32_t above_w = win[kWinBins], nf = win[kWinBins + 1];
     const uint32_t raised = ts.raised[l], overflow = ts.reroute[l];
+    const uint32_t prev = ts.prev[l], wt = ts.watch[l];  // (requested with the rest)
     __syncthreads();  // everybody has read what thread 0 clears next
     if (tid == 0) {
         win[kWinBins] = win[kWinBins + 1] = 0;
@@ -481,8 +482,7 @@ __device__ inline void select_window(uint32_t l, const SegDev &sd, uint32_t blo,
     // The window may not reach down to 1.3 k entries; then one bin below what this call
     // could see.
     const uint32_t bin2 = bin2_w != 0xFFFFFFFFu ? max(blo + bin2_w, 1u) : max(floor_bin, 2u) - 1u;
-    const uint32_t wt = ts.watch[l];
-    ts.hint[l] = next_hint(bin2, ts.prev[l], wt);
+    ts.hint[l] = next_hint(bin2, prev, wt);
     ts.prev[l] = bin2;
     if (wt) ts.watch[l] = wt - 1;
     if (nf) atomicAdd(&ts.glob[1], nf);
@@ -540,14 +540,22 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
     if (g0 >= total_chunks) return;
     const uint64_t g1 = min(g0 + span, uint64_t(total_chunks));
     for (uint32_t i = tid; i < kWinWords; i += kSpillThreads) h[i] = 0;
-    __syncthreads();
-    // last segment whose first chunk is not beyond the span's start
+    // last segment whose first chunk is not beyond the span's start.  Up to 64 segments: lane
+    // i looks at segment i, all at once (a search would be several dependent loads, which is
+    // time the workgroup's first chunk waits for)
     uint32_t l0 = 0;
-    for (uint32_t hi = L; hi - l0 > 1;) {
-        const uint32_t mid = (l0 + hi) >> 1;
-        if (uint64_t(segs[mid].sc_start) * kCandChunksPerSuper <= g0) l0 = mid;
-        else hi = mid;
+    if (L <= 64) {
+        const uint64_t first = lane < L ? uint64_t(segs[lane].sc_start) * kCandChunksPerSuper
+                                        : ~0ull;
+        l0 = uint32_t(__popcll(__ballot(first <= g0))) - 1u;  // segment 0 starts at chunk 0
+    } else {
+        for (uint32_t hi = L; hi - l0 > 1;) {
+            const uint32_t mid = (l0 + hi) >> 1;
+            if (uint64_t(segs[mid].sc_start) * kCandChunksPerSuper <= g0) l0 = mid;
+            else hi = mid;
+        }
     }
+    __syncthreads();  // h[] is clear
     uint32_t *st = stage[wib];
     uint32_t *lst_chunk = list[wib][0], *lst_off = list[wib][1], *lst_cnt = list[wib][2];
     uint4 *dw = data[wib];
@@ -841,10 +849,9 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
         }
         // The table updates are device-scope atomics, performed where every CU sees them; a
         // thread only has to wait until its own have been acknowledged before the workgroup
-        // counts as arrived.  (A device-scope release fence would also write back every dirty
-        // line of the L2, at many times the cost.)  The workgroup that arrives last drops
-        // what it may hold of the table in its caches and selects.
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        // counts as arrived.  The workgroup that arrives last drops what it may hold of the
+        // table in its caches and selects.
+        wait_own_memory_ops();
         __syncthreads();
         if (tid == 0) {
             const uint64_t c_last = s0 + n_chunks - 1;  // segment's chunks: one workgroup per span
@@ -1047,10 +1054,9 @@ hist1_kernel(const char *__restrict__ grad, uint32_t *table, SelDev *sel, uint32
         }
         // The histogram updates are device-scope atomics, performed where every CU sees
         // them; a thread only has to wait until its own have been acknowledged before the
-        // workgroup is counted as arrived.  (A device-scope release fence would also write
-        // back every dirty line of the L2, at many times the cost.)  The workgroup that
-        // arrives last drops what it may hold of the histogram in its caches and selects.
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        // workgroup is counted as arrived.  The workgroup that arrives last drops what it may
+        // hold of the histogram in its caches and selects.
+        wait_own_memory_ops();
         __syncthreads();
         if (tid == 0) s_last = atomicAdd(&ts.arrive_d[l], 1u) == gridDim.x - 1;
         __syncthreads();

@@ -99,6 +99,30 @@ def test_gpt2_block_shapes_fp32():
     assert st["n_unresolved"] <= 2
 
 
+def test_repeated_calls_on_short_fp32_segments_select_the_same_every_time():
+    """A selection must not depend on when workgroups finish.  The last workgroup of a
+    segment to arrive selects the threshold from counts that the others added with atomics;
+    each workgroup has to wait for its own adds before it counts as arrived.  Short fp32
+    segments, whose few workgroups end almost together, are where an early arrival would
+    show: every one of many calls on the same plan must give the oracle's survivors."""
+    _announce("config2 block6, repeated calls")
+    b = G.config2(seed=0, n_ranks=4)[6]
+    grads = _grads(b)
+    ores, tb = run_both(b, grads, seed=0)
+    compare_all(b, ores, tb)
+    dev = [g.cuda() for g in grads]
+    for it in range(12):
+        tb.run(dev)
+        torch.cuda.synchronize()
+        for r in range(b.n_ranks):
+            cnt = tb.rank_counts(r)
+            assert cnt["flags"] == 0 and cnt["total"] == ores.ranks[r].cnt, (it, r, cnt)
+            idx, val = tb.rank_pairs(r)
+            assert np.array_equal(idx, ores.ranks[r].idx), (it, r)
+            assert np.array_equal(val.view(np.uint32), ores.ranks[r].val.view(np.uint32))
+        assert tb.header()["U"] == ores.U and tb.status()["n_unresolved"] == 0
+
+
 def test_bf16_many_tiles_ragged_tail_student_t():
     """bf16, heavy-tailed values, length not a multiple of the tile or the vector,
     load factor 1.5 (benchmark configuration 3 at reduced length, with its overlap recipe)."""
