@@ -98,6 +98,12 @@ def parse_args():
     ap.add_argument("--decode-mode", type=int, default=0, choices=[0, 1, 2],
                     help="0 peeling only (the headline), 1 peeling + estimation of what it "
                          "leaves, 2 estimation only (section 2.2's two decompression algorithms)")
+    ap.add_argument("--only-phases", default="",
+                    help="measurement aid: comma list out of index,agg_index,sketch,agg_sketch,"
+                         "decode; the timed steps make only these calls for every bucket, on the "
+                         "buffers the warm-up steps (always the whole path) left; ms_per_step "
+                         "then describes that subset, the byte-based fractions are null and no "
+                         "per-kernel pass is made")
     ap.add_argument("--graph", type=int, default=1, choices=[0, 1],
                     help="1 (default): capture each bucket's call sequence in a HIP graph after "
                          "the warm-up and replay it in the timed steps (the library only enqueues "
@@ -305,6 +311,28 @@ def main():
                               min_bytes=need if first else None))
     stream = torch.cuda.current_stream()
     streams = [stream] + [torch.cuda.Stream() for _ in range(lanes - 1)]
+    phases = [p for p in args.only_phases.split(",") if p]
+    unknown = set(phases) - {"index", "agg_index", "sketch", "agg_sketch", "decode"}
+    if unknown:
+        sys.stderr.write("bench.py: unknown phase(s) %s\n" % ", ".join(sorted(unknown)))
+        sys.exit(2)
+    if phases:
+        args.no_profile_pass = True
+
+    def run_subset(tb, grads, s=None):
+        """The calls of one bucket that --only-phases names."""
+        if "index" in phases:
+            for r in range(N):
+                tb.compress_index(r, grads[r], s)
+        if "agg_index" in phases:
+            tb.aggregate_index(N, s)
+        if "sketch" in phases:
+            for r in range(N):
+                tb.compress_sketch(r, s)
+        if "agg_sketch" in phases:
+            tb.aggregate_sketch(N, s)
+        if "decode" in phases:
+            tb.decompress(s)
 
     step_no = [0]
 
@@ -366,7 +394,10 @@ def main():
         for i in range(n_b):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=capture_stream):
-                tbs[i].run(data[i % pool])
+                if phases:
+                    run_subset(tbs[i], data[i % pool])
+                else:
+                    tbs[i].run(data[i % pool])
             graphs.append(g)
         torch.cuda.synchronize()
 
@@ -380,6 +411,11 @@ def main():
                     graphs[i].replay()
         step()
         torch.cuda.synchronize()
+
+    if phases and not args.graph:
+        def step(one_stream=False):  # noqa: F811 -- the timed steps make the named calls only
+            for i in range(n_b):
+                run_subset(tbs[i], data[i % pool], streams[i % lanes])
 
     # ---- timed region: exactly K steps
     torch.cuda.synchronize()
@@ -398,6 +434,8 @@ def main():
             bad |= tbs[i].rank_counts(r)["flags"]
         # (with error feedback every pass starts from different accumulators, so U and the
         # residue legitimately change from pass to pass: only the flags are checked then)
+        if phases:
+            continue  # a subset of the calls leaves the buffers in between
         if bad or (not args.error_feedback and n_sets == 1 and (hdr, st) != facts[i]):
             sys.stderr.write("bench.py: bucket %d differs when run with %d buckets in flight "
                              "(flags %d)\n" % (i, lanes, bad))
@@ -469,10 +507,12 @@ def main():
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,
+                   "only_phases": phases or None,
                    "index_mode": args.index_mode, "cell_bits": args.cell_bits,
                    "graph_replay": bool(args.graph), "gradient_sets": n_sets,
                    "peel_rounds_max": rounds, "input_generation_s": round(t_gen, 2)},
-        "hbm_frac_end_to_end": round(balg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "hbm_frac_end_to_end": None if phases else round(
+            balg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "alg_bytes_per_step": balg_total,
         "stages": stages,
         "roofline": roofline,
