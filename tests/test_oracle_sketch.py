@@ -138,6 +138,35 @@ def test_float_inputs_decode_within_tolerance(dtype):
     assert np.all(err <= 1e-5 * np.maximum(np.abs(val), tau))
 
 
+@pytest.mark.parametrize("P,T", [(64, 192), (512, 1536), (1024, 3072), (8192, 12288),
+                                 (1 << 22, 3 << 22)])
+def test_partition_size_is_only_a_parameter_of_the_format(P, T):
+    """The sketch may be cut into partitions of any size, up to one partition for the whole
+    bucket (caps above U and M: the plain three-sub-table Count Sketch with no partitions at
+    all).  What is decoded is the same function of the inputs every time: bit for bit the
+    definition's sums for integer inputs, and lossless -- except that partitions of a few
+    dozen unknowns are too small for peeling at load factor 1.5 to always complete (small
+    stopping sets are no longer rare): those leave a counted residue, and everything they
+    do resolve is still exact."""
+    rng = np.random.default_rng(5)
+    n, n_ranks = 90_000, 3
+    segs = [O.Segment(0, 40_000, 40_000), O.Segment(40_000, 50_000, 25_000)]
+    grads = _int_grads(rng, n, n_ranks, density=0.9)
+    r = O.run_bucket(grads, _cfg(lf=1500, P=P, T=T), segs)
+    idx, val = D.sparse_sum(grads, O.F32, segs)
+    U = idx.size
+    want_A = max(1, -(-U // P), -(-(-(-1500 * U // 1000)) // (3 * (T // 3))))
+    assert r.A == want_A and (P < (1 << 22) or r.A == 1)
+    assert r.U == U and np.array_equal(r.decoded.idx, idx)
+    ok = r.decoded.round > 0
+    assert np.array_equal(r.decoded.val.astype(np.float64)[ok], val[ok])
+    assert r.decoded.n_unresolved == int((~ok).sum())
+    if P >= 512:
+        assert r.decoded.n_unresolved == 0
+    else:
+        assert 0 < r.decoded.n_unresolved < U // 20 and np.all(r.decoded.val[~ok] == 0)
+
+
 # ---------------------------------------------- independent peeler (P5)
 
 
