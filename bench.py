@@ -31,6 +31,17 @@ STAGES = {
     "S3b sketch sum": ["sketch_sum"],
     "S4 decode": ["enumerate", "peel", "dense"],
 }
+FUSED_STAGE = "S3b+S4 sketch sum inside decode"
+
+
+def stages_of(fused):
+    """Kernels per stage; with the fused call the last two stages are one."""
+    if not fused:
+        return STAGES
+    st = {k: v for k, v in STAGES.items() if k not in ("S3b sketch sum", "S4 decode")}
+    st[FUSED_STAGE] = ["enumerate", "sum_peel", "dense"]
+    return st
+
 
 def profile_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` as the tracked rocprofv3 counter summary of this
@@ -69,11 +80,12 @@ def parse_args():
     ap.add_argument("--lanes", type=int, default=12,
                     help="buckets in flight at once: bucket i runs on HIP stream i %% lanes with "
                          "that lane's own buffers (buckets are independent of each other)")
-    ap.add_argument("--decode-workgroups", type=int, default=64,
+    ap.add_argument("--decode-workgroups", type=int, default=-1,
                     help="with more than one bucket in flight: most workgroups of the peeling "
                          "kernel at once (it needs a compute unit's whole local memory, so "
                          "this leaves the other compute units to the other buckets' "
-                         "bandwidth-bound kernels); 0 = one per compute unit")
+                         "bandwidth-bound kernels); 0 = one per compute unit; default: 96 "
+                         "with the fused decoder, 64 without (what measured best)")
     ap.add_argument("--part-unknowns", type=int, default=0,
                     help="non-zeros per sketch partition (0 = library default)")
     ap.add_argument("--part-cells", type=int, default=0,
@@ -98,6 +110,12 @@ def parse_args():
     ap.add_argument("--decode-mode", type=int, default=0, choices=[0, 1, 2],
                     help="0 peeling only (the headline), 1 peeling + estimation of what it "
                          "leaves, 2 estimation only (section 2.2's two decompression algorithms)")
+    ap.add_argument("--fused-decode", type=int, default=1, choices=[0, 1],
+                    help="1 (default): tagc_reduce_decompress, the decoder adds up the ranks' "
+                         "sketches itself and the summed sketch is never written (float32 "
+                         "cells, default partition size, up to 32 ranks: otherwise the two "
+                         "calls are made); 0: tagc_aggregate(PHASE_SKETCH) then "
+                         "tagc_decompress")
     ap.add_argument("--only-phases", default="",
                     help="measurement aid: comma list out of index,agg_index,sketch,agg_sketch,"
                          "decode; the timed steps make only these calls for every bucket, on the "
@@ -114,6 +132,12 @@ def parse_args():
                     help="distinct gradients per bucket data set, one per step in turn (0 = 3 "
                          "with --error-feedback, where feeding the same gradient every step "
                          "would double the accumulator's scale from step to step, else 1)")
+    ap.add_argument("--arena-gb", type=int, default=-1,
+                    help="allocate and release one block of this many GiB before anything else, "
+                         "so that torch's caching allocator serves every buffer from one "
+                         "device allocation (measured: the first process on a box is 2 %% faster "
+                         "that way, later ones the same); -1 = three quarters of the free "
+                         "memory, 0 = off")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="before the timed region, copy this many MiB device to device three "
@@ -151,20 +175,26 @@ def make_buckets(args):
     return bs
 
 
-def alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1, cell=4):
+def alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1, cell=4, fused=False):
     """Algorithmic bytes per stage for one bucket: one read of the gradient (with error
     feedback also one read and one write of the accumulator), every message
-    materialised once; work-lists, histograms and degree tables are not credited."""
+    materialised once; work-lists, histograms and degree tables are not credited.
+    `fused`: the decoder sums the ranks' sketches itself, so the summed sketch is neither
+    written nor read back and is not credited either."""
     N, e = b.n_ranks, b.elem_bytes
     n_c, U, m = z.n_c, hdr["U"], hdr["m"]
     passes = 3 if ef else 1
-    return {
+    out = {
         "S1+S2 sparsify+index": passes * N * z.n_real * e + 8 * k_total + wire * N * n_c // 8,
         "S3a index OR": wire * N * n_c // 8 + n_c // 8,
         "S2' encode": 8 * k_total + N * cell * m,
-        "S3b sketch sum": (N * cell + 4) * m,
-        "S4 decode": n_c // 8 + 4 * m + 8 * U + (4 * n_c if dense else 0),
     }
+    if fused:
+        out[FUSED_STAGE] = N * cell * m + n_c // 8 + 8 * U + (4 * n_c if dense else 0)
+    else:
+        out["S3b sketch sum"] = (N * cell + 4) * m
+        out["S4 decode"] = n_c // 8 + 4 * m + 8 * U + (4 * n_c if dense else 0)
+    return out
 
 
 def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1, cell=4):
@@ -189,6 +219,7 @@ def kernel_alg_bytes(b, z, hdr, k_total, dense, ef=False, wire=1, cell=4):
         "sketch_sum": (N * cell + 4) * m,
         "enumerate": n_c // 8 + 4 * U,
         "peel": 4 * m + 8 * U,
+        "sum_peel": N * cell * m + 8 * U,
         "dense": n_c // 8 + 4 * U + 4 * n_c,
     }
 
@@ -256,6 +287,11 @@ def main():
         args.buckets, args.pool = 12, min(args.pool, 2)
         sys.stderr.write("bench.py: --error-feedback on config5 runs the first 12 buckets "
                          "(accumulators of all 32 do not fit beside the inputs)\n")
+    if args.arena_gb < 0:
+        args.arena_gb = int(torch.cuda.mem_get_info()[0] * 3 // 4) >> 30
+    if args.arena_gb:
+        arena = torch.empty(args.arena_gb << 30, dtype=torch.uint8, device="cuda")
+        del arena
     buckets = make_buckets(args)
     n_b = len(buckets)
     pool = max(1, min(args.pool, n_b))
@@ -296,6 +332,10 @@ def main():
             need[k] = max(need[k], getattr(z, f))
         B.tagc_plan_destroy(plan)
     lanes = max(1, min(args.lanes, n_b))
+    fused = bool(args.fused_decode) and args.cell_bits == 32 and N <= 32 and \
+        args.part_unknowns <= 8192 and args.part_cells <= 12288
+    if args.decode_workgroups < 0:
+        args.decode_workgroups = 96 if fused else 64
     peel_wgs = args.decode_workgroups if lanes > 1 else 0
     tbs = []
     for i, b in enumerate(buckets):
@@ -329,10 +369,13 @@ def main():
         if "sketch" in phases:
             for r in range(N):
                 tb.compress_sketch(r, s)
-        if "agg_sketch" in phases:
-            tb.aggregate_sketch(N, s)
-        if "decode" in phases:
-            tb.decompress(s)
+        if fused and "decode" in phases:
+            tb.reduce_decompress(N, s)
+        else:
+            if "agg_sketch" in phases:
+                tb.aggregate_sketch(N, s)
+            if "decode" in phases:
+                tb.decompress(s)
 
     step_no = [0]
 
@@ -341,7 +384,7 @@ def main():
         step_no[0] += 1
         for i in range(n_b):
             tbs[i].run(cur[i % pool], stream if one_stream else streams[i % lanes],
-                       whole_device_decode=one_stream)
+                       whole_device_decode=one_stream, fused=fused)
 
     for _ in range(args.warmup):
         step()
@@ -356,7 +399,7 @@ def main():
 
     # ---- per-bucket facts (U, m, pairs) for the byte accounting, from one more pass
     input_bytes = 0
-    balg = {k: 0 for k in STAGES}
+    balg = {k: 0 for k in stages_of(fused)}
     kalg = {}
     unresolved = estimated = rounds = 0
     wire = 4 if args.index_mode == B.TAGC_INDEX_ADD4 else 1
@@ -365,7 +408,7 @@ def main():
     flags = 0
     facts = []
     for i in range(n_b):
-        tbs[i].run(data[i % pool], stream)
+        tbs[i].run(data[i % pool], stream, fused=fused)
         torch.cuda.synchronize()
         hdr, st = tbs[i].header(), tbs[i].status()
         facts.append((hdr, st))
@@ -373,7 +416,7 @@ def main():
         flags |= st["flags"]
         for r in range(N):
             flags |= tbs[i].rank_counts(r)["flags"]
-        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire, cell).items():
+        for k, v in alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire, cell, fused).items():
             balg[k] += v
         for k, v in kernel_alg_bytes(buckets[i], tbs[i].sizes, hdr, kt, args.dense, args.error_feedback, wire, cell).items():
             kalg[k] = kalg.get(k, 0) + v
@@ -397,14 +440,14 @@ def main():
                 if phases:
                     run_subset(tbs[i], data[i % pool])
                 else:
-                    tbs[i].run(data[i % pool])
+                    tbs[i].run(data[i % pool], fused=fused)
             graphs.append(g)
         torch.cuda.synchronize()
 
         def step(one_stream=False):  # noqa: F811 -- the timed steps replay the graphs
             if one_stream:
                 for i in range(n_b):
-                    tbs[i].run(data[i % pool], stream, whole_device_decode=True)
+                    tbs[i].run(data[i % pool], stream, whole_device_decode=True, fused=fused)
                 return
             for i in range(n_b):
                 with torch.cuda.stream(streams[i % lanes]):
@@ -457,7 +500,7 @@ def main():
         t_prof = time.perf_counter() - t0
         prof = B.tagc_profile_read(64)
         B.tagc_profile_enable(False)
-        for sname, kernels in STAGES.items():
+        for sname, kernels in stages_of(fused).items():
             ms = sum(prof[k][0] for k in kernels if k in prof) / args.steps
             stages[sname] = {
                 "ms_per_step": round(ms, 4),
@@ -507,6 +550,7 @@ def main():
                    "pairs_per_step": k_tot, "union_nonzeros_per_step": U_tot,
                    "sketch_cells_per_step": m_tot, "n_unresolved": unresolved,
                    "n_estimated": estimated, "decode_mode": args.decode_mode,
+                   "fused_decode": fused,
                    "only_phases": phases or None,
                    "index_mode": args.index_mode, "cell_bits": args.cell_bits,
                    "graph_replay": bool(args.graph), "gradient_sets": n_sets,

@@ -373,6 +373,27 @@ int tagc_decompress(const tagc_plan_t *plan, const tagc_shared_buffers *shared,
                     void *stream);
 
 /*
+ * Algorithm 1's last two steps in one call: Reduce(count_sketch) and
+ * peeling_decompress(index, count_sketch) (section 2.2), for a master that
+ * holds the N ranks' sketches in its own memory (on one GPU: always; across
+ * GPUs: peers that write their sketches into the master's buffers).  Equal to
+ * tagc_aggregate(PHASE_SKETCH) followed by tagc_decompress -- every cell is
+ * the same float32 sum ((ranks[0].sketch[c] + ranks[1].sketch[c]) + ...) in
+ * rank order, up to the sign of a zero -- except that the summed sketch is
+ * never written or read back: part of the decoder's waves add up the next
+ * partition's cells in registers while the others peel the current one.
+ * shared->sketch is not touched; tagc_aggregate(PHASE_INDEX) must have run.
+ * ranks: host array of n_ranks structs, 1 <= n_ranks <= min(config.n_ranks,
+ * 32).  float32 cells and partitions of the default size at most
+ * (part_unknowns <= 8192, part_cells <= 12288): TAGC_EUNSUPPORTED otherwise.
+ * Outputs and status as tagc_decompress.
+ */
+int tagc_reduce_decompress(const tagc_plan_t *plan, const tagc_rank_buffers *ranks,
+                           uint32_t n_ranks, const tagc_shared_buffers *shared,
+                           uint32_t *idx_out, float *val_out, float *dense_out,
+                           void *stream);
+
+/*
  * Optional per-kernel timing.  While enabled, every kernel the library
  * launches is bracketed by HIP events on the caller's stream.
  * tagc_profile_read synchronises those events (call it after the stream is

@@ -30,7 +30,7 @@ TAGC_STATIC_WORKSPACE_BYTES = 16 << 20
 
 EXPORTS = ["tagc_plan", "tagc_plan_destroy", "tagc_plan_sizes",
            "tagc_plan_upload", "tagc_compress", "tagc_compress_static", "tagc_feedback_apply", "tagc_aggregate",
-           "tagc_decompress", "tagc_profile_enable", "tagc_profile_read",
+           "tagc_decompress", "tagc_reduce_decompress", "tagc_profile_enable", "tagc_profile_read",
            "tagc_hash_host", "tagc_strerror"]
 
 
@@ -135,6 +135,9 @@ def lib():
         L.tagc_decompress.restype = C.c_int
         L.tagc_decompress.argtypes = [vp, C.POINTER(tagc_shared_buffers), vp,
                                       vp, vp, vp]
+        L.tagc_reduce_decompress.restype = C.c_int
+        L.tagc_reduce_decompress.argtypes = [vp, C.POINTER(tagc_rank_buffers), C.c_uint32,
+                                             C.POINTER(tagc_shared_buffers), vp, vp, vp, vp]
         L.tagc_profile_enable.restype = C.c_int
         L.tagc_profile_enable.argtypes = [C.c_int]
         L.tagc_profile_read.restype = C.c_int
@@ -219,6 +222,13 @@ def tagc_decompress(plan, shared: tagc_shared_buffers, idx_out, val_out,
                     dense_out=None, stream: int = 0):
     _check(lib().tagc_decompress(plan, C.byref(shared), idx_out, val_out,
                                  dense_out, stream), "tagc_decompress")
+
+
+def tagc_reduce_decompress(plan, ranks, shared: tagc_shared_buffers, idx_out, val_out,
+                           dense_out=None, stream: int = 0):
+    arr = (tagc_rank_buffers * len(ranks))(*ranks)
+    _check(lib().tagc_reduce_decompress(plan, arr, len(ranks), C.byref(shared), idx_out,
+                                        val_out, dense_out, stream), "tagc_reduce_decompress")
 
 
 def tagc_profile_enable(on: bool):

@@ -165,16 +165,28 @@ class TagcBucket:
                           self.out_dense.data_ptr() if self.out_dense is not None else None,
                           _stream_ptr(stream))
 
-    def run(self, grads, stream=None, whole_device_decode=False):
-        """The whole hot path for one bucket; grads[r] is rank r's buffer."""
+    def reduce_decompress(self, n_ranks=None, stream=None, whole_device=False):
+        """Sketch sum and decode in one call (the summed sketch is never written)."""
+        plan = self.plan_whole if whole_device and self.plan_whole is not None else self.plan
+        B.tagc_reduce_decompress(plan, self.rk[:n_ranks or self.n_ranks], self.shared,
+                                 self.out_idx.data_ptr(), self.out_val.data_ptr(),
+                                 self.out_dense.data_ptr() if self.out_dense is not None else None,
+                                 _stream_ptr(stream))
+
+    def run(self, grads, stream=None, whole_device_decode=False, fused=False):
+        """The whole hot path for one bucket; grads[r] is rank r's buffer.  `fused`: the
+        sketches are summed by the decoder (tagc_reduce_decompress)."""
         n = len(grads)
         for r in range(n):
             self.compress_index(r, grads[r], stream)
         self.aggregate_index(n, stream)
         for r in range(n):
             self.compress_sketch(r, stream)
-        self.aggregate_sketch(n, stream)
-        self.decompress(stream, whole_device_decode)
+        if fused:
+            self.reduce_decompress(n, stream, whole_device_decode)
+        else:
+            self.aggregate_sketch(n, stream)
+            self.decompress(stream, whole_device_decode)
 
     # ---------------------------------------------------------- read-backs
 

@@ -16,6 +16,8 @@
 // whose degree has just become 1 is all a round needs; one atomic subtract removes an
 // unknown from a cell and tells, by the old degree, whether the cell joins the queue.
 // Total work is proportional to the unknowns, not to unknowns x rounds.
+#include <type_traits>
+
 #include "device_utils.h"
 #include "tagc_internal.h"
 
@@ -335,6 +337,282 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
     if (tid == 0 && max_rounds) atomicMax(&status[TAGC_ST_ROUNDS], max_rounds);
 }
 
+// ------------------------------------------------- sketch sum inside the decoder
+//
+// Reduce(count_sketch) and peeling_decompress of Algorithm 1 in one kernel, without a summed
+// sketch in memory.  The rounds of a partition are bound by dependent LDS accesses and leave
+// the memory system idle; adding up the ranks' sketches is bound by memory and leaves
+// everything else idle; run one after the other they cost the sum.  Here a workgroup's 16
+// waves split up: kLoadWaves of them do nothing but add up, in rank order, the cells of the
+// workgroup's *next* partition in their registers (48 cells per thread), while the other
+// kPeelWaves peel the current one in LDS as peel_kernel does.  The two groups meet twice per
+// partition, at hardware barriers: when the peelers are done with the LDS (the loaders then
+// write the summed cells there) and when that is written.  The peelers' own barriers (after
+// the unknowns joined their cells, one per round) must not hold up the loaders, which have
+// no part in them and may be waiting for memory: they are counted in an LDS word instead
+// (peel_barrier).
+constexpr uint32_t kLoadWaves = 4, kPeelWaves = kDecodeThreads / 64 - kLoadWaves;
+constexpr uint32_t kLoadThreads = kLoadWaves * 64, kPeelThreads = kPeelWaves * 64;
+constexpr uint32_t kLoadCells = (kDefaultPartCells + kLoadThreads - 1) / kLoadThreads;  // per thread
+constexpr uint32_t kUnit = 16;  // cells of one rank a loader thread requests at a time
+static_assert(kLoadCells == 3 * kUnit, "a rank's cells are three units per loader thread");
+constexpr uint32_t kPeelIdx = (kDefaultPartUnknowns + kPeelThreads - 1) / kPeelThreads;
+
+// Barrier among the kPeelWaves peeling waves: every wave adds 1 to an LDS word and goes on
+// when the word has reached kPeelWaves x (barriers so far).  All waves of a workgroup are
+// resident and every peeling wave reaches every such barrier (they branch on the same LDS
+// words), so the wait ends.
+__device__ inline void peel_barrier(uint32_t *word, uint32_t &expected)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's LDS accesses are done
+    expected += kPeelWaves;
+    if (lane_id() == 0) atomicAdd(word, 1u);
+    while (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < expected)
+        __builtin_amdgcn_s_sleep(1);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__global__ void __launch_bounds__(kDecodeThreads)
+sum_peel_kernel(const RankPtrs rp, uint32_t n_in, const uint32_t *__restrict__ header,
+                const uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
+                uint32_t *status, uint64_t seed, const uint32_t *__restrict__ salt,
+                uint32_t T_cap, uint32_t P_cap, uint32_t mode)
+{
+    extern __shared__ uint64_t lds64[];
+    unsigned long long *cell = reinterpret_cast<unsigned long long *>(lds64);  // [T_cap]
+    uint32_t *idx = reinterpret_cast<uint32_t *>(cell + T_cap);      // [P_cap] c-indices
+    uint32_t *claimed = idx + P_cap;                 // [P_cap/32 + 1] resolved unknowns
+    uint32_t *scratch = claimed + (P_cap / 32 + 1);  // [32]
+    uint16_t *queue = reinterpret_cast<uint16_t *>(scratch + 32);  // [T_cap] cells of degree 1
+    __shared__ uint32_t s_n[3], s_any[3];  // as in peel_kernel
+    __shared__ uint32_t s_bar;             // peel_barrier's word
+    __shared__ uint32_t s_resolved;        // unknowns the current partition resolved
+    const uint32_t tid = threadIdx.x;
+    const uint32_t U = header[TAGC_HDR_U], A = header[TAGC_HDR_A];
+    const uint32_t m_sub = header[TAGC_HDR_MSUB];
+    const uint32_t cells = 3 * m_sub;
+    if (tid == 0) s_bar = 0;
+    __syncthreads();
+
+    if (tid >= kPeelThreads) {
+        // ------------------------------------------------------------ the loaders
+        const uint32_t lt = tid - kPeelThreads;
+        // rank r's sketch: read from the kernel argument segment (explicit arguments lie
+        // there in declaration order at their natural alignment, `rp` first), because
+        // indexing the argument with a run-time r would keep all 32 pointers in registers
+        // (a pointer made from an integer has no address space the compiler knows: it is
+        // declared global here, or every load through it would be a flat one, which can
+        // only be waited for all at once)
+        typedef __attribute__((address_space(1))) const float *GlobalCells;
+        auto rank_sketch = [&](uint32_t r) -> GlobalCells {
+            typedef __attribute__((address_space(4))) const uint64_t *KernArg;
+            KernArg ka = (KernArg)__builtin_amdgcn_kernarg_segment_ptr();
+            (void)rp;
+            return (GlobalCells)ka[r];
+        };
+        float acc[kLoadCells];
+        float b0[kUnit], b1[kUnit], b2[kUnit];
+        // third t (cells [16 t, 16 t + 16) of this thread's 48) of `src`, a rank's partition.
+        // A whole tile of the default size is read from the partition's first cell on, also
+        // where the partition is smaller: a rank's sketch buffer has that much room behind
+        // its cells (tagc_plan_sizes), and only the partition's own cells are staged.
+        auto request = [&](float (&b)[kUnit], GlobalCells src, auto third) {
+            constexpr uint32_t t = decltype(third)::value;
+#pragma unroll
+            for (uint32_t i = 0; i < kUnit; ++i)
+                b[i] = __builtin_nontemporal_load(src + lt + (t * kUnit + i) * kLoadThreads);
+        };
+        // (the fences keep the compiler from moving the requests of later steps up in front
+        // of the adds of earlier ones, which it otherwise does until the registers run out)
+        auto add_unit = [&](const float (&b)[kUnit], auto third) {
+            constexpr uint32_t t = decltype(third)::value;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (uint32_t i = 0; i < kUnit; ++i) acc[t * kUnit + i] += b[i];
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        constexpr std::integral_constant<uint32_t, 0> T0{};
+        constexpr std::integral_constant<uint32_t, 1> T1{};
+        constexpr std::integral_constant<uint32_t, 2> T2{};
+        // the sum of partition `part` over the ranks, in rank order: the three thirds of a
+        // rank are in flight while those of the rank before are added
+        auto sum_partition = [&](uint32_t part) {
+#pragma unroll
+            for (uint32_t q = 0; q < kLoadCells; ++q) acc[q] = 0.0f;
+            const uint64_t tile = uint64_t(part) * cells;
+            GlobalCells src = rank_sketch(0) + tile;
+            request(b0, src, T0);
+            request(b1, src, T1);
+            request(b2, src, T2);
+            for (uint32_t r = 1; r < n_in; ++r) {
+                src = rank_sketch(r) + tile;
+                add_unit(b0, T0); request(b0, src, T0);
+                add_unit(b1, T1); request(b1, src, T1);
+                add_unit(b2, T2); request(b2, src, T2);
+            }
+            add_unit(b0, T0);
+            add_unit(b1, T1);
+            add_unit(b2, T2);
+        };
+        if (blockIdx.x < A) sum_partition(blockIdx.x);
+        for (uint32_t a = blockIdx.x; a < A; a += gridDim.x) {
+            __syncthreads();  // the peelers are done with the LDS
+#pragma unroll
+            for (uint32_t q = 0; q < kLoadCells; ++q) {
+                const uint32_t c = lt + q * kLoadThreads;
+                if (c < cells) cell[c] = __float_as_uint(acc[q]);
+            }
+            __syncthreads();  // the partition is staged
+            if (a + gridDim.x < A) sum_partition(a + gridDim.x);
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------- the peelers
+    uint32_t *meta_hi = reinterpret_cast<uint32_t *>(cell) + 1;  // meta of cell c: [2c]
+    uint32_t pre_idx[kPeelIdx];
+    auto prefetch_idx = [&](uint32_t p) {
+        const uint32_t r0 = uint32_t(uint64_t(p) * U / A);
+        const uint32_t n = uint32_t(uint64_t(p + 1) * U / A) - r0;
+#pragma unroll
+        for (uint32_t q = 0; q < kPeelIdx; ++q) {
+            const uint32_t u = tid + q * kPeelThreads;
+            pre_idx[q] = u < n ? __builtin_nontemporal_load(idx_out + r0 + u) : 0u;
+        }
+    };
+    if (blockIdx.x < A) prefetch_idx(blockIdx.x);
+    uint32_t bar_expected = 0, max_rounds = 0, Pa_prev = 0;
+    for (uint32_t a = blockIdx.x; a < A; a += gridDim.x) {
+        const uint32_t rho0 = uint32_t(uint64_t(a) * U / A);
+        const uint32_t Pa = uint32_t(uint64_t(a + 1) * U / A) - rho0;
+        const uint32_t sa = salt[a];
+        const uint32_t sw0 = seed_word(seed, 3 * sa), sw1 = seed_word(seed, 3 * sa + 1),
+                       sw2 = seed_word(seed, 3 * sa + 2);
+        __syncthreads();  // everybody is done with the previous partition
+        if (tid == 0) {
+            // what the previous partition left unresolved
+            if (a != blockIdx.x && s_resolved < Pa_prev) {
+                atomicAdd(&status[TAGC_ST_UNRESOLVED], Pa_prev - s_resolved);
+                if (mode != TAGC_DECODE_PEEL)
+                    atomicAdd(&status[TAGC_ST_ESTIMATED], Pa_prev - s_resolved);
+            }
+            s_resolved = 0;
+        }
+        for (uint32_t c = tid; c < P_cap / 32 + 1; c += kPeelThreads) claimed[c] = 0;
+        if (tid < 3) s_n[tid] = s_any[tid] = 0;
+        __syncthreads();  // the loaders have staged the cells
+
+        // ---- every unknown joins its three cells
+#pragma unroll
+        for (uint32_t q = 0; q < kPeelIdx; ++q) {
+            const uint32_t u = tid + q * kPeelThreads;
+            if (u < Pa) {
+                const uint32_t i = pre_idx[q];
+                idx[u] = i;
+                const Cells cl = cells_of(i, m_sub, sw0, sw1, sw2);
+                const unsigned long long inc = (unsigned long long)((u << 15) + 1u) << 32;
+#pragma unroll
+                for (int j = 0; j < 3; ++j) atomicAdd(&cell[cl.c[j]], inc);
+            }
+        }
+        if (a + gridDim.x < A) prefetch_idx(a + gridDim.x);
+        peel_barrier(&s_bar, bar_expected);
+        if (mode != TAGC_DECODE_ESTIMATE) {
+            for (uint32_t c0 = 0; c0 < cells; c0 += kPeelThreads) {
+                const uint32_t c = c0 + tid;
+                queue_push(c < cells && (meta_hi[2 * c] & kDegMask) == 1u, c, &s_n[1], queue);
+            }
+        }
+
+        // ---- the rounds (see peel_kernel)
+        uint32_t rounds = 0, head = 0;
+        for (uint32_t r = 1;; ++r) {
+            peel_barrier(&s_bar, bar_expected);
+            const uint32_t cur = r % 3, nxt = (r + 1) % 3, idle = (r + 2) % 3;
+            if (s_any[idle]) ++rounds;
+            const uint32_t tail = head + s_n[cur];
+            if (tail == head) break;
+            if (tid == 0) {
+                s_n[idle] = 0;
+                s_any[nxt] = 0;
+            }
+            uint16_t *next_queue = queue + tail;
+            for (uint32_t e = head + tid; e < tail; e += kPeelThreads) {
+                const uint32_t q = queue[e];
+                const unsigned long long oq = cell[q];
+                const uint32_t m = uint32_t(oq >> 32);
+                if ((m & kDegMask) != 1u) continue;
+                const uint32_t u = m >> 15, bit = 1u << (u & 31);
+                if (atomicOr(&claimed[u >> 5], bit) & bit) continue;
+                s_any[cur] = 1;
+                const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
+                const uint32_t c[3] = {cl.c[0], cl.c[1], cl.c[2]};
+                const uint32_t neg = cl.neg;
+                const uint32_t j = c[0] == q ? 0u : (c[1] == q ? 1u : 2u);
+                const float cv = __uint_as_float(uint32_t(oq));
+                const float x = ((neg >> j) & 1u) ? -cv : cv;
+                idx[u] = __float_as_uint(x);
+                const unsigned long long dec = (unsigned long long)((u << 15) + 1u) << 32;
+                unsigned long long o[3], rr[3];
+#pragma unroll
+                for (int k = 0; k < 3; ++k) o[k] = uint32_t(k) == j ? oq : cell[c[k]];
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
+                    rr[k] = atomicCAS(&cell[c[k]], o[k],
+                                      ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
+                }
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    while (rr[k] != o[k]) {
+                        o[k] = rr[k];
+                        const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
+                        rr[k] = atomicCAS(&cell[c[k]], o[k],
+                                          ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
+                    }
+                }
+                queue_push3((uint32_t(o[0] >> 32) & kDegMask) == 2u, c[0],
+                            (uint32_t(o[1] >> 32) & kDegMask) == 2u, c[1],
+                            (uint32_t(o[2] >> 32) & kDegMask) == 2u, c[2], &s_n[nxt], next_queue);
+            }
+            head = tail;
+        }
+
+        // ---- output (see peel_kernel)
+        for (uint32_t u = tid; u < Pa; u += kPeelThreads) {
+            float x = 0.0f;
+            if ((claimed[u >> 5] >> (u & 31)) & 1u) {
+                x = __uint_as_float(idx[u]);
+            } else if (mode != TAGC_DECODE_PEEL) {
+                const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
+                float rd[3];
+#pragma unroll
+                for (int j = 0; j < 3; ++j) {
+                    const float cv = __uint_as_float(uint32_t(cell[cl.c[j]]));
+                    rd[j] = ((cl.neg >> j) & 1u) ? -cv : cv;
+                }
+                x = fmaxf(fminf(rd[0], rd[1]), fminf(fmaxf(rd[0], rd[1]), rd[2]));
+            }
+            val_out[rho0 + u] = x;
+        }
+        uint32_t resolved = 0;
+        for (uint32_t c = tid; c < P_cap / 32 + 1; c += kPeelThreads) resolved += __popc(claimed[c]);
+        resolved = wave_sum(resolved);
+        if (lane_id() == 0 && resolved) atomicAdd(&s_resolved, resolved);
+        max_rounds = max(max_rounds, rounds);
+        Pa_prev = Pa;
+    }
+    // the last partition's count: every peeling wave has added its share before this barrier
+    peel_barrier(&s_bar, bar_expected);
+    if (tid == 0) {
+        if (blockIdx.x < A && s_resolved < Pa_prev) {
+            atomicAdd(&status[TAGC_ST_UNRESOLVED], Pa_prev - s_resolved);
+            if (mode != TAGC_DECODE_PEEL) atomicAdd(&status[TAGC_ST_ESTIMATED], Pa_prev - s_resolved);
+        }
+        if (max_rounds) atomicMax(&status[TAGC_ST_ROUNDS], max_rounds);
+    }
+}
+
 // Dense output: one workgroup per 1024-word chunk of the Index writes the 32768 floats
 // it covers, zeros included.  The chunk's Index words, the number of set bits before each
 // word, and the chunk's values (one contiguous run of val_out; its first kDenseStage
@@ -392,9 +670,15 @@ size_t decode_lds_bytes(uint32_t T_cap, uint32_t P_cap)
     return size_t(T_cap) * 8 + (size_t(P_cap) + (P_cap / 32 + 1) + 32) * 4 + size_t(T_cap) * 2 + 16;
 }
 
-int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t *idx_out,
+int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh,
+                  const tagc_rank_buffers *ranks, uint32_t n_ranks, uint32_t *idx_out,
                   float *val_out, float *dense_out, hipStream_t s)
 {
+    // ranks != nullptr: no summed sketch, the decoder adds up the ranks' sketches itself
+    const bool fused = ranks != nullptr;
+    if (fused && (p->T_cap > kDefaultPartCells || p->P_cap > kDefaultPartUnknowns ||
+                  n_ranks > kMaxRanksPerPass))
+        return TAGC_EUNSUPPORTED;
     const uint32_t n_words = uint32_t(p->n_c / 32);
     const uint32_t n_chunks = uint32_t(p->n_chunks);
     const uint32_t *chunkpre = static_cast<const uint32_t *>(sh->workspace);
@@ -403,7 +687,25 @@ int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t 
         enumerate_kernel<<<n_chunks, 256, 0, s>>>(sh->bitmap, n_words, chunkpre, sh->header,
                                                   idx_out);
     }
-    {
+    if (fused) {
+        ProfileScope ps("sum_peel", s);
+        RankPtrs rp{};
+        for (uint32_t r = 0; r < n_ranks; ++r) rp.p[r] = ranks[r].sketch;
+        const size_t lds = decode_lds_bytes(p->T_cap, p->P_cap);
+        uint32_t grid = uint32_t(std::min<uint64_t>(p->A_cap, uint64_t(device_cu_count())));
+        if (p->cfg.decode_workgroups) grid = std::min(grid, p->cfg.decode_workgroups);
+        static size_t attr_bytes = 0;
+        if (lds > attr_bytes) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(sum_peel_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(lds)) != hipSuccess)
+                return TAGC_EHIP;
+            attr_bytes = lds;
+        }
+        sum_peel_kernel<<<grid, kDecodeThreads, lds, s>>>(
+            rp, n_ranks, sh->header, idx_out, val_out, sh->status, p->cfg.seed,
+            sh->bounds + p->A_cap + 1, p->T_cap, p->P_cap, p->cfg.decode_mode);
+    } else {
         ProfileScope ps("peel", s);
         const size_t lds = decode_lds_bytes(p->T_cap, p->P_cap);
         // a workgroup takes partitions b, b + grid, ...: any grid size gives the same result

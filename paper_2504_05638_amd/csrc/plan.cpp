@@ -193,7 +193,11 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     const uint64_t wire = cfg->index_mode == TAGC_INDEX_ADD4 ? 4 : 1;  // bits per parameter
     z.rank_bitmap_bytes = round_up(4 * wire * std::max<uint64_t>(words, 1), 16);
     const uint64_t cell_bytes = cfg->cell_type == TAGC_CELL_BF16 ? 2 : 4;  // on the wire
-    z.rank_sketch_bytes = round_up(cell_bytes * p->m_cap, 16);
+    // (one partition of slack behind the cells: tagc_reduce_decompress reads whole tiles
+    // of the default partition size from a partition's first cell on, and stages only the
+    // partition's own cells)
+    z.rank_sketch_bytes = round_up(cell_bytes * p->m_cap, 16) +
+                          (p->cfg.cell_type == TAGC_CELL_F32 ? 4ull * kDefaultPartCells : 0ull);
     z.rank_workspace_bytes = w.total;
     z.shared_bitmap_bytes = round_up(4 * std::max<uint64_t>(words, 1), 16);
     z.shared_sketch_bytes = round_up(4 * p->m_cap, 16);
@@ -344,7 +348,32 @@ extern "C" int tagc_decompress(const tagc_plan_t *p, const tagc_shared_buffers *
     if (rc) return rc;
     if (!aligned16(idx_out) || !aligned16(val_out) || (dense_out && !aligned16(dense_out)))
         return TAGC_EINVAL;
-    return launch_decode(p, sh, idx_out, val_out, dense_out, static_cast<hipStream_t>(stream));
+    return launch_decode(p, sh, nullptr, 0, idx_out, val_out, dense_out,
+                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int tagc_reduce_decompress(const tagc_plan_t *p, const tagc_rank_buffers *ranks,
+                                      uint32_t n_ranks, const tagc_shared_buffers *sh,
+                                      uint32_t *idx_out, float *val_out, float *dense_out,
+                                      void *stream)
+{
+    if (!p || !ranks || n_ranks == 0 || n_ranks > p->cfg.n_ranks || !idx_out || !val_out)
+        return TAGC_EINVAL;
+    // float32 cells, the default partition size at most, and as many ranks as fit the
+    // kernel's argument list
+    if (n_ranks > kMaxRanksPerPass || p->cfg.cell_type != TAGC_CELL_F32 ||
+        p->T_cap > kDefaultPartCells || p->P_cap > kDefaultPartUnknowns)
+        return TAGC_EUNSUPPORTED;
+    int rc = check_shared(sh);
+    if (rc) return rc;
+    for (uint32_t r = 0; r < n_ranks; ++r) {
+        rc = check_rank(&ranks[r]);
+        if (rc) return rc;
+    }
+    if (!aligned16(idx_out) || !aligned16(val_out) || (dense_out && !aligned16(dense_out)))
+        return TAGC_EINVAL;
+    return launch_decode(p, sh, ranks, n_ranks, idx_out, val_out, dense_out,
+                         static_cast<hipStream_t>(stream));
 }
 
 extern "C" void tagc_hash_host(uint32_t i, uint64_t seed, uint32_t j, uint32_t salt,

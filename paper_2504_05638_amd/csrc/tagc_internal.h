@@ -193,7 +193,8 @@ int launch_index_or(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32
                     const tagc_shared_buffers *sh, hipStream_t s);
 int launch_sketch_sum(const tagc_plan_t *p, const tagc_rank_buffers *ranks, uint32_t n_ranks,
                       const tagc_shared_buffers *sh, hipStream_t s);
-int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh, uint32_t *idx_out,
+int launch_decode(const tagc_plan_t *p, const tagc_shared_buffers *sh,
+                  const tagc_rank_buffers *ranks, uint32_t n_ranks, uint32_t *idx_out,
                   float *val_out, float *dense_out, hipStream_t s);
 
 size_t decode_lds_bytes(uint32_t T_cap, uint32_t P_cap);

@@ -108,8 +108,9 @@ def estimate_tolerance(ores, seed, rel=1e-5):
 
 
 def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTOR, dense=True,
-             decode_mode=0, index_mode=0, cell_type=0, decode_workgroups=0):
-    """Runs oracle and library on the same inputs; returns (oracle result, TagcBucket)."""
+             decode_mode=0, index_mode=0, cell_type=0, decode_workgroups=0, fused=False):
+    """Runs oracle and library on the same inputs; returns (oracle result, TagcBucket).
+    `fused`: the library sums the sketches inside the decoder (tagc_reduce_decompress)."""
     import torch
     from paper_2504_05638_amd.bucket import TagcBucket
 
@@ -122,7 +123,7 @@ def run_both(bucket, grads_torch_cpu, seed=0, P=0, T=0, sizing=O.SIZE_LOAD_FACTO
                     index_mode=index_mode, cell_type=cell_type,
                     decode_workgroups=decode_workgroups)
     dev = [g.cuda() for g in grads_torch_cpu]
-    tb.run(dev)
+    tb.run(dev, fused=fused)
     torch.cuda.synchronize()
     return ores, tb
 

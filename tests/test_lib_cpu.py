@@ -135,6 +135,27 @@ def test_static_workspace_variant_rejects_a_plan_that_does_not_fit_before_touchi
     B.tagc_plan_destroy(plan)
 
 
+def test_fused_decode_refuses_what_its_kernel_cannot_hold_before_touching_anything():
+    """tagc_reduce_decompress takes float32 cells, partitions of the default size at most and
+    up to 32 ranks; anything else is TAGC_EUNSUPPORTED before a pointer is looked at."""
+    seg = [(0, 1 << 20, 10_000, B.TAGC_SEG_COMPRESS)]
+    rk, sh = B.tagc_rank_buffers(), B.tagc_shared_buffers()
+    for kw in (dict(cell_type=B.TAGC_CELL_BF16), dict(part_unknowns=8192, part_cells=12291),
+               dict(n_ranks=40)):
+        cfg = dict(n_ranks=2)
+        cfg.update(kw)
+        plan = B.tagc_plan(_cfg(**cfg), seg)
+        with pytest.raises(B.TagcError) as e:
+            B.tagc_reduce_decompress(plan, [rk] * cfg["n_ranks"], sh, 256, 256)
+        assert e.value.code == -3, kw
+        B.tagc_plan_destroy(plan)
+    plan = B.tagc_plan(_cfg(n_ranks=2), seg)
+    with pytest.raises(B.TagcError) as e:   # supported, but null buffers
+        B.tagc_reduce_decompress(plan, [rk, rk], sh, 256, 256)
+    assert e.value.code == -1
+    B.tagc_plan_destroy(plan)
+
+
 def test_bench_refuses_more_than_one_gpu_and_fails_loudly_without_one():
     """bench.py measures one GPU: asked for more it says so and exits; without a GPU it
     must not fall back to anything (there is no CPU path)."""
