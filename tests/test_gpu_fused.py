@@ -93,6 +93,20 @@ def test_heavy_tailed_many_partitions_fused():
     assert st["n_unresolved"] == 0
 
 
+@pytest.mark.parametrize("ratio_milli,theta_ppm", [(4000, 100_000), (10_000, 12_500)])
+def test_fixed_ratio_sketch_two_ranks_fused(ratio_milli, theta_ppm):
+    """Table 1's regimes (sketch of n / c cells, 2 ranks): the 4x one peels close to the
+    threshold over some twenty rounds, each with the peelers' own barrier."""
+    _announce("fused fixed ratio %d" % ratio_milli)
+    n = 600_000
+    b = G.Bucket("t1", G.F32, 2, [G.Seg(0, n, theta_ppm, 1, "w")], n, ratio_milli)
+    grads = [torch.from_numpy((np.random.default_rng(70 + r).standard_normal(n) * 1e-3)
+                              .astype(np.float32)) for r in range(2)]
+    ores, tb = run_both(b, grads, seed=3, sizing=O.SIZE_FIXED_RATIO, fused=True)
+    hdr, st = compare_all(b, ores, tb)
+    assert st["n_unresolved"] == 0 and hdr["m"] <= n * 1000 // ratio_milli
+
+
 def test_repeated_calls_give_the_same_result():
     """The loaders and the peelers of a workgroup meet at barriers of two kinds; nothing may
     depend on who gets there first: twenty calls on the same buffers, the same integers out."""
