@@ -290,8 +290,13 @@ def main():
     if args.arena_gb < 0:
         args.arena_gb = int(torch.cuda.mem_get_info()[0] * 3 // 4) >> 30
     if args.arena_gb:
-        arena = torch.empty(args.arena_gb << 30, dtype=torch.uint8, device="cuda")
-        del arena
+        try:
+            arena = torch.empty(args.arena_gb << 30, dtype=torch.uint8, device="cuda")
+            del arena
+        except RuntimeError:   # no block of that size to be had: allocate piecemeal
+            sys.stderr.write("bench.py: no single block of %d GiB, going on without it\n"
+                             % args.arena_gb)
+            args.arena_gb = 0
     buckets = make_buckets(args)
     n_b = len(buckets)
     pool = max(1, min(args.pool, n_b))
