@@ -214,10 +214,12 @@ typedef struct tagc_rank_buffers {
     uint32_t *bitmap;   /* [rank_bitmap_bytes / 4] local Index as it goes on the
                            wire: bit j in word j>>5, bit j&31 (bitmap_words
                            words), or 4-bit counters with TAGC_INDEX_ADD4       */
-    float *sketch;      /* [sketch_cells_capacity] local Count Sketch; cells
+    float *sketch;      /* [rank_sketch_bytes] local Count Sketch; cells
                            [0, m) are written, the rest untouched.  16-bit
-                           cells (rank_sketch_bytes covers either) with
-                           TAGC_CELL_BF16                                      */
+                           cells with TAGC_CELL_BF16.  rank_sketch_bytes covers
+                           sketch_cells_capacity cells of the plan's cell type
+                           and, for float32 cells, 48 KiB behind them that
+                           tagc_reduce_decompress may read (never use)         */
     void *workspace;    /* [rank_workspace_bytes] scratch, may be shared by ranks
                            processed one after another on one stream           */
     void *acc;          /* NULL, or [grad_elems] of the plan's dtype: the rank's
