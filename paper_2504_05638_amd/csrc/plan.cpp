@@ -144,6 +144,10 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     // PHASE_INDEX call clears before use), then plain scratch that is written before it is read
     Workspace &w = p->ws;
     const uint64_t chunks = scs * kCandChunksPerSuper;
+    if (chunks * p->cand_cap >= (1ull << 32)) {  // slot numbers are kept in 32 bits
+        delete p;
+        return TAGC_ESIZE;
+    }
     uint64_t off = 0;
     w.hist1d = off;
     off += L * kBins1 * 4;
@@ -158,8 +162,8 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     off += round_up(tiles * 8, 16);
     w.sc_cnt = off;
     off += round_up(scs * 8, 16);
-    w.chunk_cnt = off;
-    off += round_up(chunks * 4, 16);
+    w.chunk_info = off;  // per chunk: candidates found, first slot
+    off += round_up(chunks * 8, 16);
     off = round_up(off, 128);  // a chunk's slots then start on a cache-line boundary
     w.cand = off;
     off += round_up(chunks * p->cand_cap * (cfg->dtype == TAGC_F32 ? 8 : 4), 16);

@@ -504,7 +504,7 @@ template <int DTYPE>
 __global__ void __launch_bounds__(kSpillThreads)
 scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                   uint32_t *table, SelDev *sel, uint32_t *__restrict__ cand,
-                  uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
+                  uint2 *__restrict__ chunk_info, uint64_t n_slots_total, uint32_t CAP,
                   uint4 *zero_base, uint64_t zero_n16)
 {
     constexpr uint32_t EB = DTYPE == kBF16 ? 2 : 4;
@@ -518,6 +518,7 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
     __shared__ uint32_t h[kWinWords];
     __shared__ uint32_t s_sel[32];
     __shared__ uint32_t s_last;
+    __shared__ uint32_t s_region;  // slots of the workgroup's part of `cand` handed out so far
     __shared__ uint32_t stage[NW][STAGE_WORDS];
     __shared__ uint32_t list[NW][3][kSpillList];  // chunk number, staging offset, count
     __shared__ uint4 data[NW][ROWS * 64];         // each wave's current chunk
@@ -540,6 +541,7 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
     if (g0 >= total_chunks) return;
     const uint64_t g1 = min(g0 + span, uint64_t(total_chunks));
     for (uint32_t i = tid; i < kWinWords; i += kSpillThreads) h[i] = 0;
+    if (tid == 0) s_region = 0;
     // last segment whose first chunk is not beyond the span's start.  Up to 64 segments: lane
     // i looks at segment i, all at once (a search would be several dependent loads, which is
     // time the workgroup's first chunk waits for)
@@ -562,24 +564,31 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
     const bool staged = CAP <= kSpillStage;
     uint32_t n_list = 0, fill = 0;  // wave-uniform
 
-    // the staged chunks' slots and counts go out; only this wave touched what it reads
+    // The staged chunks' slots and counts go out; only this wave touched what it reads.
+    // The slots are packed: the chunks of the workgroup's span own the part
+    // [g0 * CAP, g1 * CAP) of `cand`, and every flush takes the next free stretch of it, a
+    // whole number of 128-byte lines (a line written only in part costs the memory system a
+    // read-modify-write; a stretch never needs more than its chunks' CAP slots each, so the
+    // part cannot run out).  Where a chunk's slots went is recorded beside its count.  With
+    // one fixed array of CAP slots per chunk, of which a quarter is used on average, every
+    // pass over the slots moved twice the bytes.
     auto flush = [&]() {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        for (uint32_t e = 0; e < n_list; ++e) {
-            const uint32_t off = lst_off[e];
-            // Whole 128-byte lines: a line written only in part costs the memory system a
-            // read-modify-write.  The padding words are stale staging content, which no
-            // reader looks at (the count says how many are real).
-            const uint32_t n_out = min((lst_cnt[e] + 31u) & ~31u, CAP);
-            uint32_t *slots = cand + uint64_t(lst_chunk[e]) * CAP;
-            for (uint32_t i = lane; i < n_out; i += 64) {
-                slots[i] = st[off + i];
-                if (DTYPE != kBF16) slots[n_slots_total + i] = st[kSpillStage + off + i];
-            }
+        const uint32_t n_out = (fill + 31u) & ~31u;
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&s_region, n_out);
+        at = __builtin_amdgcn_readfirstlane(at);
+        const uint32_t first = uint32_t(g0) * CAP + at;  // (the plan keeps slot numbers in 32 bits)
+        uint32_t *slots = cand + first;
+        // the padding words are stale staging content, which no reader looks at
+        for (uint32_t i = lane; i < n_out; i += 64) {
+            slots[i] = st[i];
+            if (DTYPE != kBF16) slots[n_slots_total + i] = st[kSpillStage + i];
         }
-        if (lane < n_list) chunk_cnt[lst_chunk[lane]] = lst_cnt[lane];
+        if (lane < n_list)
+            chunk_info[lst_chunk[lane]] = make_uint2(lst_cnt[lane], first + lst_off[lane]);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         n_list = 0;
@@ -782,7 +791,8 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                     place();
                 }
                 const uint32_t chunk_id = uint32_t(s0) + ch;
-                const uint32_t need = min((total + 31u) & ~31u, CAP);
+                // (a chunk's slots start on a 16-byte boundary: they are read in such groups)
+                const uint32_t need = min((total + 3u) & ~3u, CAP);
                 if (staged && (n_list == kSpillList || fill + need > kSpillStage)) flush();
                 uint32_t *slots = cand + uint64_t(chunk_id) * CAP;
                 uint32_t *slots_pos = slots + n_slots_total;  // fp32 only
@@ -829,11 +839,11 @@ scan_spill_kernel(const char *__restrict__ grad, char *acc, const SentMap sent,
                     ++n_list;
                     fill += need;
                 } else if (lane == 0) {
-                    chunk_cnt[chunk_id] = total;
+                    chunk_info[chunk_id] = make_uint2(total, chunk_id * CAP);
                 }
                 overflow |= total > CAP;
             }
-            if (staged) flush();
+            if (staged && n_list) flush();
             if (blo_w > blo && lane == 0) atomicMax(&ts.raised[l], blo_w);
             if (overflow && lane == 0)  // a chunk denser than its slots: take the dense route
                 atomicOr(&ts.reroute[l], 1u);
@@ -1115,8 +1125,8 @@ hist2_kernel(const char *__restrict__ grad, const uint32_t *__restrict__ table,
 // fp32, candidate route: the same histogram from the spilled candidates.
 __global__ void __launch_bounds__(256)
 hist2c_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel,
-              const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
-              uint32_t CAP, uint32_t *__restrict__ hist2)
+              const uint32_t *__restrict__ cand, const uint2 *__restrict__ chunk_info,
+              uint32_t n_slots_total, uint32_t CAP, uint32_t *__restrict__ hist2)
 {
     constexpr uint32_t CHUNK = 64 * 4 * kCandRows;
     const uint32_t L = table[0];
@@ -1131,9 +1141,11 @@ hist2c_kernel(const uint32_t *__restrict__ table, const SelDev *__restrict__ sel
         const uint32_t n_chunks = (sd.n + CHUNK - 1) / CHUNK;
         for (uint32_t ch = wave; ch < n_chunks; ch += n_waves) {
             const uint32_t g = sd.sc_start * kCandChunksPerSuper + ch;
-            const uint32_t c = min(chunk_cnt[g], CAP);
+            const uint2 info = chunk_info[g];  // count, first slot
+            const uint32_t c = min(info.x, CAP);
+            const uint32_t first = min(info.y, n_slots_total - CAP);
             for (uint32_t i = lane; i < c; i += 64) {
-                const uint32_t key = cand[uint64_t(g) * CAP + i] & 0x7FFFFFFFu;
+                const uint32_t key = cand[first + i] & 0x7FFFFFFFu;
                 if ((key >> 16) == bin1) atomicAdd(&gh[key & 0xFFFFu], 1u);
             }
         }
@@ -1247,7 +1259,7 @@ template <int DTYPE, bool PLACE>
 __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
                                  const uint32_t *__restrict__ table,
                                  const SelDev *__restrict__ sel,
-            const uint32_t *__restrict__ cand, const uint32_t *__restrict__ chunk_cnt,
+            const uint32_t *__restrict__ cand, const uint2 *__restrict__ chunk_info,
             uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_cnt,
             uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
             uint32_t *__restrict__ bitmap)
@@ -1279,8 +1291,11 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
         bool live = sc < total_sc;
         const uint32_t scc = live ? sc : 0u;
         const uint32_t g = scc * kCandChunksPerSuper + ch_in_sc;  // global chunk number
-        const uint32_t *sp = cand + uint64_t(g) * CAP;
-        const uint32_t craw = chunk_cnt[g];  // (only meaningful for a chunk the scan has seen)
+        // count and first slot (only meaningful for a chunk the scan has seen)
+        const uint2 cinfo = chunk_info[g];
+        const uint32_t craw = cinfo.x;
+        // (the bound keeps the reads inside `cand` whatever an unseen chunk's record holds)
+        const uint32_t *sp = cand + (min(cinfo.y, uint32_t(n_slots_total) - CAP) & ~3u);
         // segment i's table rows in lane i
         uint32_t t_start = 0xFFFFFFFFu, t_n = 0, t_coff = 0, t_T = 0, t_quota = 0, t_cnt = 0,
                  t_route = 0;
@@ -1670,11 +1685,11 @@ template <int DTYPE, uint32_t COMPACT_ROWS>
 __global__ void __launch_bounds__(kEmitThreads)
 count_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ table,
              const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
-             const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
+             const uint2 *__restrict__ chunk_info, uint64_t n_slots_total, uint32_t CAP,
              uint64_t *sc_cnt, uint64_t *tile_cnt, uint64_t *group_cnt)
 {
     if (blockIdx.x < n_emit)
-        emit_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
+        emit_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_info, n_slots_total,
                                 CAP, sc_cnt, nullptr, nullptr, nullptr);
     else
         compact_body<DTYPE, COMPACT_ROWS, false>(blockIdx.x - n_emit, gridDim.x - n_emit, grad,
@@ -1687,7 +1702,7 @@ __global__ void __launch_bounds__(kEmitThreads)
     __attribute__((amdgpu_waves_per_eu(COMPACT_ROWS == 2 ? 7 : 6, 8)))
 place_kernel(uint32_t n_emit, const char *grad, uint32_t *table,
              const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
-             const uint32_t *__restrict__ chunk_cnt, uint64_t n_slots_total, uint32_t CAP,
+             const uint2 *__restrict__ chunk_info, uint64_t n_slots_total, uint32_t CAP,
              uint64_t *sc_cnt, uint64_t *tile_cnt, uint64_t *group_cnt,
              uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
              uint32_t *__restrict__ bitmap, uint32_t *cnt)
@@ -1697,7 +1712,7 @@ place_kernel(uint32_t n_emit, const char *grad, uint32_t *table,
         write_rank_counts(table, sel, cnt, s_cnt);
     }
     if (blockIdx.x < n_emit)
-        emit_body<DTYPE, true>(blockIdx.x, n_emit, table, sel, cand, chunk_cnt, n_slots_total,
+        emit_body<DTYPE, true>(blockIdx.x, n_emit, table, sel, cand, chunk_info, n_slots_total,
                                CAP, sc_cnt, idx_out, val_out, bitmap);
     else
         compact_body<DTYPE, COMPACT_ROWS, true>(blockIdx.x - n_emit, gridDim.x - n_emit, grad,
@@ -1798,7 +1813,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     uint64_t *group_cnt = reinterpret_cast<uint64_t *>(ws + p->ws.group_cnt);
     uint64_t *sc_cnt = reinterpret_cast<uint64_t *>(ws + p->ws.sc_cnt);
     SelDev *sel = reinterpret_cast<SelDev *>(ws + p->ws.sel);
-    uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + p->ws.chunk_cnt);
+    uint2 *chunk_info = reinterpret_cast<uint2 *>(ws + p->ws.chunk_info);
     uint32_t *cand = reinterpret_cast<uint32_t *>(ws + p->ws.cand);
     const uint64_t n_slots = uint64_t(p->total_sc) * kCandChunksPerSuper * p->cand_cap;
     const char *g = static_cast<const char *>(grad);
@@ -1847,7 +1862,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     if (p->total_sc) {
         ProfileScope ps("scan_spill", s);
         scan_spill_kernel<DTYPE><<<cus * kSpillWgsPerCU, kSpillThreads, 0, s>>>(
-            g, acc, sent, table, sel, cand, chunk_cnt, n_slots, p->cand_cap,
+            g, acc, sent, table, sel, cand, chunk_info, n_slots, p->cand_cap,
             reinterpret_cast<uint4 *>(ws), zero_n16);
     }
     {
@@ -1863,7 +1878,8 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     if (DTYPE == kF32) {
         if (p->total_sc) {
             ProfileScope ps("hist2c", s);
-            hist2c_kernel<<<cus * 4, 256, 0, s>>>(table, sel, cand, chunk_cnt, p->cand_cap, hist2);
+            hist2c_kernel<<<cus * 4, 256, 0, s>>>(table, sel, cand, chunk_info, uint32_t(n_slots),
+                                                  p->cand_cap, hist2);
         }
         {
             ProfileScope ps("hist2", s);
@@ -1892,13 +1908,13 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         {
             ProfileScope ps("count", s);
             count<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
-                n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_cnt, tile_cnt,
+                n_emit, src, table, sel, cand, chunk_info, n_slots, p->cand_cap, sc_cnt, tile_cnt,
                 group_cnt);
         }
         {
             ProfileScope ps("place", s);
             place<<<n_emit + n_compact, kEmitThreads, 0, s>>>(
-                n_emit, src, table, sel, cand, chunk_cnt, n_slots, p->cand_cap, sc_cnt, tile_cnt,
+                n_emit, src, table, sel, cand, chunk_info, n_slots, p->cand_cap, sc_cnt, tile_cnt,
                 group_cnt, rk->idx, rk->val, bitmap1, rk->cnt);
         }
     }

@@ -80,7 +80,7 @@ struct RankPtrs {
 
 struct Workspace {  // byte offsets inside a rank workspace
     uint64_t hist1d, hist2, group_cnt;  // cleared by every PHASE_INDEX call before they are added to
-    uint64_t sel, tile_cnt, sc_cnt, chunk_cnt, cand, bitmap1, total;
+    uint64_t sel, tile_cnt, sc_cnt, chunk_info, cand, bitmap1, total;
 };
 
 // Device state of a plan, kept behind the segment rows of its table: all zero after
