@@ -120,6 +120,7 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
         delete p;
         return TAGC_ESIZE;
     }
+    p->emit_wide = p->cand_cap >= kWideEmitCap;
     p->n_real = n_real;
     p->n_c = c;
     p->K = K;

@@ -1477,6 +1477,186 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
     }
 }
 
+// ------------------------------------------- emit, hundreds of candidates per chunk
+
+// emit_body gives a chunk's slots to four threads, which suits the few dozen candidates a
+// chunk holds when one entry in a hundred is kept.  Where a tenth or a fifth is kept (the 4x
+// and 2x regimes of Table 1) a chunk holds hundreds.  Here a wave takes a whole super-chunk
+// and reads its chunks' slots 64 at a time, in position order, kWideBatch such reads in
+// flight.  The survivors among the 64 slots of one read are neighbours in the output, so
+// they are stored as they are found; the Index words of a chunk are collected in LDS and
+// leave when its last slots are through.  Same inputs, same outputs, same counts per
+// super-chunk as emit_body.
+constexpr uint32_t kWideBatch = 16;
+
+template <int DTYPE, bool PLACE>
+__device__ __forceinline__ void emit_wide_body(uint32_t bid, uint32_t nb,
+                                 const uint32_t *__restrict__ table,
+                                 const SelDev *__restrict__ sel,
+            const uint32_t *__restrict__ cand, const uint2 *__restrict__ chunk_info,
+            uint64_t n_slots_total, uint32_t CAP, uint64_t *sc_cnt,
+            uint32_t *__restrict__ idx_out, float *__restrict__ val_out,
+            uint32_t *__restrict__ bitmap)
+{
+    constexpr uint32_t VEC = DTYPE == kBF16 ? 8 : 4;
+    constexpr uint32_t CHUNK = 64 * VEC * kCandRows;
+    constexpr uint32_t NCH = kCandChunksPerSuper;
+    constexpr uint32_t SC_ELEMS = CHUNK * NCH;
+    constexpr uint32_t CH_WORDS = CHUNK / 32;
+    constexpr uint32_t NWV = kEmitThreads / 64;
+    static_assert(NCH <= 64 && CH_WORDS <= 64, "a lane per chunk, a lane per Index word of a chunk");
+    __shared__ uint32_t wbits[PLACE ? NWV : 1][PLACE ? CH_WORDS : 1];  // a wave's current chunk
+    const uint32_t L = table[0], total_sc = table[4];
+    const SegDev *segs = reinterpret_cast<const SegDev *>(table + 8);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t lanes_below = (1ull << lane) - 1ull;
+
+    // segment i's table rows in lane i
+    uint32_t t_start = 0xFFFFFFFFu, t_n = 0, t_coff = 0, t_T = 0, t_quota = 0, t_cnt = 0,
+             t_route = 0;
+    if (L <= 64 && lane < L) {
+        const uint4 *s4 = reinterpret_cast<const uint4 *>(segs + lane);
+        const uint4 *e4 = reinterpret_cast<const uint4 *>(sel + lane);
+        const uint4 sa = s4[0], sb = s4[1], ea = e4[0], eb4 = e4[1];
+        t_n = sa.z; t_coff = sa.w; t_start = sb.w;                 // n, c_off, sc_start
+        if (sb.x != 0 && sa.z != 0) {   // k, n: a segment that keeps nothing has no selection
+            t_T = ea.x; t_quota = ea.y; t_cnt = ea.w; t_route = eb4.w;  // T, quota, cnt, route
+        }
+    }
+    if (PLACE && lane < CH_WORDS) wbits[wave][lane] = 0;  // (no other wave touches this row)
+
+    for (uint32_t sc = bid * NWV + wave; sc < total_sc; sc += nb * NWV) {  // wave-uniform
+        // ---- segment, threshold, pair offset of the segment
+        uint32_t l, c_off, n_seg, sc_first, T, quota, seg_base, se_cnt, se_route;
+        if (L <= 64) {
+            const uint64_t le = __ballot(t_start <= sc);  // a prefix of the lanes
+            l = uint32_t(__popcll(le)) - 1u;              // segment 0 starts at 0
+            n_seg = __builtin_amdgcn_readlane(t_n, l);
+            c_off = __builtin_amdgcn_readlane(t_coff, l);
+            sc_first = __builtin_amdgcn_readlane(t_start, l);
+            T = __builtin_amdgcn_readlane(t_T, l);
+            quota = __builtin_amdgcn_readlane(t_quota, l);
+            se_cnt = __builtin_amdgcn_readlane(t_cnt, l);
+            se_route = __builtin_amdgcn_readlane(t_route, l);
+            seg_base = wave_sum<uint32_t>(lane < l ? t_cnt : 0u);
+        } else {
+            l = segment_of(L, sc, [&](uint32_t i) { return segs[i].sc_start; });
+            const SegDev sd = segs[l];
+            SelDev se{};
+            if (sd.k != 0 && sd.n != 0) se = sel[l];
+            n_seg = sd.n; c_off = sd.c_off; sc_first = sd.sc_start;
+            T = se.T; quota = se.quota; se_cnt = se.cnt; se_route = se.route;
+            uint32_t sum = 0;
+            for (uint32_t i = lane; i < l; i += 64) sum += segment_count(segs[i], sel, i);
+            seg_base = wave_sum<uint32_t>(sum);
+        }
+        const bool live = !se_route;  // the dense route writes re-routed segments
+        const uint32_t sc_rel0 = (sc - sc_first) * SC_ELEMS;
+
+        // ---- chunk `lane` of the super-chunk: its candidates and where their slots are
+        // (the bound keeps the reads inside `cand` whatever the record holds)
+        bool inseg_l = false;
+        uint32_t cnt_l = 0, first_l = 0;
+        if (lane < NCH) {
+            inseg_l = live && sc_rel0 + lane * CHUNK < n_seg;
+            if (inseg_l && se_cnt != 0) {
+                const uint2 info = chunk_info[sc * NCH + lane];
+                cnt_l = min(info.x, CAP);
+                first_l = min(info.y, uint32_t(n_slots_total) - CAP);
+            }
+        }
+        // reads of 64 slots ("groups"), numbered through the super-chunk
+        const uint32_t ngr_l = (cnt_l + 63u) >> 6;
+        const uint32_t gend_l = wave_incl_scan<uint32_t>(ngr_l);  // (lanes from NCH on: the total)
+        const uint32_t n_groups = __builtin_amdgcn_readlane(gend_l, 63);
+
+        uint32_t gb = 0, eb = 0;  // entries above / at the threshold before the current slot
+        if (PLACE) {
+            // prefix over the segment's earlier super-chunks, whose counts are all there
+            uint64_t sum = 0;
+            if (live)
+                for (uint32_t j = sc_first + lane; j < sc; j += 64) sum += sc_cnt[j];
+            sum = wave_sum<uint64_t>(sum);
+            gb = uint32_t(sum >> 31);
+            eb = uint32_t(sum & 0x7FFFFFFFu);
+            // chunks of the segment without a candidate: their Index words are zero
+            for (uint64_t em = __ballot(inseg_l && cnt_l == 0); em; em &= em - 1) {
+                const uint32_t ch = uint32_t(__builtin_ctzll(em));
+                const uint32_t rel0 = sc_rel0 + ch * CHUNK + lane * 32;
+                if (lane < CH_WORDS && rel0 < n_seg) bitmap[(c_off + rel0) >> 5] = 0;
+            }
+        }
+
+        for (uint32_t b0 = 0; b0 < n_groups; b0 += kWideBatch) {
+            // where group g lies (all wave-uniform): chunk, first slot, slots of the chunk
+            auto locate = [&](uint32_t g, uint32_t &ch, uint32_t &c, uint32_t &s0,
+                              uint32_t &first) {
+                ch = uint32_t(__popcll(__ballot(gend_l <= g)));  // chunks that end before g
+                c = __builtin_amdgcn_readlane(cnt_l, ch);
+                first = __builtin_amdgcn_readlane(first_l, ch);
+                const uint32_t gbeg = __builtin_amdgcn_readlane(gend_l, ch) -
+                                      __builtin_amdgcn_readlane(ngr_l, ch);
+                s0 = (g - gbeg) * 64;
+            };
+            uint32_t v[kWideBatch], vp[kWideBatch];
+#pragma unroll
+            for (uint32_t j = 0; j < kWideBatch; ++j) {
+                v[j] = vp[j] = 0;
+                if (b0 + j < n_groups) {
+                    uint32_t ch, c, s0, first;
+                    locate(b0 + j, ch, c, s0, first);
+                    if (s0 + lane < c) {
+                        v[j] = cand[first + s0 + lane];
+                        if (DTYPE == kF32) vp[j] = cand[n_slots_total + first + s0 + lane];
+                    }
+                }
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < kWideBatch; ++j) {
+                if (b0 + j >= n_groups) continue;
+                uint32_t ch, c, s0, first;
+                locate(b0 + j, ch, c, s0, first);
+                const bool valid = s0 + lane < c;
+                const uint32_t vbits = DTYPE == kBF16 ? (v[j] & 0xFFFF0000u) : v[j];
+                const uint32_t rel = (DTYPE == kBF16 ? (v[j] & 0xFFFFu) : vp[j]) & (CHUNK - 1u);
+                const uint32_t key = vbits & 0x7FFFFFFFu;
+                const bool is_gt = valid && key > T;
+                const bool is_eq = valid && key == T && quota != 0;
+                const uint64_t bgt = __ballot(is_gt), beq = __ballot(is_eq);
+                if (PLACE) {
+                    const uint32_t my_gb = gb + uint32_t(__popcll(bgt & lanes_below));
+                    const uint32_t my_eb = eb + uint32_t(__popcll(beq & lanes_below));
+                    // entries above T all survive, ties while the quota lasts
+                    const bool keep = is_gt || (is_eq && my_eb < quota);
+                    if (keep) {
+                        const uint32_t pos = is_gt ? my_gb + min(my_eb, quota) : my_gb + my_eb;
+                        idx_out[seg_base + pos] = c_off + sc_rel0 + ch * CHUNK + rel;
+                        val_out[seg_base + pos] = __uint_as_float(vbits);
+                        atomicOr(&wbits[wave][rel >> 5], 1u << (rel & 31));
+                    }
+                    if (s0 + 64 >= c) {  // the chunk's last slots: its Index words leave
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        if (lane < CH_WORDS) {
+                            const uint32_t w = wbits[wave][lane];
+                            wbits[wave][lane] = 0;
+                            const uint32_t rel0 = sc_rel0 + ch * CHUNK + lane * 32;
+                            if (rel0 < n_seg) bitmap[(c_off + rel0) >> 5] = w;
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                }
+                gb += uint32_t(__popcll(bgt));
+                eb += uint32_t(__popcll(beq));
+            }
+        }
+        if (!PLACE && lane == 0) sc_cnt[sc] = (uint64_t(gb) << 31) | uint64_t(eb);
+    }
+}
+
 // ---------------------------------------------------------------- compact
 
 // Dense route, count and place, over the gradient itself: one tile of kCompactThreads x ROWS
@@ -1681,23 +1861,27 @@ __device__ __forceinline__ void compact_body(uint32_t bid, uint32_t nb, const ch
 // that part costs nothing, not even an empty kernel's turn-around.
 static_assert(kEmitThreads == kCompactThreads, "one launch for both parts");
 
-template <int DTYPE, uint32_t COMPACT_ROWS>
+template <int DTYPE, uint32_t COMPACT_ROWS, bool WIDE>
 __global__ void __launch_bounds__(kEmitThreads)
 count_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ table,
              const SelDev *__restrict__ sel, const uint32_t *__restrict__ cand,
              const uint2 *__restrict__ chunk_info, uint64_t n_slots_total, uint32_t CAP,
              uint64_t *sc_cnt, uint64_t *tile_cnt, uint64_t *group_cnt)
 {
-    if (blockIdx.x < n_emit)
-        emit_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_info, n_slots_total,
-                                CAP, sc_cnt, nullptr, nullptr, nullptr);
-    else
+    if (blockIdx.x < n_emit) {
+        if (WIDE)
+            emit_wide_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
+                                         n_slots_total, CAP, sc_cnt, nullptr, nullptr, nullptr);
+        else
+            emit_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
+                                    n_slots_total, CAP, sc_cnt, nullptr, nullptr, nullptr);
+    } else
         compact_body<DTYPE, COMPACT_ROWS, false>(blockIdx.x - n_emit, gridDim.x - n_emit, grad,
                                                  table, sel, tile_cnt, group_cnt, nullptr, nullptr,
                                                  nullptr);
 }
 
-template <int DTYPE, uint32_t COMPACT_ROWS>
+template <int DTYPE, uint32_t COMPACT_ROWS, bool WIDE>
 __global__ void __launch_bounds__(kEmitThreads)
     __attribute__((amdgpu_waves_per_eu(COMPACT_ROWS == 2 ? 7 : 6, 8)))
 place_kernel(uint32_t n_emit, const char *grad, uint32_t *table,
@@ -1711,10 +1895,14 @@ place_kernel(uint32_t n_emit, const char *grad, uint32_t *table,
         __shared__ uint32_t s_cnt[8];
         write_rank_counts(table, sel, cnt, s_cnt);
     }
-    if (blockIdx.x < n_emit)
-        emit_body<DTYPE, true>(blockIdx.x, n_emit, table, sel, cand, chunk_info, n_slots_total,
-                               CAP, sc_cnt, idx_out, val_out, bitmap);
-    else
+    if (blockIdx.x < n_emit) {
+        if (WIDE)
+            emit_wide_body<DTYPE, true>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
+                                        n_slots_total, CAP, sc_cnt, idx_out, val_out, bitmap);
+        else
+            emit_body<DTYPE, true>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
+                                   n_slots_total, CAP, sc_cnt, idx_out, val_out, bitmap);
+    } else
         compact_body<DTYPE, COMPACT_ROWS, true>(blockIdx.x - n_emit, gridDim.x - n_emit, grad,
                                                 table, sel, tile_cnt, group_cnt, idx_out, val_out,
                                                 bitmap);
@@ -1830,7 +2018,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     const int cus = device_cu_count();
     const size_t lds_hist = kBins1 * sizeof(uint32_t);
     static bool a_prepare = false, a_hist = false;
-    static int occ_place[2] = {0, 0};
+    static int occ_place[2][2] = {{0, 0}, {0, 0}};
 
     if (L == 0 || (p->total_sc == 0 && p->total_tiles == 0)) {
         // nothing is compressed (or every compressed segment is empty): only the counts
@@ -1892,12 +2080,17 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
     }
     {
         // the plan fixed the compaction tile's height, and with it which kernels these are
-        const bool rows4 = p->compact_rows == 4;
-        auto count = rows4 ? count_kernel<DTYPE, 4> : count_kernel<DTYPE, 2>;
-        auto place = rows4 ? place_kernel<DTYPE, 4> : place_kernel<DTYPE, 2>;
-        const int occ = resident_blocks_per_cu(place, kEmitThreads, 0, &occ_place[rows4]);
+        // (and whether chunks hold dozens or hundreds of candidates)
+        const bool rows4 = p->compact_rows == 4, wd = p->emit_wide;
+        auto count = wd ? (rows4 ? count_kernel<DTYPE, 4, true> : count_kernel<DTYPE, 2, true>)
+                        : (rows4 ? count_kernel<DTYPE, 4, false> : count_kernel<DTYPE, 2, false>);
+        auto place = wd ? (rows4 ? place_kernel<DTYPE, 4, true> : place_kernel<DTYPE, 2, true>)
+                        : (rows4 ? place_kernel<DTYPE, 4, false> : place_kernel<DTYPE, 2, false>);
+        const int occ = resident_blocks_per_cu(place, kEmitThreads, 0, &occ_place[wd][rows4]);
         if (occ <= 0) return TAGC_EHIP;
-        const uint32_t n_emit = (p->total_sc + kEmitItems - 1) / kEmitItems;
+        // emit_body: kEmitItems super-chunks per workgroup; emit_wide_body: one per wave
+        const uint32_t per_wg = wd ? kEmitThreads / 64 : uint32_t(kEmitItems);
+        const uint32_t n_emit = (p->total_sc + per_wg - 1) / per_wg;
         // Dense route: one tile per workgroup when dense-route work is certain.  When no
         // segment is planned for this route the part is only a safety net for re-routed
         // segments and nearly always exits at once: a grid that fits the device takes the

@@ -24,7 +24,8 @@ constexpr int kEmitItems = 2;  // super-chunks per workgroup of the candidate ro
 constexpr uint32_t kSampleVectors = 4096;     // 16-byte vectors sampled per segment
 constexpr uint32_t kFastMinElems = 1u << 17;  // shorter segments take the dense path
 constexpr uint32_t kFastMinKeep = 64;
-constexpr double kFastMaxCandFrac = 0.04;  // expected candidates per element beyond which the dense path wins
+constexpr uint32_t kWideEmitCap = 192;  // candidate slots per chunk from which count / place give a wave to a super-chunk
+constexpr double kFastMaxCandFrac = 0.30;  // expected candidates per element beyond which the dense path is planned
 constexpr uint32_t kChunkWords = 1024;  // Index words per popcount chunk
 constexpr uint32_t kTileGroup = 64;     // dense-route tiles whose counts are also kept as one sum
 // A partition keeps, in LDS, 10 bytes per cell (value, meta word, queue slot) and 4 per
@@ -125,6 +126,7 @@ struct tagc_plan_s {
     uint32_t cnt_ranges;                      // word offset of the partition ranges in a rank's cnt buffer
     bool any_nonfast;                         // some non-empty segment is never streamed by scan_spill
     bool static_dense;                        // some segment with k > 0 never takes the candidate route
+    bool emit_wide;                           // chunks hold hundreds of candidates: a wave per super-chunk in count / place
     uint64_t n_real, n_c, K, U_cap, A_cap, m_cap;
     uint32_t P_cap, T_cap;
     tagc::Workspace ws;

@@ -63,7 +63,7 @@ def rank_gradient(b: Bucket, rank: int, device="cpu") -> torch.Tensor:
     """Rank `rank`'s flat gradient buffer for bucket `b` (seed = base + rank)."""
     dev = torch.device(device)
     g = _gen(dev, b.seed + rank + 1000003 * b.bucket_id)
-    out = torch.empty(b.n_elems, dtype=b.torch_dtype, device=dev)
+    out = torch.zeros(b.n_elems, dtype=b.torch_dtype, device=dev)   # (gaps between segments: 0)
     for s in b.segments:
         sig = b.sigma.get(s.name, 1e-3)
         chunk = 1 << 24

@@ -262,13 +262,20 @@ def test_config4_sharded_7b_bucket():
     _check_full_size(b, data, oracle_ranks=(0, 5))
 
 
-@pytest.mark.parametrize("keep_ppm,lf,dense_route", [(10_000, 1500, False), (100_000, 3000, True)])
-def test_config3_heavy_tails_shared_supports(keep_ppm, lf, dense_route):
-    """64 M Student-t entries per rank, half of every rank's support shared with all others;
-    at 10 % kept the plan takes the two-read route."""
-    print("\n[case] config3 at full size keep=%d lf=%d" % (keep_ppm, lf), flush=True)
+@pytest.mark.parametrize("keep_ppm,lf,offset,dense_route",
+                         [(10_000, 1500, 0, False), (100_000, 3000, 0, False),
+                          (100_000, 3000, 3, True)])
+def test_config3_heavy_tails_shared_supports(keep_ppm, lf, offset, dense_route):
+    """64 M Student-t entries per rank, half of every rank's support shared with all others.
+    At 10 % kept a chunk holds hundreds of candidates (count and place with a wave per
+    super-chunk); the same from an offset that is no multiple of a 16-byte vector, which
+    the plan sends down the route that reads the gradient three times."""
+    print("\n[case] config3 at full size keep=%d lf=%d offset=%d" % (keep_ppm, lf, offset),
+          flush=True)
     b = G.config3(0, keep_ppm=keep_ppm, sizing_milli=lf)
     assert b.n_elems == 1 << 26 and b.n_ranks == 8
+    if offset:
+        b.segments = [G.Seg(offset, b.n_elems - offset, keep_ppm, 1, "w")]
     data = [G.config3_rank_gradient(b, r, "cuda") for r in range(b.n_ranks)]
     tb = _check_full_size(b, data, oracle_ranks=(3,))
     assert (tb.rank_counts(0)["dense_segments"] == 1) == dense_route

@@ -386,17 +386,18 @@ def test_ordered_output_over_many_items_per_segment(dtype):
     """The sparsifier's last two kernels order their output through per-item counts (count,
     then place): same pairs, same Index as the oracle on the candidate route (many
     super-chunks per segment, ties at the threshold) and on the dense route (many tiles per
-    segment, ragged and unaligned ones, Table 1's 20 % regime), twice in a row on the same
-    buffers (the counters the kernels keep in the plan's table must be back at zero)."""
+    segment, ragged and unaligned ones, one that keeps two entries in five), twice in a row
+    on the same buffers (the counters the kernels keep in the plan's table must be back at
+    zero)."""
     _announce("ordered output dtype=%d" % dtype)
     segs = [G.Seg(0, (1 << 21) + 13, 10_000, 1, "long_ragged"),
             G.Seg(2_097_176, 5000, 20_000, 1, "short"),
-            G.Seg(2_102_184, (1 << 20), 200_000, 1, "keeps_a_fifth"),
+            G.Seg(2_102_184, (1 << 20), 400_000, 1, "keeps_two_fifths"),
             G.Seg(3_150_763, (1 << 19) + 64, 10_000, 1, "long_unaligned"),
             G.Seg(3_675_120, 3 << 20, 12_500, 1, "long")]
     n = 3_675_120 + (3 << 20)
     b = G.Bucket("ordered", dtype, 2, segs, n, 1500,
-                 {"long_ragged": 1e-3, "short": 1e-2, "keeps_a_fifth": 1e-4,
+                 {"long_ragged": 1e-3, "short": 1e-2, "keeps_two_fifths": 1e-4,
                   "long_unaligned": 3e-3, "long": 1e-3})
     grads = _grads(b)
     ores, tb = run_both(b, grads, seed=6)
@@ -495,20 +496,62 @@ def test_falling_scale_costs_one_fallback_not_one_per_call(dtype):
     assert dense == [0, 1, 0, 0, 0, 0, 0]
 
 
-def test_more_than_64_candidate_route_segments():
+@pytest.mark.parametrize("keep_lo,keep_hi", [(5_000, 30_000), (60_000, 220_000)])
+def test_more_than_64_candidate_route_segments(keep_lo, keep_hi):
     """70 segments that all take the candidate route (the final kernel reads the segment
     tables lane-parallel for up to 64 segments and falls back to a search beyond), with
-    ragged lengths so that super-chunks end inside chunks, and varying keep ratios."""
-    _announce("70 fast segments")
+    ragged lengths so that super-chunks end inside chunks, and varying keep ratios: a few
+    per cent (dozens of candidates per chunk) and Table 1's dense regimes (hundreds: the
+    last two kernels then give a wave to every super-chunk)."""
+    _announce("70 fast segments, keep %d-%d ppm" % (keep_lo, keep_hi))
     rng = np.random.default_rng(5)
     segs, sigma, off = [], {}, 0
     for i in range(70):
         n = (1 << 17) + int(rng.integers(0, 5000))
         name = "s%d" % i
-        segs.append(G.Seg(off, n, int(rng.integers(5_000, 30_000)), 1, name))
+        segs.append(G.Seg(off, n, int(rng.integers(keep_lo, keep_hi)), 1, name))
         sigma[name] = float(10 ** rng.uniform(-4, -2))
         off = (off + n + 7) // 8 * 8
     b = G.Bucket("many", G.BF16, 2, segs, off, 1500, sigma)
     ores, tb = run_both(b, _grads(b), seed=13)
     compare_all(b, ores, tb)
     assert [tb.rank_counts(r)["dense_segments"] for r in range(2)] == [0, 0]
+
+
+@pytest.mark.parametrize("dtype", [G.F32, G.BF16])
+@pytest.mark.parametrize("keep_ppm", [50_000, 100_000, 200_000])
+def test_hundreds_of_candidates_per_chunk(dtype, keep_ppm):
+    """Table 1's dense regimes on the candidate route: a twentieth, a tenth and a fifth of
+    the entries kept, so that a 4 KiB chunk holds hundreds of candidates (slots staged per
+    wave at the lower two ratios, written in place at the highest; count and place with a
+    wave per super-chunk).  Several super-chunks per segment, a ragged tail, one segment
+    of small integers (a tie class at the threshold that spans chunks and super-chunks, so
+    the quota of ties runs out in the middle of a read), one segment that keeps one entry
+    in a hundred among them, one short segment on the dense route; twice on the same
+    buffers, the second time from carried pre-thresholds."""
+    _announce("wide emit dtype=%d keep=%d" % (dtype, keep_ppm))
+    a = (1 << 19) + 4099
+    o1 = (a + 7) // 8 * 8
+    o2 = o1 + (3 << 17)
+    o3 = o2 + 40_000
+    n = o3 + (1 << 18) + 8
+    segs = [G.Seg(0, a, keep_ppm, 1, "ragged"),
+            G.Seg(o1, 3 << 17, keep_ppm, 1, "ints"),
+            G.Seg(o2, 40_000, keep_ppm, 1, "short"),
+            G.Seg(o3, (1 << 18) + 8, 10_000, 1, "sparse")]
+    b = G.Bucket("wide", dtype, 2, segs, n, 1500,
+                 {"ragged": 1e-3, "ints": 1.0, "short": 1e-3, "sparse": 2e-3})
+    rng = np.random.default_rng(keep_ppm + dtype)
+    td = torch.float32 if dtype == G.F32 else torch.bfloat16
+    grads = []
+    for g in _grads(b):
+        v = g.to(torch.float32).numpy().copy()
+        v[o1:o2] = rng.integers(-40, 41, o2 - o1).astype(np.float32)
+        grads.append(torch.from_numpy(v).to(td))
+    ores, tb = run_both(b, grads, seed=17)
+    compare_all(b, ores, tb, mixed_ceiling=0.1)    # (unit-scale integers beside 1e-3 values)
+    assert [tb.rank_counts(r)["dense_segments"] for r in range(2)] == [1, 1]
+    tb.run([g.cuda() for g in grads])
+    torch.cuda.synchronize()
+    compare_all(b, ores, tb, mixed_ceiling=0.1)
+    assert [tb.rank_counts(r)["dense_segments"] for r in range(2)] == [1, 1]
