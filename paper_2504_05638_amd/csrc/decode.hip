@@ -142,6 +142,53 @@ __device__ inline void queue_push3(bool p0, uint32_t v0, bool p1, uint32_t v1, b
 }
 
 
+// One entry of a round's queue: cell q, which had degree 1 when it was queued.  If it still
+// has, and its unknown has not been reached through another cell already, the unknown's
+// value is read there and taken out of its three cells; cells that thereby reach degree 1
+// are queued for the next round.  Called by any subset of a wave's lanes.
+__device__ __forceinline__ void resolve_entry(uint32_t q, unsigned long long *cell,
+                                              uint32_t *claimed, uint32_t *idx,
+                                              uint32_t *any_now, uint32_t *n_next,
+                                              uint16_t *next_queue, uint32_t m_sub,
+                                              uint32_t sw0, uint32_t sw1, uint32_t sw2)
+{
+    const unsigned long long oq = cell[q];
+    const uint32_t m = uint32_t(oq >> 32);
+    if ((m & kDegMask) != 1u) return;  // emptied since it was queued
+    const uint32_t u = m >> 15, bit = 1u << (u & 31);
+    if (atomicOr(&claimed[u >> 5], bit) & bit) return;  // reached through another cell
+    *any_now = 1;
+    const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
+    const uint32_t c[3] = {cl.c[0], cl.c[1], cl.c[2]};
+    const uint32_t neg = cl.neg;
+    const uint32_t j = c[0] == q ? 0u : (c[1] == q ? 1u : 2u);
+    const float cv = __uint_as_float(uint32_t(oq));
+    const float x = ((neg >> j) & 1u) ? -cv : cv;
+    idx[u] = __float_as_uint(x);  // the c-index has done its job: keep the value there
+    const unsigned long long dec = (unsigned long long)((u << 15) + 1u) << 32;
+    unsigned long long o[3], r[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) o[k] = uint32_t(k) == j ? oq : cell[c[k]];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
+        r[k] = atomicCAS(&cell[c[k]], o[k],
+                         ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
+    }
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        while (r[k] != o[k]) {  // another unknown of the round got there first: redo
+            o[k] = r[k];
+            const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
+            r[k] = atomicCAS(&cell[c[k]], o[k],
+                             ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
+        }
+    }
+    queue_push3((uint32_t(o[0] >> 32) & kDegMask) == 2u, c[0],
+                (uint32_t(o[1] >> 32) & kDegMask) == 2u, c[1],
+                (uint32_t(o[2] >> 32) & kDegMask) == 2u, c[2], n_next, next_queue);
+}
+
 // Peels sketch partitions: unknowns rho0 .. rho0+Pa-1 of idx_out, cells a*3*m_sub ...
 // An LDS cell is 64 bits: value bits in the low half, meta word (rank-sum << 15 | degree)
 // in the high half, so one compare-and-swap subtracts a value and removes an unknown.
@@ -261,45 +308,9 @@ peel_kernel(const float *__restrict__ sketch, const uint32_t *__restrict__ heade
             s_n[idle] = 0;     // read in round r-1, added to again in round r+1
             s_any[nxt] = 0;    // read in round r-1 (as its idle slot), set again in round r+1
         }
-        uint16_t *next_queue = queue + tail;
-        for (uint32_t e = head + tid; e < tail; e += kDecodeThreads) {
-            const uint32_t q = queue[e];
-            const unsigned long long oq = cell[q];
-            const uint32_t m = uint32_t(oq >> 32);
-            if ((m & kDegMask) != 1u) continue;  // emptied since it was queued
-            const uint32_t u = m >> 15, bit = 1u << (u & 31);
-            if (atomicOr(&claimed[u >> 5], bit) & bit) continue;  // reached through another cell
-            s_any[cur] = 1;
-            const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
-            const uint32_t c[3] = {cl.c[0], cl.c[1], cl.c[2]};
-            const uint32_t neg = cl.neg;
-            const uint32_t j = c[0] == q ? 0u : (c[1] == q ? 1u : 2u);
-            const float cv = __uint_as_float(uint32_t(oq));
-            const float x = ((neg >> j) & 1u) ? -cv : cv;
-            idx[u] = __float_as_uint(x);  // the c-index has done its job: keep the value there
-            const unsigned long long dec = (unsigned long long)((u << 15) + 1u) << 32;
-            unsigned long long o[3], r[3];
-#pragma unroll
-            for (int k = 0; k < 3; ++k) o[k] = uint32_t(k) == j ? oq : cell[c[k]];
-#pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
-                r[k] = atomicCAS(&cell[c[k]], o[k],
-                                 ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
-            }
-#pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                while (r[k] != o[k]) {  // another unknown of the round got there first: redo
-                    o[k] = r[k];
-                    const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
-                    r[k] = atomicCAS(&cell[c[k]], o[k],
-                                     ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
-                }
-            }
-            queue_push3((uint32_t(o[0] >> 32) & kDegMask) == 2u, c[0],
-                        (uint32_t(o[1] >> 32) & kDegMask) == 2u, c[1],
-                        (uint32_t(o[2] >> 32) & kDegMask) == 2u, c[2], &s_n[nxt], next_queue);
-        }
+        for (uint32_t e = head + tid; e < tail; e += kDecodeThreads)
+            resolve_entry(queue[e], cell, claimed, idx, &s_any[cur], &s_n[nxt], queue + tail,
+                          m_sub, sw0, sw1, sw2);
         head = tail;
     }
     PHASE_MARK(2);
@@ -536,45 +547,9 @@ sum_peel_kernel(const RankPtrs rp, uint32_t n_in, const uint32_t *__restrict__ h
                 s_n[idle] = 0;
                 s_any[nxt] = 0;
             }
-            uint16_t *next_queue = queue + tail;
-            for (uint32_t e = head + tid; e < tail; e += kPeelThreads) {
-                const uint32_t q = queue[e];
-                const unsigned long long oq = cell[q];
-                const uint32_t m = uint32_t(oq >> 32);
-                if ((m & kDegMask) != 1u) continue;
-                const uint32_t u = m >> 15, bit = 1u << (u & 31);
-                if (atomicOr(&claimed[u >> 5], bit) & bit) continue;
-                s_any[cur] = 1;
-                const Cells cl = cells_of(idx[u], m_sub, sw0, sw1, sw2);
-                const uint32_t c[3] = {cl.c[0], cl.c[1], cl.c[2]};
-                const uint32_t neg = cl.neg;
-                const uint32_t j = c[0] == q ? 0u : (c[1] == q ? 1u : 2u);
-                const float cv = __uint_as_float(uint32_t(oq));
-                const float x = ((neg >> j) & 1u) ? -cv : cv;
-                idx[u] = __float_as_uint(x);
-                const unsigned long long dec = (unsigned long long)((u << 15) + 1u) << 32;
-                unsigned long long o[3], rr[3];
-#pragma unroll
-                for (int k = 0; k < 3; ++k) o[k] = uint32_t(k) == j ? oq : cell[c[k]];
-#pragma unroll
-                for (int k = 0; k < 3; ++k) {
-                    const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
-                    rr[k] = atomicCAS(&cell[c[k]], o[k],
-                                      ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
-                }
-#pragma unroll
-                for (int k = 0; k < 3; ++k) {
-                    while (rr[k] != o[k]) {
-                        o[k] = rr[k];
-                        const float nv = __uint_as_float(uint32_t(o[k])) + (((neg >> k) & 1u) ? x : -x);
-                        rr[k] = atomicCAS(&cell[c[k]], o[k],
-                                          ((o[k] - dec) & 0xFFFFFFFF00000000ull) | __float_as_uint(nv));
-                    }
-                }
-                queue_push3((uint32_t(o[0] >> 32) & kDegMask) == 2u, c[0],
-                            (uint32_t(o[1] >> 32) & kDegMask) == 2u, c[1],
-                            (uint32_t(o[2] >> 32) & kDegMask) == 2u, c[2], &s_n[nxt], next_queue);
-            }
+            for (uint32_t e = head + tid; e < tail; e += kPeelThreads)
+                resolve_entry(queue[e], cell, claimed, idx, &s_any[cur], &s_n[nxt],
+                              queue + tail, m_sub, sw0, sw1, sw2);
             head = tail;
         }
 
