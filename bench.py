@@ -43,6 +43,18 @@ def stages_of(fused):
     return st
 
 
+def stage_phases(fused):
+    """The calls (--only-phases names) that make up each stage."""
+    st = {"S1+S2 sparsify+index": ["index"], "S3a index OR": ["agg_index"],
+          "S2' encode": ["sketch"]}
+    if fused:
+        st[FUSED_STAGE] = ["decode"]
+    else:
+        st["S3b sketch sum"] = ["agg_sketch"]
+        st["S4 decode"] = ["decode"]
+    return st
+
+
 def profile_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` as the tracked rocprofv3 counter summary of this
     workload has them (profiles/<workload>_all_kernels.txt, the table written from the
@@ -364,8 +376,8 @@ def main():
     if phases:
         args.no_profile_pass = True
 
-    def run_subset(tb, grads, s=None):
-        """The calls of one bucket that --only-phases names."""
+    def run_subset(tb, grads, s=None, phases=phases):
+        """The calls of one bucket that --only-phases (or `phases`) names."""
         if "index" in phases:
             for r in range(N):
                 tb.compress_index(r, grads[r], s)
@@ -536,6 +548,35 @@ def main():
                                             for k, v in sorted(prof.items(),
                                                                key=lambda kv: -kv[1][0])}}
 
+    # ---- every stage on its own in the launch configuration of the timed region (graphs
+    # replayed, `lanes` buckets in flight): the calls of that stage only, for every bucket, on
+    # the buffers the complete steps left.  The events pass above times kernels one bucket at
+    # a time, which leaves every launch's ramp-up and tail exposed; this is what a stage costs
+    # when other buckets' launches of the same kind fill them.
+    stages_in_flight = {}
+    if stages and args.graph and not phases:
+        k_steps = min(args.steps, 10)
+        for sname, which in stage_phases(fused).items():
+            gs = []
+            for i in range(n_b):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=capture_stream):
+                    run_subset(tbs[i], data[i % pool], phases=which)
+                gs.append(g)
+            torch.cuda.synchronize()
+            for timed in (False, True):   # one untimed pass first
+                t0 = time.perf_counter()
+                for _ in range(k_steps if timed else 1):
+                    for i in range(n_b):
+                        with torch.cuda.stream(streams[i % lanes]):
+                            gs[i].replay()
+                torch.cuda.synchronize()
+                ms = 1e3 * (time.perf_counter() - t0) / k_steps
+            stages_in_flight[sname] = {
+                "ms_per_step": round(ms, 4),
+                "hbm_frac": round(balg[sname] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del gs
+
     out = {
         "metric": "gradient GB/s compressed+aggregated+decoded on 1 MI355X; % of HBM peak",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -564,6 +605,7 @@ def main():
             balg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "alg_bytes_per_step": balg_total,
         "stages": stages,
+        "stages_in_flight": stages_in_flight or None,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
