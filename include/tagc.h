@@ -180,7 +180,7 @@ enum {
     TAGC_CNT_NONFINITE = 1, /* inputs with all-ones exponent seen (result then
                                unspecified but memory-safe)                      */
     TAGC_CNT_FLAGS = 2,     /* TAGC_FLAG_* bits                                  */
-    TAGC_CNT_DENSE = 3,     /* segments that took the two-read route (diagnostic) */
+    TAGC_CNT_DENSE = 3,     /* segments that took the dense route (diagnostic)    */
     TAGC_CNT_RESERVED = 4,  /* 0                                                 */
     TAGC_CNT_SEG0 = 5       /* [5 + l] = pairs of compressed segment l           */
 };

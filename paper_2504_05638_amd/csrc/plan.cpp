@@ -52,10 +52,12 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
     p->any_nonfast = false;
 
     // Candidate route: slots per chunk for 1.3 x the kept fraction plus six standard
-    // deviations.  Its second pass costs in proportion to the candidates; measured on
-    // 7B-shaped buckets it beats reading the gradient twice up to about 3 % kept (4 % of a
-    // chunk expected as candidates), beyond that (Table 1's 2x and 4x regimes) the dense
-    // route is several times faster.  Returns the slots a chunk needs, 0 = dense route.
+    // deviations.  What follows the scan costs in proportion to the candidates; with the
+    // form of count and place that suits the number of candidates per chunk (emit_body for
+    // dozens, emit_wide_body for hundreds) it beats the dense route's three reads of the
+    // gradient up to Table 1's 2x regime (a fifth kept: 26 % of a chunk expected as
+    // candidates; measured on 7B-shaped buckets).  Returns the slots a chunk needs, 0 = dense
+    // route.
     auto fast_slots = [&](const tagc_segment &s) -> uint32_t {
         const uint64_t k = uint64_t((unsigned __int128)s.length * s.keep_ppm / 1000000u);
         if (s.offset % p->vec_elems || s.length < kFastMinElems || k < kFastMinKeep) return 0;

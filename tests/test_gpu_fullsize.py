@@ -2,9 +2,9 @@
 block 0: 202 M bf16 entries x 16 ranks, load factor 1.5, default partitions, dense output),
 run exactly as bench.py runs it; one bucket of the sharded 7B workload (config4); the 64 M
 heavy-tailed bucket with half-shared supports (config3) at two of its (keep, load factor)
-points, one of which takes the two-read route.  The oracle cannot redo all of it in test
-time, so: sampled (rank, segment)
-pairs go through the oracle's sparsifier bit for bit; one rank's whole sketch and a slice of
+points (a hundredth kept: dozens of candidates per chunk; a tenth: hundreds) and once from an
+unaligned offset, which takes the dense route.  The oracle cannot redo all of it in test
+time, so: sampled (rank, segment) pairs go through the oracle's sparsifier bit for bit; one rank's whole sketch and a slice of
 the summed one go through the oracle's encode and sum; the cheap stages (Index merge, layout,
 bounds, salts) are redone in full; everything else is checked, for every rank, through what
 must hold at any size -- counts, order, Index <-> pairs, values against the gradient, the
