@@ -279,6 +279,69 @@ __device__ inline bool select_bins(const uint32_t *hist, uint32_t need, uint32_t
     return total >= need;
 }
 
+// The same for a workgroup of NT < 1024 threads (32768 bins: thread t owns the 32768 / NT
+// consecutive bins from t * 32768 / NT), without the bins in registers: every thread adds up
+// its bins as they stream by, and the one thread whose bins hold the answer reads them a
+// second time from the top down.  For kernels that are launched on the off-chance and nearly
+// always leave at once: what such a launch costs on a busy device is finding a compute unit
+// with room for its workgroup, and four waves of few registers fit where sixteen do not.
+template <uint32_t NT>
+__device__ inline bool select_bins_streamed(const uint32_t *hist, uint32_t need, uint32_t *bin_out,
+                                            uint32_t *above_out, uint32_t *at_out,
+                                            uint32_t *total_out, uint32_t *smem /* >= 24 words */,
+                                            uint32_t need2, uint32_t *bin2_out,
+                                            uint32_t tail_from, uint32_t *tail_out)
+{
+    constexpr uint32_t BPT = kBins1 / NT;
+    static_assert(BPT % 4 == 0 && BPT * NT == kBins1, "whole 16-byte groups of bins per thread");
+    const uint32_t t = threadIdx.x;
+    const uint4 *hv = reinterpret_cast<const uint4 *>(hist + uint64_t(t) * BPT);
+    uint32_t s = 0;
+    for (uint32_t i = 0; i < BPT / 4; ++i) {
+        const uint4 v = hv[i];
+        s += v.x + v.y + v.z + v.w;
+    }
+    uint32_t total;
+    const uint32_t prefix = block_excl_scan<uint32_t, NT / 64>(s, &total, smem);
+    const uint32_t suffix = total - prefix;  // bins of this thread and all higher ones
+    if (t == 0) {
+        smem[19] = 0xFFFFFFFFu;
+        smem[20] = 0;
+    }
+    __syncthreads();
+    if (tail_out && t * BPT >= tail_from && s) atomicAdd(&smem[20], s);
+    // largest bin of this thread with at least `want` entries at or above it
+    auto locate = [&](uint32_t want, uint32_t *bin, uint32_t *above, uint32_t *at) {
+        uint32_t acc = suffix - s;
+        for (int i = int(BPT / 4) - 1; i >= 0; --i) {
+            const uint4 v = hv[i];
+            const uint32_t c[4] = {v.x, v.y, v.z, v.w};
+            for (int e = 3; e >= 0; --e) {
+                if (acc + c[e] >= want) {
+                    *bin = t * BPT + 4 * uint32_t(i) + uint32_t(e);
+                    if (above) *above = acc;
+                    if (at) *at = c[e];
+                    return;
+                }
+                acc += c[e];
+            }
+        }
+    };
+    if (total >= need && suffix >= need && suffix - s < need)
+        locate(need, &smem[16], &smem[17], &smem[18]);
+    if (need2 && total >= need2 && suffix >= need2 && suffix - s < need2)
+        locate(need2, &smem[19], nullptr, nullptr);
+    __syncthreads();
+    *bin_out = smem[16];
+    *above_out = smem[17];
+    *at_out = smem[18];
+    *total_out = total;
+    if (bin2_out) *bin2_out = smem[19];
+    if (tail_out) *tail_out = smem[20];
+    __syncthreads();
+    return total >= need;
+}
+
 // ---------------------------------------------------------------- prepare
 
 // First call after the table's upload (and plans without a scan to clear for them).  One
@@ -945,10 +1008,10 @@ __device__ inline void hist_elem(uint32_t f32bits, const HistWin<WBINS> &hw)
 }
 
 // Threshold bin of one dense-route segment from the 32768-bin histogram of all its entries,
-// by a whole workgroup of kHistThreads threads.  Also leaves the pre-threshold for the next
+// by a whole workgroup of NT threads.  Also leaves the pre-threshold for the next
 // call on this plan: the bin above which about 1.3 k entries lie (what the slots per chunk
 // are sized for).
-template <int DTYPE>
+template <int DTYPE, uint32_t NT>
 __device__ inline void select_dense(uint32_t l, const SegDev &sd, const uint32_t *hist,
                                     SelDev *sel, const TableState ts,
                                     uint32_t *smem /* >= 32 words */)
@@ -958,7 +1021,10 @@ __device__ inline void select_dense(uint32_t l, const SegDev &sd, const uint32_t
     const bool fast = (sd.flags & kSegFast) != 0;
     const uint32_t want = fast ? uint32_t(1.3f * float(sd.k)) + 1u : 0u;
     // nf: inputs with an all-ones exponent fall into bins >= 0x7F80
-    const bool found = select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem, want, &bin2,
+    const bool found =
+        NT == kHistThreads
+            ? select_bins<32>(h, sd.k, &bin, &above, &at, &total, smem, want, &bin2, 0x7F80u, &nf)
+            : select_bins_streamed<NT>(h, sd.k, &bin, &above, &at, &total, smem, want, &bin2,
                                        0x7F80u, &nf);
     if (threadIdx.x != 0) return;
     if (fast) {
@@ -1002,10 +1068,14 @@ __device__ inline void select_dense(uint32_t l, const SegDev &sd, const uint32_t
 // one is that free -- just to find that there is nothing to do.  Such plans use WBINS = 4096
 // (16 KiB): the 32 octaves around the segment's last pre-threshold, where all but a
 // vanishing part of a gradient lies; the rest is added to the global histogram directly.
+// And workgroups of 256 threads, four per CU: with buckets in flight on other streams a
+// 1024-thread workgroup found room 7 us later on average, per rank and bucket, 3.3 ms per
+// step of the 7B workload -- for a launch that reads two table rows and leaves.
 constexpr uint32_t kHistWindow = 4096;
+constexpr uint32_t kHistNetThreads = 256;
 
-template <int DTYPE, uint32_t WBINS>
-__global__ void __launch_bounds__(kHistThreads)
+template <int DTYPE, uint32_t WBINS, uint32_t NT>
+__global__ void __launch_bounds__(NT)
 hist1_kernel(const char *__restrict__ grad, uint32_t *table, SelDev *sel, uint32_t *hist)
 {
     extern __shared__ uint32_t h[];
@@ -1018,7 +1088,7 @@ hist1_kernel(const char *__restrict__ grad, uint32_t *table, SelDev *sel, uint32
     if (!any_dense_route(segs, sel, L)) return;
     const TableState ts = table_state(table, L);
     const uint32_t tid = threadIdx.x;
-    for (uint32_t i = tid; i < WBINS; i += kHistThreads) h[i] = 0;
+    for (uint32_t i = tid; i < WBINS; i += NT) h[i] = 0;
     __syncthreads();
     for (uint32_t l = 0; l < L; ++l) {
         const SegDev sd = segs[l];
@@ -1034,8 +1104,8 @@ hist1_kernel(const char *__restrict__ grad, uint32_t *table, SelDev *sel, uint32
         if (sd.flags & kSegAligned) {
             const uint4 *vp = reinterpret_cast<const uint4 *>(base);
             const uint64_t nvec = sd.n / VEC;
-            const uint64_t stride = uint64_t(gridDim.x) * kHistThreads;
-            uint64_t v = uint64_t(blockIdx.x) * kHistThreads + tid;
+            const uint64_t stride = uint64_t(gridDim.x) * NT;
+            uint64_t v = uint64_t(blockIdx.x) * NT + tid;
             for (; v + 3 * stride < nvec; v += 4 * stride) {
                 const uint4 a = ld_stream(vp + v), b = ld_stream(vp + v + stride),
                             c = ld_stream(vp + v + 2 * stride), d = ld_stream(vp + v + 3 * stride);
@@ -1050,12 +1120,12 @@ hist1_kernel(const char *__restrict__ grad, uint32_t *table, SelDev *sel, uint32
                 if (i < sd.n) hist_elem(load_elem_bits(base, i, DTYPE), hw);
             }
         } else {
-            for (uint64_t i = uint64_t(blockIdx.x) * kHistThreads + tid; i < sd.n;
-                 i += uint64_t(gridDim.x) * kHistThreads)
+            for (uint64_t i = uint64_t(blockIdx.x) * NT + tid; i < sd.n;
+                 i += uint64_t(gridDim.x) * NT)
                 hist_elem(load_elem_bits(base, i, DTYPE), hw);
         }
         __syncthreads();
-        for (uint32_t i = tid; i < WBINS; i += kHistThreads) {
+        for (uint32_t i = tid; i < WBINS; i += NT) {
             uint32_t c = h[i];
             if (c) {
                 atomicAdd(&gh[hw.base + i], c);
@@ -1073,7 +1143,7 @@ hist1_kernel(const char *__restrict__ grad, uint32_t *table, SelDev *sel, uint32
         if (s_last) {  // uniform
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             if (tid == 0) ts.arrive_d[l] = 0;  // for the next call
-            select_dense<DTYPE>(l, sd, hist, sel, ts, s_sel);
+            select_dense<DTYPE, NT>(l, sd, hist, sel, ts, s_sel);
         }
         __syncthreads();
     }
@@ -2029,7 +2099,7 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         return hip_ok(hipGetLastError());
     }
     if (allow_lds(prepare_kernel<DTYPE>, lds_hist, &a_prepare) ||
-        allow_lds(hist1_kernel<DTYPE, kBins1>, lds_hist, &a_hist))
+        allow_lds(hist1_kernel<DTYPE, kBins1, kHistThreads>, lds_hist, &a_hist))
         return TAGC_EHIP;
     if (acc && p->any_nonfast) {
         ProfileScope ps("accumulate", s);
@@ -2058,10 +2128,12 @@ int launch_sparsify_t(const tagc_plan_t *p, const void *grad, const tagc_rank_bu
         // scan's selection sent it there)
         ProfileScope ps("hist1", s);
         if (p->static_dense)
-            hist1_kernel<DTYPE, kBins1><<<cus, kHistThreads, lds_hist, s>>>(src, table, sel, hist1d);
-        else
-            hist1_kernel<DTYPE, kHistWindow><<<cus, kHistThreads, kHistWindow * sizeof(uint32_t), s>>>(
+            hist1_kernel<DTYPE, kBins1, kHistThreads><<<cus, kHistThreads, lds_hist, s>>>(
                 src, table, sel, hist1d);
+        else
+            hist1_kernel<DTYPE, kHistWindow, kHistNetThreads>
+                <<<cus * (kHistThreads / kHistNetThreads), kHistNetThreads,
+                   kHistWindow * sizeof(uint32_t), s>>>(src, table, sel, hist1d);
     }
     if (DTYPE == kF32) {
         if (p->total_sc) {
