@@ -122,7 +122,13 @@ extern "C" int tagc_plan(const tagc_config *cfg, const tagc_segment *segs, uint3
         delete p;
         return TAGC_ESIZE;
     }
-    p->emit_wide = p->cand_cap >= kWideEmitCap;
+    // count / place give a wave to every super-chunk where chunks hold hundreds of
+    // candidates, and in large buckets whatever they hold: that form needs next to no LDS, so
+    // its workgroups run beside another bucket's scan, which is what large buckets are timed
+    // with (7B-shaped buckets, 12 in flight: 4 % of a step; one bucket at a time it is 3 us
+    // per rank slower than four threads per chunk, which small buckets, bound by the time
+    // a launch takes, would notice)
+    p->emit_wide = p->cand_cap >= kWideEmitCap || scs >= kWideEmitSuperChunks;
     p->n_real = n_real;
     p->n_c = c;
     p->K = K;

@@ -1547,19 +1547,20 @@ __device__ __forceinline__ void emit_body(uint32_t bid, uint32_t nb,
     }
 }
 
-// ------------------------------------------- emit, hundreds of candidates per chunk
+// ------------------------------------------------- emit, a wave per super-chunk
 
 // emit_body gives a chunk's slots to four threads, which suits the few dozen candidates a
-// chunk holds when one entry in a hundred is kept.  Where a tenth or a fifth is kept (the 4x
-// and 2x regimes of Table 1) a chunk holds hundreds.  Here a wave takes a whole super-chunk
-// and reads its chunks' slots 64 at a time, in position order, kWideBatch such reads in
+// chunk holds when one entry in a hundred is kept, and stages an item's survivors in LDS.
+// Where a tenth or a fifth is kept (the 4x and 2x regimes of Table 1) a chunk holds
+// hundreds; and the LDS (23 KiB per workgroup in place) keeps all but two of its workgroups
+// off a compute unit on which another bucket's scan is running, which is how large buckets
+// are usually processed.  Here a wave takes a whole super-chunk
+// and reads its chunks' slots 64 at a time, in position order, BATCH such reads in
 // flight.  The survivors among the 64 slots of one read are neighbours in the output, so
 // they are stored as they are found; the Index words of a chunk are collected in LDS and
 // leave when its last slots are through.  Same inputs, same outputs, same counts per
 // super-chunk as emit_body.
-constexpr uint32_t kWideBatch = 16;
-
-template <int DTYPE, bool PLACE>
+template <int DTYPE, bool PLACE, uint32_t BATCH>
 __device__ __forceinline__ void emit_wide_body(uint32_t bid, uint32_t nb,
                                  const uint32_t *__restrict__ table,
                                  const SelDev *__restrict__ sel,
@@ -1636,42 +1637,31 @@ __device__ __forceinline__ void emit_wide_body(uint32_t bid, uint32_t nb,
                 first_l = min(info.y, uint32_t(n_slots_total) - CAP);
             }
         }
-        // reads of 64 slots ("groups"), numbered through the super-chunk
+        // Reads of 64 slots ("groups"), numbered through the super-chunk.  Where no chunk
+        // needs a second read (a few dozen candidates per chunk) group g is simply chunk g.
         const uint32_t ngr_l = (cnt_l + 63u) >> 6;
         const uint32_t gend_l = wave_incl_scan<uint32_t>(ngr_l);  // (lanes from NCH on: the total)
-        const uint32_t n_groups = __builtin_amdgcn_readlane(gend_l, 63);
-
-        uint32_t gb = 0, eb = 0;  // entries above / at the threshold before the current slot
-        if (PLACE) {
-            // prefix over the segment's earlier super-chunks, whose counts are all there
-            uint64_t sum = 0;
-            if (live)
-                for (uint32_t j = sc_first + lane; j < sc; j += 64) sum += sc_cnt[j];
-            sum = wave_sum<uint64_t>(sum);
-            gb = uint32_t(sum >> 31);
-            eb = uint32_t(sum & 0x7FFFFFFFu);
-            // chunks of the segment without a candidate: their Index words are zero
-            for (uint64_t em = __ballot(inseg_l && cnt_l == 0); em; em &= em - 1) {
-                const uint32_t ch = uint32_t(__builtin_ctzll(em));
-                const uint32_t rel0 = sc_rel0 + ch * CHUNK + lane * 32;
-                if (lane < CH_WORDS && rel0 < n_seg) bitmap[(c_off + rel0) >> 5] = 0;
-            }
-        }
-
-        for (uint32_t b0 = 0; b0 < n_groups; b0 += kWideBatch) {
-            // where group g lies (all wave-uniform): chunk, first slot, slots of the chunk
-            auto locate = [&](uint32_t g, uint32_t &ch, uint32_t &c, uint32_t &s0,
-                              uint32_t &first) {
+        const bool one_each = __ballot(ngr_l > 1u) == 0;
+        const uint32_t n_groups = one_each ? NCH : __builtin_amdgcn_readlane(gend_l, 63);
+        const uint32_t ins_l = inseg_l ? 1u : 0u;
+        // where group g lies (all wave-uniform): chunk, first slot, slots of the chunk
+        auto locate = [&](uint32_t g, uint32_t &ch, uint32_t &c, uint32_t &s0, uint32_t &first) {
+            if (one_each) {
+                ch = g;
+                s0 = 0;
+            } else {
                 ch = uint32_t(__popcll(__ballot(gend_l <= g)));  // chunks that end before g
-                c = __builtin_amdgcn_readlane(cnt_l, ch);
-                first = __builtin_amdgcn_readlane(first_l, ch);
                 const uint32_t gbeg = __builtin_amdgcn_readlane(gend_l, ch) -
                                       __builtin_amdgcn_readlane(ngr_l, ch);
                 s0 = (g - gbeg) * 64;
-            };
-            uint32_t v[kWideBatch], vp[kWideBatch];
+            }
+            c = __builtin_amdgcn_readlane(cnt_l, ch);
+            first = __builtin_amdgcn_readlane(first_l, ch);
+        };
+        uint32_t v[BATCH], vp[BATCH];
+        auto request = [&](uint32_t b0) {
 #pragma unroll
-            for (uint32_t j = 0; j < kWideBatch; ++j) {
+            for (uint32_t j = 0; j < BATCH; ++j) {
                 v[j] = vp[j] = 0;
                 if (b0 + j < n_groups) {
                     uint32_t ch, c, s0, first;
@@ -1682,8 +1672,32 @@ __device__ __forceinline__ void emit_wide_body(uint32_t bid, uint32_t nb,
                     }
                 }
             }
+        };
+        request(0);  // (on their way while the prefix below is added up)
+
+        uint32_t gb = 0, eb = 0;  // entries above / at the threshold before the current slot
+        if (PLACE) {
+            // prefix over the segment's earlier super-chunks, whose counts are all there
+            uint64_t sum = 0;
+            if (live)
+                for (uint32_t j = sc_first + lane; j < sc; j += 64) sum += sc_cnt[j];
+            sum = wave_sum<uint64_t>(sum);
+            gb = uint32_t(sum >> 31);
+            eb = uint32_t(sum & 0x7FFFFFFFu);
+            // chunks of the segment without a candidate have no group of their own unless
+            // group = chunk: their Index words are zero
+            if (!one_each) {
+                for (uint64_t em = __ballot(inseg_l && cnt_l == 0); em; em &= em - 1) {
+                    const uint32_t ch = uint32_t(__builtin_ctzll(em));
+                    const uint32_t rel0 = sc_rel0 + ch * CHUNK + lane * 32;
+                    if (lane < CH_WORDS && rel0 < n_seg) bitmap[(c_off + rel0) >> 5] = 0;
+                }
+            }
+        }
+
+        for (uint32_t b0 = 0; b0 < n_groups;) {
 #pragma unroll
-            for (uint32_t j = 0; j < kWideBatch; ++j) {
+            for (uint32_t j = 0; j < BATCH; ++j) {
                 if (b0 + j >= n_groups) continue;
                 uint32_t ch, c, s0, first;
                 locate(b0 + j, ch, c, s0, first);
@@ -1705,7 +1719,8 @@ __device__ __forceinline__ void emit_wide_body(uint32_t bid, uint32_t nb,
                         val_out[seg_base + pos] = __uint_as_float(vbits);
                         atomicOr(&wbits[wave][rel >> 5], 1u << (rel & 31));
                     }
-                    if (s0 + 64 >= c) {  // the chunk's last slots: its Index words leave
+                    // the chunk's last slots: its Index words leave
+                    if (s0 + 64 >= c && __builtin_amdgcn_readlane(ins_l, ch)) {
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -1722,6 +1737,8 @@ __device__ __forceinline__ void emit_wide_body(uint32_t bid, uint32_t nb,
                 gb += uint32_t(__popcll(bgt));
                 eb += uint32_t(__popcll(beq));
             }
+            b0 += BATCH;
+            if (b0 < n_groups) request(b0);
         }
         if (!PLACE && lane == 0) sc_cnt[sc] = (uint64_t(gb) << 31) | uint64_t(eb);
     }
@@ -1940,7 +1957,7 @@ count_kernel(uint32_t n_emit, const char *grad, const uint32_t *__restrict__ tab
 {
     if (blockIdx.x < n_emit) {
         if (WIDE)
-            emit_wide_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
+            emit_wide_body<DTYPE, false, 32>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
                                          n_slots_total, CAP, sc_cnt, nullptr, nullptr, nullptr);
         else
             emit_body<DTYPE, false>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
@@ -1967,7 +1984,7 @@ place_kernel(uint32_t n_emit, const char *grad, uint32_t *table,
     }
     if (blockIdx.x < n_emit) {
         if (WIDE)
-            emit_wide_body<DTYPE, true>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
+            emit_wide_body<DTYPE, true, 16>(blockIdx.x, n_emit, table, sel, cand, chunk_info,
                                         n_slots_total, CAP, sc_cnt, idx_out, val_out, bitmap);
         else
             emit_body<DTYPE, true>(blockIdx.x, n_emit, table, sel, cand, chunk_info,

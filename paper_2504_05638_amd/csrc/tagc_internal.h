@@ -25,6 +25,7 @@ constexpr uint32_t kSampleVectors = 4096;     // 16-byte vectors sampled per seg
 constexpr uint32_t kFastMinElems = 1u << 17;  // shorter segments take the dense path
 constexpr uint32_t kFastMinKeep = 64;
 constexpr uint32_t kWideEmitCap = 192;  // candidate slots per chunk from which count / place give a wave to a super-chunk
+constexpr uint32_t kWideEmitSuperChunks = 2048;  // ... and super-chunks per bucket from which they do so anyway
 constexpr double kFastMaxCandFrac = 0.30;  // expected candidates per element beyond which the dense path is planned
 constexpr uint32_t kChunkWords = 1024;  // Index words per popcount chunk
 constexpr uint32_t kTileGroup = 64;     // dense-route tiles whose counts are also kept as one sum

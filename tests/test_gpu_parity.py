@@ -526,27 +526,34 @@ def test_hundreds_of_candidates_per_chunk(dtype, keep_ppm):
     wave at the lower two ratios, written in place at the highest; count and place with a
     wave per super-chunk).  Several super-chunks per segment, a ragged tail, one segment
     of small integers (a tie class at the threshold that spans chunks and super-chunks, so
-    the quota of ties runs out in the middle of a read), one segment that keeps one entry
-    in a hundred among them, one short segment on the dense route; twice on the same
+    the quota of ties runs out in the middle of a read), two segments that keep one entry
+    in a hundred among them (a few dozen candidates per chunk, one read per chunk; one of
+    them small integers again), one short segment on the dense route; twice on the same
     buffers, the second time from carried pre-thresholds."""
     _announce("wide emit dtype=%d keep=%d" % (dtype, keep_ppm))
     a = (1 << 19) + 4099
     o1 = (a + 7) // 8 * 8
     o2 = o1 + (3 << 17)
     o3 = o2 + 40_000
-    n = o3 + (1 << 18) + 8
+    o4 = o3 + (1 << 18) + 8
+    n = o4 + (1 << 18) + 24
     segs = [G.Seg(0, a, keep_ppm, 1, "ragged"),
             G.Seg(o1, 3 << 17, keep_ppm, 1, "ints"),
             G.Seg(o2, 40_000, keep_ppm, 1, "short"),
-            G.Seg(o3, (1 << 18) + 8, 10_000, 1, "sparse")]
+            G.Seg(o3, (1 << 18) + 8, 10_000, 1, "sparse"),
+            G.Seg(o4, (1 << 18) + 24, 10_000, 1, "sparse_ints")]
     b = G.Bucket("wide", dtype, 2, segs, n, 1500,
-                 {"ragged": 1e-3, "ints": 1.0, "short": 1e-3, "sparse": 2e-3})
+                 {"ragged": 1e-3, "ints": 1.0, "short": 1e-3, "sparse": 2e-3,
+                  "sparse_ints": 1.0})
     rng = np.random.default_rng(keep_ppm + dtype)
     td = torch.float32 if dtype == G.F32 else torch.bfloat16
     grads = []
     for g in _grads(b):
         v = g.to(torch.float32).numpy().copy()
         v[o1:o2] = rng.integers(-40, 41, o2 - o1).astype(np.float32)
+        # (one entry in a hundred kept of 81 equally likely values: the threshold class is
+        # two and a half times the quota, a few dozen candidates per chunk)
+        v[o4:n] = rng.integers(-40, 41, n - o4).astype(np.float32)
         grads.append(torch.from_numpy(v).to(td))
     ores, tb = run_both(b, grads, seed=17)
     compare_all(b, ores, tb, mixed_ceiling=0.02)   # (unit-scale integers beside 1e-3 values)
